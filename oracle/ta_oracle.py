@@ -1,0 +1,139 @@
+"""ctypes front end of the CPU oracle (test infrastructure only).
+
+Loads ``libta_oracle.so`` built from ``ta_oracle.c`` with gcc; arguments are
+numpy arrays in host memory.  bf16 tensors are passed as ``uint16`` bit
+patterns.  Nothing here is part of the product path: only tests, the smoke
+check and the benchmark's CPU-baseline leg import this module, and it imports
+nothing from the GPU package.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ta_oracle.c")
+_SO = os.path.join(_HERE, "libta_oracle.so")
+
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C11, no contraction, no fast-math)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math",
+               "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_SO)
+        vp, i32, f32, f64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_double
+        lib.ta_oracle_match.argtypes = [vp, i32, vp, i32, vp, i32, vp]
+        lib.ta_oracle_match.restype = None
+        lib.ta_oracle_expand.argtypes = [vp, vp, i32, i32, f32, f64, vp, vp]
+        lib.ta_oracle_expand.restype = None
+        lib.ta_oracle_score.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+        lib.ta_oracle_score.restype = None
+        lib.ta_oracle_utility.argtypes = [vp, vp, vp, i32, f32, f32, f32, vp]
+        lib.ta_oracle_utility.restype = None
+        lib.ta_oracle_select.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
+        lib.ta_oracle_select.restype = i32
+        lib.ta_oracle_compact.argtypes = [vp, vp, i32, i32, vp]
+        lib.ta_oracle_compact.restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def match(tok, tab_ids, tab_len):
+    """anchor[p] = 1 iff a table n-gram ends at p.  tok int32 [n]."""
+    tok = _c(tok, np.int32)
+    tab_ids = _c(tab_ids, np.int32).reshape(len(tab_len), -1) if len(tab_len) else np.zeros((0, 4), np.int32)
+    tab_len = _c(tab_len, np.int32)
+    anchor = np.zeros(tok.shape[0], np.uint8)
+    _load().ta_oracle_match(_p(tok), tok.shape[0], _p(tab_ids), tab_ids.shape[1],
+                            _p(tab_len), tab_len.shape[0], _p(anchor))
+    return anchor
+
+
+def expand(anchor, L=6, B=15.0, rho=0.8, anchor_B=None):
+    """Sponsor mask and voucher V of Eq. 2.  Returns (spons u8 [n], V f32 [n])."""
+    anchor = _c(anchor, np.uint8)
+    n = anchor.shape[0]
+    ab = None if anchor_B is None else _c(anchor_B, np.float32)
+    spons = np.zeros(n, np.uint8)
+    V = np.zeros(n, np.float32)
+    _load().ta_oracle_expand(_p(anchor), _p(ab), n, int(L), float(B), float(rho), _p(spons), _p(V))
+    return spons, V
+
+
+def score(Q, K, causal=True):
+    """A[i] = sum over the group's heads and window rows of softmax weights.
+
+    Q uint16 (bf16 bits) [G][W][d]; K uint16 [n][d].  Returns f32 [n].
+    """
+    Q = _c(Q, np.uint16)
+    K = _c(K, np.uint16)
+    G, W, d = Q.shape
+    n = K.shape[0]
+    assert K.shape[1] == d
+    A = np.zeros(n, np.float32)
+    _load().ta_oracle_score(_p(Q), _p(K), n, G, W, d, 1 if causal else 0, _p(A))
+    return A
+
+
+def utility(A, anchor, V, alpha=1.0, beta=0.5, gamma=0.3):
+    anchor = _c(anchor, np.uint8)
+    V = _c(V, np.float32)
+    n = anchor.shape[0]
+    a = None if A is None else _c(A, np.float32)
+    if a is None:
+        assert alpha == 0.0
+    u = np.zeros(n, np.float32)
+    _load().ta_oracle_utility(_p(a), _p(anchor), _p(V), n, float(alpha), float(beta), float(gamma), _p(u))
+    return u
+
+
+def select(A, anchor, spons, V, K, n_sink, n_recent, alpha=1.0, beta=0.5, gamma=0.3):
+    """Retained positions (ascending) under the (class, u, position) order."""
+    anchor = _c(anchor, np.uint8)
+    spons = _c(spons, np.uint8)
+    V = _c(V, np.float32)
+    n = anchor.shape[0]
+    a = None if A is None else _c(A, np.float32)
+    if a is None:
+        assert alpha == 0.0
+    idx = np.zeros(max(min(K, n), 1), np.int32)
+    cnt = _load().ta_oracle_select(_p(a), _p(anchor), _p(spons), _p(V), n, int(K),
+                                   int(n_sink), int(n_recent),
+                                   float(alpha), float(beta), float(gamma), _p(idx))
+    return idx[:cnt].copy()
+
+
+def compact(rows, idx):
+    """out[r,:] = rows[idx[r],:] for 16-bit row elements (bf16 bits)."""
+    rows = _c(rows, np.uint16)
+    idx = _c(idx, np.int32)
+    out = np.zeros((idx.shape[0], rows.shape[1]), np.uint16)
+    _load().ta_oracle_compact(_p(rows), _p(idx), idx.shape[0], rows.shape[1], _p(out))
+    return out
+
+
+def evict_sequence(tok, tab_ids, tab_len, L=6, B=15.0, rho=0.8, anchor_B=None):
+    """Steps 1-2 for one sequence: (anchor, spons, V)."""
+    anchor = match(tok, tab_ids, tab_len)
+    spons, V = expand(anchor, L=L, B=B, rho=rho, anchor_B=anchor_B)
+    return anchor, spons, V

@@ -1,0 +1,162 @@
+"""Seeded synthetic workloads shaped like the paper's evaluation settings.
+
+This module only draws inputs (token streams with planted anchor n-grams,
+anchor tables, N(0,1) bf16 K/V/Q); it contains none of the method's arithmetic
+and is the one piece of code that both the GPU tests and the CPU oracle tests
+use.  The shapes follow the needle-in-haystack setting (Sec. 4.1: a credential
+after an anchor at depths 0.1-0.9 of a 4K context, budgets K from 16 upward),
+the TA-Fast long-context runs (Sec. 4.7) and agentic multi-turn decode
+(Sec. 4.4); no text, prompt, dataset item or model weight is involved.
+"""
+from dataclasses import dataclass, field, replace
+from typing import List, Optional, Tuple
+
+import numpy as np
+import torch
+
+VOCAB = 32000
+RESERVED = 1024          # table IDs are drawn from the top RESERVED ids
+TABLE_WIDTH = 4          # max n-gram length; unused slots hold -1
+BASE_SEED = 20260411
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One configuration of the eviction pass."""
+    name: str
+    layers: int
+    batch: int
+    n: int
+    hq: int
+    hkv: int
+    d: int = 128
+    window: int = 32            # observation-window queries W (0: attention-free)
+    n_sink: int = 4
+    n_recent: int = 4
+    budgets: Tuple[int, ...] = (16,)
+    table_entries: int = 16
+    gram_min: int = 2
+    gram_max: int = 2
+    planted: int = 4
+    value_min: int = 8
+    value_max: int = 8
+    alpha: float = 1.0
+    beta: float = 0.5
+    gamma: float = 0.3
+    span_L: int = 6
+    sponsor_B: float = 15.0
+    rho: float = 0.8
+    seed: int = BASE_SEED
+    ragged: Optional[Tuple[int, int]] = None   # (min_len, max_len) or None
+
+
+# The five benchmark configurations.
+CONFIGS = {
+    "c1_single_layer": Workload("c1_single_layer", layers=1, batch=1, n=4096, hq=32, hkv=8,
+                                window=32, n_sink=4, n_recent=4, budgets=(16,),
+                                table_entries=16, gram_min=2, gram_max=2, planted=4,
+                                seed=BASE_SEED + 1),
+    "c2_full_model": Workload("c2_full_model", layers=32, batch=1, n=4096, hq=32, hkv=8,
+                              window=32, n_sink=4, n_recent=4, budgets=(16, 64, 256, 1024),
+                              table_entries=16, gram_min=1, gram_max=3, planted=8,
+                              seed=BASE_SEED + 2),
+    "c3_ta_fast": Workload("c3_ta_fast", layers=32, batch=16, n=32768, hq=32, hkv=8,
+                           window=0, n_sink=4, n_recent=64, budgets=(512,),
+                           table_entries=64, gram_min=1, gram_max=4, planted=32,
+                           alpha=0.0, seed=BASE_SEED + 3),
+    "c4_long_context": Workload("c4_long_context", layers=32, batch=4, n=131072, hq=32, hkv=8,
+                                window=64, n_sink=4, n_recent=128, budgets=(1024,),
+                                table_entries=64, gram_min=1, gram_max=4, planted=128,
+                                value_min=4, value_max=32, seed=BASE_SEED + 4),
+    "c5_agentic_prefill": Workload("c5_agentic_prefill", layers=32, batch=64, n=16384, hq=32, hkv=8,
+                                   window=32, n_sink=4, n_recent=4, budgets=(256,),
+                                   table_entries=16, gram_min=1, gram_max=3, planted=8,
+                                   ragged=(2048, 16384), seed=BASE_SEED + 5),
+}
+
+
+def scaled(w: Workload, **kw) -> Workload:
+    """A copy of a configuration with some sizes replaced (for oracle-sized tests)."""
+    return replace(w, **kw)
+
+
+@dataclass
+class TokenData:
+    tok: np.ndarray            # int32 [B][n] (rows padded with filler past seq_len)
+    seq_len: np.ndarray        # int32 [B]
+    tab_ids: np.ndarray        # int32 [E][TABLE_WIDTH], -1 padded
+    tab_len: np.ndarray        # int32 [E]
+    planted: List[List[int]] = field(default_factory=list)   # per sequence: anchor positions
+
+
+def make_table(w: Workload, rng: np.random.Generator):
+    """E n-grams whose IDs are all distinct and come from the reserved id range."""
+    E = w.table_entries
+    lens = rng.integers(w.gram_min, w.gram_max + 1, size=E).astype(np.int32)
+    ids = rng.permutation(RESERVED)[: E * TABLE_WIDTH].astype(np.int32) + (VOCAB - RESERVED)
+    tab = ids.reshape(E, TABLE_WIDTH).copy()
+    for e in range(E):
+        tab[e, lens[e]:] = -1
+    return tab, lens
+
+
+def make_tokens(w: Workload, clean: bool = True) -> TokenData:
+    """Token streams with w.planted anchor n-grams per sequence.
+
+    clean: filler IDs never touch the reserved range, so the planted positions
+    are exactly the anchors.  dirty: filler is uniform over the whole vocabulary,
+    so accidental (mostly 1-gram) matches and overlapping spans occur.
+    """
+    rng = np.random.default_rng(w.seed)
+    tab, lens = make_table(w, rng)
+    hi = VOCAB - RESERVED if clean else VOCAB
+    tok = rng.integers(0, hi, size=(w.batch, w.n)).astype(np.int32)
+    if w.ragged is None:
+        seq_len = np.full(w.batch, w.n, np.int32)
+    else:
+        seq_len = rng.integers(w.ragged[0], w.ragged[1] + 1, size=w.batch).astype(np.int32)
+        seq_len = np.minimum(seq_len, w.n)
+    planted = []
+    for b in range(w.batch):
+        nb = int(seq_len[b])
+        lo = w.n_sink + 2
+        hi_pos = nb - w.n_recent - 2
+        foot = w.gram_max + w.value_max + w.span_L + 1
+        P = w.planted
+        seg = (hi_pos - lo) // max(P, 1)
+        pos_list = []
+        if P > 0 and seg >= foot:
+            for s in range(P):
+                e = int(rng.integers(0, w.table_entries))
+                start = lo + s * seg + int(rng.integers(0, seg - foot + 1))
+                ln = int(lens[e])
+                tok[b, start:start + ln] = tab[e, :ln]
+                pos_list.append(start + ln - 1)          # anchor = last token of the n-gram
+        planted.append(pos_list)
+    return TokenData(tok=tok, seq_len=seq_len, tab_ids=tab, tab_len=lens, planted=planted)
+
+
+def make_qkv(w: Workload, device="cpu", layers: Optional[int] = None, with_v: bool = True):
+    """bf16 N(0,1) tensors: Q [Lyr][B][Hq][W][d], K and V [Lyr][B][Hkv][n][d]."""
+    lyr = w.layers if layers is None else layers
+    g = torch.Generator(device=device)
+    g.manual_seed(w.seed)
+
+    def draw(shape):
+        out = torch.empty(shape, dtype=torch.bfloat16, device=device)
+        flat = out.view(-1)
+        step = 1 << 26
+        for s in range(0, flat.numel(), step):
+            e = min(s + step, flat.numel())
+            flat[s:e] = torch.randn(e - s, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+        return out
+
+    K = draw((lyr, w.batch, w.hkv, w.n, w.d))
+    V = draw((lyr, w.batch, w.hkv, w.n, w.d)) if with_v else None
+    Q = draw((lyr, w.batch, w.hq, w.window, w.d)) if w.window > 0 else None
+    return Q, K, V
+
+
+def bf16_bits(t: torch.Tensor) -> np.ndarray:
+    """Raw 16-bit patterns of a bf16 tensor as a numpy uint16 array (host)."""
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
