@@ -1,0 +1,201 @@
+/*
+ * libta - Transactional Attention KV-cache eviction pass for AMD gfx950.
+ *
+ * C ABI.  One call evicts a KV cache down to a budget of K tokens per
+ * (layer, sequence, KV head) "unit":
+ *
+ *   1. ta_match_anchors  anchor n-gram match over token IDs + voucher expansion
+ *   2. ta_score          attention column sums of an observation window
+ *   3. ta_select         protected top-K under the (class, utility, position) order
+ *   4. ta_compact        gather of the retained K/V rows
+ *      ta_evict          all of the above in one call
+ *
+ * Conventions shared by every entry point
+ *   - Pointers marked DEVICE are GPU global memory owned by the caller;
+ *     pointers marked HOST are ordinary host memory read during the call.
+ *     Inputs are never written; outputs must not alias inputs.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work on it: they never synchronise, allocate or free.
+ *   - Positions are 0-based; the paper's token i is position p = i - 1.
+ *   - K, V, Q are bf16.  The head dimension d must be 128.
+ *   - Sequences of a batch are padded to a common length n; `seq_len`
+ *     (DEVICE int32 [B], nullable) gives the valid length of each sequence,
+ *     clamped to [0, n] on the device.  NULL means every sequence has length n.
+ *   - Return value: TA_OK or a negative ta_status.  All argument validation
+ *     happens on the host before anything is launched, so an error code other
+ *     than TA_ERR_HIP means no work was enqueued.
+ */
+#ifndef TA_H
+#define TA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TA_MAX_TABLE 64   /* anchor-table entries                       */
+#define TA_MAX_GRAM 4     /* tokens per anchor n-gram                   */
+#define TA_MAX_SPAN 64    /* sponsor span L                             */
+#define TA_HEAD_DIM 128   /* the only supported head dimension          */
+#define TA_MAX_ROWS 512   /* (query heads per KV head) * window rows    */
+
+typedef enum ta_status {
+    TA_OK = 0,
+    TA_ERR_NULL = -1,      /* a required pointer is NULL                                   */
+    TA_ERR_SHAPE = -2,     /* a size, stride or table entry is outside the supported range */
+    TA_ERR_BUDGET = -3,    /* K < 1 or K < n_sink + n_recent                               */
+    TA_ERR_WORKSPACE = -4, /* workspace missing or smaller than ta_workspace_bytes()       */
+    TA_ERR_ALIGN = -5,     /* a K/V/Q pointer or stride is not 16-byte aligned             */
+    TA_ERR_HIP = -6        /* a launch failed; see ta_last_hip_error()                     */
+} ta_status;
+
+/*
+ * Hyper-parameters of the retention policy (Eq. 1, Eq. 2, Eq. 3, Sec. 3.3).
+ * The pension and frequency terms of Eq. 1 have no definition in the paper and
+ * are not part of the utility (delta = lambda = 0).
+ */
+typedef struct ta_params {
+    int32_t n_sink;     /* first n_sink positions are always retained (attention sinks)   */
+    int32_t n_recent;   /* last n_recent positions are always retained (recent window)    */
+    int32_t span_L;     /* sponsor span L of Eq. 2 (paper default 6), 0..TA_MAX_SPAN      */
+    float sponsor_B;    /* sponsor budget B of Eq. 2 (paper default 15)                   */
+    double rho;         /* voucher decay base of Eq. 2 (paper: 0.8)                       */
+    float alpha;        /* weight of the attention term A_i (1.0; 0 = TA-Fast, Eq. 3)     */
+    float beta;         /* weight of the recency term R_i = (p+1)/n (0.5)                 */
+    float gamma;        /* weight of the anchor indicator S_i (0.3)                       */
+    int32_t causal;     /* 1: window query w sees keys 0..n-W+w; 0: every key             */
+} ta_params;
+
+/*
+ * Shapes and strides of the cache tensors.  Strides are in ELEMENTS (bf16).
+ * The innermost dimension d is contiguous everywhere.
+ *   K, V : [layers][batch][hkv][n][d]     strides kv_stride = {layer, batch, head, position}
+ *   Q    : [layers][batch][hq][window][d] strides q_stride  = {layer, batch, head}; rows of a
+ *          head are contiguous ([window][d]).  Row w of sequence b is the query at
+ *          position seq_len[b] - window + w (the last `window` positions).
+ * Query head h belongs to KV head h / (hq / hkv).
+ */
+typedef struct ta_layout {
+    int32_t layers, batch, hq, hkv;
+    int32_t n;          /* padded sequence length                                   */
+    int32_t window;     /* observation-window rows W (ignored when alpha == 0)      */
+    int32_t d;          /* must equal TA_HEAD_DIM                                   */
+    int64_t kv_stride[4];
+    int64_t q_stride[3];
+} ta_layout;
+
+/* Bytes of DEVICE scratch that ta_score / ta_evict need for this layout (0 when
+ * no attention term is computed).  The workspace holds per-chunk softmax row
+ * statistics; its contents are meaningless between calls. */
+size_t ta_workspace_bytes(const ta_layout *lay, const ta_params *prm);
+
+/*
+ * Steps 1+2 - anchor detection (Sec. 3.2; Alg. 1, detection step; S_i of Eq. 1)
+ * and voucher allocation (Eq. 2; Alg. 1, voucher loops; Fig. 2).
+ *
+ * anchor[b][p] = 1 iff some table entry e equals tok[b][p-len[e]+1 .. p]; the
+ * anchor is the last token of the n-gram, matches never cross a sequence start.
+ * vouch[b][j]  = sum over anchors i with i < j <= i+L of B_i * rho^(j-i),
+ *                each term B_i * (float)rho^k rounded to fp32 and added in fp32
+ *                in order of increasing k = j - i; spans are clipped at seq_len.
+ * spons[b][j]  = 1 iff an anchor lies in [j-L, j-1]  (<=> vouch > 0 for B > 0).
+ * Positions >= seq_len[b] get 0 in all three outputs.
+ *
+ *   tok       DEVICE int32 [B][n]
+ *   seq_len   DEVICE int32 [B] or NULL
+ *   tab_ids   HOST   int32 [E][TA_MAX_GRAM]; row e holds tab_len[e] token IDs (>= 0), rest ignored
+ *   tab_len   HOST   int32 [E], each in 1..TA_MAX_GRAM;  0 <= E <= TA_MAX_TABLE
+ *   anchor_B  DEVICE float [B][n] or NULL: per-anchor budget B_i read at anchor
+ *             positions (confidence-weighted sponsorship, Sec. 5.1); NULL = prm->sponsor_B
+ *   anchor, spons  DEVICE uint8 [B][n] (out);  vouch DEVICE float [B][n] (out)
+ * Errors: NULL, SHAPE (B,n < 1; E, lengths, ids, span_L out of range).
+ */
+int32_t ta_match_anchors(const int32_t *tok, const int32_t *seq_len, int32_t B, int32_t n,
+                         const int32_t *tab_ids, const int32_t *tab_len, int32_t E,
+                         const float *anchor_B, const ta_params *prm,
+                         uint8_t *anchor, uint8_t *spons, float *vouch, void *stream);
+
+/*
+ * Step 3 - attention term A_i of Eq. 1 (cumulative attention over heads and
+ * steps; dormant-token definition, App. A), computed SnapKV/H2O style over an
+ * observation window: for every unit (layer, b, g)
+ *   A[i] = sum over the hq/hkv query heads h of group g and rows w < W of
+ *          softmax_i( q_{h,w} . k_i / sqrt(d) ) over the keys visible to row w.
+ * bf16 inputs, fp32 accumulation and softmax.  A[i] = 0 for i >= seq_len[b].
+ *
+ *   Q, K   DEVICE bf16, laid out per `lay`
+ *   A      DEVICE float [layers][batch][hkv][n] (out, contiguous)
+ *   ws     DEVICE scratch of at least ta_workspace_bytes() bytes, 16-byte aligned
+ * Errors: NULL, SHAPE (d != 128, hq % hkv != 0, W < 1, W > n,
+ *         (hq/hkv)*W > TA_MAX_ROWS), ALIGN, WORKSPACE.
+ */
+int32_t ta_score(const void *Q, const void *K, const ta_layout *lay, const int32_t *seq_len,
+                 const ta_params *prm, float *A, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Step 4 - utility and protected top-K (Eq. 1 / Eq. 3; Alg. 1, utility and
+ * top-K steps; Sec. 3.3; Thm. 2-4; budget-partition table, App. D).
+ *   u_p   = alpha*A_p + beta*(p+1)/len + gamma*anchor_p + vouch_p   (fp32, each product
+ *           and sum rounded, left to right; A is not read when alpha == 0)
+ *   class = 2 if p < n_sink or p >= len - n_recent; 1 if sponsored; else 0
+ * The retained set of a unit is the first min(K, len) positions under the total
+ * order (class descending, u descending, position descending), written in
+ * ascending position order.  NaN utilities are not supported.
+ *
+ *   A       DEVICE float [layers][batch][hkv][n], or NULL when alpha == 0
+ *   anchor, spons DEVICE uint8 [batch][n]; vouch DEVICE float [batch][n]
+ *   idx     DEVICE int32 [layers][batch][hkv][K] (out; entries >= cnt are left untouched)
+ *   cnt     DEVICE int32 [layers][batch][hkv]    (out; = min(K, len))
+ * The retained set of TA-Fast does not depend on layer or head: call with
+ * layers = hkv = 1 and share idx across units (see ta_compact).
+ * Errors: NULL, SHAPE, BUDGET.
+ */
+int32_t ta_select(const float *A, const uint8_t *anchor, const uint8_t *spons, const float *vouch,
+                  const int32_t *seq_len, int32_t layers, int32_t batch, int32_t hkv, int32_t n,
+                  int32_t K, const ta_params *prm, int32_t *idx, int32_t *cnt, void *stream);
+
+/*
+ * Step 5 - eviction (Sec. 3.2 "Token selection": index_select on the KV tensors
+ * along the sequence dimension; Alg. 1, eviction step).
+ *   Kout[unit][r][:] = Kin[unit][idx[r]][:],  Vout likewise,  for r < cnt.
+ * Rows r >= cnt of the outputs are left untouched.
+ *
+ *   Kin, Vin   DEVICE bf16 per `lay` (kv_stride)
+ *   idx, cnt   DEVICE int32: [layers][batch][hkv][K] / [layers][batch][hkv], or, when
+ *              idx_shared != 0, [batch][K] / [batch] used by every layer and head
+ *   Kout, Vout DEVICE bf16 [layers][batch][hkv][K][d] (out, contiguous)
+ * Every idx entry below cnt must be a valid position (< n); entries are clamped
+ * to [0, n-1] on the device so a corrupt index cannot fault.
+ * Errors: NULL, SHAPE, ALIGN.
+ */
+int32_t ta_compact(const void *Kin, const void *Vin, const int32_t *idx, const int32_t *cnt,
+                   const ta_layout *lay, int32_t K, int32_t idx_shared,
+                   void *Kout, void *Vout, void *stream);
+
+/*
+ * The whole pass (Alg. 1 without the budget-decay step, which only matters
+ * between decode steps): match + vouchers once per sequence, then score,
+ * select and compact for every unit.  Arguments as in the four calls above.
+ * With prm->alpha == 0 (TA-Fast, Eq. 3) Q, A and ws may be NULL, the retained
+ * set is computed once per sequence and idx / cnt have the shared shapes
+ * [batch][K] / [batch]; otherwise they are per unit.
+ */
+int32_t ta_evict(const int32_t *tok, const int32_t *seq_len,
+                 const int32_t *tab_ids, const int32_t *tab_len, int32_t E, const float *anchor_B,
+                 const void *Q, const void *Kin, const void *Vin,
+                 const ta_layout *lay, const ta_params *prm, int32_t K,
+                 uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
+                 int32_t *idx, int32_t *cnt, void *Kout, void *Vout,
+                 void *ws, size_t ws_bytes, void *stream);
+
+/* Text for a ta_status value (static storage). */
+const char *ta_strerror(int32_t status);
+/* Raw hipError_t of the most recent TA_ERR_HIP on this thread (0 if none). */
+int32_t ta_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TA_H */

@@ -1,0 +1,10 @@
+"""Transactional Attention KV-cache eviction pass, native on AMD gfx950.
+
+The product is libta.so (HIP kernels behind the C ABI of include/ta.h); this
+package is its thin Python binding plus the synthetic workload generators.
+"""
+from .binding import (EvictPlan, Params, TaError, layout_of, lib, ta_compact, ta_evict,
+                      ta_match_anchors, ta_score, ta_select, ta_workspace_bytes)
+
+__all__ = ["EvictPlan", "Params", "TaError", "layout_of", "lib", "ta_compact", "ta_evict",
+           "ta_match_anchors", "ta_score", "ta_select", "ta_workspace_bytes"]

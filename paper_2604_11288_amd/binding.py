@@ -1,0 +1,270 @@
+"""ctypes binding of libta.so: argument marshalling only.
+
+Every step of the eviction pass runs in the HIP kernels behind the C ABI
+declared in include/ta.h; torch is used for device memory and the current
+stream.  There is no CPU fallback: a missing library or a failing call raises.
+"""
+import ctypes
+import os
+from dataclasses import dataclass, replace
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libta.so")
+
+TA_MAX_TABLE = 64
+TA_MAX_GRAM = 4
+TA_MAX_SPAN = 64
+TA_HEAD_DIM = 128
+TA_MAX_ROWS = 512
+
+TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
+TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
+
+EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_score", "ta_select", "ta_compact",
+           "ta_evict", "ta_strerror", "ta_last_hip_error")
+
+
+class TaError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().ta_strerror(status).decode()
+        if status == TA_ERR_HIP:
+            msg += " (hipError %d)" % lib().ta_last_hip_error()
+        super().__init__("%s: %s [%d]" % (where, msg, status))
+
+
+class CParams(ctypes.Structure):
+    _fields_ = [("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32), ("span_L", ctypes.c_int32),
+                ("sponsor_B", ctypes.c_float), ("rho", ctypes.c_double),
+                ("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("gamma", ctypes.c_float),
+                ("causal", ctypes.c_int32)]
+
+
+class CLayout(ctypes.Structure):
+    _fields_ = [("layers", ctypes.c_int32), ("batch", ctypes.c_int32), ("hq", ctypes.c_int32),
+                ("hkv", ctypes.c_int32), ("n", ctypes.c_int32), ("window", ctypes.c_int32),
+                ("d", ctypes.c_int32),
+                ("kv_stride", ctypes.c_int64 * 4), ("q_stride", ctypes.c_int64 * 3)]
+
+
+@dataclass
+class Params:
+    """Hyper-parameters (defaults: the paper's Full-TA values, Eq. 1-2)."""
+    n_sink: int = 4
+    n_recent: int = 4
+    span_L: int = 6
+    sponsor_B: float = 15.0
+    rho: float = 0.8
+    alpha: float = 1.0
+    beta: float = 0.5
+    gamma: float = 0.3
+    causal: bool = True
+
+    def c(self) -> CParams:
+        return CParams(self.n_sink, self.n_recent, self.span_L, self.sponsor_B, self.rho,
+                       self.alpha, self.beta, self.gamma, 1 if self.causal else 0)
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libta.so is not built: run paper_2604_11288_amd/build.py "
+                               "(or __graft_entry__.build()) first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.ta_workspace_bytes.argtypes = [vp, vp]
+        L.ta_workspace_bytes.restype = sz
+        L.ta_match_anchors.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+        L.ta_match_anchors.restype = i32
+        L.ta_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ta_score.restype = i32
+        L.ta_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+        L.ta_select.restype = i32
+        L.ta_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.ta_compact.restype = i32
+        L.ta_evict.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32,
+                               vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ta_evict.restype = i32
+        L.ta_strerror.argtypes = [i32]
+        L.ta_strerror.restype = ctypes.c_char_p
+        L.ta_last_hip_error.argtypes = []
+        L.ta_last_hip_error.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(rc, where):
+    if rc != TA_OK:
+        raise TaError(rc, where)
+
+
+def _table(tab_ids, tab_len):
+    """Host copies of the anchor table in the ABI's [E][TA_MAX_GRAM] / [E] int32 form."""
+    tab_len = np.ascontiguousarray(np.asarray(tab_len, dtype=np.int32))
+    E = int(tab_len.shape[0])
+    ids = np.full((max(E, 1), TA_MAX_GRAM), -1, np.int32)
+    if E:
+        src = np.asarray(tab_ids, dtype=np.int32).reshape(E, -1)
+        ids[:E, :min(src.shape[1], TA_MAX_GRAM)] = src[:, :TA_MAX_GRAM]
+    return ids, tab_len, E
+
+
+def layout_of(K: torch.Tensor, Q: Optional[torch.Tensor] = None, window: Optional[int] = None) -> CLayout:
+    """ta_layout of a [Lyr][B][Hkv][n][d] cache tensor (and its [Lyr][B][Hq][W][d] queries)."""
+    assert K.dim() == 5 and K.dtype == torch.bfloat16 and K.stride(4) == 1
+    lay = CLayout()
+    lay.layers, lay.batch, lay.hkv, lay.n, lay.d = K.shape
+    for i in range(4):
+        lay.kv_stride[i] = K.stride(i)
+    if Q is not None:
+        assert Q.dim() == 5 and Q.dtype == torch.bfloat16 and Q.stride(4) == 1
+        assert Q.stride(3) == Q.shape[4], "rows of a query head must be contiguous"
+        lay.hq, lay.window = Q.shape[2], Q.shape[3]
+        for i in range(3):
+            lay.q_stride[i] = Q.stride(i)
+    else:
+        lay.hq, lay.window = lay.hkv, (window or 0)
+    return lay
+
+
+def ta_workspace_bytes(lay: CLayout, params: Params) -> int:
+    cp = params.c()
+    return int(lib().ta_workspace_bytes(ctypes.byref(lay), ctypes.byref(cp)))
+
+
+def ta_match_anchors(tok, tab_ids, tab_len, params: Params, seq_len=None, anchor_B=None,
+                     out=None, stream=None):
+    """Steps 1+2.  tok int32 [B][n] (device).  Returns (anchor u8, spons u8, vouch f32), each [B][n]."""
+    assert tok.dtype == torch.int32 and tok.dim() == 2 and tok.is_contiguous()
+    B, n = tok.shape
+    ids, lens, E = _table(tab_ids, tab_len)
+    if out is None:
+        anchor = torch.empty((B, n), dtype=torch.uint8, device=tok.device)
+        spons = torch.empty((B, n), dtype=torch.uint8, device=tok.device)
+        vouch = torch.empty((B, n), dtype=torch.float32, device=tok.device)
+    else:
+        anchor, spons, vouch = out
+    cp = params.c()
+    rc = lib().ta_match_anchors(_ptr(tok), _ptr(seq_len), B, n, ids.ctypes.data, lens.ctypes.data, E,
+                                _ptr(anchor_B), ctypes.byref(cp), _ptr(anchor), _ptr(spons), _ptr(vouch),
+                                _stream(stream))
+    _check(rc, "ta_match_anchors")
+    return anchor, spons, vouch
+
+
+def ta_score(Q, K, params: Params, seq_len=None, A=None, ws=None, stream=None):
+    """Step 3.  Returns A f32 [Lyr][B][Hkv][n]."""
+    lay = layout_of(K, Q)
+    if A is None:
+        A = torch.empty((lay.layers, lay.batch, lay.hkv, lay.n), dtype=torch.float32, device=K.device)
+    need = ta_workspace_bytes(lay, replace(params, alpha=1.0))   # sized as for a scored pass
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=K.device)
+    cp = params.c()
+    rc = lib().ta_score(_ptr(Q), _ptr(K), ctypes.byref(lay), _ptr(seq_len), ctypes.byref(cp),
+                        _ptr(A), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "ta_score")
+    return A
+
+
+def ta_select(A, anchor, spons, vouch, K: int, params: Params, layers: int, hkv: int,
+              seq_len=None, out=None, stream=None):
+    """Step 4.  Returns (idx i32 [layers][B][hkv][K], cnt i32 [layers][B][hkv])."""
+    B, n = anchor.shape
+    if out is None:
+        idx = torch.full((layers, B, hkv, K), -1, dtype=torch.int32, device=anchor.device)
+        cnt = torch.zeros((layers, B, hkv), dtype=torch.int32, device=anchor.device)
+    else:
+        idx, cnt = out
+    cp = params.c()
+    rc = lib().ta_select(_ptr(A), _ptr(anchor), _ptr(spons), _ptr(vouch), _ptr(seq_len),
+                         layers, B, hkv, n, K, ctypes.byref(cp), _ptr(idx), _ptr(cnt), _stream(stream))
+    _check(rc, "ta_select")
+    return idx, cnt
+
+
+def ta_compact(Kin, Vin, idx, cnt, K: int, idx_shared: bool = False, out=None, stream=None):
+    """Step 5.  Returns (Kout, Vout) bf16 [Lyr][B][Hkv][K][d]."""
+    lay = layout_of(Kin)
+    assert Vin.shape == Kin.shape and Vin.stride() == Kin.stride()
+    if out is None:
+        shape = (lay.layers, lay.batch, lay.hkv, K, lay.d)
+        Kout = torch.zeros(shape, dtype=torch.bfloat16, device=Kin.device)
+        Vout = torch.zeros(shape, dtype=torch.bfloat16, device=Kin.device)
+    else:
+        Kout, Vout = out
+    rc = lib().ta_compact(_ptr(Kin), _ptr(Vin), _ptr(idx), _ptr(cnt), ctypes.byref(lay), K,
+                          1 if idx_shared else 0, _ptr(Kout), _ptr(Vout), _stream(stream))
+    _check(rc, "ta_compact")
+    return Kout, Vout
+
+
+class EvictPlan:
+    """Pre-allocated outputs and marshalled arguments of one ta_evict configuration.
+
+    run() only performs the C call, so it can sit inside a timed loop.
+    """
+
+    def __init__(self, tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params,
+                 seq_len=None, anchor_B=None):
+        dev = Kin.device
+        self.params, self.K = params, int(K)
+        self.scored = params.alpha != 0.0
+        self.lay = layout_of(Kin, Q if self.scored else None)
+        lay = self.lay
+        self.tok, self.seq_len, self.anchor_B = tok, seq_len, anchor_B
+        self.Q, self.Kin, self.Vin = (Q if self.scored else None), Kin, Vin
+        self.ids, self.lens, self.E = _table(tab_ids, tab_len)
+        B, n = lay.batch, lay.n
+        self.anchor = torch.empty((B, n), dtype=torch.uint8, device=dev)
+        self.spons = torch.empty((B, n), dtype=torch.uint8, device=dev)
+        self.vouch = torch.empty((B, n), dtype=torch.float32, device=dev)
+        if self.scored:
+            self.A = torch.empty((lay.layers, B, lay.hkv, n), dtype=torch.float32, device=dev)
+            self.idx = torch.full((lay.layers, B, lay.hkv, self.K), -1, dtype=torch.int32, device=dev)
+            self.cnt = torch.zeros((lay.layers, B, lay.hkv), dtype=torch.int32, device=dev)
+            nbytes = ta_workspace_bytes(lay, params)
+            self.ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+        else:
+            self.A, self.ws = None, None
+            self.idx = torch.full((B, self.K), -1, dtype=torch.int32, device=dev)
+            self.cnt = torch.zeros((B,), dtype=torch.int32, device=dev)
+        shape = (lay.layers, B, lay.hkv, self.K, lay.d)
+        self.Kout = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+        self.Vout = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+        self._cp = params.c()
+
+    def run(self, stream=None):
+        ws_bytes = 0 if self.ws is None else self.ws.numel()
+        rc = lib().ta_evict(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
+                            self.E, _ptr(self.anchor_B), _ptr(self.Q), _ptr(self.Kin), _ptr(self.Vin),
+                            ctypes.byref(self.lay), ctypes.byref(self._cp), self.K,
+                            _ptr(self.anchor), _ptr(self.spons), _ptr(self.vouch), _ptr(self.A),
+                            _ptr(self.idx), _ptr(self.cnt), _ptr(self.Kout), _ptr(self.Vout),
+                            _ptr(self.ws), ws_bytes, _stream(stream))
+        _check(rc, "ta_evict")
+        return self
+
+
+def ta_evict(tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params, seq_len=None, anchor_B=None,
+             stream=None) -> EvictPlan:
+    """The whole pass in one call; returns the plan object holding every output tensor."""
+    return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B).run(stream)

@@ -1,0 +1,268 @@
+// C-ABI front end: argument validation on the host, then launches.  Every
+// check happens before the first launch, so any status other than TA_ERR_HIP
+// means nothing was enqueued.
+#include <math.h>
+#include <string.h>
+
+#include "ta_internal.h"
+
+namespace {
+
+thread_local int32_t t_last_hip_error = 0;
+
+int32_t hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return TA_OK;
+    t_last_hip_error = (int32_t)e;
+    return TA_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int32_t check_params(const ta_params* prm)
+{
+    if (!prm) return TA_ERR_NULL;
+    if (prm->n_sink < 0 || prm->n_recent < 0) return TA_ERR_SHAPE;
+    if (prm->span_L < 0 || prm->span_L > TA_MAX_SPAN) return TA_ERR_SHAPE;
+    if (!(prm->rho >= 0.0) || !isfinite(prm->rho)) return TA_ERR_SHAPE;
+    if (!isfinite(prm->alpha) || !isfinite(prm->beta) || !isfinite(prm->gamma) ||
+        !isfinite(prm->sponsor_B))
+        return TA_ERR_SHAPE;
+    return TA_OK;
+}
+
+int32_t check_budget(const ta_params* prm, int32_t K)
+{
+    if (K < 1) return TA_ERR_BUDGET;
+    if ((int64_t)prm->n_sink + prm->n_recent > K) return TA_ERR_BUDGET;
+    return TA_OK;
+}
+
+// Shapes shared by score / compact / evict.
+int32_t check_layout(const ta_layout* lay, bool need_q)
+{
+    if (!lay) return TA_ERR_NULL;
+    if (lay->layers < 1 || lay->batch < 1 || lay->hkv < 1 || lay->n < 1) return TA_ERR_SHAPE;
+    if (lay->d != TA_HEAD_DIM) return TA_ERR_SHAPE;
+    if (lay->batch > 65535) return TA_ERR_SHAPE;
+    if ((int64_t)lay->layers * lay->batch * lay->hkv > (1 << 24)) return TA_ERR_SHAPE;
+    for (int i = 0; i < 4; ++i)
+        if (lay->kv_stride[i] < 0) return TA_ERR_SHAPE;
+    if (lay->kv_stride[3] < lay->d) return TA_ERR_SHAPE;
+    for (int i = 0; i < 4; ++i)
+        if (lay->kv_stride[i] % 8 != 0) return TA_ERR_ALIGN;
+    if (need_q) {
+        if (lay->hq < 1 || lay->hq % lay->hkv != 0) return TA_ERR_SHAPE;
+        if (lay->window < 1 || lay->window > lay->n) return TA_ERR_SHAPE;
+        if ((int64_t)(lay->hq / lay->hkv) * lay->window > TA_MAX_ROWS) return TA_ERR_SHAPE;
+        for (int i = 0; i < 3; ++i) {
+            if (lay->q_stride[i] < 0) return TA_ERR_SHAPE;
+            if (lay->q_stride[i] % 8 != 0) return TA_ERR_ALIGN;
+        }
+        if (lay->q_stride[2] < (int64_t)lay->window * lay->d) return TA_ERR_SHAPE;
+    }
+    return TA_OK;
+}
+
+int32_t build_table(const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const ta_params* prm,
+                    ta::MatchTable* out)
+{
+    if (E < 0 || E > TA_MAX_TABLE) return TA_ERR_SHAPE;
+    if (E > 0 && (!tab_ids || !tab_len)) return TA_ERR_NULL;
+    memset(out, 0, sizeof(*out));
+    for (int e = 0; e < E; ++e) {
+        const int32_t len = tab_len[e];
+        if (len < 1 || len > TA_MAX_GRAM) return TA_ERR_SHAPE;
+        for (int t = 0; t < len; ++t) {
+            const int32_t id = tab_ids[e * TA_MAX_GRAM + t];
+            if (id < 0) return TA_ERR_SHAPE;
+            out->rid[e][len - 1 - t] = id;                  // reversed: last token first
+        }
+        for (int t = len; t < TA_MAX_GRAM; ++t) out->rid[e][t] = -1;
+        out->len[e] = len;
+    }
+    out->E = E;
+    out->L = prm->span_L;
+    out->B = prm->sponsor_B;
+    for (int k = 0; k <= TA_MAX_SPAN; ++k) out->pw[k] = (float)pow(prm->rho, (double)k);
+    return TA_OK;
+}
+
+size_t workspace_bytes(const ta_layout* lay)
+{
+    const int64_t rows = (int64_t)(lay->hq / lay->hkv) * lay->window;
+    const int64_t rows_pad = ta::score_padded_rows((int32_t)rows);
+    const int64_t ck = ta::score_chunk_keys(lay->n);
+    const int64_t nchunks = (lay->n + ck - 1) / ck;
+    const int64_t units = (int64_t)lay->layers * lay->batch * lay->hkv;
+    return (size_t)(units * nchunks * rows_pad * 2 * (int64_t)sizeof(float));
+}
+
+int32_t check_match(const int32_t* tok, int32_t B, int32_t n, const ta_params* prm,
+                    const uint8_t* anchor, const uint8_t* spons, const float* vouch)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    if (!tok || !anchor || !spons || !vouch) return TA_ERR_NULL;
+    if (B < 1 || n < 1 || B > 65535) return TA_ERR_SHAPE;
+    return TA_OK;
+}
+
+int32_t check_score(const void* Q, const void* K, const ta_layout* lay, const ta_params* prm,
+                    const float* A, const void* ws, size_t ws_bytes)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    rc = check_layout(lay, true);
+    if (rc != TA_OK) return rc;
+    if (!Q || !K || !A) return TA_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K)) return TA_ERR_ALIGN;
+    if (!ws || ws_bytes < workspace_bytes(lay)) return TA_ERR_WORKSPACE;
+    if (!aligned16(ws)) return TA_ERR_ALIGN;
+    if ((int64_t)lay->layers * lay->batch * lay->hkv *
+            ((lay->n + ta::score_chunk_keys(lay->n) - 1) / ta::score_chunk_keys(lay->n)) >
+        0x7FFFFFFFll)
+        return TA_ERR_SHAPE;
+    return TA_OK;
+}
+
+int32_t check_select(const float* A, const uint8_t* anchor, const uint8_t* spons, const float* vouch,
+                     int32_t layers, int32_t batch, int32_t hkv, int32_t n, int32_t K,
+                     const ta_params* prm, const int32_t* idx, const int32_t* cnt)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    if (!anchor || !spons || !vouch || !idx || !cnt) return TA_ERR_NULL;
+    if (prm->alpha != 0.0f && !A) return TA_ERR_NULL;
+    if (layers < 1 || batch < 1 || hkv < 1 || n < 1) return TA_ERR_SHAPE;
+    if ((int64_t)layers * batch * hkv > (1 << 24)) return TA_ERR_SHAPE;
+    return check_budget(prm, K);
+}
+
+int32_t check_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
+                      const ta_layout* lay, int32_t K, const void* Kout, const void* Vout)
+{
+    int32_t rc = check_layout(lay, false);
+    if (rc != TA_OK) return rc;
+    if (!Kin || !Vin || !idx || !cnt || !Kout || !Vout) return TA_ERR_NULL;
+    if (K < 1) return TA_ERR_SHAPE;
+    if (!aligned16(Kin) || !aligned16(Vin) || !aligned16(Kout) || !aligned16(Vout)) return TA_ERR_ALIGN;
+    const int64_t units = (int64_t)lay->layers * lay->batch * lay->hkv;
+    if (units * ((K + 63) / 64) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
+    return TA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ta_workspace_bytes(const ta_layout* lay, const ta_params* prm)
+{
+    if (!lay || !prm) return 0;
+    if (prm->alpha == 0.0f) return 0;
+    if (check_layout(lay, true) != TA_OK) return 0;
+    return workspace_bytes(lay);
+}
+
+int32_t ta_match_anchors(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
+                         const int32_t* tab_ids, const int32_t* tab_len, int32_t E,
+                         const float* anchor_B, const ta_params* prm,
+                         uint8_t* anchor, uint8_t* spons, float* vouch, void* stream)
+{
+    int32_t rc = check_match(tok, B, n, prm, anchor, spons, vouch);
+    if (rc != TA_OK) return rc;
+    ta::MatchTable tab;
+    rc = build_table(tab_ids, tab_len, E, prm, &tab);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_match(tok, seq_len, B, n, tab, anchor_B, anchor, spons, vouch,
+                                       (hipStream_t)stream));
+}
+
+int32_t ta_score(const void* Q, const void* K, const ta_layout* lay, const int32_t* seq_len,
+                 const ta_params* prm, float* A, void* ws, size_t ws_bytes, void* stream)
+{
+    int32_t rc = check_score(Q, K, lay, prm, A, ws, ws_bytes);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws,
+                                       (hipStream_t)stream));
+}
+
+int32_t ta_select(const float* A, const uint8_t* anchor, const uint8_t* spons, const float* vouch,
+                  const int32_t* seq_len, int32_t layers, int32_t batch, int32_t hkv, int32_t n,
+                  int32_t K, const ta_params* prm, int32_t* idx, int32_t* cnt, void* stream)
+{
+    int32_t rc = check_select(A, anchor, spons, vouch, layers, batch, hkv, n, K, prm, idx, cnt);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_select(A, anchor, spons, vouch, seq_len, layers, batch, hkv, n, K,
+                                        *prm, idx, cnt, (hipStream_t)stream));
+}
+
+int32_t ta_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
+                   const ta_layout* lay, int32_t K, int32_t idx_shared,
+                   void* Kout, void* Vout, void* stream)
+{
+    int32_t rc = check_compact(Kin, Vin, idx, cnt, lay, K, Kout, Vout);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, idx_shared, Kout, Vout,
+                                         (hipStream_t)stream));
+}
+
+int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
+                 const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                 const void* Q, const void* Kin, const void* Vin,
+                 const ta_layout* lay, const ta_params* prm, int32_t K,
+                 uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                 int32_t* idx, int32_t* cnt, void* Kout, void* Vout,
+                 void* ws, size_t ws_bytes, void* stream)
+{
+    // validate every stage first: nothing runs unless all of them can
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    if (!lay) return TA_ERR_NULL;
+    const bool scored = prm->alpha != 0.0f;
+    rc = check_match(tok, lay->batch, lay->n, prm, anchor, spons, vouch);
+    if (rc != TA_OK) return rc;
+    ta::MatchTable tab;
+    rc = build_table(tab_ids, tab_len, E, prm, &tab);
+    if (rc != TA_OK) return rc;
+    if (scored) {
+        rc = check_score(Q, Kin, lay, prm, A, ws, ws_bytes);
+        if (rc != TA_OK) return rc;
+    }
+    const int32_t sel_layers = scored ? lay->layers : 1;
+    const int32_t sel_hkv = scored ? lay->hkv : 1;
+    rc = check_select(A, anchor, spons, vouch, sel_layers, lay->batch, sel_hkv, lay->n, K, prm, idx, cnt);
+    if (rc != TA_OK) return rc;
+    rc = check_compact(Kin, Vin, idx, cnt, lay, K, Kout, Vout);
+    if (rc != TA_OK) return rc;
+
+    hipStream_t st = (hipStream_t)stream;
+    rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, anchor, spons, vouch, st));
+    if (rc != TA_OK) return rc;
+    if (scored) {
+        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, st));
+        if (rc != TA_OK) return rc;
+    }
+    rc = hip_status(ta::launch_select(A, anchor, spons, vouch, seq_len, sel_layers, lay->batch, sel_hkv,
+                                      lay->n, K, *prm, idx, cnt, st));
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, st));
+}
+
+const char* ta_strerror(int32_t status)
+{
+    switch (status) {
+        case TA_OK: return "ok";
+        case TA_ERR_NULL: return "a required pointer is NULL";
+        case TA_ERR_SHAPE: return "a size, stride or table entry is outside the supported range";
+        case TA_ERR_BUDGET: return "budget K is below 1 or below n_sink + n_recent";
+        case TA_ERR_WORKSPACE: return "workspace missing or too small";
+        case TA_ERR_ALIGN: return "a K/V/Q pointer or stride is not 16-byte aligned";
+        case TA_ERR_HIP: return "a HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int32_t ta_last_hip_error(void) { return t_last_hip_error; }
+
+}  // extern "C"

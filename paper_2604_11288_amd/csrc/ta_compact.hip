@@ -1,0 +1,107 @@
+// Step 5 of the eviction pass: gather of the retained K/V rows (index_select
+// along the sequence dimension, Sec. 3.2 "Token selection"; Alg. 1, eviction
+// step).  Pure data movement, bound by HBM.
+//
+// A 256-byte row (d = 128 bf16) is moved by 16 lanes with one 16-byte load and
+// one 16-byte store each, so a wavefront moves 4 rows per instruction.  A
+// workgroup takes ROWS_PER_BLOCK consecutive output rows of one unit and issues
+// all of its loads (K and V) before the first store to keep many requests in
+// flight per lane.
+#include "ta_internal.h"
+
+namespace ta {
+
+namespace {
+
+constexpr int COMPACT_THREADS = 256;
+constexpr int ROWS_PER_ITER = COMPACT_THREADS / 16;     // 16 rows per pass over the block
+constexpr int COMPACT_ITERS = 4;
+constexpr int ROWS_PER_BLOCK = ROWS_PER_ITER * COMPACT_ITERS;
+
+struct CompactArgs {
+    const uint4* Kin;
+    const uint4* Vin;
+    const int32_t* idx;
+    const int32_t* cnt;
+    uint4* Kout;
+    uint4* Vout;
+    int64_t s_layer, s_batch, s_head, s_pos;   // input strides in 16-byte units
+    int32_t batch, hkv, n, K;
+    int32_t idx_shared;
+    int32_t blocks_per_unit;
+};
+
+__global__ void __launch_bounds__(COMPACT_THREADS)
+compact_kernel(CompactArgs a)
+{
+    const int32_t unit = (int32_t)(blockIdx.x / (uint32_t)a.blocks_per_unit);
+    const int32_t blk = (int32_t)(blockIdx.x % (uint32_t)a.blocks_per_unit);
+    const int32_t h = unit % a.hkv;
+    const int32_t b = (unit / a.hkv) % a.batch;
+    const int32_t l = unit / (a.hkv * a.batch);
+    const int32_t sel = a.idx_shared ? b : unit;
+    int32_t cnt = a.cnt[sel];
+    cnt = cnt > a.K ? a.K : cnt;
+    const int32_t* idx = a.idx + (size_t)sel * (size_t)a.K;
+    const int64_t in_base = l * a.s_layer + b * a.s_batch + h * a.s_head;
+    const int64_t out_base = (int64_t)unit * a.K * 16;
+
+    const int lane16 = threadIdx.x & 15;
+    const int rsub = threadIdx.x >> 4;
+    if (blk * ROWS_PER_BLOCK >= cnt) return;              // whole block past the retained rows
+    // named registers (not an indexed array) so the loads stay in VGPRs
+    const int32_t row0 = blk * ROWS_PER_BLOCK + rsub;
+    auto src = [&](int32_t r) -> int64_t {
+        r = r < cnt ? r : cnt - 1;                          // tail lanes re-read the last row, store nothing
+        int32_t p = idx[r];
+        p = p < 0 ? 0 : (p >= a.n ? a.n - 1 : p);
+        return in_base + (int64_t)p * a.s_pos + lane16;
+    };
+    static_assert(COMPACT_ITERS == 4, "loads below are written out four times");
+    const int64_t o0 = src(row0), o1 = src(row0 + ROWS_PER_ITER);
+    const int64_t o2 = src(row0 + 2 * ROWS_PER_ITER), o3 = src(row0 + 3 * ROWS_PER_ITER);
+    const uint4 k0 = a.Kin[o0], k1 = a.Kin[o1], k2 = a.Kin[o2], k3 = a.Kin[o3];
+    const uint4 v0 = a.Vin[o0], v1 = a.Vin[o1], v2 = a.Vin[o2], v3 = a.Vin[o3];
+    auto put = [&](int32_t r, const uint4& kk, const uint4& vv) {
+        if (r < cnt) {
+            const int64_t off = out_base + (int64_t)r * 16 + lane16;
+            a.Kout[off] = kk;
+            a.Vout[off] = vv;
+        }
+    };
+    put(row0, k0, v0);
+    put(row0 + ROWS_PER_ITER, k1, v1);
+    put(row0 + 2 * ROWS_PER_ITER, k2, v2);
+    put(row0 + 3 * ROWS_PER_ITER, k3, v3);
+}
+
+}  // namespace
+
+hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
+                          const ta_layout& lay, int32_t K, int32_t idx_shared,
+                          void* Kout, void* Vout, hipStream_t st)
+{
+    CompactArgs a;
+    a.Kin = (const uint4*)Kin;
+    a.Vin = (const uint4*)Vin;
+    a.idx = idx;
+    a.cnt = cnt;
+    a.Kout = (uint4*)Kout;
+    a.Vout = (uint4*)Vout;
+    a.s_layer = lay.kv_stride[0] / 8;
+    a.s_batch = lay.kv_stride[1] / 8;
+    a.s_head = lay.kv_stride[2] / 8;
+    a.s_pos = lay.kv_stride[3] / 8;
+    a.batch = lay.batch;
+    a.hkv = lay.hkv;
+    a.n = lay.n;
+    a.K = K;
+    a.idx_shared = idx_shared;
+    a.blocks_per_unit = (K + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
+    int64_t blocks = units * a.blocks_per_unit;
+    hipLaunchKernelGGL(compact_kernel, dim3((unsigned)blocks), dim3(COMPACT_THREADS), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace ta

@@ -1,0 +1,43 @@
+// Internal launcher interface between the C-ABI front end (ta_api.hip) and the
+// kernels.  Launchers assume validated arguments and only enqueue work.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ta.h"
+
+namespace ta {
+
+// ---- match + voucher expansion -------------------------------------------
+struct MatchTable {
+    int32_t rid[TA_MAX_TABLE][TA_MAX_GRAM];  // n-gram reversed: rid[e][0] is its last token
+    int32_t len[TA_MAX_TABLE];
+    int32_t E;
+    int32_t L;
+    float B;
+    float pw[TA_MAX_SPAN + 1];               // pw[k] = (float) rho^k
+};
+
+hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
+                        const MatchTable& tab, const float* anchor_B,
+                        uint8_t* anchor, uint8_t* spons, float* vouch, hipStream_t st);
+
+// ---- score ------------------------------------------------------------------
+// Keys per workgroup chunk; the workspace holds 2 floats per (unit, chunk, padded row).
+int32_t score_chunk_keys(int32_t n);
+int32_t score_padded_rows(int32_t rows);
+hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
+                        int causal, float* A, float* ws, hipStream_t st);
+
+// ---- select -----------------------------------------------------------------
+hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* spons,
+                         const float* vouch, const int32_t* seq_len,
+                         int32_t layers, int32_t batch, int32_t hkv, int32_t n, int32_t K,
+                         const ta_params& prm, int32_t* idx, int32_t* cnt, hipStream_t st);
+
+// ---- compact ----------------------------------------------------------------
+hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
+                          const ta_layout& lay, int32_t K, int32_t idx_shared,
+                          void* Kout, void* Vout, hipStream_t st);
+
+}  // namespace ta

@@ -1,0 +1,341 @@
+// Step 3 of the eviction pass: the attention term A_i of Eq. 1 as column sums
+// of the observation window's softmax (cumulative attention over heads and
+// steps, App. A dormant-token definition; SnapKV/H2O-style scoring, Sec. 2).
+//
+// Per unit (layer, sequence, KV head): S = Q K^T with M = G*W query rows
+// (G query heads of the group x W window rows), d = 128, n keys; row softmax
+// over the visible keys; A[i] = sum over rows of the softmax column i.
+//
+// Column sums need every row's (max, normaliser) over ALL keys before any row
+// can be added into a column, so the keys are swept twice:
+//   sweep 1 (stats)  : per row, online (m, Z) over a chunk of keys -> workspace
+//   sweep 2 (colsum) : merge the chunk statistics of a row into one constant
+//                      c_r = m_r + log2 Z_r, recompute S, p = 2^(s - c_r),
+//                      sum p over the rows -> A
+// Both sweeps are one kernel template.  A workgroup (4 wavefronts) owns one
+// chunk of keys of one unit; wavefront w owns 32*RT query rows whose Q
+// fragments stay in registers for the whole chunk, while K streams through LDS
+// in 64-key stages (double buffered, 16-byte chunks XOR-swizzled by row so both
+// the staging stores and the ds_read_b128 fragment loads are conflict free).
+// The contraction runs on v_mfma_f32_32x32x16_bf16:
+//   sweep 1 computes K Q^T (keys x rows): a lane then holds 16 keys of ONE
+//           query row, so (m, Z) are two registers per lane and need no
+//           cross-lane traffic until the end of the chunk;
+//   sweep 2 computes Q K^T (rows x keys): a lane holds 16 rows of ONE key, so
+//           the column sum is a register accumulation plus one half-wave swap.
+#include <math.h>
+
+#include "ta_internal.h"
+
+namespace ta {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int SC_THREADS = 256;
+constexpr int SC_WAVES = 4;
+constexpr int STAGE_KEYS = 64;
+constexpr int STAGE_UNITS = STAGE_KEYS * 16;     // 16-byte units per stage (256 B per key)
+
+struct ScoreArgs {
+    const uint4* Q;
+    const uint4* K;
+    const int32_t* seq_len;
+    float* A;
+    float* ws;
+    int64_t q_sl, q_sb, q_sh;          // Q strides (layer, batch, head) in 16-byte units
+    int64_t k_sl, k_sb, k_sh, k_sp;    // K strides (layer, batch, head, position) in 16-byte units
+    int32_t batch, hkv, G, W, n;
+    int32_t rows, rows_pad;            // M = G*W and M rounded up to 128*RT
+    int32_t chunk_keys, nchunks;
+    int32_t causal;
+    float scale_log2;                  // log2(e) / sqrt(d)
+};
+
+__device__ __forceinline__ bf16x8 as_frag(uint4 v)
+{
+    union { uint4 u; bf16x8 b; } c;
+    c.u = v;
+    return c.b;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int RT, bool COLSUM>
+__global__ void __launch_bounds__(SC_THREADS)
+score_kernel(ScoreArgs a)
+{
+    __shared__ uint4 s_k[2][STAGE_UNITS];                  // 2 x 16 KB
+    __shared__ float s_c[COLSUM ? 128 * RT : 1];           // per-row constant m + log2 Z
+    __shared__ int32_t s_lim[COLSUM ? 128 * RT : 1];       // per-row last visible key
+    __shared__ float s_part[COLSUM ? 2 : 1][SC_WAVES][STAGE_KEYS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int c32 = lane & 31, hf = lane >> 5;
+
+    const int32_t chunk = (int32_t)(blockIdx.x % (uint32_t)a.nchunks);
+    const int32_t unit = (int32_t)(blockIdx.x / (uint32_t)a.nchunks);
+    const int32_t g = unit % a.hkv;
+    const int32_t b = (unit / a.hkv) % a.batch;
+    const int32_t l = unit / (a.hkv * a.batch);
+    const int32_t n = a.n, W = a.W;
+    int32_t nb = a.seq_len ? a.seq_len[b] : n;
+    nb = nb < 0 ? 0 : (nb > n ? n : nb);
+
+    const int32_t key_lo = chunk * a.chunk_keys;
+    int32_t key_hi = key_lo + a.chunk_keys;
+    key_hi = key_hi > n ? n : key_hi;
+    const int nstages = (key_hi - key_lo + STAGE_KEYS - 1) / STAGE_KEYS;
+    // keys <= min_lim are visible to every live row of a full window
+    const int32_t min_lim = a.causal ? nb - W : nb - 1;
+
+    // ---- Q fragments of this wavefront's rows (registers, whole chunk) ------
+    bf16x8 qf[RT][8];
+    int32_t my_lim[RT];                                    // sweep 1: last visible key of this lane's row
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        const int32_t r = 32 * (wave * RT + t) + c32;
+        int32_t lim = -1;
+        if (r < a.rows) {
+            const int32_t h = r / W, w = r - h * W;
+            const uint4* qrow = a.Q + l * a.q_sl + b * a.q_sb + (int64_t)(g * a.G + h) * a.q_sh + (int64_t)w * 16;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) qf[t][ks] = as_frag(qrow[2 * ks + hf]);
+            lim = a.causal ? nb - W + w : nb - 1;
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) qf[t][ks] = as_frag(make_uint4(0, 0, 0, 0));
+        }
+        my_lim[t] = lim;
+    }
+
+    // ---- sweep 2 prologue: merge chunk statistics into per-row constants ----
+    float cst[RT][16];
+    if constexpr (COLSUM) {
+        for (int r = tid; r < 128 * RT; r += SC_THREADS) {
+            float c = INFINITY;
+            int32_t lim = -1;
+            if (r < a.rows) {
+                const float* st = a.ws + ((size_t)unit * a.nchunks * a.rows_pad + r) * 2;
+                const size_t step = (size_t)a.rows_pad * 2;
+                float mstar = -INFINITY;
+                for (int ch = 0; ch < a.nchunks; ++ch) mstar = fmaxf(mstar, st[ch * step]);
+                float Z = 0.0f;
+                for (int ch = 0; ch < a.nchunks; ++ch) {
+                    float mc = st[ch * step], zc = st[ch * step + 1];
+                    if (zc > 0.0f) Z += zc * fast_exp2(mc - mstar);
+                }
+                if (Z > 0.0f) c = mstar + log2f(Z);
+                const int32_t h = r / W, w = r - h * W;
+                lim = a.causal ? nb - W + w : nb - 1;
+            }
+            s_c[r] = c;
+            s_lim[r] = lim;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                cst[t][i] = s_c[32 * (wave * RT + t) + 8 * (i >> 2) + 4 * hf + (i & 3)];
+    }
+
+    // ---- K staging --------------------------------------------------------------
+    const uint4* kbase = a.K + l * a.k_sl + b * a.k_sb + g * a.k_sh;
+    const int srow = tid >> 4, sch = tid & 15;             // staging: 16 lanes per key row
+    uint4 stage_reg[4];
+    auto stage_load = [&](int s) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int32_t key = key_lo + s * STAGE_KEYS + srow + 16 * j;
+            key = key > n - 1 ? n - 1 : key;               // stay inside the tensor; masked later
+            stage_reg[j] = kbase[(int64_t)key * a.k_sp + sch];
+        }
+    };
+    auto stage_store = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = srow + 16 * j;
+            s_k[buf][row * 16 + (sch ^ (row & 15))] = stage_reg[j];
+        }
+    };
+
+    float m_run[RT], z_run[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) { m_run[t] = -INFINITY; z_run[t] = 0.0f; }
+    const float sc = a.scale_log2;
+
+    if (nstages > 0) {
+        stage_load(0);
+        stage_store(0);
+    }
+    __syncthreads();
+
+    for (int s = 0; s < nstages; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < nstages) stage_load(s + 1);
+        const int32_t stage_key0 = key_lo + s * STAGE_KEYS;
+        const bool all_visible = (stage_key0 + STAGE_KEYS - 1) <= min_lim;
+
+#pragma unroll
+        for (int kt = 0; kt < STAGE_KEYS / 32; ++kt) {
+            const int32_t tile_key0 = stage_key0 + 32 * kt;
+            bf16x8 kf[8];
+            const int krow = 32 * kt + c32;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                kf[ks] = as_frag(s_k[buf][krow * 16 + ((2 * ks + hf) ^ (krow & 15))]);
+
+            float colsum = 0.0f;
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
+                f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if constexpr (!COLSUM) {
+                    // keys x rows: acc[i] = key tile_key0 + 8*(i/4) + 4*hf + i%4, this lane's query row
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[t][ks], acc, 0, 0, 0);
+                    float x[16];
+                    if (all_visible) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) x[i] = acc[i];
+                    } else {
+                        const int32_t lim = my_lim[t];
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int32_t key = tile_key0 + 8 * (i >> 2) + 4 * hf + (i & 3);
+                            x[i] = key <= lim ? acc[i] : -INFINITY;
+                        }
+                    }
+                    float tmax = x[0];
+#pragma unroll
+                    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, x[i]);
+                    const float mnew = fmaxf(m_run[t], tmax * sc);
+                    if (mnew > -INFINITY) {
+                        float sum = 0.0f;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(x[i], sc, -mnew));
+                        z_run[t] = z_run[t] * fast_exp2(m_run[t] - mnew) + sum;
+                        m_run[t] = mnew;
+                    }
+                } else {
+                    // rows x keys: acc[i] = query row 32*tile + 8*(i/4) + 4*hf + i%4, key tile_key0 + c32
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t][ks], kf[ks], acc, 0, 0, 0);
+                    if (all_visible) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
+                    } else {
+                        const int32_t key = tile_key0 + c32;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int row = 32 * (wave * RT + t) + 8 * (i >> 2) + 4 * hf + (i & 3);
+                            const float p = fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
+                            colsum += key <= s_lim[row] ? p : 0.0f;
+                        }
+                    }
+                }
+            }
+            if constexpr (COLSUM) {
+                colsum += __shfl_xor(colsum, 32);
+                if (hf == 0) s_part[buf][wave][32 * kt + c32] = colsum;
+            }
+        }
+
+        if (s + 1 < nstages) stage_store(buf ^ 1);
+        __syncthreads();
+        if (COLSUM && tid < STAGE_KEYS) {
+            const int32_t key = stage_key0 + tid;
+            if (key < key_hi) {
+                float v = s_part[buf][0][tid];
+#pragma unroll
+                for (int w = 1; w < SC_WAVES; ++w) v += s_part[buf][w][tid];
+                a.A[(size_t)unit * n + key] = v;
+            }
+        }
+    }
+
+    if constexpr (!COLSUM) {
+        // merge the two half-waves (disjoint key subsets of the same row), then store
+        float* st = a.ws + (((size_t)unit * a.nchunks + chunk) * a.rows_pad) * 2;
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            const float mo = __shfl_xor(m_run[t], 32), zo = __shfl_xor(z_run[t], 32);
+            const float mf = fmaxf(m_run[t], mo);
+            float zf = 0.0f;
+            if (mf > -INFINITY) zf = z_run[t] * fast_exp2(m_run[t] - mf) + zo * fast_exp2(mo - mf);
+            if (hf == 0) {
+                const int32_t r = 32 * (wave * RT + t) + c32;
+                st[r * 2] = mf;
+                st[r * 2 + 1] = zf;
+            }
+        }
+    }
+}
+
+template <int RT>
+void launch_rt(const ScoreArgs& a, unsigned blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL((score_kernel<RT, false>), dim3(blocks), dim3(SC_THREADS), 0, st, a);
+    hipLaunchKernelGGL((score_kernel<RT, true>), dim3(blocks), dim3(SC_THREADS), 0, st, a);
+}
+
+}  // namespace
+
+int32_t score_padded_rows(int32_t rows)
+{
+    if (rows <= 128) return 128;
+    if (rows <= 256) return 256;
+    return 512;
+}
+
+int32_t score_chunk_keys(int32_t n)
+{
+    // at most 32 chunks per unit so that merging chunk statistics stays cheap
+    int32_t ck = 512;
+    while ((int64_t)ck * 32 < n) ck *= 2;
+    return ck;
+}
+
+hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
+                        int causal, float* A, float* ws, hipStream_t st)
+{
+    ScoreArgs a;
+    a.Q = (const uint4*)Q;
+    a.K = (const uint4*)K;
+    a.seq_len = seq_len;
+    a.A = A;
+    a.ws = ws;
+    a.q_sl = lay.q_stride[0] / 8;
+    a.q_sb = lay.q_stride[1] / 8;
+    a.q_sh = lay.q_stride[2] / 8;
+    a.k_sl = lay.kv_stride[0] / 8;
+    a.k_sb = lay.kv_stride[1] / 8;
+    a.k_sh = lay.kv_stride[2] / 8;
+    a.k_sp = lay.kv_stride[3] / 8;
+    a.batch = lay.batch;
+    a.hkv = lay.hkv;
+    a.G = lay.hq / lay.hkv;
+    a.W = lay.window;
+    a.n = lay.n;
+    a.rows = a.G * a.W;
+    a.rows_pad = score_padded_rows(a.rows);
+    a.chunk_keys = score_chunk_keys(lay.n);
+    a.nchunks = (lay.n + a.chunk_keys - 1) / a.chunk_keys;
+    a.causal = causal;
+    a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
+    const int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
+    const unsigned blocks = (unsigned)(units * a.nchunks);
+    switch (a.rows_pad) {
+        case 128: launch_rt<1>(a, blocks, st); break;
+        case 256: launch_rt<2>(a, blocks, st); break;
+        default: launch_rt<4>(a, blocks, st); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace ta

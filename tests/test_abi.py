@@ -1,0 +1,159 @@
+"""The C-ABI library loads, exports what include/ta.h declares, and rejects bad
+arguments on the host before anything is launched (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_11288_amd import binding as tb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(tb.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return tb.lib()
+
+
+def test_exports_match_header(L):
+    text = open(os.path.join(ROOT, "include", "ta.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ta_[a-z_]+)\s*\(", text))
+    assert declared == set(tb.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_strerror_covers_every_status(L):
+    seen = set()
+    for code in range(0, -7, -1):
+        msg = L.ta_strerror(code).decode()
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 7
+    assert L.ta_strerror(-99).decode() == "unknown status"
+    assert L.ta_last_hip_error() == 0
+
+
+FAKE = ctypes.c_void_p(0x7f0000001000)      # never dereferenced: validation fails first
+
+
+def _lay(**kw):
+    lay = tb.CLayout()
+    lay.layers, lay.batch, lay.hq, lay.hkv, lay.n, lay.window, lay.d = 2, 1, 32, 8, 4096, 32, 128
+    st = [8 * 4096 * 128, 8 * 4096 * 128, 4096 * 128, 128]
+    qs = [32 * 32 * 128, 32 * 32 * 128, 32 * 128]
+    for i in range(4):
+        lay.kv_stride[i] = st[i]
+    for i in range(3):
+        lay.q_stride[i] = qs[i]
+    for k, v in kw.items():
+        if k in ("kv_stride", "q_stride"):
+            for i, x in enumerate(v):
+                getattr(lay, k)[i] = x
+        else:
+            setattr(lay, k, v)
+    return lay
+
+
+def _table():
+    ids = np.array([[5, 6, -1, -1], [7, -1, -1, -1]], np.int32)
+    lens = np.array([2, 1], np.int32)
+    return ids, lens
+
+
+def test_match_error_paths(L):
+    ids, lens = _table()
+    cp = tb.Params().c()
+    ok_args = lambda: [FAKE, None, 1, 128, ids.ctypes.data, lens.ctypes.data, 2, None, ctypes.byref(cp),
+                       FAKE, FAKE, FAKE, None]
+    a = ok_args(); a[0] = None
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_NULL
+    a = ok_args(); a[11] = None
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_NULL
+    a = ok_args(); a[8] = None
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_NULL
+    a = ok_args(); a[3] = 0
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_SHAPE
+    a = ok_args(); a[6] = tb.TA_MAX_TABLE + 1
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_SHAPE
+    a = ok_args(); a[4] = None
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_NULL
+    bad_len = np.array([5, 1], np.int32)
+    a = ok_args(); a[5] = bad_len.ctypes.data
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_SHAPE
+    bad_ids = ids.copy(); bad_ids[0, 1] = -3
+    a = ok_args(); a[4] = bad_ids.ctypes.data
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_SHAPE
+    cp_bad = tb.Params(span_L=tb.TA_MAX_SPAN + 1).c()
+    a = ok_args(); a[8] = ctypes.byref(cp_bad)
+    assert L.ta_match_anchors(*a) == tb.TA_ERR_SHAPE
+
+
+def test_score_error_paths(L):
+    cp = tb.Params().c()
+    lay = _lay()
+    need = L.ta_workspace_bytes(ctypes.byref(lay), ctypes.byref(cp))
+    # 2 layers * 8 heads units, 8 chunks of 512 keys, 128 padded rows, (m, Z) floats
+    assert need == 16 * 8 * 128 * 2 * 4
+    ok = lambda lay_=lay, ws=FAKE, nbytes=need: [FAKE, FAKE, ctypes.byref(lay_), None, ctypes.byref(cp),
+                                                 FAKE, ws, nbytes, None]
+    a = ok(); a[0] = None
+    assert L.ta_score(*a) == tb.TA_ERR_NULL
+    assert L.ta_score(*ok(ws=None)) == tb.TA_ERR_WORKSPACE
+    assert L.ta_score(*ok(nbytes=need - 1)) == tb.TA_ERR_WORKSPACE
+    assert L.ta_score(*ok(_lay(d=64))) == tb.TA_ERR_SHAPE
+    assert L.ta_score(*ok(_lay(hq=30))) == tb.TA_ERR_SHAPE
+    assert L.ta_score(*ok(_lay(window=0))) == tb.TA_ERR_SHAPE
+    assert L.ta_score(*ok(_lay(window=5000))) == tb.TA_ERR_SHAPE
+    assert L.ta_score(*ok(_lay(window=256), nbytes=1 << 40)) == tb.TA_ERR_SHAPE      # 4*256 rows > TA_MAX_ROWS
+    assert L.ta_score(*ok(_lay(kv_stride=[8 * 4096 * 128, 8 * 4096 * 128, 4096 * 128, 132]))) == tb.TA_ERR_ALIGN
+    a = ok(); a[1] = ctypes.c_void_p(0x7f0000001008)
+    assert L.ta_score(*a) == tb.TA_ERR_ALIGN
+    cp0 = tb.Params(alpha=0.0).c()
+    assert L.ta_workspace_bytes(ctypes.byref(lay), ctypes.byref(cp0)) == 0
+
+
+def test_select_and_compact_error_paths(L):
+    cp = tb.Params(n_sink=4, n_recent=4).c()
+    sel = lambda K=16, A=FAKE, prm=cp: [A, FAKE, FAKE, FAKE, None, 1, 1, 8, 4096, K, ctypes.byref(prm),
+                                        FAKE, FAKE, None]
+    assert L.ta_select(*sel(K=0)) == tb.TA_ERR_BUDGET
+    assert L.ta_select(*sel(K=7)) == tb.TA_ERR_BUDGET                 # K < n_sink + n_recent
+    assert L.ta_select(*sel(A=None)) == tb.TA_ERR_NULL                # alpha != 0 needs A
+    a = sel(); a[7] = 0
+    assert L.ta_select(*a) == tb.TA_ERR_SHAPE
+    a = sel(); a[11] = None
+    assert L.ta_select(*a) == tb.TA_ERR_NULL
+    lay = _lay()
+    cmp_ = lambda lay_=lay, K=16: [FAKE, FAKE, FAKE, FAKE, ctypes.byref(lay_), K, 0, FAKE, FAKE, None]
+    a = cmp_(); a[7] = None
+    assert L.ta_compact(*a) == tb.TA_ERR_NULL
+    assert L.ta_compact(*cmp_(K=0)) == tb.TA_ERR_SHAPE
+    assert L.ta_compact(*cmp_(_lay(d=96))) == tb.TA_ERR_SHAPE
+    a = cmp_(); a[0] = ctypes.c_void_p(0x7f0000001004)
+    assert L.ta_compact(*a) == tb.TA_ERR_ALIGN
+
+
+def test_evict_validates_every_stage_before_launching(L):
+    ids, lens = _table()
+    cp = tb.Params().c()
+    lay = _lay()
+    need = L.ta_workspace_bytes(ctypes.byref(lay), ctypes.byref(cp))
+
+    def args(K=16, ws=FAKE, nbytes=need, Q=FAKE, prm=cp, E=2):
+        return [FAKE, None, ids.ctypes.data, lens.ctypes.data, E, None, Q, FAKE, FAKE,
+                ctypes.byref(lay), ctypes.byref(prm), K, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                ws, nbytes, None]
+    assert L.ta_evict(*args(K=3)) == tb.TA_ERR_BUDGET
+    assert L.ta_evict(*args(ws=None)) == tb.TA_ERR_WORKSPACE
+    assert L.ta_evict(*args(Q=None)) == tb.TA_ERR_NULL
+    assert L.ta_evict(*args(E=65)) == tb.TA_ERR_SHAPE
+    # TA-Fast needs neither Q nor a workspace, but still a sane budget
+    cp0 = tb.Params(alpha=0.0).c()
+    assert L.ta_evict(*args(K=3, Q=None, ws=None, nbytes=0, prm=cp0)) == tb.TA_ERR_BUDGET
