@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the TA eviction pass on one MI355X.
+
+One step = one full eviction pass (anchor match + vouchers, window attention
+scores, protected top-K, K/V gather) over all 32 layers of the full-model
+workload, through the fused C-ABI entry point.  Inputs are synthetic and
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def kv_bytes_per_pass(w, budget):
+    """Bytes of KV the pass must move: K read once for scoring + K/V rows gathered and written."""
+    units = w.layers * w.batch * w.hkv
+    row = w.d * 2
+    score = units * w.n * row if w.alpha != 0.0 else 0
+    kept = min(budget, w.n)
+    compact = units * kept * row * 2 * 2          # two tensors, read + write
+    return score, compact
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_full_model")
+    ap.add_argument("--budget", type=int, default=1024, help="retention budget K of the timed steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the budget sweep (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy kernel (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the eviction pass has no multi-GPU path in this build "
+              "(units are independent; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2604_11288_amd as ta
+    from paper_2604_11288_amd import workloads as wl
+
+    if not os.path.exists(ta.binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    ta.lib()
+
+    w = wl.CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    td = wl.make_tokens(w)
+    Q, K, V = wl.make_qkv(w, device=dev)
+    tok = torch.from_numpy(td.tok).to(dev)
+    seq = torch.from_numpy(td.seq_len).to(dev) if w.ragged else None
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent, span_L=w.span_L, sponsor_B=w.sponsor_B,
+                    rho=w.rho, alpha=w.alpha, beta=w.beta, gamma=w.gamma)
+    budget = args.budget
+    plan = ta.EvictPlan(tok, td.tab_ids, td.tab_len, Q, K, V, budget, prm, seq_len=seq)
+    stream = torch.cuda.current_stream()
+
+    # ---- headline: K steps of the fused pass -----------------------------------------
+    for _ in range(args.warmup):
+        plan.run(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan.run(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    score_b, compact_b = kv_bytes_per_pass(w, budget)
+    value = (score_b + compact_b) / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations: the same steps issued stage by stage, HIP events on the launch stream
+    scored = w.alpha != 0.0
+    names = ["match_expand"] + (["score"] if scored else []) + ["select", "compact"]
+    ev = {k: [] for k in names}
+
+    def timed(name, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn()
+        e1.record(stream)
+        ev[name].append((e0, e1))
+
+    sel_layers, sel_hkv = (w.layers, w.hkv) if scored else (1, 1)
+    for it in range(args.warmup + args.steps):
+        if it == args.warmup:
+            ev = {k: [] for k in names}
+        timed("match_expand", lambda: ta.ta_match_anchors(tok, td.tab_ids, td.tab_len, prm, seq_len=seq,
+                                                          out=(plan.anchor, plan.spons, plan.vouch), stream=stream))
+        if scored:
+            timed("score", lambda: ta.ta_score(Q, K, prm, seq_len=seq, A=plan.A, ws=plan.ws, stream=stream))
+        timed("select", lambda: ta.ta_select(plan.A, plan.anchor, plan.spons, plan.vouch, budget, prm,
+                                             sel_layers, sel_hkv, seq_len=seq, out=(plan.idx, plan.cnt), stream=stream))
+        timed("compact", lambda: ta.ta_compact(K, V, plan.idx, plan.cnt, budget, idx_shared=not scored,
+                                               out=(plan.Kout, plan.Vout), stream=stream))
+    torch.cuda.synchronize()
+    kern_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in ev.items()}
+
+    # ---- roofline of the dominant kernel ---------------------------------------------
+    units = w.layers * w.batch * w.hkv
+    G = w.hq // w.hkv
+    if scored:
+        # algorithmic traffic of scoring: K once, Q once, A written once
+        alg_bytes = units * (w.n * w.d * 2 + G * w.window * w.d * 2 + w.n * 4)
+        alg_flops = units * 2 * G * w.window * w.n * w.d
+        dom, dur = "score (stats sweep + column-sum sweep)", kern_us["score"] * 1e-6
+        achieved = alg_bytes / dur / 1e9
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_launch_us": round(kern_us["score"], 2),
+                    "mfma_tflops": round(alg_flops / dur / 1e12, 1),
+                    "mfma_frac": round(alg_flops / dur / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    else:
+        alg_bytes = compact_b
+        dur = kern_us["compact"] * 1e-6
+        achieved = alg_bytes / dur / 1e9
+        roofline = {"kernel": "compact", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_launch_us": round(kern_us["compact"], 2)}
+
+    # ---- budget sweep of the same workload (context, outside the headline timing) ----------
+    sweep = {}
+    if args.calibrate_copy:
+        src = torch.empty(1 << 27, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # 256 MiB read + 256 MiB written by one elementwise kernel
+        torch.cuda.synchronize()
+    for kb in (() if args.no_sweep else w.budgets):
+        p = plan if kb == budget else ta.EvictPlan(tok, td.tab_ids, td.tab_len, Q, K, V, kb, prm, seq_len=seq)
+        for _ in range(3):
+            p.run(stream)
+        torch.cuda.synchronize()
+        s0 = time.perf_counter()
+        for _ in range(20):
+            p.run(stream)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - s0) * 1e6 / 20
+        sb, cb = kv_bytes_per_pass(w, kb)
+        sweep[str(kb)] = {"us_per_pass": round(us, 1), "GB/s": round((sb + cb) / us / 1e3, 1)}
+
+    # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample --------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ta_oracle as ora
+        ora.build()
+        max_units = min(units, 256)
+        Kh = K.cpu() if K.numel() * 2 <= (1 << 30) else None
+        sample = []
+        for u in range(max_units):
+            l, rem = divmod(u, w.batch * w.hkv)
+            b, g = divmod(rem, w.hkv)
+            sample.append((l, b, g))
+        c0 = time.perf_counter()
+        seqs = {}
+        done = 0
+        for (l, b, g) in sample:
+            nb = int(td.seq_len[b])
+            if b not in seqs:
+                seqs[b] = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len, L=w.span_L,
+                                             B=w.sponsor_B, rho=w.rho)
+            a, s, v = seqs[b]
+            Kunit = wl.bf16_bits(Kh[l, b, g, :nb] if Kh is not None else K[l, b, g, :nb])
+            Vunit = wl.bf16_bits(V[l, b, g, :nb])
+            A = None
+            if scored:
+                A = ora.score(wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]), Kunit)
+            idx = ora.select(A, a, s, v, budget, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
+            ora.compact(Kunit, idx)
+            ora.compact(Vunit, idx)
+            done += 1
+            if time.perf_counter() - c0 > 25.0:
+                break
+        cpu_s = time.perf_counter() - c0
+        per_unit_bytes = (score_b + compact_b) / units
+        cpu = {"value": round(done * per_unit_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": 1,
+               "kind": "oracle",
+               "sample": "%d of %d units of %s at K=%d (device->host copies of each unit included), %.1f s"
+                         % (done, units, w.name, budget, cpu_s),
+               "us_per_unit": round(cpu_s / done * 1e6, 1)}
+
+    out = {
+        "metric": "evict+compact GB/s of KV",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d layers, batch %d, n=%d, %dq/%dkv heads, d=%d, window %d, sinks %d, recent %d"
+                               % (w.name, w.layers, w.batch, w.n, w.hq, w.hkv, w.d, w.window, w.n_sink, w.n_recent),
+                   "budget_K": budget, "entry_point": "ta_evict"},
+        "us_per_pass": round(ms_per_step * 1e3, 1),
+        "hbm_frac": round(value / HBM_PEAK_GBS, 4),
+        "kernels_us": {k: round(v, 2) for k, v in kern_us.items()},
+        "budget_sweep": sweep,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -9,7 +9,9 @@ LIB = os.path.join(HERE, "libta.so")
 SOURCES = ["ta_api.hip", "ta_match.hip", "ta_score.hip", "ta_select.hip", "ta_compact.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA accumulators in VGPRs: the softmax reads them with plain VALU ops
+         "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def _compile(src):

@@ -49,6 +49,7 @@ int32_t check_layout(const ta_layout* lay, bool need_q)
     for (int i = 0; i < 4; ++i)
         if (lay->kv_stride[i] < 0) return TA_ERR_SHAPE;
     if (lay->kv_stride[3] < lay->d) return TA_ERR_SHAPE;
+    if ((lay->kv_stride[3] / 8) * (int64_t)lay->n >= 0x7FFFFFFFll) return TA_ERR_SHAPE;   // 32-bit row offsets
     for (int i = 0; i < 4; ++i)
         if (lay->kv_stride[i] % 8 != 0) return TA_ERR_ALIGN;
     if (need_q) {

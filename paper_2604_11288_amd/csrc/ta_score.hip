@@ -12,14 +12,17 @@
 //   sweep 2 (colsum) : merge the chunk statistics of a row into one constant
 //                      c_r = m_r + log2 Z_r, recompute S, p = 2^(s - c_r),
 //                      sum p over the rows -> A
-// Both sweeps are one kernel template.  A workgroup (4 wavefronts) owns one
-// chunk of keys of one unit; wavefront w owns 32*RT query rows whose Q
-// fragments stay in registers for the whole chunk, while K streams through LDS
-// in 64-key stages (double buffered, 16-byte chunks XOR-swizzled by row so both
-// the staging stores and the ds_read_b128 fragment loads are conflict free).
+// Both sweeps are one kernel template.  A workgroup owns one chunk of keys of
+// one unit and streams it through LDS in 64-key stages (double buffered,
+// 16-byte chunks XOR-swizzled by row so that the staging stores and the
+// ds_read_b128 fragment loads are both conflict free).  The M rows are split
+// into RG groups of 64; the workgroup has 2*RG wavefronts, wavefront (rg, kt)
+// owns row group rg (its Q fragments stay in 64 registers for the whole chunk)
+// and the kt-th 32-key tile of every stage, so one K fragment read from LDS
+// feeds two MFMA row tiles.
 // The contraction runs on v_mfma_f32_32x32x16_bf16:
 //   sweep 1 computes K Q^T (keys x rows): a lane then holds 16 keys of ONE
-//           query row, so (m, Z) are two registers per lane and need no
+//           query row, so (m, Z) are two registers per row tile and need no
 //           cross-lane traffic until the end of the chunk;
 //   sweep 2 computes Q K^T (rows x keys): a lane holds 16 rows of ONE key, so
 //           the column sum is a register accumulation plus one half-wave swap.
@@ -34,10 +37,9 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int SC_THREADS = 256;
-constexpr int SC_WAVES = 4;
 constexpr int STAGE_KEYS = 64;
 constexpr int STAGE_UNITS = STAGE_KEYS * 16;     // 16-byte units per stage (256 B per key)
+constexpr int ROW_TILES = 2;                     // 32-row MFMA tiles per wavefront
 
 struct ScoreArgs {
     const uint4* Q;
@@ -46,9 +48,10 @@ struct ScoreArgs {
     float* A;
     float* ws;
     int64_t q_sl, q_sb, q_sh;          // Q strides (layer, batch, head) in 16-byte units
-    int64_t k_sl, k_sb, k_sh, k_sp;    // K strides (layer, batch, head, position) in 16-byte units
+    int64_t k_sl, k_sb, k_sh;          // K strides (layer, batch, head) in 16-byte units
+    int32_t k_sp;                      // K position stride in 16-byte units (n * k_sp < 2^31)
     int32_t batch, hkv, G, W, n;
-    int32_t rows, rows_pad;            // M = G*W and M rounded up to 128*RT
+    int32_t rows, rows_pad;            // M = G*W and M rounded up to 64*RG
     int32_t chunk_keys, nchunks;
     int32_t causal;
     float scale_log2;                  // log2(e) / sqrt(d)
@@ -63,18 +66,24 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int RT, bool COLSUM>
-__global__ void __launch_bounds__(SC_THREADS)
+template <int RG, bool COLSUM>
+__global__ void __launch_bounds__(128 * RG)
 score_kernel(ScoreArgs a)
 {
+    constexpr int THREADS = 128 * RG;
+    constexpr int LOADS = STAGE_UNITS / THREADS;           // 16-byte staging loads per thread per stage
+    constexpr int ROWS_PER_PASS = THREADS / 16;            // key rows covered by one staging load
+    static_assert(LOADS == 1 || LOADS == 2 || LOADS == 4, "unsupported row-group count");
+
     __shared__ uint4 s_k[2][STAGE_UNITS];                  // 2 x 16 KB
-    __shared__ float s_c[COLSUM ? 128 * RT : 1];           // per-row constant m + log2 Z
-    __shared__ int32_t s_lim[COLSUM ? 128 * RT : 1];       // per-row last visible key
-    __shared__ float s_part[COLSUM ? 2 : 1][SC_WAVES][STAGE_KEYS];
+    __shared__ float s_c[COLSUM ? 64 * RG : 1];            // per-row constant m + log2 Z
+    __shared__ int32_t s_lim[COLSUM ? 64 * RG : 1];        // per-row last visible key
+    __shared__ float s_part[COLSUM ? 2 : 1][RG][STAGE_KEYS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int c32 = lane & 31, hf = lane >> 5;
+    const int rg = wave % RG, kt = wave / RG;              // row group, key tile of the stage
 
     const int32_t chunk = (int32_t)(blockIdx.x % (uint32_t)a.nchunks);
     const int32_t unit = (int32_t)(blockIdx.x / (uint32_t)a.nchunks);
@@ -92,12 +101,40 @@ score_kernel(ScoreArgs a)
     // keys <= min_lim are visible to every live row of a full window
     const int32_t min_lim = a.causal ? nb - W : nb - 1;
 
-    // ---- Q fragments of this wavefront's rows (registers, whole chunk) ------
-    bf16x8 qf[RT][8];
-    int32_t my_lim[RT];                                    // sweep 1: last visible key of this lane's row
+    // ---- K staging: thread -> (row srow + ROWS_PER_PASS*j, 16-byte chunk sch) -------
+    const uint4* kbase = a.K + l * a.k_sl + b * a.k_sb + g * a.k_sh;
+    const int srow = tid >> 4, sch = tid & 15;
+    // named registers (an indexed array here ends up in scratch memory)
+    uint4 sr0 = make_uint4(0, 0, 0, 0), sr1 = sr0, sr2 = sr0, sr3 = sr0;
+    auto stage_addr = [&](int s, int j) -> const uint4* {
+        int32_t key = key_lo + s * STAGE_KEYS + srow + ROWS_PER_PASS * j;
+        key = key > n - 1 ? n - 1 : key;                   // stay inside the tensor; masked later
+        return kbase + (uint32_t)(key * a.k_sp + sch);
+    };
+    auto stage_load = [&](int s) {
+        sr0 = *stage_addr(s, 0);
+        if (LOADS > 1) sr1 = *stage_addr(s, 1);
+        if (LOADS > 2) sr2 = *stage_addr(s, 2);
+        if (LOADS > 2) sr3 = *stage_addr(s, 3);
+    };
+    auto stage_slot = [&](int j) -> int {
+        const int row = srow + ROWS_PER_PASS * j;
+        return row * 16 + (sch ^ (row & 15));
+    };
+    auto stage_store = [&](int buf) {
+        s_k[buf][stage_slot(0)] = sr0;
+        if (LOADS > 1) s_k[buf][stage_slot(1)] = sr1;
+        if (LOADS > 2) s_k[buf][stage_slot(2)] = sr2;
+        if (LOADS > 2) s_k[buf][stage_slot(3)] = sr3;
+    };
+    if (nstages > 0) stage_load(0);                        // in flight while Q and the statistics load
+
+    // ---- Q fragments of this wavefront's 64 rows (registers, whole chunk) -----------
+    bf16x8 qf[ROW_TILES][8];
+    int32_t my_lim[ROW_TILES];                             // sweep 1: last visible key of this lane's row
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-        const int32_t r = 32 * (wave * RT + t) + c32;
+    for (int t = 0; t < ROW_TILES; ++t) {
+        const int32_t r = 64 * rg + 32 * t + c32;
         int32_t lim = -1;
         if (r < a.rows) {
             const int32_t h = r / W, w = r - h * W;
@@ -112,10 +149,10 @@ score_kernel(ScoreArgs a)
         my_lim[t] = lim;
     }
 
-    // ---- sweep 2 prologue: merge chunk statistics into per-row constants ----
-    float cst[RT][16];
+    // ---- sweep 2 prologue: merge chunk statistics into per-row constants ------------
+    float cst[ROW_TILES][16];
     if constexpr (COLSUM) {
-        for (int r = tid; r < 128 * RT; r += SC_THREADS) {
+        for (int r = tid; r < 64 * RG; r += THREADS) {
             float c = INFINITY;
             int32_t lim = -1;
             if (r < a.rows) {
@@ -137,139 +174,136 @@ score_kernel(ScoreArgs a)
         }
         __syncthreads();
 #pragma unroll
-        for (int t = 0; t < RT; ++t)
+        for (int t = 0; t < ROW_TILES; ++t)
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                cst[t][i] = s_c[32 * (wave * RT + t) + 8 * (i >> 2) + 4 * hf + (i & 3)];
+                cst[t][i] = s_c[64 * rg + 32 * t + 8 * (i >> 2) + 4 * hf + (i & 3)];
     }
 
-    // ---- K staging --------------------------------------------------------------
-    const uint4* kbase = a.K + l * a.k_sl + b * a.k_sb + g * a.k_sh;
-    const int srow = tid >> 4, sch = tid & 15;             // staging: 16 lanes per key row
-    uint4 stage_reg[4];
-    auto stage_load = [&](int s) {
+    float m_run[ROW_TILES], z_run[ROW_TILES];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int32_t key = key_lo + s * STAGE_KEYS + srow + 16 * j;
-            key = key > n - 1 ? n - 1 : key;               // stay inside the tensor; masked later
-            stage_reg[j] = kbase[(int64_t)key * a.k_sp + sch];
-        }
-    };
-    auto stage_store = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = srow + 16 * j;
-            s_k[buf][row * 16 + (sch ^ (row & 15))] = stage_reg[j];
-        }
-    };
-
-    float m_run[RT], z_run[RT];
-#pragma unroll
-    for (int t = 0; t < RT; ++t) { m_run[t] = -INFINITY; z_run[t] = 0.0f; }
+    for (int t = 0; t < ROW_TILES; ++t) { m_run[t] = -INFINITY; z_run[t] = 0.0f; }
     const float sc = a.scale_log2;
 
-    if (nstages > 0) {
-        stage_load(0);
-        stage_store(0);
-    }
+    // LDS slots of this lane's eight K fragments inside a stage buffer
+    const int krow = 32 * kt + c32;
+    int kslot[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kslot[ks] = krow * 16 + ((2 * ks + hf) ^ (krow & 15));
+
+    if (nstages > 0) stage_store(0);
+    // Drain every outstanding global load (Q fragments included) before the loop, so that
+    // inside it the only loads in flight are the next stage's prefetch and nothing in the
+    // MFMA sequence has to wait for them.
+    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
     __syncthreads();
 
     for (int s = 0; s < nstages; ++s) {
         const int buf = s & 1;
         if (s + 1 < nstages) stage_load(s + 1);
-        const int32_t stage_key0 = key_lo + s * STAGE_KEYS;
-        const bool all_visible = (stage_key0 + STAGE_KEYS - 1) <= min_lim;
+        const int32_t tile_key0 = key_lo + s * STAGE_KEYS + 32 * kt;
+        const bool all_visible = (key_lo + s * STAGE_KEYS + STAGE_KEYS - 1) <= min_lim;
 
+        bf16x8 kf[8];
 #pragma unroll
-        for (int kt = 0; kt < STAGE_KEYS / 32; ++kt) {
-            const int32_t tile_key0 = stage_key0 + 32 * kt;
-            bf16x8 kf[8];
-            const int krow = 32 * kt + c32;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                kf[ks] = as_frag(s_k[buf][krow * 16 + ((2 * ks + hf) ^ (krow & 15))]);
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = as_frag(s_k[buf][kslot[ks]]);
 
-            float colsum = 0.0f;
+        float colsum = 0.0f;
 #pragma unroll
-            for (int t = 0; t < RT; ++t) {
-                f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                if constexpr (!COLSUM) {
-                    // keys x rows: acc[i] = key tile_key0 + 8*(i/4) + 4*hf + i%4, this lane's query row
+        for (int t = 0; t < ROW_TILES; ++t) {
+            f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if constexpr (!COLSUM) {
+                // keys x rows: acc[i] = key tile_key0 + 8*(i/4) + 4*hf + i%4, this lane's query row
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks)
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[t][ks], acc, 0, 0, 0);
-                    float x[16];
-                    if (all_visible) {
+                for (int ks = 0; ks < 8; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[t][ks], acc, 0, 0, 0);
+                if (!all_visible) {
+                    const int32_t lim = my_lim[t];
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) x[i] = acc[i];
-                    } else {
-                        const int32_t lim = my_lim[t];
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int32_t key = tile_key0 + 8 * (i >> 2) + 4 * hf + (i & 3);
-                            x[i] = key <= lim ? acc[i] : -INFINITY;
-                        }
+                    for (int i = 0; i < 16; ++i) {
+                        const int32_t key = tile_key0 + 8 * (i >> 2) + 4 * hf + (i & 3);
+                        acc[i] = key <= lim ? acc[i] : -INFINITY;
                     }
-                    float tmax = x[0];
+                }
+                float tmax = acc[0];
 #pragma unroll
-                    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, x[i]);
-                    const float mnew = fmaxf(m_run[t], tmax * sc);
-                    if (mnew > -INFINITY) {
-                        float sum = 0.0f;
+                for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+                const float mnew = fmaxf(m_run[t], tmax * sc);
+                if (mnew > -INFINITY) {
+                    float sum = 0.0f;
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(x[i], sc, -mnew));
-                        z_run[t] = z_run[t] * fast_exp2(m_run[t] - mnew) + sum;
-                        m_run[t] = mnew;
-                    }
+                    for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], sc, -mnew));
+                    z_run[t] = z_run[t] * fast_exp2(m_run[t] - mnew) + sum;
+                    m_run[t] = mnew;
+                }
+            } else {
+                // rows x keys: acc[i] = query row 64*rg + 32*t + 8*(i/4) + 4*hf + i%4, key tile_key0 + c32
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t][ks], kf[ks], acc, 0, 0, 0);
+                if (all_visible) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
                 } else {
-                    // rows x keys: acc[i] = query row 32*tile + 8*(i/4) + 4*hf + i%4, key tile_key0 + c32
+                    const int32_t key = tile_key0 + c32;
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks)
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t][ks], kf[ks], acc, 0, 0, 0);
-                    if (all_visible) {
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
-                    } else {
-                        const int32_t key = tile_key0 + c32;
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int row = 32 * (wave * RT + t) + 8 * (i >> 2) + 4 * hf + (i & 3);
-                            const float p = fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
-                            colsum += key <= s_lim[row] ? p : 0.0f;
-                        }
+                    for (int i = 0; i < 16; ++i) {
+                        const int row = 64 * rg + 32 * t + 8 * (i >> 2) + 4 * hf + (i & 3);
+                        const float p = fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
+                        colsum += key <= s_lim[row] ? p : 0.0f;
                     }
                 }
             }
-            if constexpr (COLSUM) {
-                colsum += __shfl_xor(colsum, 32);
-                if (hf == 0) s_part[buf][wave][32 * kt + c32] = colsum;
-            }
+        }
+        if constexpr (COLSUM) {
+            colsum += __shfl_xor(colsum, 32);
+            if (hf == 0) s_part[buf][rg][32 * kt + c32] = colsum;
         }
 
         if (s + 1 < nstages) stage_store(buf ^ 1);
         __syncthreads();
         if (COLSUM && tid < STAGE_KEYS) {
-            const int32_t key = stage_key0 + tid;
+            const int32_t key = key_lo + s * STAGE_KEYS + tid;
             if (key < key_hi) {
                 float v = s_part[buf][0][tid];
 #pragma unroll
-                for (int w = 1; w < SC_WAVES; ++w) v += s_part[buf][w][tid];
+                for (int w = 1; w < RG; ++w) v += s_part[buf][w][tid];
                 a.A[(size_t)unit * n + key] = v;
             }
         }
     }
 
     if constexpr (!COLSUM) {
-        // merge the two half-waves (disjoint key subsets of the same row), then store
-        float* st = a.ws + (((size_t)unit * a.nchunks + chunk) * a.rows_pad) * 2;
+        // merge the two half-waves (disjoint key subsets of the same row), then the two
+        // key-tile wavefronts of the row group through LDS, then store
+        float* s_m = reinterpret_cast<float*>(&s_k[0][0]);     // staging buffers are idle now
+        float* s_z = s_m + 64 * RG;
 #pragma unroll
-        for (int t = 0; t < RT; ++t) {
+        for (int t = 0; t < ROW_TILES; ++t) {
             const float mo = __shfl_xor(m_run[t], 32), zo = __shfl_xor(z_run[t], 32);
             const float mf = fmaxf(m_run[t], mo);
             float zf = 0.0f;
             if (mf > -INFINITY) zf = z_run[t] * fast_exp2(m_run[t] - mf) + zo * fast_exp2(mo - mf);
-            if (hf == 0) {
-                const int32_t r = 32 * (wave * RT + t) + c32;
+            m_run[t] = mf;
+            z_run[t] = zf;
+        }
+        if (kt == 1 && hf == 0) {
+#pragma unroll
+            for (int t = 0; t < ROW_TILES; ++t) {
+                s_m[64 * rg + 32 * t + c32] = m_run[t];
+                s_z[64 * rg + 32 * t + c32] = z_run[t];
+            }
+        }
+        __syncthreads();
+        if (kt == 0 && hf == 0) {
+            float* st = a.ws + (((size_t)unit * a.nchunks + chunk) * a.rows_pad) * 2;
+#pragma unroll
+            for (int t = 0; t < ROW_TILES; ++t) {
+                const int32_t r = 64 * rg + 32 * t + c32;
+                const float mo = s_m[r], zo = s_z[r];
+                const float mf = fmaxf(m_run[t], mo);
+                float zf = 0.0f;
+                if (mf > -INFINITY) zf = z_run[t] * fast_exp2(m_run[t] - mf) + zo * fast_exp2(mo - mf);
                 st[r * 2] = mf;
                 st[r * 2 + 1] = zf;
             }
@@ -277,11 +311,11 @@ score_kernel(ScoreArgs a)
     }
 }
 
-template <int RT>
-void launch_rt(const ScoreArgs& a, unsigned blocks, hipStream_t st)
+template <int RG>
+void launch_rg(const ScoreArgs& a, unsigned blocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((score_kernel<RT, false>), dim3(blocks), dim3(SC_THREADS), 0, st, a);
-    hipLaunchKernelGGL((score_kernel<RT, true>), dim3(blocks), dim3(SC_THREADS), 0, st, a);
+    hipLaunchKernelGGL((score_kernel<RG, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
+    hipLaunchKernelGGL((score_kernel<RG, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
 }
 
 }  // namespace
@@ -316,7 +350,7 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.k_sl = lay.kv_stride[0] / 8;
     a.k_sb = lay.kv_stride[1] / 8;
     a.k_sh = lay.kv_stride[2] / 8;
-    a.k_sp = lay.kv_stride[3] / 8;
+    a.k_sp = (int32_t)(lay.kv_stride[3] / 8);
     a.batch = lay.batch;
     a.hkv = lay.hkv;
     a.G = lay.hq / lay.hkv;
@@ -331,9 +365,9 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     const int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
     const unsigned blocks = (unsigned)(units * a.nchunks);
     switch (a.rows_pad) {
-        case 128: launch_rt<1>(a, blocks, st); break;
-        case 256: launch_rt<2>(a, blocks, st); break;
-        default: launch_rt<4>(a, blocks, st); break;
+        case 128: launch_rg<2>(a, blocks, st); break;
+        case 256: launch_rg<4>(a, blocks, st); break;
+        default: launch_rg<8>(a, blocks, st); break;
     }
     return hipGetLastError();
 }
