@@ -53,6 +53,7 @@ struct ScoreArgs {
     int32_t batch, hkv, G, W, n;
     int32_t rows, rows_pad;            // M = G*W and M rounded up to 64*RG
     int32_t chunk_keys, nchunks;
+    int32_t unit0;                     // first unit of this launch
     int32_t causal;
     float scale_log2;                  // log2(e) / sqrt(d)
 };
@@ -86,7 +87,7 @@ score_kernel(ScoreArgs a)
     const int rg = wave % RG, kt = wave / RG;              // row group, key tile of the stage
 
     const int32_t chunk = (int32_t)(blockIdx.x % (uint32_t)a.nchunks);
-    const int32_t unit = (int32_t)(blockIdx.x / (uint32_t)a.nchunks);
+    const int32_t unit = a.unit0 + (int32_t)(blockIdx.x / (uint32_t)a.nchunks);
     const int32_t g = unit % a.hkv;
     const int32_t b = (unit / a.hkv) % a.batch;
     const int32_t l = unit / (a.hkv * a.batch);
@@ -312,8 +313,12 @@ score_kernel(ScoreArgs a)
 }
 
 template <int RG>
-void launch_rg(const ScoreArgs& a, unsigned blocks, hipStream_t st)
+void launch_rg(ScoreArgs a, int64_t units, hipStream_t st)
 {
+    // One launch per sweep over all units.  (Splitting the units into cache-sized groups
+    // so that sweep 2 re-reads its keys from the last-level cache was measured slower.)
+    const unsigned blocks = (unsigned)(units * a.nchunks);
+    a.unit0 = 0;
     hipLaunchKernelGGL((score_kernel<RG, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
     hipLaunchKernelGGL((score_kernel<RG, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
 }
@@ -363,11 +368,11 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.causal = causal;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
     const int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
-    const unsigned blocks = (unsigned)(units * a.nchunks);
+    a.unit0 = 0;
     switch (a.rows_pad) {
-        case 128: launch_rg<2>(a, blocks, st); break;
-        case 256: launch_rg<4>(a, blocks, st); break;
-        default: launch_rg<8>(a, blocks, st); break;
+        case 128: launch_rg<2>(a, units, st); break;
+        case 256: launch_rg<4>(a, units, st); break;
+        default: launch_rg<8>(a, units, st); break;
     }
     return hipGetLastError();
 }
