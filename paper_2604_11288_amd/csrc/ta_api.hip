@@ -89,15 +89,7 @@ int32_t build_table(const int32_t* tab_ids, const int32_t* tab_len, int32_t E, c
     return TA_OK;
 }
 
-size_t workspace_bytes(const ta_layout* lay)
-{
-    const int64_t rows = (int64_t)(lay->hq / lay->hkv) * lay->window;
-    const int64_t rows_pad = ta::score_padded_rows((int32_t)rows);
-    const int64_t ck = ta::score_chunk_keys(lay->n);
-    const int64_t nchunks = (lay->n + ck - 1) / ck;
-    const int64_t units = (int64_t)lay->layers * lay->batch * lay->hkv;
-    return (size_t)(units * nchunks * rows_pad * 2 * (int64_t)sizeof(float));
-}
+size_t workspace_bytes(const ta_layout* lay) { return ta::score_workspace_bytes(*lay); }
 
 int32_t check_match(const int32_t* tok, int32_t B, int32_t n, const ta_params* prm,
                     const uint8_t* anchor, const uint8_t* spons, const float* vouch)
@@ -120,10 +112,7 @@ int32_t check_score(const void* Q, const void* K, const ta_layout* lay, const ta
     if (!aligned16(Q) || !aligned16(K)) return TA_ERR_ALIGN;
     if (!ws || ws_bytes < workspace_bytes(lay)) return TA_ERR_WORKSPACE;
     if (!aligned16(ws)) return TA_ERR_ALIGN;
-    if ((int64_t)lay->layers * lay->batch * lay->hkv *
-            ((lay->n + ta::score_chunk_keys(lay->n) - 1) / ta::score_chunk_keys(lay->n)) >
-        0x7FFFFFFFll)
-        return TA_ERR_SHAPE;
+    if (ta::score_grid_blocks(*lay) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
     return TA_OK;
 }
 

@@ -23,9 +23,9 @@ hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, i
                         uint8_t* anchor, uint8_t* spons, float* vouch, hipStream_t st);
 
 // ---- score ------------------------------------------------------------------
-// Keys per workgroup chunk; the workspace holds 2 floats per (unit, chunk, padded row).
-int32_t score_chunk_keys(int32_t n);
-int32_t score_padded_rows(int32_t rows);
+// Scratch bytes and grid size of the score step for a validated layout.
+size_t score_workspace_bytes(const ta_layout& lay);
+int64_t score_grid_blocks(const ta_layout& lay);
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
                         int causal, float* A, float* ws, hipStream_t st);
 

@@ -28,44 +28,14 @@
 //           the column sum is a register accumulation plus one half-wave swap.
 #include <math.h>
 
-#include "ta_internal.h"
+#include "ta_score_common.h"
 
 namespace ta {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 constexpr int STAGE_KEYS = 64;
 constexpr int STAGE_UNITS = STAGE_KEYS * 16;     // 16-byte units per stage (256 B per key)
-constexpr int ROW_TILES = 2;                     // 32-row MFMA tiles per wavefront
-
-struct ScoreArgs {
-    const uint4* Q;
-    const uint4* K;
-    const int32_t* seq_len;
-    float* A;
-    float* ws;
-    int64_t q_sl, q_sb, q_sh;          // Q strides (layer, batch, head) in 16-byte units
-    int64_t k_sl, k_sb, k_sh;          // K strides (layer, batch, head) in 16-byte units
-    int32_t k_sp;                      // K position stride in 16-byte units (n * k_sp < 2^31)
-    int32_t batch, hkv, G, W, n;
-    int32_t rows, rows_pad;            // M = G*W and M rounded up to 64*RG
-    int32_t chunk_keys, nchunks;
-    int32_t unit0;                     // first unit of this launch
-    int32_t causal;
-    float scale_log2;                  // log2(e) / sqrt(d)
-};
-
-__device__ __forceinline__ bf16x8 as_frag(uint4 v)
-{
-    union { uint4 u; bf16x8 b; } c;
-    c.u = v;
-    return c.b;
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <int RG, bool COLSUM>
 __global__ void __launch_bounds__(128 * RG)
@@ -325,24 +295,52 @@ void launch_rg(ScoreArgs a, int64_t units, hipStream_t st)
 
 }  // namespace
 
-int32_t score_padded_rows(int32_t rows)
+namespace {
+
+int32_t padded_rows(int32_t rows)
 {
     if (rows <= 128) return 128;
     if (rows <= 256) return 256;
     return 512;
 }
 
-int32_t score_chunk_keys(int32_t n)
+struct ScorePlan {
+    int32_t rows, rows_pad, chunk_keys, nchunks;
+    int64_t units;
+};
+
+ScorePlan make_plan(const ta_layout& lay)
 {
+    ScorePlan p;
+    p.rows = (lay.hq / lay.hkv) * lay.window;
+    p.rows_pad = padded_rows(p.rows);
     // at most 32 chunks per unit so that merging chunk statistics stays cheap
-    int32_t ck = 512;
-    while ((int64_t)ck * 32 < n) ck *= 2;
-    return ck;
+    p.chunk_keys = 512;
+    while ((int64_t)p.chunk_keys * 32 < lay.n) p.chunk_keys *= 2;
+    p.nchunks = (lay.n + p.chunk_keys - 1) / p.chunk_keys;
+    p.units = (int64_t)lay.layers * lay.batch * lay.hkv;
+    return p;
+}
+
+}  // namespace
+
+size_t score_workspace_bytes(const ta_layout& lay)
+{
+    const ScorePlan p = make_plan(lay);
+    // per-chunk row statistics (m, Z)
+    return (size_t)p.units * p.nchunks * p.rows_pad * 2 * sizeof(float);
+}
+
+int64_t score_grid_blocks(const ta_layout& lay)
+{
+    const ScorePlan p = make_plan(lay);
+    return p.units * p.nchunks;
 }
 
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
                         int causal, float* A, float* ws, hipStream_t st)
 {
+    const ScorePlan p = make_plan(lay);
     ScoreArgs a;
     a.Q = (const uint4*)Q;
     a.K = (const uint4*)K;
@@ -361,18 +359,17 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.G = lay.hq / lay.hkv;
     a.W = lay.window;
     a.n = lay.n;
-    a.rows = a.G * a.W;
-    a.rows_pad = score_padded_rows(a.rows);
-    a.chunk_keys = score_chunk_keys(lay.n);
-    a.nchunks = (lay.n + a.chunk_keys - 1) / a.chunk_keys;
+    a.rows = p.rows;
+    a.rows_pad = p.rows_pad;
+    a.chunk_keys = p.chunk_keys;
+    a.nchunks = p.nchunks;
+    a.unit0 = 0;
     a.causal = causal;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
-    const int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
-    a.unit0 = 0;
     switch (a.rows_pad) {
-        case 128: launch_rg<2>(a, units, st); break;
-        case 256: launch_rg<4>(a, units, st); break;
-        default: launch_rg<8>(a, units, st); break;
+        case 128: launch_rg<2>(a, p.units, st); break;
+        case 256: launch_rg<4>(a, p.units, st); break;
+        default: launch_rg<8>(a, p.units, st); break;
     }
     return hipGetLastError();
 }

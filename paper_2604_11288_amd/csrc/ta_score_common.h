@@ -1,0 +1,38 @@
+// Types and launch arguments of the score kernels.
+#pragma once
+#include "ta_internal.h"
+
+namespace ta {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int ROW_TILES = 2;                     // 32-row MFMA tiles per wavefront
+
+struct ScoreArgs {
+    const uint4* Q;
+    const uint4* K;
+    const int32_t* seq_len;
+    float* A;
+    float* ws;
+    int64_t q_sl, q_sb, q_sh;          // Q strides (layer, batch, head) in 16-byte units
+    int64_t k_sl, k_sb, k_sh;          // K strides (layer, batch, head) in 16-byte units
+    int32_t k_sp;                      // K position stride in 16-byte units (n * k_sp < 2^31)
+    int32_t batch, hkv, G, W, n;
+    int32_t rows, rows_pad;            // M = G*W and M rounded up to 64*RG
+    int32_t chunk_keys, nchunks;
+    int32_t unit0;                     // first unit of this launch
+    int32_t causal;
+    float scale_log2;                  // log2(e) / sqrt(d)
+};
+
+__device__ __forceinline__ bf16x8 as_frag(uint4 v)
+{
+    union { uint4 u; bf16x8 b; } c;
+    c.u = v;
+    return c.b;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+}  // namespace ta
