@@ -66,6 +66,7 @@ typedef struct ta_params {
     float beta;         /* weight of the recency term R_i = (p+1)/n (0.5)                 */
     float gamma;        /* weight of the anchor indicator S_i (0.3)                       */
     int32_t causal;     /* 1: window query w sees keys 0..n-W+w; 0: every key             */
+    float budget_decay; /* per-step decay of sponsor budgets (paper: 0.9); decode steps   */
 } ta_params;
 
 /*
@@ -189,6 +190,78 @@ int32_t ta_evict(const int32_t *tok, const int32_t *seq_len,
                  uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
                  int32_t *idx, int32_t *cnt, void *Kout, void *Vout,
                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Incremental form: the same retention policy applied after every generation
+ * step (Sec. 3.1 "after each generation step"; Alg. 1 including its last step,
+ * the budget decay B_i <- decay * B_i of Sec. 3.2 "Token selection").
+ *
+ * State (all DEVICE memory owned by the caller, sized by the fields below):
+ *   per sequence  tok    int32 [batch][cap]   token stream
+ *                 len    int32 [batch]        current length
+ *                 anchor uint8 [batch][cap]   anchor flags
+ *                 budget float [batch][cap]   CURRENT budget B_i of each anchor, 0 elsewhere
+ *   per unit      Kc, Vc bf16  [layers][batch][hkv][K+1][d]  cache slots
+ *                 pos    int32 [layers][batch][hkv][K+1]     absolute position of a slot, -1 = free
+ *                 A      float [layers][batch][hkv][K+1]     cumulative attention of a slot
+ * A unit keeps at most K rows; the extra slot receives the next token.  Slots
+ * are stable: an evicted slot is reused, rows are never moved (keys are stored
+ * with their positional encoding, so slot order does not matter to attention).
+ */
+typedef struct ta_decode_state {
+    int32_t layers, batch, hq, hkv, d;
+    int32_t K;       /* budget per unit; slots per unit = K + 1, 1 <= K <= TA_MAX_DECODE_K */
+    int32_t cap;     /* positions the per-sequence arrays can hold                        */
+    int32_t *tok;
+    int32_t *len;
+    uint8_t *anchor;
+    float *budget;
+    void *Kc, *Vc;
+    int32_t *pos;
+    float *A;
+} ta_decode_state;
+
+#define TA_MAX_DECODE_K 2047
+
+/*
+ * Fills a decode state from the outputs of a prefill eviction (ta_evict /
+ * ta_match_anchors + ta_score + ta_select + ta_compact with per-unit idx):
+ * tokens, anchor flags and budgets (anchor_B, or prm->sponsor_B at anchors) are
+ * copied for positions < seq_len; slot r < cnt of a unit gets row r of
+ * Kout/Vout, position idx[r] and attention A[idx[r]] (0 when A is NULL); the
+ * remaining slots are free.
+ *   tok int32 [batch][n], seq_len int32 [batch] or NULL, anchor uint8 [batch][n],
+ *   anchor_B float [batch][n] or NULL, A float [layers][batch][hkv][n] or NULL,
+ *   idx int32 [layers][batch][hkv][K], cnt int32 [layers][batch][hkv],
+ *   Kout, Vout bf16 [layers][batch][hkv][K][d]           (all DEVICE)
+ * Errors: NULL, SHAPE (n > cap, K out of range, d != 128, hq % hkv != 0), ALIGN.
+ */
+int32_t ta_decode_init(const ta_decode_state *st, const int32_t *tok, const int32_t *seq_len, int32_t n,
+                       const uint8_t *anchor, const float *anchor_B, const float *A,
+                       const int32_t *idx, const int32_t *cnt, const void *Kout, const void *Vout,
+                       const ta_params *prm, void *stream);
+
+/*
+ * One generation step for every sequence and unit:
+ *   1. append new_tok[b] at position p = len[b]; the anchor flag of p follows the
+ *      rule of ta_match_anchors evaluated at p only; its budget is sponsor_B; len += 1
+ *   2. per unit: the new k/v row goes into the lowest-numbered free slot with A = 0;
+ *      with alpha != 0 each of the hq/hkv decode queries of the group adds its
+ *      softmax weights over the occupied slots (q.k/sqrt(d), fp32) to A
+ *   3. per unit, if no slot is free: the slot ranking last under the order of
+ *      ta_select - classes and the recency term taken from absolute positions and
+ *      the new length, vouchers recomputed from the current budgets - is freed
+ *   4. every budget is multiplied by prm->budget_decay
+ *   new_tok int32 [batch]; q_new bf16 [layers][batch][hq][d] (NULL when alpha == 0);
+ *   k_new, v_new bf16 [layers][batch][hkv][d]; table as in ta_match_anchors (HOST);
+ *   evicted int32 [layers][batch][hkv] or NULL: position freed in step 3, -1 if none.
+ * The caller keeps len[b] < cap; a sequence at capacity is left unchanged.
+ * Errors: NULL, SHAPE, BUDGET (K < n_sink + n_recent), ALIGN.
+ */
+int32_t ta_decode_step(const ta_decode_state *st, const int32_t *new_tok, const void *q_new,
+                       const void *k_new, const void *v_new,
+                       const int32_t *tab_ids, const int32_t *tab_len, int32_t E,
+                       const ta_params *prm, int32_t *evicted, void *stream);
 
 /* Text for a ta_status value (static storage). */
 const char *ta_strerror(int32_t status);

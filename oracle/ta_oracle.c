@@ -12,7 +12,9 @@
  *
  * Parity pins live in tests/ (printed voucher values, the budget-partition
  * example, softmax row sums, closed forms, brute force on tiny inputs,
- * numpy/torch library routines).  Unpinned: nothing in this file; the values
+ * numpy/torch library routines; the incremental form: sliding-window reduction,
+ * decay closed form, softmax sums, tuple-order arg-min).  Unpinned: nothing in
+ * this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
 #include <math.h>
@@ -249,4 +251,176 @@ void ta_oracle_compact(const uint16_t *in, const int32_t *idx, int32_t cnt,
     for (int32_t r = 0; r < cnt; ++r)
         memcpy(out + (size_t)r * row_elems, in + (size_t)idx[r] * row_elems,
                sizeof(uint16_t) * (size_t)row_elems);
+}
+
+/* ======================================================================
+ * Incremental (per generation step) form of the same pass
+ * ("a retention policy selects a subset ... after each generation step",
+ * Sec. 3.1; Alg. 1 run once per step, including its last step: the budget
+ * decay B_i <- 0.9 B_i of Sec. 3.2 "Token selection").
+ *
+ * Per sequence the state is the token stream, the anchor flags and the
+ * CURRENT budget of every anchor (0 where there is no anchor).  Per unit the
+ * cache holds K+1 slots: K occupied and one free.  One step appends one
+ * token: the new k/v row goes into the free slot, the decode queries of the
+ * group add their softmax weights over the K+1 cached rows to the cumulative
+ * attention A of each slot (H2O-style accumulation, Eq. 1 "cumulative
+ * attention across heads and steps"), the slot that ranks last under the
+ * (class, u, position) order is evicted and becomes the free slot, and
+ * finally every budget decays.  Vouchers are recomputed from the current
+ * budgets each step (Alg. 1 rebuilds V from B_i every time it runs); classes
+ * and the recency term use absolute positions and the current length.
+ * ====================================================================== */
+
+/* Append one token to a sequence: anchor flag of the new position (same rule
+ * as ta_oracle_match, evaluated at the new position only) and its budget. */
+void ta_oracle_decode_append(int32_t *tok, uint8_t *anchor, float *budget, int32_t len,
+                             int32_t new_tok,
+                             const int32_t *tab_ids, int32_t tab_stride,
+                             const int32_t *tab_len, int32_t E, float B)
+{
+    tok[len] = new_tok;
+    uint8_t hit = 0;
+    for (int32_t e = 0; e < E; ++e) {
+        int32_t l = tab_len[e];
+        if (l < 1 || len - l + 1 < 0)
+            continue;
+        int ok = 1;
+        for (int32_t t = 0; t < l; ++t)
+            if (tok[len - l + 1 + t] != tab_ids[(size_t)e * tab_stride + t])
+                ok = 0;
+        if (ok)
+            hit = 1;
+    }
+    anchor[len] = hit;
+    budget[len] = hit ? B : 0.0f;
+}
+
+/* Voucher and sponsor flag of position p from the current budgets (Eq. 2). */
+void ta_oracle_decode_vouch(const uint8_t *anchor, const float *budget, int32_t p,
+                            int32_t L, double rho, float *V, uint8_t *spons)
+{
+    float v = 0.0f;
+    uint8_t s = 0;
+    for (int32_t k = 1; k <= L; ++k) {
+        int32_t i = p - k;
+        if (i < 0 || !anchor[i])
+            continue;
+        float pw = (float)pow(rho, (double)k);
+        float term = budget[i] * pw;
+        v = v + term;
+        s = 1;
+    }
+    *V = v;
+    *spons = s;
+}
+
+/* Budget decay at the end of a step (Alg. 1, last step). */
+void ta_oracle_decode_decay(float *budget, int32_t len, float decay)
+{
+    for (int32_t i = 0; i < len; ++i)
+        budget[i] = decay * budget[i];
+}
+
+/*
+ * One step of one unit.  Kc/Vc: [slots][d] bf16 bits, pos[slots] (absolute
+ * position, -1 = free; at least one slot is free on entry), A[slots].
+ * q: [G][d] decode queries of the group, k_new/v_new: [d].
+ * The new row takes the lowest-numbered free slot.  Attention runs over the
+ * occupied slots.  If no slot is free afterwards (the cache holds more than
+ * its budget of slots-1 rows) the slot ranking last is evicted, otherwise
+ * nothing is.
+ * rank_A (nullable): attention values to rank with instead of the unit's own
+ * updated A (lets a caller impose scores computed elsewhere, in the same
+ * precision on both sides of a comparison).
+ * Returns the evicted slot or -1; u_out (nullable, [slots]) receives the
+ * utilities of the occupied slots.
+ */
+int32_t ta_oracle_decode_unit(uint16_t *Kc, uint16_t *Vc, int32_t *pos, float *A,
+                              int32_t slots, int32_t d,
+                              const uint16_t *q, int32_t G,
+                              const uint16_t *k_new, const uint16_t *v_new, int32_t p_new,
+                              const uint8_t *anchor, const float *budget, int32_t len_new,
+                              int32_t n_sink, int32_t n_recent, int32_t L, double rho,
+                              float alpha, float beta, float gamma,
+                              const float *rank_A, float *u_out)
+{
+    int32_t f = -1;
+    for (int32_t s = slots - 1; s >= 0; --s)
+        if (pos[s] < 0)
+            f = s;
+    if (f < 0)
+        return -1;
+    memcpy(Kc + (size_t)f * d, k_new, sizeof(uint16_t) * (size_t)d);
+    memcpy(Vc + (size_t)f * d, v_new, sizeof(uint16_t) * (size_t)d);
+    pos[f] = p_new;
+    A[f] = 0.0f;
+
+    /* attention of the decode queries over every cached row */
+    if (alpha != 0.0f) {
+        double *add = (double *)calloc((size_t)slots, sizeof(double));
+        double *sc = (double *)malloc(sizeof(double) * (size_t)slots);
+        const double scale = 1.0 / sqrt((double)d);
+        for (int32_t h = 0; h < G; ++h) {
+            double m = -INFINITY;
+            for (int32_t s = 0; s < slots; ++s) {
+                if (pos[s] < 0)
+                    continue;
+                double dot = 0.0;
+                for (int32_t c = 0; c < d; ++c)
+                    dot += bf16_to_double(q[(size_t)h * d + c]) * bf16_to_double(Kc[(size_t)s * d + c]);
+                sc[s] = dot * scale;
+                if (sc[s] > m)
+                    m = sc[s];
+            }
+            double Z = 0.0;
+            for (int32_t s = 0; s < slots; ++s)
+                if (pos[s] >= 0)
+                    Z += exp(sc[s] - m);
+            for (int32_t s = 0; s < slots; ++s)
+                if (pos[s] >= 0)
+                    add[s] += exp(sc[s] - m) / Z;
+        }
+        for (int32_t s = 0; s < slots; ++s)
+            if (pos[s] >= 0)
+                A[s] = (float)((double)A[s] + add[s]);
+        free(sc);
+        free(add);
+    }
+
+    /* rank every occupied slot; if the cache is over budget the last one under the order goes */
+    ta_oracle_key worst;
+    int32_t worst_slot = -1, nfree = 0;
+    for (int32_t s = 0; s < slots; ++s) {
+        int32_t p = pos[s];
+        if (p < 0) {
+            ++nfree;
+            continue;
+        }
+        float V;
+        uint8_t sp;
+        ta_oracle_decode_vouch(anchor, budget, p, L, rho, &V, &sp);
+        float a = rank_A ? rank_A[s] : A[s];
+        float r = (float)(p + 1) / (float)len_new;
+        float t = (alpha != 0.0f) ? alpha * a : 0.0f;
+        float b = beta * r;
+        t = t + b;
+        float g = gamma * (float)anchor[p];
+        t = t + g;
+        t = t + V;
+        if (u_out)
+            u_out[s] = t;
+        ta_oracle_key k;
+        k.cls = (p < n_sink || p >= len_new - n_recent) ? 2 : (sp ? 1 : 0);
+        k.u = t;
+        k.pos = p;
+        if (worst_slot < 0 || key_before(&worst, &k) < 0) { /* worst ranks before k: k is worse */
+            worst = k;
+            worst_slot = s;
+        }
+    }
+    if (nfree > 0)
+        return -1;
+    pos[worst_slot] = -1;
+    return worst_slot;
 }

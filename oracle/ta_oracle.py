@@ -46,6 +46,15 @@ def _load():
         lib.ta_oracle_select.restype = i32
         lib.ta_oracle_compact.argtypes = [vp, vp, i32, i32, vp]
         lib.ta_oracle_compact.restype = None
+        lib.ta_oracle_decode_append.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, i32, f32]
+        lib.ta_oracle_decode_append.restype = None
+        lib.ta_oracle_decode_vouch.argtypes = [vp, vp, i32, i32, f64, vp, vp]
+        lib.ta_oracle_decode_vouch.restype = None
+        lib.ta_oracle_decode_decay.argtypes = [vp, i32, f32]
+        lib.ta_oracle_decode_decay.restype = None
+        lib.ta_oracle_decode_unit.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, vp, vp, i32,
+                                              i32, i32, i32, f64, f32, f32, f32, vp, vp]
+        lib.ta_oracle_decode_unit.restype = i32
         _lib = lib
     return _lib
 
@@ -137,3 +146,71 @@ def evict_sequence(tok, tab_ids, tab_len, L=6, B=15.0, rho=0.8, anchor_B=None):
     anchor = match(tok, tab_ids, tab_len)
     spons, V = expand(anchor, L=L, B=B, rho=rho, anchor_B=anchor_B)
     return anchor, spons, V
+
+
+# ---------------------------------------------------------------------------
+# incremental (per generation step) form
+# ---------------------------------------------------------------------------
+class DecodeSeq:
+    """Per-sequence state of the incremental pass: tokens, anchor flags, current budgets."""
+
+    def __init__(self, tok, tab_ids, tab_len, cap, B=15.0):
+        tok = _c(tok, np.int32)
+        self.len = int(tok.shape[0])
+        self.cap = int(cap)
+        self.tok = np.zeros(cap, np.int32)
+        self.tok[:self.len] = tok
+        self.tab_len = _c(tab_len, np.int32)
+        E = len(self.tab_len)
+        self.tab_ids = _c(tab_ids, np.int32).reshape(E, -1) if E else np.zeros((0, 4), np.int32)
+        self.B = float(B)
+        self.anchor = np.zeros(cap, np.uint8)
+        self.anchor[:self.len] = match(tok, self.tab_ids, self.tab_len)
+        self.budget = np.where(self.anchor == 1, np.float32(B), np.float32(0)).astype(np.float32)
+
+    def append(self, new_tok):
+        assert self.len < self.cap
+        _load().ta_oracle_decode_append(_p(self.tok), _p(self.anchor), _p(self.budget), self.len, int(new_tok),
+                                        _p(self.tab_ids), self.tab_ids.shape[1], _p(self.tab_len),
+                                        self.tab_len.shape[0], self.B)
+        self.len += 1
+        return self.len - 1
+
+    def vouch(self, p, L=6, rho=0.8):
+        V = np.zeros(1, np.float32)
+        sp = np.zeros(1, np.uint8)
+        _load().ta_oracle_decode_vouch(_p(self.anchor), _p(self.budget), int(p), int(L), float(rho), _p(V), _p(sp))
+        return float(V[0]), int(sp[0])
+
+    def decay(self, factor=0.9):
+        _load().ta_oracle_decode_decay(_p(self.budget), self.len, float(factor))
+
+
+class DecodeUnit:
+    """Per-unit cache state: K+1 slots of K/V rows, their positions and cumulative attention."""
+
+    def __init__(self, Krows, Vrows, idx, A_kept):
+        Krows, Vrows = _c(Krows, np.uint16), _c(Vrows, np.uint16)
+        K, d = Krows.shape
+        self.slots, self.d = K + 1, d
+        self.Kc = np.zeros((K + 1, d), np.uint16)
+        self.Vc = np.zeros((K + 1, d), np.uint16)
+        self.Kc[:K], self.Vc[:K] = Krows, Vrows
+        self.pos = np.full(K + 1, -1, np.int32)
+        self.pos[:K] = _c(idx, np.int32)
+        self.A = np.zeros(K + 1, np.float32)
+        self.A[:K] = _c(A_kept, np.float32)
+
+    def step(self, seq, q, k_new, v_new, p_new, n_sink, n_recent, L=6, rho=0.8,
+             alpha=1.0, beta=0.5, gamma=0.3, rank_A=None):
+        """q uint16 [G][d].  Returns (evicted slot, utilities [slots])."""
+        q = _c(q, np.uint16)
+        k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
+        ra = None if rank_A is None else _c(rank_A, np.float32)
+        u = np.zeros(self.slots, np.float32)
+        e = _load().ta_oracle_decode_unit(_p(self.Kc), _p(self.Vc), _p(self.pos), _p(self.A), self.slots, self.d,
+                                          _p(q), q.shape[0], _p(k_new), _p(v_new), int(p_new),
+                                          _p(seq.anchor), _p(seq.budget), seq.len,
+                                          int(n_sink), int(n_recent), int(L), float(rho),
+                                          float(alpha), float(beta), float(gamma), _p(ra), _p(u))
+        return int(e), u

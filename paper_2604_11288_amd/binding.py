@@ -25,7 +25,7 @@ TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
 TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_score", "ta_select", "ta_compact",
-           "ta_evict", "ta_strerror", "ta_last_hip_error")
+           "ta_evict", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
 class TaError(RuntimeError):
@@ -41,7 +41,15 @@ class CParams(ctypes.Structure):
     _fields_ = [("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32), ("span_L", ctypes.c_int32),
                 ("sponsor_B", ctypes.c_float), ("rho", ctypes.c_double),
                 ("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("gamma", ctypes.c_float),
-                ("causal", ctypes.c_int32)]
+                ("causal", ctypes.c_int32), ("budget_decay", ctypes.c_float)]
+
+
+class CDecodeState(ctypes.Structure):
+    _fields_ = [("layers", ctypes.c_int32), ("batch", ctypes.c_int32), ("hq", ctypes.c_int32),
+                ("hkv", ctypes.c_int32), ("d", ctypes.c_int32), ("K", ctypes.c_int32), ("cap", ctypes.c_int32),
+                ("tok", ctypes.c_void_p), ("len", ctypes.c_void_p), ("anchor", ctypes.c_void_p),
+                ("budget", ctypes.c_void_p), ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
+                ("pos", ctypes.c_void_p), ("A", ctypes.c_void_p)]
 
 
 class CLayout(ctypes.Structure):
@@ -63,10 +71,11 @@ class Params:
     beta: float = 0.5
     gamma: float = 0.3
     causal: bool = True
+    budget_decay: float = 0.9
 
     def c(self) -> CParams:
         return CParams(self.n_sink, self.n_recent, self.span_L, self.sponsor_B, self.rho,
-                       self.alpha, self.beta, self.gamma, 1 if self.causal else 0)
+                       self.alpha, self.beta, self.gamma, 1 if self.causal else 0, self.budget_decay)
 
 
 _lib = None
@@ -94,6 +103,10 @@ def lib():
         L.ta_evict.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32,
                                vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ta_evict.restype = i32
+        L.ta_decode_init.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ta_decode_init.restype = i32
+        L.ta_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+        L.ta_decode_step.restype = i32
         L.ta_strerror.argtypes = [i32]
         L.ta_strerror.restype = ctypes.c_char_p
         L.ta_last_hip_error.argtypes = []
@@ -268,3 +281,48 @@ def ta_evict(tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params, seq_len
              stream=None) -> EvictPlan:
     """The whole pass in one call; returns the plan object holding every output tensor."""
     return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B).run(stream)
+
+
+class DecodeState:
+    """Device tensors of the incremental pass (see ta_decode_state in include/ta.h)."""
+
+    def __init__(self, layers, batch, hq, hkv, K, cap, device, d=TA_HEAD_DIM):
+        self.layers, self.batch, self.hq, self.hkv, self.K, self.cap, self.d = layers, batch, hq, hkv, K, cap, d
+        i32, dev = torch.int32, device
+        self.tok = torch.zeros((batch, cap), dtype=i32, device=dev)
+        self.len = torch.zeros((batch,), dtype=i32, device=dev)
+        self.anchor = torch.zeros((batch, cap), dtype=torch.uint8, device=dev)
+        self.budget = torch.zeros((batch, cap), dtype=torch.float32, device=dev)
+        self.Kc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
+        self.Vc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
+        self.pos = torch.full((layers, batch, hkv, K + 1), -1, dtype=i32, device=dev)
+        self.A = torch.zeros((layers, batch, hkv, K + 1), dtype=torch.float32, device=dev)
+
+    def c(self) -> CDecodeState:
+        return CDecodeState(self.layers, self.batch, self.hq, self.hkv, self.d, self.K, self.cap,
+                            self.tok.data_ptr(), self.len.data_ptr(), self.anchor.data_ptr(),
+                            self.budget.data_ptr(), self.Kc.data_ptr(), self.Vc.data_ptr(),
+                            self.pos.data_ptr(), self.A.data_ptr())
+
+
+def ta_decode_init(state: DecodeState, tok, anchor, idx, cnt, Kout, Vout, params: Params,
+                   seq_len=None, anchor_B=None, A=None, stream=None):
+    """Fill a decode state from the outputs of a prefill eviction (per-unit idx / cnt)."""
+    cs, cp = state.c(), params.c()
+    rc = lib().ta_decode_init(ctypes.byref(cs), _ptr(tok), _ptr(seq_len), tok.shape[1], _ptr(anchor),
+                              _ptr(anchor_B), _ptr(A), _ptr(idx), _ptr(cnt), _ptr(Kout), _ptr(Vout),
+                              ctypes.byref(cp), _stream(stream))
+    _check(rc, "ta_decode_init")
+    return state
+
+
+def ta_decode_step(state: DecodeState, new_tok, q_new, k_new, v_new, tab_ids, tab_len, params: Params,
+                   evicted=None, stream=None):
+    """One generation step: append, accumulate attention, evict one row per unit, decay budgets."""
+    ids, lens, E = _table(tab_ids, tab_len)
+    cs, cp = state.c(), params.c()
+    rc = lib().ta_decode_step(ctypes.byref(cs), _ptr(new_tok), _ptr(q_new), _ptr(k_new), _ptr(v_new),
+                              ids.ctypes.data, lens.ctypes.data, E, ctypes.byref(cp), _ptr(evicted),
+                              _stream(stream))
+    _check(rc, "ta_decode_step")
+    return evicted

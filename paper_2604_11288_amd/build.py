@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libta.so")
-SOURCES = ["ta_api.hip", "ta_match.hip", "ta_score.hip", "ta_select.hip", "ta_compact.hip"]
+SOURCES = ["ta_api.hip", "ta_match.hip", "ta_score.hip", "ta_select.hip", "ta_compact.hip", "ta_decode.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -142,6 +142,22 @@ int32_t check_compact(const void* Kin, const void* Vin, const int32_t* idx, cons
     return TA_OK;
 }
 
+int32_t check_decode_state(const ta_decode_state* st)
+{
+    if (!st) return TA_ERR_NULL;
+    if (!st->tok || !st->len || !st->anchor || !st->budget || !st->Kc || !st->Vc || !st->pos || !st->A)
+        return TA_ERR_NULL;
+    if (st->layers < 1 || st->batch < 1 || st->hkv < 1 || st->hq < 1 || st->hq % st->hkv != 0) return TA_ERR_SHAPE;
+    if (st->hq / st->hkv > 8) return TA_ERR_SHAPE;
+    if (st->d != TA_HEAD_DIM) return TA_ERR_SHAPE;
+    if (st->K < 1 || st->K > TA_MAX_DECODE_K) return TA_ERR_SHAPE;
+    if ((int64_t)(st->hq / st->hkv) * (st->K + 1) > 15360) return TA_ERR_SHAPE;      // logits of a unit sit in LDS
+    if (st->cap < 1 || st->cap >= (1 << 30) || st->batch > 65535) return TA_ERR_SHAPE;
+    if ((int64_t)st->layers * st->batch * st->hkv > (1 << 24)) return TA_ERR_SHAPE;
+    if (!aligned16(st->Kc) || !aligned16(st->Vc)) return TA_ERR_ALIGN;
+    return TA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -237,6 +253,44 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
                                       lay->n, K, *prm, idx, cnt, st));
     if (rc != TA_OK) return rc;
     return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, st));
+}
+
+int32_t ta_decode_init(const ta_decode_state* st, const int32_t* tok, const int32_t* seq_len, int32_t n,
+                       const uint8_t* anchor, const float* anchor_B, const float* A,
+                       const int32_t* idx, const int32_t* cnt, const void* Kout, const void* Vout,
+                       const ta_params* prm, void* stream)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    rc = check_decode_state(st);
+    if (rc != TA_OK) return rc;
+    if (!tok || !anchor || !idx || !cnt || !Kout || !Vout) return TA_ERR_NULL;
+    if (n < 1 || n > st->cap) return TA_ERR_SHAPE;
+    if (!aligned16(Kout) || !aligned16(Vout)) return TA_ERR_ALIGN;
+    return hip_status(ta::launch_decode_init(*st, tok, seq_len, n, anchor, anchor_B, A, idx, cnt, Kout, Vout,
+                                             prm->sponsor_B, (hipStream_t)stream));
+}
+
+int32_t ta_decode_step(const ta_decode_state* st, const int32_t* new_tok, const void* q_new,
+                       const void* k_new, const void* v_new,
+                       const int32_t* tab_ids, const int32_t* tab_len, int32_t E,
+                       const ta_params* prm, int32_t* evicted, void* stream)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    rc = check_decode_state(st);
+    if (rc != TA_OK) return rc;
+    if (!new_tok || !k_new || !v_new) return TA_ERR_NULL;
+    if (prm->alpha != 0.0f && !q_new) return TA_ERR_NULL;
+    if (!isfinite(prm->budget_decay)) return TA_ERR_SHAPE;
+    if (!aligned16(k_new) || !aligned16(v_new) || (q_new && !aligned16(q_new))) return TA_ERR_ALIGN;
+    rc = check_budget(prm, st->K);
+    if (rc != TA_OK) return rc;
+    ta::MatchTable tab;
+    rc = build_table(tab_ids, tab_len, E, prm, &tab);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_decode_step(*st, new_tok, q_new, k_new, v_new, tab, *prm, evicted,
+                                             (hipStream_t)stream));
 }
 
 const char* ta_strerror(int32_t status)

@@ -1,0 +1,359 @@
+// Incremental form of the eviction pass: one generation step for every
+// sequence and unit (Sec. 3.1 "after each generation step"; Alg. 1 with its
+// budget-decay step; Sec. 3.2 "Token selection").
+//
+// Kernels per step:
+//   decode_seq_kernel    one workgroup per sequence: append the token, test the
+//                        anchor table at the new position only, set its budget
+//   decode_unit_kernel   one workgroup per unit: write the new k/v row into the
+//                        free slot, add the decode queries' softmax weights over
+//                        the cached rows to A (H2O-style cumulative attention,
+//                        Eq. 1), free the slot that ranks last under the
+//                        (class, u, position) order
+//   decode_decay_kernel  B_i <- decay * B_i for every position
+// The unit kernel is the hot one: it reads the unit's K slots once (HBM bound,
+// (K+1) * 256 B per unit per step).  With 4 query heads per group the
+// contraction is a 4-row GEMV, so it runs on the vector ALUs: 16 lanes share a
+// 256-byte key row (one 16-byte load each) and reduce their partial dot
+// products with four cross-lane adds.
+#include <math.h>
+
+#include "ta_internal.h"
+
+namespace ta {
+
+namespace {
+
+constexpr int DU_THREADS = 256;
+constexpr int DU_WAVES = DU_THREADS / 64;
+constexpr int MAX_GROUP = 8;                               // query heads per KV head
+
+struct DecodeTable {
+    int32_t rid[TA_MAX_TABLE][TA_MAX_GRAM];                // n-grams reversed: rid[e][0] = last token
+    int32_t len[TA_MAX_TABLE];
+    int32_t E;
+    float B;
+};
+
+// ---- state initialisation -----------------------------------------------------
+__global__ void decode_init_seq_kernel(ta_decode_state st, const int32_t* tok, const int32_t* seq_len, int32_t n,
+                                       const uint8_t* anchor, const float* anchor_B, float B)
+{
+    const int b = blockIdx.y;
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    int32_t nb = seq_len ? seq_len[b] : n;
+    nb = nb < 0 ? 0 : (nb > n ? n : nb);
+    if (p == 0) st.len[b] = nb;
+    if (p >= st.cap) return;
+    const size_t o = (size_t)b * st.cap + p;
+    if (p < nb) {
+        const size_t i = (size_t)b * n + p;
+        const uint8_t a = anchor[i];
+        st.tok[o] = tok[i];
+        st.anchor[o] = a;
+        st.budget[o] = a ? (anchor_B ? anchor_B[i] : B) : 0.0f;
+    } else {
+        st.tok[o] = 0;
+        st.anchor[o] = 0;
+        st.budget[o] = 0.0f;
+    }
+}
+
+__global__ void __launch_bounds__(DU_THREADS)
+decode_init_unit_kernel(ta_decode_state st, int32_t n, const float* A, const int32_t* idx, const int32_t* cnt,
+                        const uint4* Kout, const uint4* Vout)
+{
+    const int unit = blockIdx.x;
+    const int slots = st.K + 1;
+    int32_t c = cnt[unit];
+    c = c < 0 ? 0 : (c > st.K ? st.K : c);
+    for (int s = threadIdx.x; s < slots; s += DU_THREADS) {
+        int32_t p = -1;
+        float a = 0.0f;
+        if (s < c) {
+            p = idx[(size_t)unit * st.K + s];
+            p = p < 0 ? 0 : (p >= n ? n - 1 : p);
+            if (A) a = A[(size_t)unit * n + p];
+        }
+        st.pos[(size_t)unit * slots + s] = p;
+        st.A[(size_t)unit * slots + s] = a;
+    }
+    uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (size_t)unit * slots * 16;
+    uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (size_t)unit * slots * 16;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    for (int i = threadIdx.x; i < slots * 16; i += DU_THREADS) {
+        const int s = i >> 4;
+        Kc[i] = s < c ? Kout[(size_t)unit * st.K * 16 + i] : zero;
+        Vc[i] = s < c ? Vout[(size_t)unit * st.K * 16 + i] : zero;
+    }
+}
+
+// ---- step, sequence part ---------------------------------------------------------
+__global__ void __launch_bounds__(64)
+decode_seq_kernel(ta_decode_state st, const int32_t* new_tok, DecodeTable tab)
+{
+    const int b = blockIdx.x;
+    const int32_t p = st.len[b];
+    if (p < 0 || p >= st.cap) return;                      // at capacity: sequence left unchanged
+    int32_t* tok = st.tok + (size_t)b * st.cap;
+    const int32_t t0 = new_tok[b];
+    const int e = threadIdx.x;
+    bool hit = false;
+    if (e < tab.E && t0 == tab.rid[e][0]) {
+        const int32_t len = tab.len[e];
+        hit = p - len + 1 >= 0;
+        for (int k = 1; k < len && hit; ++k) hit = tok[p - k] == tab.rid[e][k];
+    }
+    const bool any = __ballot(hit) != 0ull;
+    if (threadIdx.x == 0) {
+        tok[p] = t0;
+        st.anchor[(size_t)b * st.cap + p] = any ? 1 : 0;
+        st.budget[(size_t)b * st.cap + p] = any ? tab.B : 0.0f;
+        st.len[b] = p + 1;
+    }
+}
+
+__global__ void decode_decay_kernel(ta_decode_state st, float decay)
+{
+    const int b = blockIdx.y;
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < st.len[b] && p < st.cap) {
+        float* B = st.budget + (size_t)b * st.cap + p;
+        *B = __fmul_rn(decay, *B);
+    }
+}
+
+// ---- step, unit part ----------------------------------------------------------------
+struct UnitArgs {
+    const uint4* q_new;
+    const uint4* k_new;
+    const uint4* v_new;
+    int32_t* evicted;
+    int32_t n_sink, n_recent, L;
+    float alpha, beta, gamma;
+    float scale_log2;
+    float pw[TA_MAX_SPAN + 1];
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+__device__ __forceinline__ float dot8(const uint4& a, const uint4& b)
+{
+    float s = bf16_lo(a.x) * bf16_lo(b.x);
+    s = fmaf(bf16_hi(a.x), bf16_hi(b.x), s);
+    s = fmaf(bf16_lo(a.y), bf16_lo(b.y), s);
+    s = fmaf(bf16_hi(a.y), bf16_hi(b.y), s);
+    s = fmaf(bf16_lo(a.z), bf16_lo(b.z), s);
+    s = fmaf(bf16_hi(a.z), bf16_hi(b.z), s);
+    s = fmaf(bf16_lo(a.w), bf16_lo(b.w), s);
+    s = fmaf(bf16_hi(a.w), bf16_hi(b.w), s);
+    return s;
+}
+
+__device__ __forceinline__ uint32_t ordered_bits(float u)
+{
+    uint32_t b = __float_as_uint(u);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+template <typename T, typename Op>
+__device__ __forceinline__ T block_reduce(T v, T* s_red, Op op)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = op(v, __shfl_xor(v, o));
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();
+    if (lane == 0) s_red[wave] = v;
+    __syncthreads();
+    T r = s_red[0];
+#pragma unroll
+    for (int w = 1; w < DU_WAVES; ++w) r = op(r, s_red[w]);
+    return r;
+}
+
+__global__ void __launch_bounds__(DU_THREADS)
+decode_unit_kernel(ta_decode_state st, UnitArgs a)
+{
+    extern __shared__ float s_dyn[];                       // [G][slots] scaled logits
+    __shared__ float s_redf[DU_WAVES];
+    __shared__ unsigned long long s_redu[DU_WAVES];
+    __shared__ int s_redi[DU_WAVES];
+
+    const int tid = threadIdx.x;
+    const int unit = blockIdx.x;
+    const int slots = st.K + 1;
+    const int G = st.hq / st.hkv;
+    const int g = unit % st.hkv;
+    const int b = (unit / st.hkv) % st.batch;
+    const int l = unit / (st.hkv * st.batch);
+    const int32_t len_new = st.len[b];                     // the sequence part of the step has run
+    const int32_t p_new = len_new - 1;
+    int32_t* pos = st.pos + (size_t)unit * slots;
+    float* A = st.A + (size_t)unit * slots;
+    uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (size_t)unit * slots * 16;
+    uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (size_t)unit * slots * 16;
+
+    // lowest-numbered free slot
+    int first_free = 0x7FFFFFFF;
+    for (int s = tid; s < slots; s += DU_THREADS)
+        if (pos[s] < 0) first_free = first_free < s ? first_free : s;
+    const int f = block_reduce<int>(first_free, s_redi, [](int x, int y) { return x < y ? x : y; });
+    if (f >= slots || p_new < 0) {                         // no room (or empty sequence): nothing to do
+        if (tid == 0 && a.evicted) a.evicted[unit] = -1;
+        return;
+    }
+    const uint4* kn = a.k_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
+    const uint4* vn = a.v_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
+    if (tid < 16) Kc[f * 16 + tid] = kn[tid];
+    else if (tid < 32) Vc[f * 16 + tid - 16] = vn[tid - 16];
+
+    // ---- attention of the group's decode queries over the occupied slots ----------
+    const bool scored = a.alpha != 0.0f;
+    if (scored) {
+        const int sub = tid & 15, rowgrp = tid >> 4;       // 16 lanes per key row
+        uint4 qv[MAX_GROUP];
+#pragma unroll
+        for (int h = 0; h < MAX_GROUP; ++h)
+            if (h < G) qv[h] = a.q_new[((size_t)(l * st.batch + b) * st.hq + g * G + h) * 16 + sub];
+        for (int s0 = 0; s0 < slots; s0 += DU_THREADS / 16) {
+            const int s = s0 + rowgrp;
+            const bool valid = s < slots;
+            const bool occ = valid && (s == f || pos[s] >= 0);
+            uint4 kv = make_uint4(0, 0, 0, 0);
+            if (occ) kv = (s == f) ? kn[sub] : Kc[s * 16 + sub];
+#pragma unroll
+            for (int h = 0; h < MAX_GROUP; ++h) {
+                if (h < G) {
+                    float d = dot8(qv[h], kv);
+                    d += __shfl_xor(d, 8);
+                    d += __shfl_xor(d, 4);
+                    d += __shfl_xor(d, 2);
+                    d += __shfl_xor(d, 1);
+                    if (valid && sub == 0) s_dyn[h * slots + s] = occ ? d * a.scale_log2 : -INFINITY;
+                }
+            }
+        }
+        __syncthreads();
+        // per head: softmax over the slots, weights accumulated per slot in head order
+        float add[(TA_MAX_DECODE_K + 1 + DU_THREADS - 1) / DU_THREADS];
+#pragma unroll
+        for (int j = 0; j < (int)(sizeof(add) / sizeof(float)); ++j) add[j] = 0.0f;
+        for (int h = 0; h < G; ++h) {
+            const float* sh = s_dyn + h * slots;
+            float m = -INFINITY;
+            for (int s = tid; s < slots; s += DU_THREADS) m = fmaxf(m, sh[s]);
+            m = block_reduce<float>(m, s_redf, [](float x, float y) { return fmaxf(x, y); });
+            float z = 0.0f;
+            for (int s = tid; s < slots; s += DU_THREADS) z += __builtin_amdgcn_exp2f(sh[s] - m);
+            z = block_reduce<float>(z, s_redf, [](float x, float y) { return x + y; });
+            const float inv = 1.0f / z;
+#pragma unroll
+            for (int j = 0; j < (int)(sizeof(add) / sizeof(float)); ++j) {
+                const int s = tid + j * DU_THREADS;
+                if (s < slots) add[j] += __builtin_amdgcn_exp2f(sh[s] - m) * inv;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < (int)(sizeof(add) / sizeof(float)); ++j) {
+            const int s = tid + j * DU_THREADS;
+            if (s < slots && (s == f || pos[s] >= 0)) A[s] = (s == f ? 0.0f : A[s]) + add[j];
+        }
+    } else {
+        if (tid == 0) A[f] = 0.0f;
+    }
+    __syncthreads();                                       // A and the new row are in place for this block
+
+    // ---- rank the occupied slots; evict the last one if the cache is over budget -----
+    const size_t srow = (size_t)b * st.cap;
+    const uint8_t* anchor = st.anchor + srow;
+    const float* budget = st.budget + srow;
+    const float lenf = (float)len_new;
+    unsigned long long worst = ~0ull;
+    int nfree = 0;
+    for (int s = tid; s < slots; s += DU_THREADS) {
+        const int32_t p = (s == f) ? p_new : pos[s];
+        if (p < 0) { ++nfree; continue; }
+        float v = 0.0f;
+        bool sp = false;
+        for (int k = 1; k <= a.L; ++k) {
+            const int32_t i = p - k;
+            if (i >= 0 && anchor[i]) {
+                v = __fadd_rn(v, __fmul_rn(budget[i], a.pw[k]));
+                sp = true;
+            }
+        }
+        const float r = __fdiv_rn((float)(p + 1), lenf);
+        float t = scored ? __fmul_rn(a.alpha, A[s]) : 0.0f;
+        t = __fadd_rn(t, __fmul_rn(a.beta, r));
+        t = __fadd_rn(t, __fmul_rn(a.gamma, (float)anchor[p]));
+        t = __fadd_rn(t, v);
+        const unsigned cls = (p < a.n_sink || p >= len_new - a.n_recent) ? 2u : (sp ? 1u : 0u);
+        // (class, u, position) packed so that the smallest integer ranks last
+        const unsigned long long key = ((unsigned long long)cls << 62) |
+                                       ((unsigned long long)ordered_bits(t) << 30) | (unsigned long long)(uint32_t)p;
+        worst = key < worst ? key : worst;
+    }
+    const int free_total = block_reduce<int>(nfree, s_redi, [](int x, int y) { return x + y; });
+    const unsigned long long wmin =
+        block_reduce<unsigned long long>(worst, s_redu, [](unsigned long long x, unsigned long long y) { return x < y ? x : y; });
+    const int32_t evict_pos = free_total > 0 ? -1 : (int32_t)(wmin & 0x3FFFFFFFull);
+    for (int s = tid; s < slots; s += DU_THREADS) {
+        const int32_t p = (s == f) ? p_new : pos[s];
+        if (s == f || (p >= 0 && p == evict_pos)) pos[s] = (p == evict_pos) ? -1 : p;
+    }
+    if (tid == 0 && a.evicted) a.evicted[unit] = evict_pos;
+}
+
+}  // namespace
+
+hipError_t launch_decode_init(const ta_decode_state& st, const int32_t* tok, const int32_t* seq_len, int32_t n,
+                              const uint8_t* anchor, const float* anchor_B, const float* A,
+                              const int32_t* idx, const int32_t* cnt, const void* Kout, const void* Vout,
+                              float B, hipStream_t s)
+{
+    dim3 g1((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
+    hipLaunchKernelGGL(decode_init_seq_kernel, g1, dim3(256), 0, s, st, tok, seq_len, n, anchor, anchor_B, B);
+    const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
+    hipLaunchKernelGGL(decode_init_unit_kernel, dim3(units), dim3(DU_THREADS), 0, s, st, n, A, idx, cnt,
+                       (const uint4*)Kout, (const uint4*)Vout);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok, const void* q_new,
+                              const void* k_new, const void* v_new, const MatchTable& tab,
+                              const ta_params& prm, int32_t* evicted, hipStream_t s)
+{
+    DecodeTable dt;
+    for (int e = 0; e < TA_MAX_TABLE; ++e) {
+        for (int k = 0; k < TA_MAX_GRAM; ++k) dt.rid[e][k] = tab.rid[e][k];
+        dt.len[e] = tab.len[e];
+    }
+    dt.E = tab.E;
+    dt.B = tab.B;
+    hipLaunchKernelGGL(decode_seq_kernel, dim3((unsigned)st.batch), dim3(64), 0, s, st, new_tok, dt);
+
+    UnitArgs a;
+    a.q_new = (const uint4*)q_new;
+    a.k_new = (const uint4*)k_new;
+    a.v_new = (const uint4*)v_new;
+    a.evicted = evicted;
+    a.n_sink = prm.n_sink;
+    a.n_recent = prm.n_recent;
+    a.L = prm.span_L;
+    a.alpha = prm.alpha;
+    a.beta = prm.beta;
+    a.gamma = prm.gamma;
+    a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)st.d));
+    for (int k = 0; k <= TA_MAX_SPAN; ++k) a.pw[k] = tab.pw[k];
+    const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
+    const int G = st.hq / st.hkv;
+    const size_t lds = prm.alpha != 0.0f ? (size_t)G * (st.K + 1) * sizeof(float) : 0;
+    hipLaunchKernelGGL(decode_unit_kernel, dim3(units), dim3(DU_THREADS), lds, s, st, a);
+
+    dim3 g3((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
+    hipLaunchKernelGGL(decode_decay_kernel, g3, dim3(256), 0, s, st, prm.budget_decay);
+    return hipGetLastError();
+}
+
+}  // namespace ta

@@ -40,4 +40,13 @@ hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, 
                           const ta_layout& lay, int32_t K, int32_t idx_shared,
                           void* Kout, void* Vout, hipStream_t st);
 
+// ---- incremental (decode) form ------------------------------------------------
+hipError_t launch_decode_init(const ta_decode_state& st, const int32_t* tok, const int32_t* seq_len, int32_t n,
+                              const uint8_t* anchor, const float* anchor_B, const float* A,
+                              const int32_t* idx, const int32_t* cnt, const void* Kout, const void* Vout,
+                              float B, hipStream_t s);
+hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok, const void* q_new,
+                              const void* k_new, const void* v_new, const MatchTable& tab,
+                              const ta_params& prm, int32_t* evicted, hipStream_t s);
+
 }  // namespace ta

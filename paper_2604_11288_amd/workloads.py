@@ -160,3 +160,38 @@ def make_qkv(w: Workload, device="cpu", layers: Optional[int] = None, with_v: bo
 def bf16_bits(t: torch.Tensor) -> np.ndarray:
     """Raw 16-bit patterns of a bf16 tensor as a numpy uint16 array (host)."""
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def make_decode_stream(w: Workload, td: TokenData, steps: int, p_anchor: float = 0.02, clean: bool = True):
+    """Token IDs appended during decode: int32 [steps][B].
+
+    Per step and sequence: if an n-gram emission is pending, its next token; else with
+    probability p_anchor a table entry is picked uniformly and its emission starts (it
+    completes len-1 steps later); else a filler ID.
+    """
+    rng = np.random.default_rng(w.seed + 7919)
+    hi = VOCAB - RESERVED if clean else VOCAB
+    out = np.zeros((steps, w.batch), np.int32)
+    pending = [[] for _ in range(w.batch)]
+    for t in range(steps):
+        for b in range(w.batch):
+            if pending[b]:
+                out[t, b] = pending[b].pop(0)
+            elif w.table_entries > 0 and rng.random() < p_anchor:
+                e = int(rng.integers(0, w.table_entries))
+                gram = td.tab_ids[e, :td.tab_len[e]].tolist()
+                out[t, b] = gram[0]
+                pending[b] = gram[1:]
+            else:
+                out[t, b] = int(rng.integers(0, hi))
+    return out
+
+
+def make_decode_qkv(w: Workload, step: int, device="cpu", layers: Optional[int] = None):
+    """bf16 N(0,1) rows of one decode step: q [Lyr][B][Hq][d], k and v [Lyr][B][Hkv][d]."""
+    lyr = w.layers if layers is None else layers
+    g = torch.Generator(device=device)
+    g.manual_seed(w.seed * 1000003 + step)
+    def draw(shape):
+        return torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    return draw((lyr, w.batch, w.hq, w.d)), draw((lyr, w.batch, w.hkv, w.d)), draw((lyr, w.batch, w.hkv, w.d))

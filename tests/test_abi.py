@@ -157,3 +157,37 @@ def test_evict_validates_every_stage_before_launching(L):
     # TA-Fast needs neither Q nor a workspace, but still a sane budget
     cp0 = tb.Params(alpha=0.0).c()
     assert L.ta_evict(*args(K=3, Q=None, ws=None, nbytes=0, prm=cp0)) == tb.TA_ERR_BUDGET
+
+
+def _decode_state(**kw):
+    st = tb.CDecodeState(2, 3, 32, 8, 128, 256, 5000, *([0x7f0000001000] * 8))
+    for k, v in kw.items():
+        setattr(st, k, v)
+    return st
+
+
+def test_decode_error_paths(L):
+    ids, lens = _table()
+    cp = tb.Params().c()
+    st = _decode_state()
+    init = lambda st_=st, n=4096, prm=cp: [ctypes.byref(st_), FAKE, None, n, FAKE, None, None, FAKE, FAKE, FAKE, FAKE,
+                                            ctypes.byref(prm), None]
+    assert L.ta_decode_init(*init(_decode_state(K=0))) == tb.TA_ERR_SHAPE
+    assert L.ta_decode_init(*init(_decode_state(K=2048))) == tb.TA_ERR_SHAPE
+    assert L.ta_decode_init(*init(_decode_state(d=64))) == tb.TA_ERR_SHAPE
+    assert L.ta_decode_init(*init(_decode_state(hq=30))) == tb.TA_ERR_SHAPE
+    assert L.ta_decode_init(*init(_decode_state(pos=None))) == tb.TA_ERR_NULL
+    assert L.ta_decode_init(*init(n=6000)) == tb.TA_ERR_SHAPE                       # prefill longer than cap
+    assert L.ta_decode_init(*init(_decode_state(Kc=0x7f0000001008))) == tb.TA_ERR_ALIGN
+    a = init(); a[1] = None
+    assert L.ta_decode_init(*a) == tb.TA_ERR_NULL
+    step = lambda st_=st, q=FAKE, prm=cp, E=2: [ctypes.byref(st_), FAKE, q, FAKE, FAKE, ids.ctypes.data,
+                                                 lens.ctypes.data, E, ctypes.byref(prm), None, None]
+    assert L.ta_decode_step(*step(q=None)) == tb.TA_ERR_NULL                        # alpha != 0 needs queries
+    assert L.ta_decode_step(*step(E=70)) == tb.TA_ERR_SHAPE
+    assert L.ta_decode_step(*step(_decode_state(K=6))) == tb.TA_ERR_BUDGET          # K < n_sink + n_recent
+    assert L.ta_decode_step(*step(_decode_state(hq=128))) == tb.TA_ERR_SHAPE        # 16 heads per group
+    a = step(); a[3] = ctypes.c_void_p(0x7f0000001004)
+    assert L.ta_decode_step(*a) == tb.TA_ERR_ALIGN
+    a = step(); a[1] = None
+    assert L.ta_decode_step(*a) == tb.TA_ERR_NULL

@@ -1,0 +1,132 @@
+"""GPU parity of the incremental (per generation step) form against the oracle.
+
+The decode state of both sides starts from their own prefill eviction of the
+same inputs.  Every step compares: anchor flags and budgets (bit-exact), slot
+positions and the evicted position (exact; both sides rank with the GPU's fp32
+cumulative attention, the oracle's own double-accumulated A is compared within
+tolerance), and at the end the cached K/V rows (bit-exact).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_11288_amd as ta
+from oracle import ta_oracle as ora
+from paper_2604_11288_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _run_decode(w, K, steps, p_anchor=0.05, check_every=1):
+    td = wl.make_tokens(w, clean=False)
+    lyr, B, G = w.layers, w.batch, w.hq // w.hkv
+    scored = w.alpha != 0.0
+    Q, Kc, Vc = wl.make_qkv(w, device=DEV)
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent, alpha=w.alpha, beta=w.beta, gamma=w.gamma)
+    tok = _dev(td.tok)
+    seq_len = _dev(td.seq_len)
+    # prefill eviction on the GPU (per-unit index lists even for the attention-free setting)
+    anchor, spons, vouch = ta.ta_match_anchors(tok, td.tab_ids, td.tab_len, prm, seq_len=seq_len)
+    A = ta.ta_score(Q, Kc, prm, seq_len=seq_len) if scored else None
+    idx, cnt = ta.ta_select(A, anchor, spons, vouch, K, prm, lyr, w.hkv, seq_len=seq_len)
+    Ko, Vo = ta.ta_compact(Kc, Vc, idx, cnt, K)
+    cap = w.n + steps + 4
+    st = ta.DecodeState(lyr, B, w.hq, w.hkv, K, cap, DEV)
+    ta.ta_decode_init(st, tok, anchor, idx, cnt, Ko, Vo, prm, seq_len=seq_len, A=A)
+    torch.cuda.synchronize()
+
+    # the oracle's own prefill and state
+    seqs, units = [], {}
+    for b in range(B):
+        nb = int(td.seq_len[b])
+        seqs.append(ora.DecodeSeq(td.tok[b, :nb], td.tab_ids, td.tab_len, cap))
+        a, s, v = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len)
+        for l in range(lyr):
+            for g in range(w.hkv):
+                Kb, Vb = wl.bf16_bits(Kc[l, b, g, :nb]), wl.bf16_bits(Vc[l, b, g, :nb])
+                A_ref = ora.score(wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]), Kb) if scored else None
+                idx_ref = ora.select(A_ref, a, s, v, K, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
+                assert np.array_equal(idx[l, b, g, :len(idx_ref)].cpu().numpy(), idx_ref)
+                A_kept = A_ref[idx_ref] if scored else np.zeros(len(idx_ref), np.float32)
+                u = ora.DecodeUnit(np.zeros((K, w.d), np.uint16), np.zeros((K, w.d), np.uint16),
+                                   np.full(K, -1, np.int32), np.zeros(K, np.float32))
+                c = len(idx_ref)
+                u.Kc[:c], u.Vc[:c], u.pos[:c], u.A[:c] = Kb[idx_ref], Vb[idx_ref], idx_ref, A_kept
+                units[(l, b, g)] = u
+    assert np.array_equal(st.pos.cpu().numpy().reshape(-1, K + 1),
+                          np.stack([units[(l, b, g)].pos for l in range(lyr) for b in range(B) for g in range(w.hkv)]))
+
+    stream = wl.make_decode_stream(w, td, steps, p_anchor=p_anchor, clean=False)
+    evicted = torch.zeros((lyr, B, w.hkv), dtype=torch.int32, device=DEV)
+    n_evictions = 0
+    for t in range(steps):
+        q, kn, vn = wl.make_decode_qkv(w, t, device=DEV)
+        ta.ta_decode_step(st, _dev(stream[t]), q if scored else None, kn, vn, td.tab_ids, td.tab_len, prm,
+                          evicted=evicted)
+        torch.cuda.synchronize()
+        gA, gpos, gev = st.A.cpu().numpy(), st.pos.cpu().numpy(), evicted.cpu().numpy()
+        qb, kb, vb = wl.bf16_bits(q), wl.bf16_bits(kn), wl.bf16_bits(vn)
+        for b in range(B):
+            p = seqs[b].append(int(stream[t, b]))
+            for l in range(lyr):
+                for g in range(w.hkv):
+                    u = units[(l, b, g)]
+                    pos_before = u.pos.copy()
+                    e, _ = u.step(seqs[b], qb[l, b, g * G:(g + 1) * G], kb[l, b, g], vb[l, b, g], p,
+                                  w.n_sink, w.n_recent, alpha=w.alpha, beta=w.beta, gamma=w.gamma,
+                                  rank_A=gA[l, b, g])
+                    if e >= 0:
+                        ev_pos = p if pos_before[e] < 0 else int(pos_before[e])
+                        n_evictions += 1
+                    else:
+                        ev_pos = -1
+                    assert gev[l, b, g] == ev_pos, (t, l, b, g)
+                    assert np.array_equal(gpos[l, b, g], u.pos), (t, l, b, g)
+                    occ = u.pos >= 0
+                    if scored:
+                        assert np.all(np.abs(gA[l, b, g][occ] - u.A[occ]) <= 1e-3 * np.abs(u.A[occ]) + 1e-6), (t, l, b, g)
+            seqs[b].decay(0.9)
+        if t % check_every == 0 or t == steps - 1:
+            glen = st.len.cpu().numpy()
+            ganc, gbud, gtok = st.anchor.cpu().numpy(), st.budget.cpu().numpy(), st.tok.cpu().numpy()
+            for b in range(B):
+                n_ = seqs[b].len
+                assert glen[b] == n_
+                assert np.array_equal(gtok[b, :n_], seqs[b].tok[:n_])
+                assert np.array_equal(ganc[b, :n_], seqs[b].anchor[:n_])
+                assert np.array_equal(gbud[b, :n_].view(np.uint32), seqs[b].budget[:n_].view(np.uint32))
+    gK, gV = wl.bf16_bits(st.Kc), wl.bf16_bits(st.Vc)
+    for (l, b, g), u in units.items():
+        occ = u.pos >= 0
+        assert np.array_equal(gK[l, b, g][occ], u.Kc[occ]) and np.array_equal(gV[l, b, g][occ], u.Vc[occ])
+    anchors_in_decode = sum(int(seqs[b].anchor[int(td.seq_len[b]):seqs[b].len].sum()) for b in range(B))
+    return n_evictions, anchors_in_decode
+
+
+def test_decode_steps_match_oracle_scored():
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=3, n=1200, hq=8, hkv=2, ragged=(700, 1200))
+    ev, anc = _run_decode(w, K=64, steps=48, p_anchor=0.08)
+    assert ev == 48 * 2 * 3 * 2 and anc >= 2
+
+
+def test_decode_steps_match_oracle_c5_shape_one_layer():
+    # the benchmark shape of a unit: 32q/8kv heads, K = 256 (257 slots)
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=2, n=2100, ragged=(2048, 2100))
+    ev, _ = _run_decode(w, K=256, steps=12, p_anchor=0.1, check_every=4)
+    assert ev == 12 * 2 * 8
+
+
+def test_decode_attention_free_and_partly_filled_cache():
+    # TA-Fast setting (no queries); sequence 0 is shorter than the budget, so its cache fills up
+    # before anything is evicted
+    w = wl.scaled(wl.CONFIGS["c3_ta_fast"], layers=1, batch=2, n=400, hq=8, hkv=2, n_recent=8, planted=3,
+                  ragged=(40, 400))
+    td = wl.make_tokens(w, clean=False)
+    assert td.seq_len.min() < 256 < td.seq_len.max()
+    ev, _ = _run_decode(w, K=256, steps=70, p_anchor=0.1, check_every=10)
+    assert 0 < ev < 70 * 2 * 2
