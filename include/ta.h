@@ -9,6 +9,8 @@
  *   3. ta_select         protected top-K under the (class, utility, position) order
  *   4. ta_compact        gather of the retained K/V rows
  *      ta_evict          all of the above in one call
+ *      ta_decode_init /  the same policy applied after every generation step
+ *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
  *
  * Conventions shared by every entry point
  *   - Pointers marked DEVICE are GPU global memory owned by the caller;
