@@ -13,9 +13,12 @@
 //                      c_r = m_r + log2 Z_r, recompute S, p = 2^(s - c_r),
 //                      sum p over the rows -> A
 // Both sweeps are one kernel template.  A workgroup owns one chunk of keys of
-// one unit and streams it through LDS in 64-key stages (double buffered,
-// 16-byte chunks XOR-swizzled by row so that the staging stores and the
-// ds_read_b128 fragment loads are both conflict free).  The M rows are split
+// one unit and streams it through LDS in 64-key stages: a ring of four 16 KB
+// buffers filled by direct global->LDS loads issued three stages ahead (no
+// staging registers), 16-byte chunks XOR-swizzled by row so that the
+// ds_read_b128 fragment loads are conflict free.  Blocks are numbered so that
+// all chunks of a unit run on one XCD (block b lands on XCD b mod 8): the
+// unit's Q rows and chunk statistics are then fetched into one L2 only.  The M rows are split
 // into RG groups of 64; the workgroup has 2*RG wavefronts, wavefront (rg, kt)
 // owns row group rg (its Q fragments stay in 64 registers for the whole chunk)
 // and the kt-th 32-key tile of every stage, so one K fragment read from LDS
@@ -36,17 +39,34 @@ namespace {
 
 constexpr int STAGE_KEYS = 64;
 constexpr int STAGE_UNITS = STAGE_KEYS * 16;     // 16-byte units per stage (256 B per key)
+constexpr int RING = 4;                          // stage buffers; loads run RING-1 stages ahead
+
+// Direct global->LDS load of 16 bytes per lane: lane i's data lands at lds_base + 16*i
+// (lds_base wave-uniform, passed in M0).  Written as inline assembly on purpose: the
+// compiler would otherwise make every later LDS read wait for ALL outstanding direct loads,
+// which would serialise the stage pipeline; the waits for these loads are explicit below.
+// Extra outstanding loads only make the compiler's own vmcnt waits more conservative.
+__device__ __forceinline__ void load_to_lds_16(const uint4* src, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(src)
+                 : "memory", "m0");
+}
+
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 template <int RG, bool COLSUM>
 __global__ void __launch_bounds__(128 * RG)
 score_kernel(ScoreArgs a)
 {
     constexpr int THREADS = 128 * RG;
-    constexpr int LOADS = STAGE_UNITS / THREADS;           // 16-byte staging loads per thread per stage
-    constexpr int ROWS_PER_PASS = THREADS / 16;            // key rows covered by one staging load
-    static_assert(LOADS == 1 || LOADS == 2 || LOADS == 4, "unsupported row-group count");
+    constexpr int WAVES = 2 * RG;
+    constexpr int LPS = 16 / WAVES;                        // 1 KB direct loads per wavefront per stage
+    static_assert(LPS >= 1, "unsupported row-group count");
 
-    __shared__ uint4 s_k[2][STAGE_UNITS];                  // 2 x 16 KB
+    __shared__ uint4 s_k[RING][STAGE_UNITS];               // 4 x 16 KB
     __shared__ float s_c[COLSUM ? 64 * RG : 1];            // per-row constant m + log2 Z
     __shared__ int32_t s_lim[COLSUM ? 64 * RG : 1];        // per-row last visible key
     __shared__ float s_part[COLSUM ? 2 : 1][RG][STAGE_KEYS];
@@ -56,8 +76,12 @@ score_kernel(ScoreArgs a)
     const int c32 = lane & 31, hf = lane >> 5;
     const int rg = wave % RG, kt = wave / RG;              // row group, key tile of the stage
 
-    const int32_t chunk = (int32_t)(blockIdx.x % (uint32_t)a.nchunks);
-    const int32_t unit = a.unit0 + (int32_t)(blockIdx.x / (uint32_t)a.nchunks);
+    // XCD x = block % 8 runs the units [x * units_per_xcd, (x+1) * units_per_xcd)
+    const int32_t seq_in_xcd = (int32_t)(blockIdx.x >> 3);
+    const int32_t unit_in_xcd = seq_in_xcd / a.nchunks;
+    const int32_t chunk = seq_in_xcd - unit_in_xcd * a.nchunks;
+    const int32_t unit = (int32_t)(blockIdx.x & 7u) * a.units_per_xcd + unit_in_xcd;
+    if (unit >= a.units) return;
     const int32_t g = unit % a.hkv;
     const int32_t b = (unit / a.hkv) % a.batch;
     const int32_t l = unit / (a.hkv * a.batch);
@@ -72,33 +96,26 @@ score_kernel(ScoreArgs a)
     // keys <= min_lim are visible to every live row of a full window
     const int32_t min_lim = a.causal ? nb - W : nb - 1;
 
-    // ---- K staging: thread -> (row srow + ROWS_PER_PASS*j, 16-byte chunk sch) -------
+    // ---- K staging: direct global->LDS loads, 1 KB (4 key rows) per wavefront instruction.
+    // Lane i of a load lands at (buffer + block*1 KB + 16*i): LDS slot row*16 + c' receives the
+    // 16-byte chunk c' ^ (row & 15) of key row `row`.
     const uint4* kbase = a.K + l * a.k_sl + b * a.k_sb + g * a.k_sh;
-    const int srow = tid >> 4, sch = tid & 15;
-    // named registers (an indexed array here ends up in scratch memory)
-    uint4 sr0 = make_uint4(0, 0, 0, 0), sr1 = sr0, sr2 = sr0, sr3 = sr0;
-    auto stage_addr = [&](int s, int j) -> const uint4* {
-        int32_t key = key_lo + s * STAGE_KEYS + srow + ROWS_PER_PASS * j;
-        key = key > n - 1 ? n - 1 : key;                   // stay inside the tensor; masked later
-        return kbase + (uint32_t)(key * a.k_sp + sch);
+    auto stage_issue = [&](int s) {
+        const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)&s_k[s % RING][0];
+#pragma unroll
+        for (int j = 0; j < LPS; ++j) {
+            const int blk = wave + WAVES * j;
+            const int row = blk * 4 + (lane >> 4);
+            const int csrc = (lane & 15) ^ (row & 15);
+            int32_t key = key_lo + s * STAGE_KEYS + row;
+            key = key > n - 1 ? n - 1 : key;               // stay inside the tensor; masked later
+            const uint4* src = kbase + (uint32_t)(key * a.k_sp + csrc);
+            load_to_lds_16(src, __builtin_amdgcn_readfirstlane(dst + blk * 1024));
+        }
     };
-    auto stage_load = [&](int s) {
-        sr0 = *stage_addr(s, 0);
-        if (LOADS > 1) sr1 = *stage_addr(s, 1);
-        if (LOADS > 2) sr2 = *stage_addr(s, 2);
-        if (LOADS > 2) sr3 = *stage_addr(s, 3);
-    };
-    auto stage_slot = [&](int j) -> int {
-        const int row = srow + ROWS_PER_PASS * j;
-        return row * 16 + (sch ^ (row & 15));
-    };
-    auto stage_store = [&](int buf) {
-        s_k[buf][stage_slot(0)] = sr0;
-        if (LOADS > 1) s_k[buf][stage_slot(1)] = sr1;
-        if (LOADS > 2) s_k[buf][stage_slot(2)] = sr2;
-        if (LOADS > 2) s_k[buf][stage_slot(3)] = sr3;
-    };
-    if (nstages > 0) stage_load(0);                        // in flight while Q and the statistics load
+#pragma unroll
+    for (int s = 0; s < RING - 1; ++s)
+        if (s < nstages) stage_issue(s);                   // in flight while Q and the statistics load
 
     // ---- Q fragments of this wavefront's 64 rows (registers, whole chunk) -----------
     bf16x8 qf[ROW_TILES][8];
@@ -162,16 +179,24 @@ score_kernel(ScoreArgs a)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) kslot[ks] = krow * 16 + ((2 * ks + hf) ^ (krow & 15));
 
-    if (nstages > 0) stage_store(0);
-    // Drain every outstanding global load (Q fragments included) before the loop, so that
-    // inside it the only loads in flight are the next stage's prefetch and nothing in the
-    // MFMA sequence has to wait for them.
-    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
+    // Drain every outstanding load (first stages, Q fragments, statistics) before the loop, so
+    // that inside it the only loads in flight are the direct loads of later stages.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
 
     for (int s = 0; s < nstages; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < nstages) stage_load(s + 1);
+        const int buf = s % RING;
+        const int ps = s & 1;
+        if (s > 0) {
+            // stage s has landed once at most the loads of the later stages issued so far
+            // (up to two) are outstanding; loads complete in issue order
+            const int later = nstages - 1 - s;
+            if (later >= 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * LPS));
+            else if (later == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPS));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __syncthreads();                               // every wavefront: stage s landed, stage s-1 consumed
+        }
+        if (s + RING - 1 < nstages) stage_issue(s + RING - 1);   // overwrites the buffer of stage s-1
         const int32_t tile_key0 = key_lo + s * STAGE_KEYS + 32 * kt;
         const bool all_visible = (key_lo + s * STAGE_KEYS + STAGE_KEYS - 1) <= min_lim;
 
@@ -228,18 +253,19 @@ score_kernel(ScoreArgs a)
         }
         if constexpr (COLSUM) {
             colsum += __shfl_xor(colsum, 32);
-            if (hf == 0) s_part[buf][rg][32 * kt + c32] = colsum;
+            if (hf == 0) s_part[ps][rg][32 * kt + c32] = colsum;
         }
 
-        if (s + 1 < nstages) stage_store(buf ^ 1);
-        __syncthreads();
-        if (COLSUM && tid < STAGE_KEYS) {
-            const int32_t key = key_lo + s * STAGE_KEYS + tid;
-            if (key < key_hi) {
-                float v = s_part[buf][0][tid];
+        if constexpr (COLSUM) {
+            __syncthreads();                               // partial column sums of every row group are in LDS
+            if (tid < STAGE_KEYS) {
+                const int32_t key = key_lo + s * STAGE_KEYS + tid;
+                if (key < key_hi) {
+                    float v = s_part[ps][0][tid];
 #pragma unroll
-                for (int w = 1; w < RG; ++w) v += s_part[buf][w][tid];
-                a.A[(size_t)unit * n + key] = v;
+                    for (int w = 1; w < RG; ++w) v += s_part[ps][w][tid];
+                    a.A[(size_t)unit * n + key] = v;
+                }
             }
         }
     }
@@ -247,7 +273,8 @@ score_kernel(ScoreArgs a)
     if constexpr (!COLSUM) {
         // merge the two half-waves (disjoint key subsets of the same row), then the two
         // key-tile wavefronts of the row group through LDS, then store
-        float* s_m = reinterpret_cast<float*>(&s_k[0][0]);     // staging buffers are idle now
+        __syncthreads();                                       // staging buffers are idle now
+        float* s_m = reinterpret_cast<float*>(&s_k[0][0]);
         float* s_z = s_m + 64 * RG;
 #pragma unroll
         for (int t = 0; t < ROW_TILES; ++t) {
@@ -287,8 +314,9 @@ void launch_rg(ScoreArgs a, int64_t units, hipStream_t st)
 {
     // One launch per sweep over all units.  (Splitting the units into cache-sized groups
     // so that sweep 2 re-reads its keys from the last-level cache was measured slower.)
-    const unsigned blocks = (unsigned)(units * a.nchunks);
-    a.unit0 = 0;
+    a.units = (int32_t)units;
+    a.units_per_xcd = (int32_t)((units + 7) / 8);
+    const unsigned blocks = (unsigned)(8ll * a.units_per_xcd * a.nchunks);
     hipLaunchKernelGGL((score_kernel<RG, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
     hipLaunchKernelGGL((score_kernel<RG, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
 }
@@ -304,6 +332,19 @@ int32_t padded_rows(int32_t rows)
     return 512;
 }
 
+int compute_units()
+{
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
+            cu = 256;                                      // MI355X
+        cached = cu;
+    }
+    return cached;
+}
+
 struct ScorePlan {
     int32_t rows, rows_pad, chunk_keys, nchunks;
     int64_t units;
@@ -314,11 +355,18 @@ ScorePlan make_plan(const ta_layout& lay)
     ScorePlan p;
     p.rows = (lay.hq / lay.hkv) * lay.window;
     p.rows_pad = padded_rows(p.rows);
-    // at most 32 chunks per unit so that merging chunk statistics stays cheap
-    p.chunk_keys = 512;
-    while ((int64_t)p.chunk_keys * 32 < lay.n) p.chunk_keys *= 2;
-    p.nchunks = (lay.n + p.chunk_keys - 1) / p.chunk_keys;
+    // Chunks as long as possible (the per-workgroup prologue - Q fragments, first stages,
+    // statistics merge - is amortised over the chunk) while the grid still offers about two
+    // workgroups per compute unit; never more than 32 chunks per unit.
     p.units = (int64_t)lay.layers * lay.batch * lay.hkv;
+    const int64_t want_blocks = 2 * (int64_t)compute_units();
+    int64_t per_unit = (want_blocks + p.units - 1) / p.units;            // chunks per unit we would like
+    per_unit = per_unit < 1 ? 1 : (per_unit > 32 ? 32 : per_unit);
+    int64_t ck = ((lay.n + per_unit - 1) / per_unit + STAGE_KEYS - 1) / STAGE_KEYS * STAGE_KEYS;
+    if (ck < 512) ck = 512;
+    while (ck * 32 < lay.n) ck += STAGE_KEYS;
+    p.chunk_keys = (int32_t)ck;
+    p.nchunks = (lay.n + p.chunk_keys - 1) / p.chunk_keys;
     return p;
 }
 
@@ -334,7 +382,7 @@ size_t score_workspace_bytes(const ta_layout& lay)
 int64_t score_grid_blocks(const ta_layout& lay)
 {
     const ScorePlan p = make_plan(lay);
-    return p.units * p.nchunks;
+    return 8 * ((p.units + 7) / 8) * p.nchunks;
 }
 
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
@@ -363,7 +411,6 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.rows_pad = p.rows_pad;
     a.chunk_keys = p.chunk_keys;
     a.nchunks = p.nchunks;
-    a.unit0 = 0;
     a.causal = causal;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
     switch (a.rows_pad) {

@@ -21,7 +21,7 @@ struct ScoreArgs {
     int32_t batch, hkv, G, W, n;
     int32_t rows, rows_pad;            // M = G*W and M rounded up to 64*RG
     int32_t chunk_keys, nchunks;
-    int32_t unit0;                     // first unit of this launch
+    int32_t units, units_per_xcd;      // units in total and per XCD (block -> unit mapping)
     int32_t causal;
     float scale_log2;                  // log2(e) / sqrt(d)
 };
