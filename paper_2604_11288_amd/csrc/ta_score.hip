@@ -31,6 +31,8 @@
 //           the column sum is a register accumulation plus one half-wave swap.
 #include <math.h>
 
+#include <type_traits>
+
 #include "ta_score_common.h"
 
 namespace ta {
@@ -95,6 +97,20 @@ score_kernel(ScoreArgs a)
     const int nstages = (key_hi - key_lo + STAGE_KEYS - 1) / STAGE_KEYS;
     // keys <= min_lim are visible to every live row of a full window
     const int32_t min_lim = a.causal ? nb - W : nb - 1;
+
+    if (key_lo >= nb) {
+        // the whole chunk lies past the end of this sequence: nothing is visible
+        if constexpr (!COLSUM) {
+            float* st = a.ws + (((size_t)unit * a.nchunks + chunk) * a.rows_pad) * 2;
+            for (int r = tid; r < a.rows_pad; r += THREADS) {
+                st[r * 2] = -INFINITY;
+                st[r * 2 + 1] = 0.0f;
+            }
+        } else {
+            for (int32_t key = key_lo + tid; key < key_hi; key += THREADS) a.A[(size_t)unit * n + key] = 0.0f;
+        }
+        return;
+    }
 
     // ---- K staging: direct global->LDS loads, 1 KB (4 key rows) per wavefront instruction.
     // Lane i of a load lands at (buffer + block*1 KB + 16*i): LDS slot row*16 + c' receives the
@@ -184,9 +200,11 @@ score_kernel(ScoreArgs a)
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
 
-    for (int s = 0; s < nstages; ++s) {
-        const int buf = s % RING;
-        const int ps = s & 1;
+    // ---- main loop, software pipelined over stages -------------------------------------
+    // Iteration s issues the MFMAs of stage s while the vector ALUs reduce the
+    // accumulators of stage s-1 (softmax statistics or column sums), so the matrix pipe
+    // and the VALU of a wavefront overlap instead of alternating.
+    const auto stage_sync = [&](int s) {
         if (s > 0) {
             // stage s has landed once at most the loads of the later stages issued so far
             // (up to two) are outstanding; loads complete in issue order
@@ -197,55 +215,62 @@ score_kernel(ScoreArgs a)
             __syncthreads();                               // every wavefront: stage s landed, stage s-1 consumed
         }
         if (s + RING - 1 < nstages) stage_issue(s + RING - 1);   // overwrites the buffer of stage s-1
-        const int32_t tile_key0 = key_lo + s * STAGE_KEYS + 32 * kt;
-        const bool all_visible = (key_lo + s * STAGE_KEYS + STAGE_KEYS - 1) <= min_lim;
-
+    };
+    const auto mma = [&](int s, f32x16 (&acc)[ROW_TILES]) {
+        const uint4* buf = &s_k[s % RING][0];
         bf16x8 kf[8];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[ks] = as_frag(s_k[buf][kslot[ks]]);
-
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = as_frag(buf[kslot[ks]]);
+#pragma unroll
+        for (int t = 0; t < ROW_TILES; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int t = 0; t < ROW_TILES; ++t) {
+                if constexpr (!COLSUM)   // keys x rows: acc[t][i] = key tile + 8*(i/4) + 4*hf + i%4, this lane's row
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[t][ks], acc[t], 0, 0, 0);
+                else                     // rows x keys: acc[t][i] = row 64*rg + 32*t + 8*(i/4) + 4*hf + i%4, key tile + c32
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t][ks], kf[ks], acc[t], 0, 0, 0);
+            }
+    };
+    // reduction of the accumulators of stage s; MASKED: some key of the stage is hidden from some row
+    const auto reduce = [&](int s, f32x16 (&acc)[ROW_TILES], auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const int32_t tile_key0 = key_lo + s * STAGE_KEYS + 32 * kt;
         float colsum = 0.0f;
 #pragma unroll
         for (int t = 0; t < ROW_TILES; ++t) {
-            f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             if constexpr (!COLSUM) {
-                // keys x rows: acc[i] = key tile_key0 + 8*(i/4) + 4*hf + i%4, this lane's query row
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[t][ks], acc, 0, 0, 0);
-                if (!all_visible) {
+                if constexpr (MASKED) {
                     const int32_t lim = my_lim[t];
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int32_t key = tile_key0 + 8 * (i >> 2) + 4 * hf + (i & 3);
-                        acc[i] = key <= lim ? acc[i] : -INFINITY;
+                        acc[t][i] = key <= lim ? acc[t][i] : -INFINITY;
                     }
                 }
-                float tmax = acc[0];
+                float tmax = acc[t][0];
 #pragma unroll
-                for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+                for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[t][i]);
                 const float mnew = fmaxf(m_run[t], tmax * sc);
-                if (mnew > -INFINITY) {
-                    float sum = 0.0f;
+                const float mref = (MASKED && mnew == -INFINITY) ? 0.0f : mnew;   // every key hidden so far
+                float sum = 0.0f;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], sc, -mnew));
-                    z_run[t] = z_run[t] * fast_exp2(m_run[t] - mnew) + sum;
-                    m_run[t] = mnew;
-                }
+                for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[t][i], sc, -mref));
+                z_run[t] = z_run[t] * fast_exp2(m_run[t] - mref) + sum;
+                m_run[t] = mnew;
             } else {
-                // rows x keys: acc[i] = query row 64*rg + 32*t + 8*(i/4) + 4*hf + i%4, key tile_key0 + c32
+                if constexpr (!MASKED) {
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t][ks], kf[ks], acc, 0, 0, 0);
-                if (all_visible) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
+                    for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[t][i], sc, -cst[t][i]));
                 } else {
                     const int32_t key = tile_key0 + c32;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int row = 64 * rg + 32 * t + 8 * (i >> 2) + 4 * hf + (i & 3);
-                        const float p = fast_exp2(fmaf(acc[i], sc, -cst[t][i]));
+                        const float p = fast_exp2(fmaf(acc[t][i], sc, -cst[t][i]));
                         colsum += key <= s_lim[row] ? p : 0.0f;
                     }
                 }
@@ -253,21 +278,75 @@ score_kernel(ScoreArgs a)
         }
         if constexpr (COLSUM) {
             colsum += __shfl_xor(colsum, 32);
-            if (hf == 0) s_part[ps][rg][32 * kt + c32] = colsum;
+            if (hf == 0) s_part[s & 1][rg][32 * kt + c32] = colsum;
         }
-
+    };
+    // column sums of stage s: add the row groups' partial sums (complete after the next barrier)
+    const auto flush = [&](int s) {
         if constexpr (COLSUM) {
-            __syncthreads();                               // partial column sums of every row group are in LDS
             if (tid < STAGE_KEYS) {
                 const int32_t key = key_lo + s * STAGE_KEYS + tid;
                 if (key < key_hi) {
-                    float v = s_part[ps][0][tid];
+                    float v = s_part[s & 1][0][tid];
 #pragma unroll
-                    for (int w = 1; w < RG; ++w) v += s_part[ps][w][tid];
+                    for (int w = 1; w < RG; ++w) v += s_part[s & 1][w][tid];
                     a.A[(size_t)unit * n + key] = v;
                 }
             }
         }
+    };
+    using fast_tag = std::integral_constant<bool, false>;
+    using masked_tag = std::integral_constant<bool, true>;
+
+    // stages whose keys are all visible to every row: [0, nfast)
+    int nfast = min_lim >= key_lo + STAGE_KEYS - 1 ? (min_lim - key_lo + 1) / STAGE_KEYS : 0;
+    nfast = nfast > nstages ? nstages : nfast;
+
+    int flushed = 0, reduced = 0;                          // stages whose column sums are written / in LDS
+    const auto flush_pending = [&]() {
+        for (; flushed < reduced; ++flushed) flush(flushed);
+    };
+
+    // (A) fully visible stages: MFMAs of stage s and the reduction of stage s-1 in one block
+    f32x16 acc_prev[ROW_TILES];
+    if (nfast > 0) {
+        stage_sync(0);
+        mma(0, acc_prev);
+        for (int s = 1; s < nfast; ++s) {
+            stage_sync(s);
+            flush_pending();                               // reductions before this barrier are complete
+            f32x16 acc_cur[ROW_TILES];
+            mma(s, acc_cur);
+            reduce(s - 1, acc_prev, fast_tag{});
+            reduced = s;
+#pragma unroll
+            for (int t = 0; t < ROW_TILES; ++t) acc_prev[t] = acc_cur[t];
+        }
+        if constexpr (COLSUM) {
+            // the drain below writes the partial-sum buffer that the last flush above read
+            __syncthreads();
+            flush_pending();
+        }
+        reduce(nfast - 1, acc_prev, fast_tag{});
+        reduced = nfast;
+        if constexpr (COLSUM) {
+            // both partial-sum buffers are pending here; empty them before loop (B) reuses one
+            __syncthreads();
+            flush_pending();
+        }
+    }
+    // (B) the few stages near the causal diagonal or past the sequence end: masked, not pipelined
+    for (int s = nfast; s < nstages; ++s) {
+        stage_sync(s);
+        flush_pending();
+        f32x16 acc_cur[ROW_TILES];
+        mma(s, acc_cur);
+        reduce(s, acc_cur, masked_tag{});
+        reduced = s + 1;
+    }
+    if constexpr (COLSUM) {
+        __syncthreads();
+        flush_pending();
     }
 
     if constexpr (!COLSUM) {

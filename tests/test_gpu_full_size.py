@@ -164,3 +164,18 @@ def test_c5_agentic_full_prefill_and_decode_steps():
             assert np.all(np.abs(gA[occ] - u.A[occ]) <= 1e-3 * np.abs(u.A[occ]) + 1e-6)
         for b in seqs:
             seqs[b].decay(0.9)
+
+
+def test_score_run_to_run_identical_with_long_chunks():
+    """Many units and one long chunk per workgroup (hundreds of pipelined stages): the column
+    sums must not depend on wavefront timing."""
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=8)
+    td = wl.make_tokens(w)
+    Q, Kc, _ = wl.make_qkv(w, device=DEV, with_v=False)
+    seq = _dev(td.seq_len)
+    prm = _prm(w)
+    first = ta.ta_score(Q, Kc, prm, seq_len=seq).clone()
+    for _ in range(3):
+        again = ta.ta_score(Q, Kc, prm, seq_len=seq)
+        torch.cuda.synchronize()
+        assert torch.equal(first.view(torch.int32), again.view(torch.int32))
