@@ -43,16 +43,17 @@ constexpr int STAGE_KEYS = 64;
 constexpr int STAGE_UNITS = STAGE_KEYS * 16;     // 16-byte units per stage (256 B per key)
 constexpr int RING = 4;                          // stage buffers; loads run RING-1 stages ahead
 
-// Direct global->LDS load of 16 bytes per lane: lane i's data lands at lds_base + 16*i
-// (lds_base wave-uniform, passed in M0).  Written as inline assembly on purpose: the
-// compiler would otherwise make every later LDS read wait for ALL outstanding direct loads,
-// which would serialise the stage pipeline; the waits for these loads are explicit below.
-// Extra outstanding loads only make the compiler's own vmcnt waits more conservative.
-__device__ __forceinline__ void load_to_lds_16(const uint4* src, uint32_t lds_base)
+// Direct global->LDS load of 16 bytes per lane: lane i reads 16 bytes at base + off (base
+// wave-uniform, off per lane) and its data lands at lds_base + 16*i (lds_base wave-uniform,
+// passed in M0).  Written as inline assembly on purpose: the compiler would otherwise make
+// every later LDS read wait for ALL outstanding direct loads, which would serialise the stage
+// pipeline; the waits for these loads are explicit below.  Extra outstanding loads only make
+// the compiler's own vmcnt waits more conservative.
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_base), "v"(src)
+                 : "s"(lds_base), "v"(off), "s"(base)
                  : "memory", "m0");
 }
 
@@ -112,21 +113,52 @@ score_kernel(ScoreArgs a)
         return;
     }
 
+    // Stages whose keys are all visible to every row, [0, nfast), are visited in rotated
+    // order, starting at a stage that differs from block to block.  Chunks start at
+    // multiples of a large power of two, so blocks that advance in step would otherwise
+    // all read the same offset within their chunk at the same time and crowd a few
+    // memory channels.
+    int nfast = min_lim >= key_lo + STAGE_KEYS - 1 ? (min_lim - key_lo + 1) / STAGE_KEYS : 0;
+    nfast = nfast > nstages ? nstages : nfast;
+    const int rot = nfast > 1 ? (int)((seq_in_xcd + 5 * (int32_t)(blockIdx.x & 7u)) % nfast) : 0;
+    // The column-sum sweep visits them in the reverse order of the statistics sweep: what
+    // that sweep read last is the likeliest to still sit in the last-level cache.
+    const auto stage_pos = [&](int s) {
+        if (s >= nfast) return s;
+        const int p = (COLSUM ? nfast - 1 - s : s) + rot;
+        return p >= nfast ? p - nfast : p;
+    };
+
     // ---- K staging: direct global->LDS loads, 1 KB (4 key rows) per wavefront instruction.
     // Lane i of a load lands at (buffer + block*1 KB + 16*i): LDS slot row*16 + c' receives the
     // 16-byte chunk c' ^ (row & 15) of key row `row`.
+    // The byte offset of a lane's 16 bytes inside a stage does not depend on the stage, so a
+    // stage costs one scalar base address and no vector arithmetic (except the ragged last one).
     const uint4* kbase = a.K + l * a.k_sl + b * a.k_sb + g * a.k_sh;
-    auto stage_issue = [&](int s) {
-        const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)&s_k[s % RING][0];
+    const uint32_t lds_ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)&s_k[0][0];
+    const uint32_t lds_wave = lds_ring + 1024u * (uint32_t)__builtin_amdgcn_readfirstlane(wave);
+    uint32_t lane_off[LPS];
 #pragma unroll
-        for (int j = 0; j < LPS; ++j) {
-            const int blk = wave + WAVES * j;
-            const int row = blk * 4 + (lane >> 4);
-            const int csrc = (lane & 15) ^ (row & 15);
-            int32_t key = key_lo + s * STAGE_KEYS + row;
-            key = key > n - 1 ? n - 1 : key;               // stay inside the tensor; masked later
-            const uint4* src = kbase + (uint32_t)(key * a.k_sp + csrc);
-            load_to_lds_16(src, __builtin_amdgcn_readfirstlane(dst + blk * 1024));
+    for (int j = 0; j < LPS; ++j) {
+        const int row = (wave + WAVES * j) * 4 + (lane >> 4);
+        lane_off[j] = (uint32_t)(row * a.k_sp + ((lane & 15) ^ (row & 15))) * 16u;
+    }
+    auto stage_issue = [&](int s) {
+        const int32_t key0 = key_lo + stage_pos(s) * STAGE_KEYS;
+        const uint4* sbase = kbase + (int64_t)key0 * a.k_sp;
+        const uint32_t dst = lds_wave + (uint32_t)(s % RING) * (STAGE_UNITS * 16u);
+        if (key0 + STAGE_KEYS <= n) {
+#pragma unroll
+            for (int j = 0; j < LPS; ++j) load_to_lds_16(sbase, lane_off[j], dst + WAVES * j * 1024u);
+        } else {
+#pragma unroll
+            for (int j = 0; j < LPS; ++j) {
+                const int row = (wave + WAVES * j) * 4 + (lane >> 4);
+                const int32_t last = n - 1 - key0;         // stay inside the tensor; masked later
+                const int32_t rclamp = row > last ? last : row;
+                const uint32_t off = (uint32_t)(rclamp * a.k_sp + ((lane & 15) ^ (row & 15))) * 16u;
+                load_to_lds_16(sbase, off, dst + WAVES * j * 1024u);
+            }
         }
     };
 #pragma unroll
@@ -238,7 +270,7 @@ score_kernel(ScoreArgs a)
     // reduction of the accumulators of stage s; MASKED: some key of the stage is hidden from some row
     const auto reduce = [&](int s, f32x16 (&acc)[ROW_TILES], auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const int32_t tile_key0 = key_lo + s * STAGE_KEYS + 32 * kt;
+        const int32_t tile_key0 = key_lo + stage_pos(s) * STAGE_KEYS + 32 * kt;
         float colsum = 0.0f;
 #pragma unroll
         for (int t = 0; t < ROW_TILES; ++t) {
@@ -285,7 +317,7 @@ score_kernel(ScoreArgs a)
     const auto flush = [&](int s) {
         if constexpr (COLSUM) {
             if (tid < STAGE_KEYS) {
-                const int32_t key = key_lo + s * STAGE_KEYS + tid;
+                const int32_t key = key_lo + stage_pos(s) * STAGE_KEYS + tid;
                 if (key < key_hi) {
                     float v = s_part[s & 1][0][tid];
 #pragma unroll
@@ -298,36 +330,45 @@ score_kernel(ScoreArgs a)
     using fast_tag = std::integral_constant<bool, false>;
     using masked_tag = std::integral_constant<bool, true>;
 
-    // stages whose keys are all visible to every row: [0, nfast)
-    int nfast = min_lim >= key_lo + STAGE_KEYS - 1 ? (min_lim - key_lo + 1) / STAGE_KEYS : 0;
-    nfast = nfast > nstages ? nstages : nfast;
-
     int flushed = 0, reduced = 0;                          // stages whose column sums are written / in LDS
     const auto flush_pending = [&]() {
         for (; flushed < reduced; ++flushed) flush(flushed);
     };
 
-    // (A) fully visible stages: MFMAs of stage s and the reduction of stage s-1 in one block
-    f32x16 acc_prev[ROW_TILES];
+    // (A) fully visible stages: MFMAs of stage s and the reduction of stage s-1 in one block.
+    // Two accumulator sets alternate (loop unrolled by two) so that no registers are copied.
     if (nfast > 0) {
+        f32x16 acc_even[ROW_TILES], acc_odd[ROW_TILES];
         stage_sync(0);
-        mma(0, acc_prev);
-        for (int s = 1; s < nfast; ++s) {
+        mma(0, acc_even);
+        int s = 1;
+        for (; s + 1 < nfast; s += 2) {
             stage_sync(s);
             flush_pending();                               // reductions before this barrier are complete
-            f32x16 acc_cur[ROW_TILES];
-            mma(s, acc_cur);
-            reduce(s - 1, acc_prev, fast_tag{});
+            mma(s, acc_odd);
+            reduce(s - 1, acc_even, fast_tag{});
             reduced = s;
-#pragma unroll
-            for (int t = 0; t < ROW_TILES; ++t) acc_prev[t] = acc_cur[t];
+            stage_sync(s + 1);
+            flush_pending();
+            mma(s + 1, acc_even);
+            reduce(s, acc_odd, fast_tag{});
+            reduced = s + 1;
+        }
+        const bool odd_left = s < nfast;                   // one more stage, into the odd set
+        if (odd_left) {
+            stage_sync(s);
+            flush_pending();
+            mma(s, acc_odd);
+            reduce(s - 1, acc_even, fast_tag{});
+            reduced = s;
         }
         if constexpr (COLSUM) {
             // the drain below writes the partial-sum buffer that the last flush above read
             __syncthreads();
             flush_pending();
         }
-        reduce(nfast - 1, acc_prev, fast_tag{});
+        if (odd_left) reduce(nfast - 1, acc_odd, fast_tag{});
+        else reduce(nfast - 1, acc_even, fast_tag{});
         reduced = nfast;
         if constexpr (COLSUM) {
             // both partial-sum buffers are pending here; empty them before loop (B) reuses one
