@@ -189,7 +189,7 @@ int32_t ta_score(const void* Q, const void* K, const ta_layout* lay, const int32
 {
     int32_t rc = check_score(Q, K, lay, prm, A, ws, ws_bytes);
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws,
+    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws, nullptr,
                                        (hipStream_t)stream));
 }
 
@@ -243,10 +243,13 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
     if (rc != TA_OK) return rc;
 
     hipStream_t st = (hipStream_t)stream;
-    rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, anchor, spons, vouch, st));
-    if (rc != TA_OK) return rc;
     if (scored) {
-        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, st));
+        // the match rides along with the first sweep of the scores (one launch fewer in front of them)
+        const ta::MatchRider rider = {tok, anchor_B, anchor, spons, vouch, &tab};
+        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, &rider, st));
+        if (rc != TA_OK) return rc;
+    } else {
+        rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, anchor, spons, vouch, st));
         if (rc != TA_OK) return rc;
     }
     rc = hip_status(ta::launch_select(A, anchor, spons, vouch, seq_len, sel_layers, lay->batch, sel_hkv,

@@ -22,12 +22,24 @@ hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, i
                         const MatchTable& tab, const float* anchor_B,
                         uint8_t* anchor, uint8_t* spons, float* vouch, hipStream_t st);
 
+// Arguments of a match that rides along with the first sweep of the score step.
+struct MatchRider {
+    const int32_t* tok;
+    const float* anchor_B;
+    uint8_t* anchor;
+    uint8_t* spons;
+    float* vouch;
+    const MatchTable* tab;
+};
+
 // ---- score ------------------------------------------------------------------
 // Scratch bytes and grid size of the score step for a validated layout.
 size_t score_workspace_bytes(const ta_layout& lay);
 int64_t score_grid_blocks(const ta_layout& lay);
+// With `rider` set, the match + voucher expansion of all sequences runs as trailing workgroups
+// of the first sweep's launch (it depends on the tokens only and is needed after the score).
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
-                        int causal, float* A, float* ws, hipStream_t st);
+                        int causal, float* A, float* ws, const MatchRider* rider, hipStream_t st);
 
 // ---- select -----------------------------------------------------------------
 hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* spons,

@@ -33,6 +33,7 @@
 
 #include <type_traits>
 
+#include "ta_match_device.h"
 #include "ta_score_common.h"
 
 namespace ta {
@@ -60,16 +61,49 @@ __device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, u
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
+// Statistics sweep that also carries the match tiles: workgroups past the score grid each run
+// one tile of the anchor match (they start as the first score workgroups retire).
+struct RiderArgs {
+    MatchArgs m;
+    MatchTable tab;
+    uint32_t score_blocks;
+};
+
+template <int RG, bool COLSUM>
+__device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS]);
+
 template <int RG, bool COLSUM>
 __global__ void __launch_bounds__(128 * RG)
 score_kernel(ScoreArgs a)
+{
+    __shared__ uint4 s_k[RING][STAGE_UNITS];               // 4 x 16 KB
+    score_body<RG, COLSUM>(a, s_k);
+}
+
+template <int RG>
+__global__ void __launch_bounds__(128 * RG)
+score_stats_match_kernel(ScoreArgs a, RiderArgs r)
+{
+    __shared__ uint4 s_k[RING][STAGE_UNITS];
+    static_assert(sizeof(MatchLds) <= sizeof(uint4) * RING * STAGE_UNITS, "match tile must fit the stage ring");
+    if (blockIdx.x >= r.score_blocks) {
+        if (threadIdx.x >= MATCH_THREADS) return;          // a tile is the work of four wavefronts
+        const uint32_t t = blockIdx.x - r.score_blocks;
+        match_expand_tile(r.m, r.tab, (int32_t)(t % (uint32_t)r.m.tiles), (int32_t)(t / (uint32_t)r.m.tiles),
+                          (int)threadIdx.x, *reinterpret_cast<MatchLds*>(&s_k[0][0]));
+        return;
+    }
+    score_body<RG, false>(a, s_k);
+}
+
+template <int RG, bool COLSUM>
+__device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS])
 {
     constexpr int THREADS = 128 * RG;
     constexpr int WAVES = 2 * RG;
     constexpr int LPS = 16 / WAVES;                        // 1 KB direct loads per wavefront per stage
     static_assert(LPS >= 1, "unsupported row-group count");
 
-    __shared__ uint4 s_k[RING][STAGE_UNITS];               // 4 x 16 KB
     __shared__ float s_c[COLSUM ? 64 * RG : 1];            // per-row constant m + log2 Z
     __shared__ int32_t s_lim[COLSUM ? 64 * RG : 1];        // per-row last visible key
     __shared__ float s_part[COLSUM ? 2 : 1][RG][STAGE_KEYS];
@@ -161,10 +195,6 @@ score_kernel(ScoreArgs a)
             }
         }
     };
-#pragma unroll
-    for (int s = 0; s < RING - 1; ++s)
-        if (s < nstages) stage_issue(s);                   // in flight while Q and the statistics load
-
     // ---- Q fragments of this wavefront's 64 rows (registers, whole chunk) -----------
     bf16x8 qf[ROW_TILES][8];
     int32_t my_lim[ROW_TILES];                             // sweep 1: last visible key of this lane's row
@@ -184,22 +214,41 @@ score_kernel(ScoreArgs a)
         }
         my_lim[t] = lim;
     }
-
-    // ---- sweep 2 prologue: merge chunk statistics into per-row constants ------------
-    float cst[ROW_TILES][16];
+    // ---- sweep 2: merge the chunk statistics of a row into its constant (before any direct
+    // load is issued: these are ordinary loads, and waiting for them later would also wait for
+    // every direct load issued in between).  Chunks are added in index order, four loads in flight.
     if constexpr (COLSUM) {
         for (int r = tid; r < 64 * RG; r += THREADS) {
             float c = INFINITY;
             int32_t lim = -1;
             if (r < a.rows) {
-                const float* st = a.ws + ((size_t)unit * a.nchunks * a.rows_pad + r) * 2;
-                const size_t step = (size_t)a.rows_pad * 2;
-                float mstar = -INFINITY;
-                for (int ch = 0; ch < a.nchunks; ++ch) mstar = fmaxf(mstar, st[ch * step]);
+                const float2* st = reinterpret_cast<const float2*>(a.ws) + ((size_t)unit * a.nchunks * a.rows_pad + r);
+                const size_t step = (size_t)a.rows_pad;
+                const int last_ch = a.nchunks - 1;
+                float2 first[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) first[j] = st[(size_t)(j < last_ch ? j : last_ch) * step];
+                float mstar = first[0].x;
+#pragma unroll
+                for (int j = 1; j < 4; ++j) mstar = fmaxf(mstar, first[j].x);
+                for (int ch0 = 4; ch0 < a.nchunks; ch0 += 4) {
+                    float2 more[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) more[j] = st[(size_t)(ch0 + j < last_ch ? ch0 + j : last_ch) * step];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) mstar = fmaxf(mstar, more[j].x);
+                }
                 float Z = 0.0f;
-                for (int ch = 0; ch < a.nchunks; ++ch) {
-                    float mc = st[ch * step], zc = st[ch * step + 1];
-                    if (zc > 0.0f) Z += zc * fast_exp2(mc - mstar);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (j <= last_ch && first[j].y > 0.0f) Z += first[j].y * fast_exp2(first[j].x - mstar);
+                for (int ch0 = 4; ch0 < a.nchunks; ch0 += 4) {
+                    float2 more[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) more[j] = st[(size_t)(ch0 + j < last_ch ? ch0 + j : last_ch) * step];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (ch0 + j <= last_ch && more[j].y > 0.0f) Z += more[j].y * fast_exp2(more[j].x - mstar);
                 }
                 if (Z > 0.0f) c = mstar + log2f(Z);
                 const int32_t h = r / W, w = r - h * W;
@@ -208,7 +257,28 @@ score_kernel(ScoreArgs a)
             s_c[r] = c;
             s_lim[r] = lim;
         }
-        __syncthreads();
+    }
+
+    // The compiler waits for ordinary loads with a count that knows nothing of the direct loads
+    // below: a wait placed after them would also wait for every stage in flight.  Using the
+    // fragments here puts that wait before the first direct load is issued.
+    static_assert(ROW_TILES == 2, "operand list below");
+    asm volatile("" ::"v"(qf[0][0]), "v"(qf[0][1]), "v"(qf[0][2]), "v"(qf[0][3]), "v"(qf[0][4]), "v"(qf[0][5]),
+                 "v"(qf[0][6]), "v"(qf[0][7]), "v"(qf[1][0]), "v"(qf[1][1]), "v"(qf[1][2]), "v"(qf[1][3]),
+                 "v"(qf[1][4]), "v"(qf[1][5]), "v"(qf[1][6]), "v"(qf[1][7])
+                 : "memory");
+
+    // ---- first stages of K; the loop starts as soon as stage 0 is in ---------------------
+#pragma unroll
+    for (int s = 0; s < RING - 1; ++s)
+        if (s < nstages) stage_issue(s);
+    if (nstages >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * LPS));   // loads complete in issue order
+    else if (nstages == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPS));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+
+    float cst[ROW_TILES][16];
+    if constexpr (COLSUM) {
+        __syncthreads();                                   // per-row constants are in LDS
 #pragma unroll
         for (int t = 0; t < ROW_TILES; ++t)
 #pragma unroll
@@ -227,9 +297,8 @@ score_kernel(ScoreArgs a)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) kslot[ks] = krow * 16 + ((2 * ks + hf) ^ (krow & 15));
 
-    // Drain every outstanding load (first stages, Q fragments, statistics) before the loop, so
-    // that inside it the only loads in flight are the direct loads of later stages.
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    // Every wavefront has waited for its own part of stage 0 above; the only loads in flight
+    // from here on are the direct loads of later stages.
     __syncthreads();
 
     // ---- main loop, software pipelined over stages -------------------------------------
@@ -430,14 +499,24 @@ score_kernel(ScoreArgs a)
 }
 
 template <int RG>
-void launch_rg(ScoreArgs a, int64_t units, hipStream_t st)
+void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t st)
 {
     // One launch per sweep over all units.  (Splitting the units into cache-sized groups
     // so that sweep 2 re-reads its keys from the last-level cache was measured slower.)
     a.units = (int32_t)units;
     a.units_per_xcd = (int32_t)((units + 7) / 8);
     const unsigned blocks = (unsigned)(8ll * a.units_per_xcd * a.nchunks);
-    hipLaunchKernelGGL((score_kernel<RG, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
+    if (rider) {
+        RiderArgs r;
+        r.m = make_match_args(rider->tok, a.seq_len, a.batch, a.n, rider->anchor_B, rider->anchor, rider->spons,
+                              rider->vouch);
+        r.tab = *rider->tab;
+        r.score_blocks = blocks;
+        const unsigned extra = (unsigned)r.m.tiles * (unsigned)r.m.batch;
+        hipLaunchKernelGGL((score_stats_match_kernel<RG>), dim3(blocks + extra), dim3(128 * RG), 0, st, a, r);
+    } else {
+        hipLaunchKernelGGL((score_kernel<RG, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
+    }
     hipLaunchKernelGGL((score_kernel<RG, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
 }
 
@@ -506,7 +585,7 @@ int64_t score_grid_blocks(const ta_layout& lay)
 }
 
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
-                        int causal, float* A, float* ws, hipStream_t st)
+                        int causal, float* A, float* ws, const MatchRider* rider, hipStream_t st)
 {
     const ScorePlan p = make_plan(lay);
     ScoreArgs a;
@@ -534,9 +613,9 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.causal = causal;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
     switch (a.rows_pad) {
-        case 128: launch_rg<2>(a, p.units, st); break;
-        case 256: launch_rg<4>(a, p.units, st); break;
-        default: launch_rg<8>(a, p.units, st); break;
+        case 128: launch_rg<2>(a, p.units, rider, st); break;
+        case 256: launch_rg<4>(a, p.units, rider, st); break;
+        default: launch_rg<8>(a, p.units, rider, st); break;
     }
     return hipGetLastError();
 }
