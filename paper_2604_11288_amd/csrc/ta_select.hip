@@ -35,6 +35,8 @@ struct SelectArgs {
     int32_t* idx;
     int32_t* cnt;
     int32_t batch, hkv, n, K;
+    int32_t units, units_per_xcd;
+    int32_t vec_ok;
     int32_t n_sink, n_recent;
     float alpha, beta, gamma;
 };
@@ -118,11 +120,21 @@ __device__ __forceinline__ RadixState radix_pick(uint32_t (*s_hist)[256], uint32
     return *s_state;
 }
 
+// Four consecutive positions ("a quad") are one thread's unit of work: their operands arrive
+// as one 16-byte load each for A and the vouchers and one 4-byte load each for the two flag
+// arrays, their keys sit in one 16-byte LDS slot, and their retained members leave in order.
+struct Quad {
+    float A[4];
+    float v[4];
+    uint8_t sp[4];
+    uint8_t an[4];
+};
+
 template <bool CACHED>
 __global__ void __launch_bounds__(SEL_THREADS)
 select_kernel(SelectArgs a)
 {
-    extern __shared__ uint32_t s_key[];                     // [n] when CACHED
+    extern __shared__ uint32_t s_key[];                     // [roundup4(n)] when CACHED
     __shared__ uint32_t s_hist[HIST_COPIES][256];
     __shared__ uint32_t s_h[256];
     __shared__ int s_red[SEL_WAVES];
@@ -130,7 +142,11 @@ select_kernel(SelectArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int32_t unit = blockIdx.x;
+    // Same block -> unit numbering as the score step (block b runs on XCD b mod 8, which
+    // scored the units [x * units_per_xcd, (x+1) * units_per_xcd)): A is then read from the
+    // L2 that holds it.
+    const int32_t unit = (int32_t)(blockIdx.x & 7u) * a.units_per_xcd + (int32_t)(blockIdx.x >> 3);
+    if (unit >= a.units) return;
     const int32_t b = (unit / a.hkv) % a.batch;
     const int32_t n = a.n, K = a.K;
     int32_t nb = a.seq_len ? a.seq_len[b] : n;
@@ -153,34 +169,104 @@ select_kernel(SelectArgs a)
     int32_t rs = nb - a.n_recent;                            // recent window = [rs, nb)
     rs = rs < ns ? ns : rs;
     const int32_t c2 = ns + (nb - rs);
+    const int32_t nquads = (nb + 3) >> 2;
+    const bool use_A = (a.alpha != 0.0f);
+    const bool vec = a.vec_ok != 0;                          // n % 4 == 0 and aligned rows
 
     for (int i = tid; i < HIST_COPIES * 256; i += SEL_THREADS) (&s_hist[0][0])[i] = 0;
 
+    auto load_flags = [&](const uint8_t* src, int32_t q, uint8_t (&out)[4]) {
+        if (vec) {
+            const uchar4 f = *reinterpret_cast<const uchar4*>(src + 4 * q);   // 4q + 3 < n: inside the row
+            out[0] = f.x; out[1] = f.y; out[2] = f.z; out[3] = f.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[c] = (4 * q + c < nb) ? src[4 * q + c] : (uint8_t)0;
+        }
+    };
+    auto load_floats = [&](const float* src, int32_t q, float (&out)[4]) {
+        if (vec) {
+            const float4 f = *reinterpret_cast<const float4*>(src + 4 * q);
+            out[0] = f.x; out[1] = f.y; out[2] = f.z; out[3] = f.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[c] = (4 * q + c < nb) ? src[4 * q + c] : 0.0f;
+        }
+    };
+    auto load_rest = [&](int32_t q, Quad& x) {               // everything but the sponsor flags
+        load_flags(anchor, q, x.an);
+        load_floats(vouch, q, x.v);
+        if (use_A) load_floats(A, q, x.A);
+        else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x.A[c] = 0.0f;
+        }
+    };
+
+    // ---- class-1 population; the first quad's other operands are requested before the
+    // reduction so that their latency hides behind it
+    Quad first;
     int local = 0;
-    for (int32_t p = ns + tid; p < rs; p += SEL_THREADS) local += spons[p] ? 1 : 0;
+    for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
+        uint8_t sp[4];
+        load_flags(spons, q, sp);
+        if (q == tid) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) first.sp[c] = sp[c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int32_t p = 4 * q + c;
+            local += (p >= ns && p < rs && sp[c]) ? 1 : 0;
+        }
+    }
+    if (tid < nquads) load_rest(tid, first);
     const int32_t c1 = block_sum(local, s_red);
 
     const int bclass = (c2 + c1 <= K) ? 0 : 1;
     const int32_t R = bclass == 0 ? K - c2 - c1 : K - c2;    // slots for the boundary class
     const float nf = (float)nb;
-    const bool use_A = (a.alpha != 0.0f);
 
     // order-preserving key of position p if it belongs to the boundary class, else 0
-    auto make_key = [&](int32_t p) -> uint32_t {
+    auto key_of = [&](int32_t p, float Ap, uint8_t an, uint8_t sp, float v) -> uint32_t {
         if (p < ns || p >= rs) return 0u;
-        if ((spons[p] != 0) != (bclass == 1)) return 0u;
+        if ((sp != 0) != (bclass == 1)) return 0u;
         float r = __fdiv_rn((float)(p + 1), nf);
-        float t = use_A ? __fmul_rn(a.alpha, A[p]) : 0.0f;
+        float t = use_A ? __fmul_rn(a.alpha, Ap) : 0.0f;
         t = __fadd_rn(t, __fmul_rn(a.beta, r));
-        t = __fadd_rn(t, __fmul_rn(a.gamma, (float)anchor[p]));
-        t = __fadd_rn(t, vouch[p]);
+        t = __fadd_rn(t, __fmul_rn(a.gamma, (float)an));
+        t = __fadd_rn(t, v);
         uint32_t k = ordered_bits(t);
         return k == 0u ? 1u : k;
     };
-    auto key_at = [&](int32_t p) -> uint32_t { return CACHED ? s_key[p] : make_key(p); };
+    auto quad_keys = [&](int32_t q, const Quad& x, uint32_t (&k)[4]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) k[c] = key_of(4 * q + c, x.A[c], x.an[c], x.sp[c], x.v[c]);
+    };
+    auto keys_at = [&](int32_t q, uint32_t (&k)[4]) {
+        if (CACHED) {
+            const uint4 kk = *reinterpret_cast<const uint4*>(&s_key[4 * q]);
+            k[0] = kk.x; k[1] = kk.y; k[2] = kk.z; k[3] = kk.w;
+        } else {
+            Quad x;
+            load_flags(spons, q, x.sp);
+            load_rest(q, x);
+            quad_keys(q, x, k);
+        }
+    };
 
     if (CACHED) {
-        for (int32_t p = tid; p < nb; p += SEL_THREADS) s_key[p] = make_key(p);
+        for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
+            Quad x;
+            if (q == tid) x = first;
+            else {
+                load_flags(spons, q, x.sp);
+                load_rest(q, x);
+            }
+            uint32_t k[4];
+            quad_keys(q, x, k);
+            *reinterpret_cast<uint4*>(&s_key[4 * q]) = make_uint4(k[0], k[1], k[2], k[3]);
+        }
     }
     __syncthreads();
 
@@ -192,10 +278,15 @@ select_kernel(SelectArgs a)
         bool done = false;
         for (int pass = 0; pass < 4 && !done; ++pass) {
             const int shift = 24 - 8 * pass;
-            for (int32_t p = tid; p < nb; p += SEL_THREADS) {
-                uint32_t k = key_at(p);
-                bool in = k != 0u && (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8)));
-                if (in) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][(k >> shift) & 255u], 1u);
+            for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
+                uint32_t k4[4];
+                keys_at(q, k4);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t k = k4[c];
+                    bool in = k != 0u && (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8)));
+                    if (in) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][(k >> shift) & 255u], 1u);
+                }
             }
             __syncthreads();
             RadixState r = radix_pick(s_hist, s_h, &s_state, need);
@@ -213,15 +304,20 @@ select_kernel(SelectArgs a)
                 uint32_t pprefix = 0, pneed = need;
                 for (int pp = 0; pp < ppasses; ++pp) {
                     const int ps = 8 * (ppasses - 1 - pp);
-                    for (int32_t p = tid; p < nb; p += SEL_THREADS) {
-                        bool in = key_at(p) == T &&
-                                  (pp == 0 || ((uint32_t)p >> (ps + 8)) == (pprefix >> (ps + 8)));
-                        if (in) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][((uint32_t)p >> ps) & 255u], 1u);
+                    for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
+                        uint32_t k4[4];
+                        keys_at(q, k4);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const uint32_t p = (uint32_t)(4 * q + c);
+                            bool in = k4[c] == T && (pp == 0 || (p >> (ps + 8)) == (pprefix >> (ps + 8)));
+                            if (in) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][(p >> ps) & 255u], 1u);
+                        }
                     }
                     __syncthreads();
-                    RadixState q = radix_pick(s_hist, s_h, &s_state, pneed);
-                    pprefix |= q.digit << ps;
-                    pneed = q.need;
+                    RadixState qs = radix_pick(s_hist, s_h, &s_state, pneed);
+                    pprefix |= qs.digit << ps;
+                    pneed = qs.need;
                 }
                 Pt = (int32_t)pprefix;                       // positions are unique: pneed == 1 here
                 done = true;
@@ -229,28 +325,43 @@ select_kernel(SelectArgs a)
         }
     }
 
-    // ---- ascending write-out ----------------------------------------------
+    // ---- ascending write-out: one scan over per-quad counts per round of 4096 positions ----
     int32_t base = 0;
-    for (int32_t p0 = 0; p0 < nb; p0 += SEL_THREADS) {
-        const int32_t p = p0 + tid;
-        bool keep = false;
-        if (p < nb) {
-            if (p < ns || p >= rs) {
-                keep = true;
-            } else {
-                const bool sp = spons[p] != 0;
-                if (sp != (bclass == 1)) {
-                    keep = sp;                               // class 1 above the boundary class, class 0 below it
-                } else {
-                    uint32_t k = key_at(p);
-                    keep = (k > T) || (k == T && p >= Pt);
+    for (int32_t q0 = 0; q0 < nquads; q0 += SEL_THREADS) {
+        const int32_t q = q0 + tid;
+        uint32_t keep = 0;                                   // bit c: position 4q + c is retained
+        if (q < nquads) {
+            uint8_t sp[4];
+            load_flags(spons, q, sp);
+            uint32_t k4[4] = {0u, 0u, 0u, 0u};
+            bool need_keys = false;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int32_t p = 4 * q + c;
+                need_keys = need_keys || (p >= ns && p < rs && ((sp[c] != 0) == (bclass == 1)));
+            }
+            if (need_keys) keys_at(q, k4);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int32_t p = 4 * q + c;
+                bool kp = false;
+                if (p < nb) {
+                    if (p < ns || p >= rs) kp = true;
+                    else if ((sp[c] != 0) != (bclass == 1)) kp = sp[c] != 0;   // class 1 above the boundary class, class 0 below it
+                    else kp = (k4[c] > T) || (k4[c] == T && p >= Pt);
                 }
+                keep |= kp ? (1u << c) : 0u;
             }
         }
-        unsigned long long m = __ballot(keep);
-        int before = __popcll(m & ((1ull << lane) - 1ull));
+        const int mine = __popc(keep);
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            int up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
         __syncthreads();
-        if (lane == 0) s_red[wave] = __popcll(m);
+        if (lane == 63) s_red[wave] = incl;
         __syncthreads();
         int woff = 0, total = 0;
         for (int w = 0; w < SEL_WAVES; ++w) {
@@ -258,8 +369,14 @@ select_kernel(SelectArgs a)
             woff += (w < wave) ? c : 0;
             total += c;
         }
-        const int32_t slot = base + woff + before;
-        if (keep && slot < K) idx[slot] = p;
+        int32_t slot = base + woff + incl - mine;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (keep & (1u << c)) {
+                if (slot < K) idx[slot] = 4 * q + c;
+                ++slot;
+            }
+        }
         base += total;
     }
     if (tid == 0) a.cnt[unit] = base < K ? base : K;
@@ -291,7 +408,12 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
     a.alpha = prm.alpha;
     a.beta = prm.beta;
     a.gamma = prm.gamma;
-    const unsigned units = (unsigned)((int64_t)layers * batch * hkv);
+    const int64_t units = (int64_t)layers * batch * hkv;
+    a.units = (int32_t)units;
+    a.units_per_xcd = (int32_t)((units + 7) / 8);
+    a.vec_ok = (n % 4 == 0) && ((uintptr_t)anchor % 4 == 0) && ((uintptr_t)spons % 4 == 0) &&
+               ((uintptr_t)vouch % 16 == 0) && (a.A == nullptr || (uintptr_t)a.A % 16 == 0);
+    const unsigned blocks = 8u * (unsigned)a.units_per_xcd;
     if (n <= SEL_CACHE_MAX_N) {
         hipError_t attr_err = hipSuccess;
         std::call_once(g_attr_once, [&]() {
@@ -300,10 +422,10 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
                                            SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
         });
         if (attr_err != hipSuccess) return attr_err;
-        hipLaunchKernelGGL(select_kernel<true>, dim3(units), dim3(SEL_THREADS),
-                           (size_t)n * sizeof(uint32_t), st, a);
+        hipLaunchKernelGGL(select_kernel<true>, dim3(blocks), dim3(SEL_THREADS),
+                           (size_t)((n + 3) / 4 * 4) * sizeof(uint32_t), st, a);
     } else {
-        hipLaunchKernelGGL(select_kernel<false>, dim3(units), dim3(SEL_THREADS), 0, st, a);
+        hipLaunchKernelGGL(select_kernel<false>, dim3(blocks), dim3(SEL_THREADS), 0, st, a);
     }
     return hipGetLastError();
 }
