@@ -13,6 +13,8 @@ namespace ta {
 
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int COMPACT_THREADS = 256;
 constexpr int ROWS_PER_ITER = COMPACT_THREADS / 16;     // 16 rows per pass over the block
 constexpr int COMPACT_ITERS = 4;
@@ -60,13 +62,19 @@ compact_kernel(CompactArgs a)
     static_assert(COMPACT_ITERS == 4, "loads below are written out four times");
     const int64_t o0 = src(row0), o1 = src(row0 + ROWS_PER_ITER);
     const int64_t o2 = src(row0 + 2 * ROWS_PER_ITER), o3 = src(row0 + 3 * ROWS_PER_ITER);
-    const uint4 k0 = a.Kin[o0], k1 = a.Kin[o1], k2 = a.Kin[o2], k3 = a.Kin[o3];
-    const uint4 v0 = a.Vin[o0], v1 = a.Vin[o1], v2 = a.Vin[o2], v3 = a.Vin[o3];
-    auto put = [&](int32_t r, const uint4& kk, const uint4& vv) {
+    // The compacted rows are not read again by this pass: streaming stores keep them from
+    // lingering in the caches as dirty lines that the next kernel's reads would have to evict.
+    const u32x4* Kin = reinterpret_cast<const u32x4*>(a.Kin);
+    const u32x4* Vin = reinterpret_cast<const u32x4*>(a.Vin);
+    u32x4* Kout = reinterpret_cast<u32x4*>(a.Kout);
+    u32x4* Vout = reinterpret_cast<u32x4*>(a.Vout);
+    const u32x4 k0 = Kin[o0], k1 = Kin[o1], k2 = Kin[o2], k3 = Kin[o3];
+    const u32x4 v0 = Vin[o0], v1 = Vin[o1], v2 = Vin[o2], v3 = Vin[o3];
+    auto put = [&](int32_t r, const u32x4& kk, const u32x4& vv) {
         if (r < cnt) {
             const int64_t off = out_base + (int64_t)r * 16 + lane16;
-            a.Kout[off] = kk;
-            a.Vout[off] = vv;
+            __builtin_nontemporal_store(kk, &Kout[off]);
+            __builtin_nontemporal_store(vv, &Vout[off]);
         }
     };
     put(row0, k0, v0);
