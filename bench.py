@@ -33,8 +33,8 @@ def kv_bytes_per_pass(w, budget):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c2_full_model")
     ap.add_argument("--budget", type=int, default=1024, help="retention budget K of the timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -109,7 +109,8 @@ def main():
         timed("compact", lambda: ta.ta_compact(K, V, plan.idx, plan.cnt, budget, idx_shared=not scored,
                                                out=(plan.Kout, plan.Vout), stream=stream))
     torch.cuda.synchronize()
-    kern_us = {k: 1e3 * sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in ev.items()}
+    # median over the steps: a host hiccup between an event and its launch does not count as kernel time
+    kern_us = {k: 1e3 * float(np.median([a.elapsed_time(b) for a, b in v])) for k, v in ev.items()}
 
     # ---- roofline of the dominant kernel ---------------------------------------------
     units = w.layers * w.batch * w.hkv

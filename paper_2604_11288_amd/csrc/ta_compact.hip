@@ -68,8 +68,10 @@ compact_kernel(CompactArgs a)
     const u32x4* Vin = reinterpret_cast<const u32x4*>(a.Vin);
     u32x4* Kout = reinterpret_cast<u32x4*>(a.Kout);
     u32x4* Vout = reinterpret_cast<u32x4*>(a.Vout);
-    const u32x4 k0 = Kin[o0], k1 = Kin[o1], k2 = Kin[o2], k3 = Kin[o3];
-    const u32x4 v0 = Vin[o0], v1 = Vin[o1], v2 = Vin[o2], v3 = Vin[o3];
+    const u32x4 k0 = __builtin_nontemporal_load(&Kin[o0]), k1 = __builtin_nontemporal_load(&Kin[o1]);
+    const u32x4 k2 = __builtin_nontemporal_load(&Kin[o2]), k3 = __builtin_nontemporal_load(&Kin[o3]);
+    const u32x4 v0 = __builtin_nontemporal_load(&Vin[o0]), v1 = __builtin_nontemporal_load(&Vin[o1]);
+    const u32x4 v2 = __builtin_nontemporal_load(&Vin[o2]), v3 = __builtin_nontemporal_load(&Vin[o3]);
     auto put = [&](int32_t r, const u32x4& kk, const u32x4& vv) {
         if (r < cnt) {
             const int64_t off = out_base + (int64_t)r * 16 + lane16;
