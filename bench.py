@@ -20,13 +20,14 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
 
-def kv_bytes_per_pass(w, budget):
-    """Bytes of KV the pass must move: K read once for scoring + K/V rows gathered and written."""
-    units = w.layers * w.batch * w.hkv
+def kv_bytes_per_pass(w, budget, seq_len=None):
+    """Bytes of KV the pass must move: K read once for scoring + K/V rows gathered and written.
+    Ragged batches count the live positions of each sequence, not the padded length."""
+    per_seq = w.layers * w.hkv
     row = w.d * 2
-    score = units * w.n * row if w.alpha != 0.0 else 0
-    kept = min(budget, w.n)
-    compact = units * kept * row * 2 * 2          # two tensors, read + write
+    lens = [w.n] * w.batch if seq_len is None else [min(int(x), w.n) for x in seq_len]
+    score = per_seq * sum(lens) * row if w.alpha != 0.0 else 0
+    compact = per_seq * sum(min(budget, x) for x in lens) * row * 2 * 2     # two tensors, read + write
     return score, compact
 
 
@@ -110,7 +111,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    score_b, compact_b = kv_bytes_per_pass(w, budget)
+    score_b, compact_b = kv_bytes_per_pass(w, budget, td.seq_len)
     value = (score_b + compact_b) / (ms_per_step * 1e-3) / 1e9
 
     # ---- per-kernel durations: the same steps issued stage by stage, HIP events on the launch stream
@@ -146,8 +147,9 @@ def main():
     G = w.hq // w.hkv
     if scored:
         # algorithmic traffic of scoring: K once, Q once, A written once
-        alg_bytes = units * (w.n * w.d * 2 + G * w.window * w.d * 2 + w.n * 4)
-        alg_flops = units * 2 * G * w.window * w.n * w.d
+        live = sum(min(int(x), w.n) for x in td.seq_len) * w.layers * w.hkv      # key rows that exist
+        alg_bytes = live * (w.d * 2 + 4) + units * G * w.window * w.d * 2
+        alg_flops = 2 * G * w.window * live * w.d
         dom, dur = "score (stats sweep + column-sum sweep)", kern_us["score"] * 1e-6
         achieved = alg_bytes / dur / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -181,7 +183,7 @@ def main():
             p.run(stream)
         torch.cuda.synchronize()
         us = (time.perf_counter() - s0) * 1e6 / 20
-        sb, cb = kv_bytes_per_pass(w, kb)
+        sb, cb = kv_bytes_per_pass(w, kb, td.seq_len)
         sweep[str(kb)] = {"us_per_pass": round(us, 1), "GB/s": round((sb + cb) / us / 1e3, 1)}
 
     # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample --------------

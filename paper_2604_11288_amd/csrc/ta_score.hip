@@ -42,7 +42,9 @@ namespace {
 
 constexpr int STAGE_KEYS = 64;
 constexpr int STAGE_UNITS = STAGE_KEYS * 16;     // 16-byte units per stage (256 B per key)
-constexpr int RING = 4;                          // stage buffers; loads run RING-1 stages ahead
+// Stage buffers per workgroup; loads run that many minus one stages ahead.  (Eight buffers for
+// the wider workgroups, which have a compute unit to themselves, were measured: no gain.)
+constexpr int ring_of(int) { return 4; }
 
 // Direct global->LDS load of 16 bytes per lane: lane i reads 16 bytes at base + off (base
 // wave-uniform, off per lane) and its data lands at lds_base + 16*i (lds_base wave-uniform,
@@ -76,7 +78,7 @@ template <int RG, bool COLSUM>
 __global__ void __launch_bounds__(128 * RG)
 score_kernel(ScoreArgs a)
 {
-    __shared__ uint4 s_k[RING][STAGE_UNITS];               // 4 x 16 KB
+    __shared__ uint4 s_k[ring_of(RG)][STAGE_UNITS];        // 16 KB per stage
     score_body<RG, COLSUM>(a, s_k);
 }
 
@@ -84,8 +86,8 @@ template <int RG>
 __global__ void __launch_bounds__(128 * RG)
 score_stats_match_kernel(ScoreArgs a, RiderArgs r)
 {
-    __shared__ uint4 s_k[RING][STAGE_UNITS];
-    static_assert(sizeof(MatchLds) <= sizeof(uint4) * RING * STAGE_UNITS, "match tile must fit the stage ring");
+    __shared__ uint4 s_k[ring_of(RG)][STAGE_UNITS];
+    static_assert(sizeof(MatchLds) <= sizeof(uint4) * ring_of(RG) * STAGE_UNITS, "match tile must fit the stage ring");
     if (blockIdx.x >= r.score_blocks) {
         if (threadIdx.x >= MATCH_THREADS) return;          // a tile is the work of four wavefronts
         const uint32_t t = blockIdx.x - r.score_blocks;
@@ -103,6 +105,20 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     constexpr int WAVES = 2 * RG;
     constexpr int LPS = 16 / WAVES;                        // 1 KB direct loads per wavefront per stage
     static_assert(LPS >= 1, "unsupported row-group count");
+    constexpr int RING = ring_of(RG);
+    // waits until the loads of at most k later stages are outstanding (loads complete in issue order)
+    const auto wait_but = [](int k) {
+        static_assert(RING - 2 <= 6, "cases below");
+        switch (k) {
+            case 0: __builtin_amdgcn_s_waitcnt(vmcnt_imm(0)); break;
+            case 1: __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPS)); break;
+            case 2: __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * LPS)); break;
+            case 3: __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * LPS)); break;
+            case 4: __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * LPS)); break;
+            case 5: __builtin_amdgcn_s_waitcnt(vmcnt_imm(5 * LPS)); break;
+            default: __builtin_amdgcn_s_waitcnt(vmcnt_imm(6 * LPS)); break;
+        }
+    };
 
     __shared__ float s_c[COLSUM ? 64 * RG : 1];            // per-row constant m + log2 Z
     __shared__ int32_t s_lim[COLSUM ? 64 * RG : 1];        // per-row last visible key
@@ -129,7 +145,10 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     const int32_t key_lo = chunk * a.chunk_keys;
     int32_t key_hi = key_lo + a.chunk_keys;
     key_hi = key_hi > n ? n : key_hi;
-    const int nstages = (key_hi - key_lo + STAGE_KEYS - 1) / STAGE_KEYS;
+    // keys at or past the end of a ragged sequence are visible to no row: their stages are not
+    // streamed at all (their column sums are written as zeros at the end)
+    const int32_t key_end = key_hi < nb ? key_hi : nb;
+    const int nstages = key_end > key_lo ? (key_end - key_lo + STAGE_KEYS - 1) / STAGE_KEYS : 0;
     // keys <= min_lim are visible to every live row of a full window
     const int32_t min_lim = a.causal ? nb - W : nb - 1;
 
@@ -272,9 +291,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
 #pragma unroll
     for (int s = 0; s < RING - 1; ++s)
         if (s < nstages) stage_issue(s);
-    if (nstages >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * LPS));   // loads complete in issue order
-    else if (nstages == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPS));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    wait_but(nstages - 1 < RING - 2 ? nstages - 1 : RING - 2);          // stage 0 is in
 
     float cst[ROW_TILES][16];
     if constexpr (COLSUM) {
@@ -308,11 +325,9 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     const auto stage_sync = [&](int s) {
         if (s > 0) {
             // stage s has landed once at most the loads of the later stages issued so far
-            // (up to two) are outstanding; loads complete in issue order
+            // (up to RING - 2 of them) are outstanding
             const int later = nstages - 1 - s;
-            if (later >= 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * LPS));
-            else if (later == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPS));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            wait_but(later < RING - 2 ? later : RING - 2);
             __syncthreads();                               // every wavefront: stage s landed, stage s-1 consumed
         }
         if (s + RING - 1 < nstages) stage_issue(s + RING - 1);   // overwrites the buffer of stage s-1
@@ -457,6 +472,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     if constexpr (COLSUM) {
         __syncthreads();
         flush_pending();
+        for (int32_t key = key_lo + nstages * STAGE_KEYS + tid; key < key_hi; key += THREADS)
+            a.A[(size_t)unit * n + key] = 0.0f;
     }
 
     if constexpr (!COLSUM) {
