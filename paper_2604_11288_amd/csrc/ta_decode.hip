@@ -135,20 +135,43 @@ struct UnitArgs {
     float pw[TA_MAX_SPAN + 1];
 };
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
+{
+    union { uint32_t u; bf16x2 v; } x, y;
+    x.u = a;
+    y.u = b;
+    return __builtin_amdgcn_fdot2_f32_bf16(x.v, y.v, c, false);   // a.lo*b.lo + a.hi*b.hi + c in fp32
+}
+
+// dot product of eight bf16 pairs, fp32 accumulation
 __device__ __forceinline__ float dot8(const uint4& a, const uint4& b)
 {
-    float s = bf16_lo(a.x) * bf16_lo(b.x);
-    s = fmaf(bf16_hi(a.x), bf16_hi(b.x), s);
-    s = fmaf(bf16_lo(a.y), bf16_lo(b.y), s);
-    s = fmaf(bf16_hi(a.y), bf16_hi(b.y), s);
-    s = fmaf(bf16_lo(a.z), bf16_lo(b.z), s);
-    s = fmaf(bf16_hi(a.z), bf16_hi(b.z), s);
-    s = fmaf(bf16_lo(a.w), bf16_lo(b.w), s);
-    s = fmaf(bf16_hi(a.w), bf16_hi(b.w), s);
+    float s = dot2(a.x, b.x, 0.0f);
+    s = dot2(a.y, b.y, s);
+    s = dot2(a.z, b.z, s);
+    s = dot2(a.w, b.w, s);
     return s;
+}
+
+// v + (v of another lane of the same row of 16), through the data-parallel-primitive path of
+// the vector ALU (no LDS traffic).  After the four steps below every lane of a 16-lane group
+// holds the group's sum.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true);
+    return v + __int_as_float(o);
+}
+
+__device__ __forceinline__ float sum16(float d)
+{
+    d = dpp_add<0xB1>(d);      // quad_perm [1,0,3,2]: lane ^ 1
+    d = dpp_add<0x4E>(d);      // quad_perm [2,3,0,1]: lane ^ 2
+    d = dpp_add<0x141>(d);     // row_half_mirror: the other quad of each 8
+    d = dpp_add<0x140>(d);     // row_mirror: the other half of the 16
+    return d;
 }
 
 __device__ __forceinline__ uint32_t ordered_bits(float u)
@@ -172,15 +195,33 @@ __device__ __forceinline__ T block_reduce(T v, T* s_red, Op op)
     return r;
 }
 
-__global__ void __launch_bounds__(DU_THREADS)
+constexpr int DW_ROWS = 4;                                 // key rows in flight per 16-lane group
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// One wavefront per unit, no workgroup barriers: the step of a unit is a chain of short
+// phases, and what hides their latency is the number of units in flight per compute unit.
+// LDS (private to the wavefront): slot table, accumulated attention, [G][slots] logits.
+template <int GH>                                         // query heads per KV head the loops are unrolled for
+__global__ void __launch_bounds__(64)
 decode_unit_kernel(ta_decode_state st, UnitArgs a)
 {
-    extern __shared__ float s_dyn[];                       // [G][slots] scaled logits
-    __shared__ float s_redf[DU_WAVES];
-    __shared__ unsigned long long s_redu[DU_WAVES];
-    __shared__ int s_redi[DU_WAVES];
+    extern __shared__ float s_dyn[];
 
-    const int tid = threadIdx.x;
+    const int lane = threadIdx.x;
+    const int sub = lane & 15, grp = lane >> 4;            // 16 lanes per key row, 4 rows per instruction
     const int unit = blockIdx.x;
     const int slots = st.K + 1;
     const int G = st.hq / st.hkv;
@@ -193,86 +234,138 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
     float* A = st.A + (size_t)unit * slots;
     uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (size_t)unit * slots * 16;
     uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (size_t)unit * slots * 16;
+    const bool scored = a.alpha != 0.0f;
+    int32_t* s_pos = reinterpret_cast<int32_t*>(s_dyn);
+    float* s_A = s_dyn + slots;
+    float* s_w = s_dyn + 2 * slots;
 
-    // lowest-numbered free slot
-    int first_free = 0x7FFFFFFF;
-    for (int s = tid; s < slots; s += DU_THREADS)
-        if (pos[s] < 0) first_free = first_free < s ? first_free : s;
-    const int f = block_reduce<int>(first_free, s_redi, [](int x, int y) { return x < y ? x : y; });
+    // first key rows and the queries are requested before anything else.  A lane's rows of one
+    // batch are 1 KB apart, so they share one address register; only the batch that runs past
+    // the last slot clamps its rows.
+    uint4 qv[GH];
+    uint4 krow[DW_ROWS];
+    const uint4* lane_rows = Kc + grp * 16 + sub;          // row grp, this lane's 16 bytes
+    const auto load_rows = [&](int s0, uint4 (&dst)[DW_ROWS]) {
+        if (s0 + 4 * DW_ROWS <= slots) {
+#pragma unroll
+            for (int r = 0; r < DW_ROWS; ++r) dst[r] = lane_rows[(s0 + 4 * r) * 16];
+        } else {
+#pragma unroll
+            for (int r = 0; r < DW_ROWS; ++r) {
+                const int s = s0 + 4 * r + grp;
+                dst[r] = Kc[(s < slots ? s : slots - 1) * 16 + sub];
+            }
+        }
+    };
+    if (scored) {
+#pragma unroll
+        for (int h = 0; h < GH; ++h)
+            qv[h] = h < G ? a.q_new[((size_t)(l * st.batch + b) * st.hq + g * G + h) * 16 + sub] : make_uint4(0, 0, 0, 0);
+        load_rows(0, krow);
+    }
+    int first_free = 0x7FFFFFFF;                           // lowest-numbered free slot
+    for (int s = lane; s < slots; s += 64) {
+        const int32_t p = pos[s];
+        s_pos[s] = p;
+        s_A[s] = A[s];
+        if (p < 0) first_free = first_free < s ? first_free : s;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const int other = __shfl_xor(first_free, o);
+        first_free = other < first_free ? other : first_free;
+    }
+    const int f = first_free;
     if (f >= slots || p_new < 0) {                         // no room (or empty sequence): nothing to do
-        if (tid == 0 && a.evicted) a.evicted[unit] = -1;
+        if (lane == 0 && a.evicted) a.evicted[unit] = -1;
         return;
     }
     const uint4* kn = a.k_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
     const uint4* vn = a.v_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
-    if (tid < 16) Kc[f * 16 + tid] = kn[tid];
-    else if (tid < 32) Vc[f * 16 + tid - 16] = vn[tid - 16];
+    const uint4 kn_sub = kn[sub];
+    if (lane < 16) Kc[f * 16 + lane] = kn_sub;
+    else if (lane < 32) Vc[f * 16 + lane - 16] = vn[lane - 16];
+    __builtin_amdgcn_wave_barrier();                       // the slot table is in LDS for every lane
 
     // ---- attention of the group's decode queries over the occupied slots ----------
-    const bool scored = a.alpha != 0.0f;
     if (scored) {
-        const int sub = tid & 15, rowgrp = tid >> 4;       // 16 lanes per key row
-        uint4 qv[MAX_GROUP];
+        // logits of one key row for all heads: every lane of the group ends up with all head
+        // sums, lane h keeps head h's and the group stores its G logits with one instruction
+        const auto row_logits = [&](const uint4& kv, int s, bool occ) {
+            float mine = 0.0f;
 #pragma unroll
-        for (int h = 0; h < MAX_GROUP; ++h)
-            if (h < G) qv[h] = a.q_new[((size_t)(l * st.batch + b) * st.hq + g * G + h) * 16 + sub];
-        for (int s0 = 0; s0 < slots; s0 += DU_THREADS / 16) {
-            const int s = s0 + rowgrp;
-            const bool valid = s < slots;
-            const bool occ = valid && (s == f || pos[s] >= 0);
-            uint4 kv = make_uint4(0, 0, 0, 0);
-            if (occ) kv = (s == f) ? kn[sub] : Kc[s * 16 + sub];
+            for (int h = 0; h < GH; ++h) {
+                const float d = sum16(dot8(qv[h], kv));
+                mine = sub == h ? d : mine;
+            }
+            if (sub < G) s_w[sub * slots + s] = occ ? mine * a.scale_log2 : -INFINITY;
+        };
+        for (int s0 = 0; s0 < slots; s0 += 4 * DW_ROWS) {
+            uint4 knext[DW_ROWS];
+            const bool more = s0 + 4 * DW_ROWS < slots;
+            if (more) load_rows(s0 + 4 * DW_ROWS, knext);  // next rows in flight while these are reduced
 #pragma unroll
-            for (int h = 0; h < MAX_GROUP; ++h) {
-                if (h < G) {
-                    float d = dot8(qv[h], kv);
-                    d += __shfl_xor(d, 8);
-                    d += __shfl_xor(d, 4);
-                    d += __shfl_xor(d, 2);
-                    d += __shfl_xor(d, 1);
-                    if (valid && sub == 0) s_dyn[h * slots + s] = occ ? d * a.scale_log2 : -INFINITY;
-                }
+            for (int r = 0; r < DW_ROWS; ++r) {
+                const int s = s0 + 4 * r + grp;
+                if (s < slots) row_logits(krow[r], s, s_pos[s] >= 0);
+            }
+            if (more) {
+#pragma unroll
+                for (int r = 0; r < DW_ROWS; ++r) krow[r] = knext[r];
             }
         }
-        __syncthreads();
-        // per head: softmax over the slots, weights accumulated per slot in head order
-        float add[(TA_MAX_DECODE_K + 1 + DU_THREADS - 1) / DU_THREADS];
+        // the row that has just been written is not read back: its logits come from the
+        // registers (whatever the loop stored for that slot is replaced here)
+        __builtin_amdgcn_wave_barrier();
+        if (grp == 0) row_logits(kn_sub, f, true);
+        __builtin_amdgcn_wave_barrier();
+        // softmax statistics of every head, then the weights are added per slot in head order
+        // (H2O-style cumulative attention)
+        float m_h[GH], inv_h[GH];
 #pragma unroll
-        for (int j = 0; j < (int)(sizeof(add) / sizeof(float)); ++j) add[j] = 0.0f;
-        for (int h = 0; h < G; ++h) {
-            const float* sh = s_dyn + h * slots;
-            float m = -INFINITY;
-            for (int s = tid; s < slots; s += DU_THREADS) m = fmaxf(m, sh[s]);
-            m = block_reduce<float>(m, s_redf, [](float x, float y) { return fmaxf(x, y); });
-            float z = 0.0f;
-            for (int s = tid; s < slots; s += DU_THREADS) z += __builtin_amdgcn_exp2f(sh[s] - m);
-            z = block_reduce<float>(z, s_redf, [](float x, float y) { return x + y; });
-            const float inv = 1.0f / z;
-#pragma unroll
-            for (int j = 0; j < (int)(sizeof(add) / sizeof(float)); ++j) {
-                const int s = tid + j * DU_THREADS;
-                if (s < slots) add[j] += __builtin_amdgcn_exp2f(sh[s] - m) * inv;
+        for (int h = 0; h < GH; ++h) {
+            m_h[h] = 0.0f;
+            inv_h[h] = 0.0f;
+            if (h < G) {
+                const float* sh = s_w + h * slots;
+                float m = -INFINITY;
+                for (int s = lane; s < slots; s += 64) m = fmaxf(m, sh[s]);
+                m = wave_max(m);
+                float z = 0.0f;
+                for (int s = lane; s < slots; s += 64) z += __builtin_amdgcn_exp2f(sh[s] - m);
+                z = wave_sum(z);
+                m_h[h] = m;
+                inv_h[h] = 1.0f / z;
             }
         }
+        for (int s = lane; s < slots; s += 64) {
+            if (s == f || s_pos[s] >= 0) {
+                float add = 0.0f;
 #pragma unroll
-        for (int j = 0; j < (int)(sizeof(add) / sizeof(float)); ++j) {
-            const int s = tid + j * DU_THREADS;
-            if (s < slots && (s == f || pos[s] >= 0)) A[s] = (s == f ? 0.0f : A[s]) + add[j];
+                for (int h = 0; h < GH; ++h)
+                    if (h < G) add += __builtin_amdgcn_exp2f(s_w[h * slots + s] - m_h[h]) * inv_h[h];
+                const float v = (s == f ? 0.0f : s_A[s]) + add;
+                s_A[s] = v;
+                A[s] = v;
+            }
         }
     } else {
-        if (tid == 0) A[f] = 0.0f;
+        if (lane == 0) {
+            s_A[f] = 0.0f;
+            A[f] = 0.0f;
+        }
     }
-    __syncthreads();                                       // A and the new row are in place for this block
 
     // ---- rank the occupied slots; evict the last one if the cache is over budget -----
+    // (every lane ranks the slots it wrote s_A for)
     const size_t srow = (size_t)b * st.cap;
     const uint8_t* anchor = st.anchor + srow;
     const float* budget = st.budget + srow;
     const float lenf = (float)len_new;
     unsigned long long worst = ~0ull;
     int nfree = 0;
-    for (int s = tid; s < slots; s += DU_THREADS) {
-        const int32_t p = (s == f) ? p_new : pos[s];
+    for (int s = lane; s < slots; s += 64) {
+        const int32_t p = (s == f) ? p_new : s_pos[s];
         if (p < 0) { ++nfree; continue; }
         float v = 0.0f;
         bool sp = false;
@@ -284,7 +377,7 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
             }
         }
         const float r = __fdiv_rn((float)(p + 1), lenf);
-        float t = scored ? __fmul_rn(a.alpha, A[s]) : 0.0f;
+        float t = scored ? __fmul_rn(a.alpha, s_A[s]) : 0.0f;
         t = __fadd_rn(t, __fmul_rn(a.beta, r));
         t = __fadd_rn(t, __fmul_rn(a.gamma, (float)anchor[p]));
         t = __fadd_rn(t, v);
@@ -294,15 +387,18 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
                                        ((unsigned long long)ordered_bits(t) << 30) | (unsigned long long)(uint32_t)p;
         worst = key < worst ? key : worst;
     }
-    const int free_total = block_reduce<int>(nfree, s_redi, [](int x, int y) { return x + y; });
-    const unsigned long long wmin =
-        block_reduce<unsigned long long>(worst, s_redu, [](unsigned long long x, unsigned long long y) { return x < y ? x : y; });
-    const int32_t evict_pos = free_total > 0 ? -1 : (int32_t)(wmin & 0x3FFFFFFFull);
-    for (int s = tid; s < slots; s += DU_THREADS) {
-        const int32_t p = (s == f) ? p_new : pos[s];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        nfree += __shfl_xor(nfree, o);
+        const unsigned long long other = __shfl_xor(worst, o);
+        worst = other < worst ? other : worst;
+    }
+    const int32_t evict_pos = nfree > 0 ? -1 : (int32_t)(worst & 0x3FFFFFFFull);
+    for (int s = lane; s < slots; s += 64) {
+        const int32_t p = (s == f) ? p_new : s_pos[s];
         if (s == f || (p >= 0 && p == evict_pos)) pos[s] = (p == evict_pos) ? -1 : p;
     }
-    if (tid == 0 && a.evicted) a.evicted[unit] = evict_pos;
+    if (lane == 0 && a.evicted) a.evicted[unit] = evict_pos;
 }
 
 }  // namespace
@@ -348,8 +444,9 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     for (int k = 0; k <= TA_MAX_SPAN; ++k) a.pw[k] = tab.pw[k];
     const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
     const int G = st.hq / st.hkv;
-    const size_t lds = prm.alpha != 0.0f ? (size_t)G * (st.K + 1) * sizeof(float) : 0;
-    hipLaunchKernelGGL(decode_unit_kernel, dim3(units), dim3(DU_THREADS), lds, s, st, a);
+    const size_t lds = (size_t)((prm.alpha != 0.0f ? G : 0) + 2) * (st.K + 1) * sizeof(float);
+    if (G <= 4) hipLaunchKernelGGL(decode_unit_kernel<4>, dim3(units), dim3(64), lds, s, st, a);
+    else hipLaunchKernelGGL(decode_unit_kernel<MAX_GROUP>, dim3(units), dim3(64), lds, s, st, a);
 
     dim3 g3((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
     hipLaunchKernelGGL(decode_decay_kernel, g3, dim3(256), 0, s, st, prm.budget_decay);
