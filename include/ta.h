@@ -203,6 +203,9 @@ int32_t ta_evict(const int32_t *tok, const int32_t *seq_len,
  *                 len    int32 [batch]        current length
  *                 anchor uint8 [batch][cap]   anchor flags
  *                 budget float [batch][cap]   CURRENT budget B_i of each anchor, 0 elsewhere
+ *                 vouch  float [batch][cap]   scratch of a step: voucher of each position from
+ *                 spons  uint8 [batch][cap]   the current budgets, and its sponsor flag (Eq. 2);
+ *                                             rewritten by every ta_decode_step, never read back
  *   per unit      Kc, Vc bf16  [layers][batch][hkv][K+1][d]  cache slots
  *                 pos    int32 [layers][batch][hkv][K+1]     absolute position of a slot, -1 = free
  *                 A      float [layers][batch][hkv][K+1]     cumulative attention of a slot
@@ -218,6 +221,8 @@ typedef struct ta_decode_state {
     int32_t *len;
     uint8_t *anchor;
     float *budget;
+    float *vouch;
+    uint8_t *spons;
     void *Kc, *Vc;
     int32_t *pos;
     float *A;

@@ -48,7 +48,8 @@ class CDecodeState(ctypes.Structure):
     _fields_ = [("layers", ctypes.c_int32), ("batch", ctypes.c_int32), ("hq", ctypes.c_int32),
                 ("hkv", ctypes.c_int32), ("d", ctypes.c_int32), ("K", ctypes.c_int32), ("cap", ctypes.c_int32),
                 ("tok", ctypes.c_void_p), ("len", ctypes.c_void_p), ("anchor", ctypes.c_void_p),
-                ("budget", ctypes.c_void_p), ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
+                ("budget", ctypes.c_void_p), ("vouch", ctypes.c_void_p), ("spons", ctypes.c_void_p),
+                ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
                 ("pos", ctypes.c_void_p), ("A", ctypes.c_void_p)]
 
 
@@ -293,6 +294,8 @@ class DecodeState:
         self.len = torch.zeros((batch,), dtype=i32, device=dev)
         self.anchor = torch.zeros((batch, cap), dtype=torch.uint8, device=dev)
         self.budget = torch.zeros((batch, cap), dtype=torch.float32, device=dev)
+        self.vouch = torch.zeros((batch, cap), dtype=torch.float32, device=dev)
+        self.spons = torch.zeros((batch, cap), dtype=torch.uint8, device=dev)
         self.Kc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
         self.Vc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
         self.pos = torch.full((layers, batch, hkv, K + 1), -1, dtype=i32, device=dev)
@@ -301,7 +304,8 @@ class DecodeState:
     def c(self) -> CDecodeState:
         return CDecodeState(self.layers, self.batch, self.hq, self.hkv, self.d, self.K, self.cap,
                             self.tok.data_ptr(), self.len.data_ptr(), self.anchor.data_ptr(),
-                            self.budget.data_ptr(), self.Kc.data_ptr(), self.Vc.data_ptr(),
+                            self.budget.data_ptr(), self.vouch.data_ptr(), self.spons.data_ptr(),
+                            self.Kc.data_ptr(), self.Vc.data_ptr(),
                             self.pos.data_ptr(), self.A.data_ptr())
 
 

@@ -145,7 +145,8 @@ int32_t check_compact(const void* Kin, const void* Vin, const int32_t* idx, cons
 int32_t check_decode_state(const ta_decode_state* st)
 {
     if (!st) return TA_ERR_NULL;
-    if (!st->tok || !st->len || !st->anchor || !st->budget || !st->Kc || !st->Vc || !st->pos || !st->A)
+    if (!st->tok || !st->len || !st->anchor || !st->budget || !st->vouch || !st->spons || !st->Kc || !st->Vc ||
+        !st->pos || !st->A)
         return TA_ERR_NULL;
     if (st->layers < 1 || st->batch < 1 || st->hkv < 1 || st->hq < 1 || st->hq % st->hkv != 0) return TA_ERR_SHAPE;
     if (st->hq / st->hkv > 8) return TA_ERR_SHAPE;

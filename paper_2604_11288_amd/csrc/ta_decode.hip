@@ -123,16 +123,43 @@ __global__ void decode_decay_kernel(ta_decode_state st, float decay)
     }
 }
 
+// Voucher and sponsor flag of every position from the current budgets (Eq. 2): the same for all
+// units of a sequence, so it is computed once per sequence and step, not once per cached row.
+struct VouchArgs {
+    int32_t L;
+    float pw[TA_MAX_SPAN + 1];
+};
+
+__global__ void decode_vouch_kernel(ta_decode_state st, VouchArgs a)
+{
+    const int b = blockIdx.y;
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= st.len[b] || p >= st.cap) return;
+    const size_t row = (size_t)b * st.cap;
+    const uint8_t* anchor = st.anchor + row;
+    const float* budget = st.budget + row;
+    float v = 0.0f;
+    uint8_t sp = 0;
+    for (int k = 1; k <= a.L; ++k) {
+        const int32_t i = p - k;
+        if (i >= 0 && anchor[i]) {
+            v = __fadd_rn(v, __fmul_rn(budget[i], a.pw[k]));
+            sp = 1;
+        }
+    }
+    st.vouch[row + p] = v;
+    st.spons[row + p] = sp;
+}
+
 // ---- step, unit part ----------------------------------------------------------------
 struct UnitArgs {
     const uint4* q_new;
     const uint4* k_new;
     const uint4* v_new;
     int32_t* evicted;
-    int32_t n_sink, n_recent, L;
+    int32_t n_sink, n_recent;
     float alpha, beta, gamma;
     float scale_log2;
-    float pw[TA_MAX_SPAN + 1];
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -165,6 +192,14 @@ __device__ __forceinline__ float dpp_add(float v)
     return v + __int_as_float(o);
 }
 
+// keep + (send of the lane selected by CTRL)
+template <int CTRL>
+__device__ __forceinline__ float dpp_add_other(float keep, float send)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(send), CTRL, 0xF, 0xF, true);
+    return keep + __int_as_float(o);
+}
+
 __device__ __forceinline__ float sum16(float d)
 {
     d = dpp_add<0xB1>(d);      // quad_perm [1,0,3,2]: lane ^ 1
@@ -195,7 +230,7 @@ __device__ __forceinline__ T block_reduce(T v, T* s_red, Op op)
     return r;
 }
 
-constexpr int DW_ROWS = 4;                                 // key rows in flight per 16-lane group
+constexpr int DW_ROWS = 6;                                 // key rows in flight per 16-lane group
 
 __device__ __forceinline__ float wave_max(float v)
 {
@@ -264,11 +299,24 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
         load_rows(0, krow);
     }
     int first_free = 0x7FFFFFFF;                           // lowest-numbered free slot
-    for (int s = lane; s < slots; s += 64) {
-        const int32_t p = pos[s];
-        s_pos[s] = p;
-        s_A[s] = A[s];
-        if (p < 0) first_free = first_free < s ? first_free : s;
+    for (int s0 = lane; s0 < slots; s0 += 4 * 64) {        // four slots per lane and round trip
+        int32_t p4[4];
+        float a4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int s = s0 + 64 * j;
+            p4[j] = s < slots ? pos[s] : 0;
+            a4[j] = s < slots ? A[s] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int s = s0 + 64 * j;
+            if (s < slots) {
+                s_pos[s] = p4[j];
+                s_A[s] = a4[j];
+                if (p4[j] < 0) first_free = first_free < s ? first_free : s;
+            }
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -289,16 +337,37 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
 
     // ---- attention of the group's decode queries over the occupied slots ----------
     if (scored) {
-        // logits of one key row for all heads: every lane of the group ends up with all head
-        // sums, lane h keeps head h's and the group stores its G logits with one instruction
+        // Logits of one key row for all heads.  The 16 partial dot products of a head are summed
+        // across the group's lanes; with four heads the first two exchange steps also halve the
+        // number of heads a lane carries (lane keeps heads {0,1} or {2,3}, then one of them), so a
+        // row costs 5 cross-lane adds instead of 16.  Lanes 0..3 of the group end up with heads
+        // 0, 2, 1, 3 and store them.
+        const bool odd1 = (sub & 1) != 0, odd2 = (sub & 2) != 0;
+        const int my_head = GH == 4 ? 2 * (sub & 1) + ((sub >> 1) & 1) : sub;
         const auto row_logits = [&](const uint4& kv, int s, bool occ) {
-            float mine = 0.0f;
+            float mine;
+            if constexpr (GH == 4) {
+                const float d0 = dot8(qv[0], kv), d1 = dot8(qv[1], kv), d2 = dot8(qv[2], kv), d3 = dot8(qv[3], kv);
+                // lane ^ 1: even lanes keep heads 0 and 1, odd lanes heads 2 and 3
+                const float ka = odd1 ? d2 : d0, sa = odd1 ? d0 : d2;
+                const float kb = odd1 ? d3 : d1, sb = odd1 ? d1 : d3;
+                const float a2 = dpp_add_other<0xB1>(ka, sa);
+                const float b2 = dpp_add_other<0xB1>(kb, sb);
+                // lane ^ 2: keep one of the two
+                const float kc = odd2 ? b2 : a2, scn = odd2 ? a2 : b2;
+                float v = dpp_add_other<0x4E>(kc, scn);
+                v = dpp_add<0x124>(v);     // row_ror:4 and row_ror:8 keep the low two lane bits,
+                v = dpp_add<0x128>(v);     // i.e. the head: sum over lanes i, i+4, i+8, i+12
+                mine = v;
+            } else {
+                mine = 0.0f;
 #pragma unroll
-            for (int h = 0; h < GH; ++h) {
-                const float d = sum16(dot8(qv[h], kv));
-                mine = sub == h ? d : mine;
+                for (int h = 0; h < GH; ++h) {
+                    const float d = sum16(dot8(qv[h], kv));
+                    mine = sub == h ? d : mine;
+                }
             }
-            if (sub < G) s_w[sub * slots + s] = occ ? mine * a.scale_log2 : -INFINITY;
+            if (sub < GH && my_head < G) s_w[my_head * slots + s] = occ ? mine * a.scale_log2 : -INFINITY;
         };
         for (int s0 = 0; s0 < slots; s0 += 4 * DW_ROWS) {
             uint4 knext[DW_ROWS];
@@ -360,32 +429,41 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
     // (every lane ranks the slots it wrote s_A for)
     const size_t srow = (size_t)b * st.cap;
     const uint8_t* anchor = st.anchor + srow;
-    const float* budget = st.budget + srow;
+    const uint8_t* spons = st.spons + srow;
+    const float* vouch = st.vouch + srow;
     const float lenf = (float)len_new;
     unsigned long long worst = ~0ull;
     int nfree = 0;
-    for (int s = lane; s < slots; s += 64) {
-        const int32_t p = (s == f) ? p_new : s_pos[s];
-        if (p < 0) { ++nfree; continue; }
-        float v = 0.0f;
-        bool sp = false;
-        for (int k = 1; k <= a.L; ++k) {
-            const int32_t i = p - k;
-            if (i >= 0 && anchor[i]) {
-                v = __fadd_rn(v, __fmul_rn(budget[i], a.pw[k]));
-                sp = true;
-            }
+    for (int s0 = lane; s0 < slots; s0 += 4 * 64) {        // four slots per lane and round trip
+        int32_t p4[4];
+        float v4[4];
+        uint8_t sp4[4], an4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int s = s0 + 64 * j;
+            p4[j] = s < slots ? ((s == f) ? p_new : s_pos[s]) : -2;
+            const int32_t pc = p4[j] < 0 ? 0 : p4[j];
+            v4[j] = vouch[pc];
+            sp4[j] = spons[pc];
+            an4[j] = anchor[pc];
         }
-        const float r = __fdiv_rn((float)(p + 1), lenf);
-        float t = scored ? __fmul_rn(a.alpha, s_A[s]) : 0.0f;
-        t = __fadd_rn(t, __fmul_rn(a.beta, r));
-        t = __fadd_rn(t, __fmul_rn(a.gamma, (float)anchor[p]));
-        t = __fadd_rn(t, v);
-        const unsigned cls = (p < a.n_sink || p >= len_new - a.n_recent) ? 2u : (sp ? 1u : 0u);
-        // (class, u, position) packed so that the smallest integer ranks last
-        const unsigned long long key = ((unsigned long long)cls << 62) |
-                                       ((unsigned long long)ordered_bits(t) << 30) | (unsigned long long)(uint32_t)p;
-        worst = key < worst ? key : worst;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int s = s0 + 64 * j;
+            const int32_t p = p4[j];
+            if (p == -2) continue;                         // past the last slot
+            if (p < 0) { ++nfree; continue; }
+            const float r = __fdiv_rn((float)(p + 1), lenf);
+            float t = scored ? __fmul_rn(a.alpha, s_A[s]) : 0.0f;
+            t = __fadd_rn(t, __fmul_rn(a.beta, r));
+            t = __fadd_rn(t, __fmul_rn(a.gamma, (float)an4[j]));
+            t = __fadd_rn(t, v4[j]);
+            const unsigned cls = (p < a.n_sink || p >= len_new - a.n_recent) ? 2u : (sp4[j] ? 1u : 0u);
+            // (class, u, position) packed so that the smallest integer ranks last
+            const unsigned long long key = ((unsigned long long)cls << 62) |
+                                           ((unsigned long long)ordered_bits(t) << 30) | (unsigned long long)(uint32_t)p;
+            worst = key < worst ? key : worst;
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -429,6 +507,12 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     dt.B = tab.B;
     hipLaunchKernelGGL(decode_seq_kernel, dim3((unsigned)st.batch), dim3(64), 0, s, st, new_tok, dt);
 
+    VouchArgs va;
+    va.L = prm.span_L;
+    for (int k = 0; k <= TA_MAX_SPAN; ++k) va.pw[k] = tab.pw[k];
+    dim3 gv((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
+    hipLaunchKernelGGL(decode_vouch_kernel, gv, dim3(256), 0, s, st, va);
+
     UnitArgs a;
     a.q_new = (const uint4*)q_new;
     a.k_new = (const uint4*)k_new;
@@ -436,12 +520,10 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     a.evicted = evicted;
     a.n_sink = prm.n_sink;
     a.n_recent = prm.n_recent;
-    a.L = prm.span_L;
     a.alpha = prm.alpha;
     a.beta = prm.beta;
     a.gamma = prm.gamma;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)st.d));
-    for (int k = 0; k <= TA_MAX_SPAN; ++k) a.pw[k] = tab.pw[k];
     const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
     const int G = st.hq / st.hkv;
     const size_t lds = (size_t)((prm.alpha != 0.0f ? G : 0) + 2) * (st.K + 1) * sizeof(float);

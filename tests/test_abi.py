@@ -160,7 +160,7 @@ def test_evict_validates_every_stage_before_launching(L):
 
 
 def _decode_state(**kw):
-    st = tb.CDecodeState(2, 3, 32, 8, 128, 256, 5000, *([0x7f0000001000] * 8))
+    st = tb.CDecodeState(2, 3, 32, 8, 128, 256, 5000, *([0x7f0000001000] * 10))
     for k, v in kw.items():
         setattr(st, k, v)
     return st
