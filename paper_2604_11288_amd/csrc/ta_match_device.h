@@ -5,14 +5,17 @@
 //
 // MATCH_THREADS threads own a tile of MATCH_TILE consecutive positions of one sequence.
 //   phase 0  build a 32768-bit filter of the table's last-token IDs in LDS
-//   phase 1  stage the tile's tokens plus a left halo of L + 3 tokens in LDS
-//   phase 2  anchor flag for every position of [tile - L, tile end): one LDS
-//            filter probe per position, full n-gram compare only on a filter hit
-//            (the table itself sits in the kernel-argument segment, read through
-//            the scalar cache because the entry index is wave-uniform)
-//   phase 3  voucher = fixed-order fp32 sum over the L preceding positions,
-//            sponsor flag = any anchor among them; 4 positions per lane so that
-//            flags leave as 4-byte and vouchers as 16-byte stores
+//   phase 1  stage the tile's tokens plus a left halo of 64 + 3 tokens in LDS
+//   phase 2  anchor flag for every position of [tile - 64, tile end): one LDS
+//            filter probe per position; a position that passes is compared with
+//            the whole table at once, lane e holding entry e in registers; the
+//            flags go to LDS as one bit per position
+//   phase 3  a lane takes 4 consecutive positions: the 68 flag bits before and at
+//            them are one LDS read; bit-reversed, the L bits before a position
+//            list its sponsoring anchors by distance, so the voucher is a
+//            fixed-order fp32 sum over the SET bits only (anchors are rare) and
+//            the sponsor flag is "any bit set"; flags leave as 4-byte and
+//            vouchers as 16-byte stores
 #pragma once
 #include "ta_internal.h"
 
@@ -20,7 +23,8 @@ namespace ta {
 
 constexpr int MATCH_THREADS = 256;
 constexpr int MATCH_TILE = 1024;                 // positions per workgroup (4 per lane)
-constexpr int MATCH_HALO_MAX = TA_MAX_SPAN + 4;  // roundup4(L + 3) <= 68
+constexpr int MATCH_MARGIN = 64;                 // flags are kept for this many positions before the tile (>= TA_MAX_SPAN)
+constexpr int MATCH_HALO = MATCH_MARGIN + 4;     // tokens before the tile: margin + (TA_MAX_GRAM - 1), rounded up to 4
 constexpr int FILTER_BITS = 32768;
 
 struct MatchArgs {
@@ -39,9 +43,11 @@ struct MatchArgs {
 // LDS a tile needs; the caller provides it (16-byte aligned).
 struct MatchLds {
     uint32_t filter[FILTER_BITS / 32];
-    int32_t tok[MATCH_TILE + MATCH_HALO_MAX];
-    uint8_t anc[MATCH_TILE + TA_MAX_SPAN];
+    int32_t tok[MATCH_TILE + MATCH_HALO];
+    uint32_t bits[(MATCH_TILE + MATCH_MARGIN) / 32 + 2];   // bit j: anchor at position tile0 - MATCH_MARGIN + j
 };
+
+static_assert(MATCH_MARGIN >= TA_MAX_SPAN && MATCH_MARGIN % 64 == 0, "flag margin");
 
 MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
                           const float* anchor_B, uint8_t* anchor, uint8_t* spons, float* vouch);
@@ -55,14 +61,27 @@ __device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const Matc
 {
     uint32_t* s_filter = lds.filter;
     int32_t* s_tok = lds.tok;
-    uint8_t* s_anc = lds.anc;
+    uint32_t* s_bits = lds.bits;
+    const int lane = tid & 63, wave = tid >> 6;
     const int32_t n = a.n;
     int32_t nb = a.seq_len ? a.seq_len[b] : n;
     nb = nb < 0 ? 0 : (nb > n ? n : nb);
     const int32_t tile0 = tile * MATCH_TILE;
     const int32_t L = tab.L;
-    const int32_t halo = (L + 3 + 3) & ~3;
     const size_t row = (size_t)b * (size_t)n;
+
+    // phase 1 first: the tokens of [tile0 - HALO, tile0 + TILE) are requested before the filter is
+    // built, so that their latency overlaps it; positions outside the sequence hold a value no
+    // table ID can equal (IDs are validated >= 0)
+    const int32_t base = tile0 - MATCH_HALO;
+    constexpr int TOK_ROUNDS = (MATCH_TILE + MATCH_HALO + MATCH_THREADS - 1) / MATCH_THREADS;
+    int32_t tk[TOK_ROUNDS];
+#pragma unroll
+    for (int r = 0; r < TOK_ROUNDS; ++r) {
+        const int i = tid + r * MATCH_THREADS;
+        const int32_t p = base + i;
+        tk[r] = (i < MATCH_TILE + MATCH_HALO && p >= 0 && p < nb) ? a.tok[row + (size_t)p] : INT32_MIN;
+    }
 
     // phase 0: last-token filter
     for (int i = tid; i < FILTER_BITS / 32; i += MATCH_THREADS) s_filter[i] = 0u;
@@ -71,44 +90,58 @@ __device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const Matc
         uint32_t h = filter_slot(tab.rid[tid][0]);
         atomicOr(&s_filter[h >> 5], 1u << (h & 31));
     }
-
-    // phase 1: tokens of [tile0 - halo, tile0 + TILE); positions outside the
-    // sequence hold a value no table ID can equal (IDs are validated >= 0)
-    const int32_t base = tile0 - halo;
-    for (int i = tid; i < MATCH_TILE + halo; i += MATCH_THREADS) {
-        int32_t p = base + i;
-        s_tok[i] = (p >= 0 && p < nb) ? a.tok[row + (size_t)p] : INT32_MIN;
+#pragma unroll
+    for (int r = 0; r < TOK_ROUNDS; ++r) {
+        const int i = tid + r * MATCH_THREADS;
+        if (i < MATCH_TILE + MATCH_HALO) s_tok[i] = tk[r];
     }
     __syncthreads();
 
-    // phase 2: anchor flags of [tile0 - L, tile0 + TILE)
-    for (int j = tid; j < MATCH_TILE + L; j += MATCH_THREADS) {
-        int32_t q = tile0 - L + j;
-        uint8_t hit = 0;
+    // phase 2: anchor flags of [tile0 - MARGIN, tile0 + TILE), 64 positions per wavefront and
+    // round.  Lane e keeps table entry e in registers (the table has at most 64 entries); a
+    // position that passes the filter is compared with all entries at once, one entry per lane.
+    int32_t e0 = -1, e1 = -1, e2 = -1, e3 = -1, elen = 0;
+    if (lane < tab.E) {
+        e0 = tab.rid[lane][0];
+        e1 = tab.rid[lane][1];
+        e2 = tab.rid[lane][2];
+        e3 = tab.rid[lane][3];
+        elen = tab.len[lane];
+    }
+    for (int j0 = 64 * wave; j0 < MATCH_TILE + MATCH_MARGIN; j0 += MATCH_THREADS) {
+        const int32_t q = tile0 - MATCH_MARGIN + j0 + lane;
+        bool cand = false;
         if (q >= 0 && q < nb) {
-            const int32_t* t = &s_tok[q - base];          // t[0] is the token at q, t[-k] at q-k
-            int32_t t0 = t[0];
-            uint32_t h = filter_slot(t0);
-            if ((s_filter[h >> 5] >> (h & 31)) & 1u) {
-                int32_t t1 = t[-1], t2 = t[-2], t3 = t[-3];   // q-3 >= base by construction
-                for (int e = 0; e < tab.E; ++e) {
-                    if (t0 != tab.rid[e][0]) continue;
-                    int32_t len = tab.len[e];
-                    bool ok = true;
-                    if (len > 1) ok = ok && (t1 == tab.rid[e][1]);
-                    if (len > 2) ok = ok && (t2 == tab.rid[e][2]);
-                    if (len > 3) ok = ok && (t3 == tab.rid[e][3]);
-                    if (ok) hit = 1;
-                }
-            }
+            const uint32_t h = filter_slot(s_tok[q - base]);
+            cand = ((s_filter[h >> 5] >> (h & 31)) & 1u) != 0u;
         }
-        s_anc[j] = hit;
+        unsigned long long todo = __ballot(cand), m = 0ull;
+        while (todo) {
+            const int i = __ffsll((long long)todo) - 1;
+            todo &= todo - 1ull;
+            const int32_t* t = &s_tok[tile0 - MATCH_MARGIN + j0 + i - base];   // same address in every lane; t[-3] >= s_tok
+            const int32_t a0 = t[0], a1 = t[-1], a2 = t[-2], a3 = t[-3];
+            const bool ok = elen >= 1 && a0 == e0 && (elen < 2 || a1 == e1) && (elen < 3 || a2 == e2) &&
+                            (elen < 4 || a3 == e3);
+            if (__ballot(ok) != 0ull) m |= 1ull << i;
+        }
+        if (lane == 0) {
+            s_bits[j0 / 32] = (uint32_t)m;
+            s_bits[j0 / 32 + 1] = (uint32_t)(m >> 32);
+        }
     }
     __syncthreads();
 
     // phase 3: vouchers and sponsor flags, 4 consecutive positions per lane
     const int32_t p0 = tile0 + 4 * tid;
     if (p0 >= n) return;
+    // flag bits of positions p0 - 64 .. p0 + 3: bit i of (f_hi:f_lo) is position p0 - 64 + i
+    const int w0 = (4 * tid) >> 5, sh = (4 * tid) & 31;
+    const uint32_t x0 = s_bits[w0], x1 = s_bits[w0 + 1], x2 = s_bits[w0 + 2];
+    const unsigned long long lo64 = ((unsigned long long)x1 << 32) | x0;
+    const unsigned long long f_lo = sh ? ((lo64 >> sh) | ((unsigned long long)x2 << (64 - sh))) : lo64;
+    const uint32_t f_hi = (x2 >> sh) & 0xFu;               // positions p0 .. p0 + 3
+    const unsigned long long span_mask = L >= 64 ? ~0ull : ((1ull << L) - 1ull);
     uint8_t anc4[4], sp4[4];
     float v4[4];
 #pragma unroll
@@ -117,14 +150,16 @@ __device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const Matc
         uint8_t an = 0, sp = 0;
         float v = 0.0f;
         if (p < nb) {
-            const int j = p - tile0 + L;                   // index of p in s_anc
-            an = s_anc[j];
-            for (int k = 1; k <= L; ++k) {
-                if (s_anc[j - k]) {
-                    float Bi = a.anchor_B ? a.anchor_B[row + (size_t)(p - k)] : tab.B;
-                    v = __fadd_rn(v, __fmul_rn(Bi, tab.pw[k]));
-                    sp = 1;
-                }
+            an = (uint8_t)((f_hi >> c) & 1u);
+            // bits c .. c+63 are positions p - 64 .. p - 1; reversed, bit k-1 is position p - k
+            const unsigned long long win = c ? ((f_lo >> c) | ((unsigned long long)f_hi << (64 - c))) : f_lo;
+            unsigned long long near = __brevll(win) & span_mask;
+            sp = near != 0ull ? 1 : 0;
+            while (near) {                                  // increasing distance k, as in the fixed-order sum
+                const int k = __ffsll((long long)near);
+                near &= near - 1ull;
+                float Bi = a.anchor_B ? a.anchor_B[row + (size_t)(p - k)] : tab.B;
+                v = __fadd_rn(v, __fmul_rn(Bi, tab.pw[k]));
             }
         }
         anc4[c] = an;
