@@ -23,7 +23,8 @@ namespace {
 
 constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
-constexpr int HIST_COPIES = 8;
+constexpr int HIST_COPIES = 16;               // privatised histograms, one per lane % 16
+constexpr int HIST_STRIDE = 257;              // odd stride: the same bin of different copies sits in different LDS banks
 constexpr int SEL_CACHE_MAX_N = 32768;        // keys cached in LDS up to this length
 
 struct SelectArgs {
@@ -70,7 +71,7 @@ struct RadixState {
 
 // After a histogram pass: s_hist[copy][bin] hold the counts.  Finds the largest
 // digit d with sum_{d' >= d} h[d'] >= need.  All threads get the result.
-__device__ __forceinline__ RadixState radix_pick(uint32_t (*s_hist)[256], uint32_t* s_h,
+__device__ __forceinline__ RadixState radix_pick(uint32_t (*s_hist)[HIST_STRIDE], uint32_t* s_h,
                                                  RadixState* s_state, uint32_t need)
 {
     const int tid = threadIdx.x;
@@ -135,7 +136,7 @@ __global__ void __launch_bounds__(SEL_THREADS)
 select_kernel(SelectArgs a)
 {
     extern __shared__ uint32_t s_key[];                     // [roundup4(n)] when CACHED
-    __shared__ uint32_t s_hist[HIST_COPIES][256];
+    __shared__ uint32_t s_hist[HIST_COPIES][HIST_STRIDE];
     __shared__ uint32_t s_h[256];
     __shared__ int s_red[SEL_WAVES];
     __shared__ RadixState s_state;
@@ -173,7 +174,7 @@ select_kernel(SelectArgs a)
     const bool use_A = (a.alpha != 0.0f);
     const bool vec = a.vec_ok != 0;                          // n % 4 == 0 and aligned rows
 
-    for (int i = tid; i < HIST_COPIES * 256; i += SEL_THREADS) (&s_hist[0][0])[i] = 0;
+    for (int i = tid; i < HIST_COPIES * HIST_STRIDE; i += SEL_THREADS) (&s_hist[0][0])[i] = 0;
 
     auto load_flags = [&](const uint8_t* src, int32_t q, uint8_t (&out)[4]) {
         if (vec) {
