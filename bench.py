@@ -37,10 +37,11 @@ def kv_bytes_per_pass(w, budget, seq_len=None):
 # sources still hash to what was profiled, and is null otherwise.
 SCORE_TRAFFIC = {
     "workload": "c2_full_model",
-    "bytes_per_step": 564.1e6,
+    "bytes_per_step": 564.2e6,
     "sources": {
-        "ta_score.hip": "890447d609c9026315f4752ba9790b5d0cbb3d7bf17f54546089607c51576b51",
+        "ta_score.hip": "d3da90c86ada77aa966458dcf3f202dc10d53455bae7104dc946a829f26405e2",
         "ta_score_common.h": "a5b19090cb7b621ee55fb63227fecd9b95bbd6aef7344737e826d7e480caf31d",
+        "ta_match_device.h": "4f84fb2d69d2fbeeecfa969531451986c9e9342e7ccc822bb80070460680ac64",
     },
 }
 
