@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--budget", type=int, default=1024, help="retention budget K of the timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the budget sweep (profiling runs)")
+    ap.add_argument("--decode-steps", type=int, default=0,
+                    help="also time this many generation steps of the incremental form after the pass "
+                         "(needs a scored workload; reported as decode_step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy kernel (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -187,6 +190,30 @@ def main():
         sb, cb = kv_bytes_per_pass(w, kb, td.seq_len)
         sweep[str(kb)] = {"us_per_pass": round(us, 1), "GB/s": round((sb + cb) / us / 1e3, 1)}
 
+    # ---- incremental form: append / accumulate / evict-one / decay, per generation step ---------
+    decode = None
+    if args.decode_steps > 0 and scored:
+        cap = w.n + args.decode_steps + 16
+        st = ta.DecodeState(w.layers, w.batch, w.hq, w.hkv, budget, cap, dev)
+        ta.ta_decode_init(st, tok, plan.anchor, plan.idx, plan.cnt, plan.Kout, plan.Vout, prm, seq_len=seq, A=plan.A)
+        warm = min(8, args.decode_steps)
+        toks = torch.from_numpy(wl.make_decode_stream(w, td, warm + args.decode_steps, p_anchor=0.02)).to(dev)
+        q1, k1, v1 = wl.make_decode_qkv(w, 0, device=dev)
+        evicted = torch.zeros((w.layers, w.batch, w.hkv), dtype=torch.int32, device=dev)
+        for t in range(warm):
+            ta.ta_decode_step(st, toks[t], q1, k1, v1, td.tab_ids, td.tab_len, prm, evicted=evicted, stream=stream)
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        d0.record(stream)
+        for t in range(warm, warm + args.decode_steps):
+            ta.ta_decode_step(st, toks[t], q1, k1, v1, td.tab_ids, td.tab_len, prm, evicted=evicted, stream=stream)
+        d1.record(stream)
+        torch.cuda.synchronize()
+        step_us = d0.elapsed_time(d1) * 1e3 / args.decode_steps
+        row_bytes = units * (budget + 1) * w.d * 2              # every slot's key row once per step
+        decode = {"us_per_step": round(step_us, 1), "steps": args.decode_steps,
+                  "key_rows_GB/s": round(row_bytes / step_us / 1e3, 1),
+                  "hbm_frac": round(row_bytes / step_us / 1e3 / HBM_PEAK_GBS, 4)}
+
     # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample --------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -247,6 +274,7 @@ def main():
         "hbm_frac": round(value / HBM_PEAK_GBS, 4),
         "kernels_us": {k: round(v, 2) for k, v in kern_us.items()},
         "budget_sweep": sweep,
+        "decode_step": decode,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
