@@ -71,19 +71,21 @@ struct RiderArgs {
     uint32_t score_blocks;
 };
 
-template <int RG, bool COLSUM>
+// RG row groups of RT 32-row MFMA tiles each per workgroup; 2 * RG wavefronts.
+template <int RG, int RT, bool COLSUM>
 __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS]);
 
-template <int RG, bool COLSUM>
-__global__ void __launch_bounds__(128 * RG)
+// one tile per wavefront: four wavefronts per SIMD (at most 128 registers each)
+template <int RG, int RT, bool COLSUM>
+__global__ void __launch_bounds__(128 * RG, RT == 1 ? 4 : 2)
 score_kernel(ScoreArgs a)
 {
     __shared__ uint4 s_k[ring_of(RG)][STAGE_UNITS];        // 16 KB per stage
-    score_body<RG, COLSUM>(a, s_k);
+    score_body<RG, RT, COLSUM>(a, s_k);
 }
 
-template <int RG>
-__global__ void __launch_bounds__(128 * RG)
+template <int RG, int RT>
+__global__ void __launch_bounds__(128 * RG, RT == 1 ? 4 : 2)
 score_stats_match_kernel(ScoreArgs a, RiderArgs r)
 {
     __shared__ uint4 s_k[ring_of(RG)][STAGE_UNITS];
@@ -95,12 +97,14 @@ score_stats_match_kernel(ScoreArgs a, RiderArgs r)
                           (int)threadIdx.x, *reinterpret_cast<MatchLds*>(&s_k[0][0]));
         return;
     }
-    score_body<RG, false>(a, s_k);
+    score_body<RG, RT, false>(a, s_k);
 }
 
-template <int RG, bool COLSUM>
+template <int RG, int RT, bool COLSUM>
 __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS])
 {
+    constexpr int ROW_TILES = RT;
+    constexpr int GROUP_ROWS = 32 * RT;                    // rows of one wavefront
     constexpr int THREADS = 128 * RG;
     constexpr int WAVES = 2 * RG;
     constexpr int LPS = 16 / WAVES;                        // 1 KB direct loads per wavefront per stage
@@ -120,8 +124,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         }
     };
 
-    __shared__ float s_c[COLSUM ? 64 * RG : 1];            // per-row constant m + log2 Z
-    __shared__ int32_t s_lim[COLSUM ? 64 * RG : 1];        // per-row last visible key
+    __shared__ float s_c[COLSUM ? GROUP_ROWS * RG : 1];            // per-row constant m + log2 Z
+    __shared__ int32_t s_lim[COLSUM ? GROUP_ROWS * RG : 1];        // per-row last visible key
     __shared__ float s_part[COLSUM ? 2 : 1][RG][STAGE_KEYS];
 
     const int tid = threadIdx.x;
@@ -219,7 +223,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     int32_t my_lim[ROW_TILES];                             // sweep 1: last visible key of this lane's row
 #pragma unroll
     for (int t = 0; t < ROW_TILES; ++t) {
-        const int32_t r = 64 * rg + 32 * t + c32;
+        const int32_t r = GROUP_ROWS * rg + 32 * t + c32;
         int32_t lim = -1;
         if (r < a.rows) {
             const int32_t h = r / W, w = r - h * W;
@@ -237,7 +241,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     // load is issued: these are ordinary loads, and waiting for them later would also wait for
     // every direct load issued in between).  Chunks are added in index order, four loads in flight.
     if constexpr (COLSUM) {
-        for (int r = tid; r < 64 * RG; r += THREADS) {
+        for (int r = tid; r < GROUP_ROWS * RG; r += THREADS) {
             float c = INFINITY;
             int32_t lim = -1;
             if (r < a.rows) {
@@ -281,11 +285,11 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     // The compiler waits for ordinary loads with a count that knows nothing of the direct loads
     // below: a wait placed after them would also wait for every stage in flight.  Using the
     // fragments here puts that wait before the first direct load is issued.
-    static_assert(ROW_TILES == 2, "operand list below");
-    asm volatile("" ::"v"(qf[0][0]), "v"(qf[0][1]), "v"(qf[0][2]), "v"(qf[0][3]), "v"(qf[0][4]), "v"(qf[0][5]),
-                 "v"(qf[0][6]), "v"(qf[0][7]), "v"(qf[1][0]), "v"(qf[1][1]), "v"(qf[1][2]), "v"(qf[1][3]),
-                 "v"(qf[1][4]), "v"(qf[1][5]), "v"(qf[1][6]), "v"(qf[1][7])
-                 : "memory");
+#pragma unroll
+    for (int t = 0; t < ROW_TILES; ++t)
+        asm volatile("" ::"v"(qf[t][0]), "v"(qf[t][1]), "v"(qf[t][2]), "v"(qf[t][3]), "v"(qf[t][4]), "v"(qf[t][5]),
+                     "v"(qf[t][6]), "v"(qf[t][7])
+                     : "memory");
 
     // ---- first stages of K; the loop starts as soon as stage 0 is in ---------------------
 #pragma unroll
@@ -300,7 +304,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         for (int t = 0; t < ROW_TILES; ++t)
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                cst[t][i] = s_c[64 * rg + 32 * t + 8 * (i >> 2) + 4 * hf + (i & 3)];
+                cst[t][i] = s_c[GROUP_ROWS * rg + 32 * t + 8 * (i >> 2) + 4 * hf + (i & 3)];
     }
 
     float m_run[ROW_TILES], z_run[ROW_TILES];
@@ -385,7 +389,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
                     const int32_t key = tile_key0 + c32;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const int row = 64 * rg + 32 * t + 8 * (i >> 2) + 4 * hf + (i & 3);
+                        const int row = GROUP_ROWS * rg + 32 * t + 8 * (i >> 2) + 4 * hf + (i & 3);
                         const float p = fast_exp2(fmaf(acc[t][i], sc, -cst[t][i]));
                         colsum += key <= s_lim[row] ? p : 0.0f;
                     }
@@ -481,7 +485,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         // key-tile wavefronts of the row group through LDS, then store
         __syncthreads();                                       // staging buffers are idle now
         float* s_m = reinterpret_cast<float*>(&s_k[0][0]);
-        float* s_z = s_m + 64 * RG;
+        float* s_z = s_m + GROUP_ROWS * RG;
 #pragma unroll
         for (int t = 0; t < ROW_TILES; ++t) {
             const float mo = __shfl_xor(m_run[t], 32), zo = __shfl_xor(z_run[t], 32);
@@ -494,8 +498,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         if (kt == 1 && hf == 0) {
 #pragma unroll
             for (int t = 0; t < ROW_TILES; ++t) {
-                s_m[64 * rg + 32 * t + c32] = m_run[t];
-                s_z[64 * rg + 32 * t + c32] = z_run[t];
+                s_m[GROUP_ROWS * rg + 32 * t + c32] = m_run[t];
+                s_z[GROUP_ROWS * rg + 32 * t + c32] = z_run[t];
             }
         }
         __syncthreads();
@@ -503,7 +507,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
             float* st = a.ws + (((size_t)unit * a.nchunks + chunk) * a.rows_pad) * 2;
 #pragma unroll
             for (int t = 0; t < ROW_TILES; ++t) {
-                const int32_t r = 64 * rg + 32 * t + c32;
+                const int32_t r = GROUP_ROWS * rg + 32 * t + c32;
                 const float mo = s_m[r], zo = s_z[r];
                 const float mf = fmaxf(m_run[t], mo);
                 float zf = 0.0f;
@@ -515,7 +519,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     }
 }
 
-template <int RG>
+template <int RG, int RT>
 void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t st)
 {
     // One launch per sweep over all units.  (Splitting the units into cache-sized groups
@@ -530,11 +534,11 @@ void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t 
         r.tab = *rider->tab;
         r.score_blocks = blocks;
         const unsigned extra = (unsigned)r.m.tiles * (unsigned)r.m.batch;
-        hipLaunchKernelGGL((score_stats_match_kernel<RG>), dim3(blocks + extra), dim3(128 * RG), 0, st, a, r);
+        hipLaunchKernelGGL((score_stats_match_kernel<RG, RT>), dim3(blocks + extra), dim3(128 * RG), 0, st, a, r);
     } else {
-        hipLaunchKernelGGL((score_kernel<RG, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
+        hipLaunchKernelGGL((score_kernel<RG, RT, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
     }
-    hipLaunchKernelGGL((score_kernel<RG, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
+    hipLaunchKernelGGL((score_kernel<RG, RT, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
 }
 
 }  // namespace
@@ -630,9 +634,11 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.causal = causal;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
     switch (a.rows_pad) {
-        case 128: launch_rg<2>(a, p.units, rider, st); break;
-        case 256: launch_rg<4>(a, p.units, rider, st); break;
-        default: launch_rg<8>(a, p.units, rider, st); break;
+        // two 32-row tiles per wavefront (one tile per wavefront with twice the wavefronts - four
+        // per SIMD instead of two - was measured: same time at 128 rows, 5 % slower at 256)
+        case 128: launch_rg<2, 2>(a, p.units, rider, st); break;
+        case 256: launch_rg<4, 2>(a, p.units, rider, st); break;
+        default: launch_rg<8, 2>(a, p.units, rider, st); break;
     }
     return hipGetLastError();
 }

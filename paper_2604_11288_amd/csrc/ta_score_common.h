@@ -7,7 +7,6 @@ namespace ta {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int ROW_TILES = 2;                     // 32-row MFMA tiles per wavefront
 
 struct ScoreArgs {
     const uint4* Q;
