@@ -8,7 +8,11 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libta.so")
 SOURCES = ["ta_api.hip", "ta_match.hip", "ta_score.hip", "ta_select.hip", "ta_compact.hip", "ta_decode.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+# -ffp-contract=off: the utility, voucher and ranking arithmetic is specified operation by
+# operation in fp32 (the rounded-operation intrinsics of the HIP headers are plain * and +, which
+# the default contraction mode may fuse into an FMA and so change the last bit); the kernels that
+# want fused multiply-adds call fmaf explicitly.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA accumulators in VGPRs: the softmax reads them with plain VALU ops
          "-mllvm", "-amdgpu-mfma-vgpr-form"]

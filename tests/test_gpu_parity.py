@@ -95,6 +95,39 @@ def test_match_per_anchor_budget_and_empty_table():
     assert not anchor.any() and not spons.any() and not vouch.any()
 
 
+@pytest.mark.parametrize("L", [6, 64])
+def test_match_nested_table_on_a_tiny_vocabulary(L):
+    """Entries that share their last token (a 1-gram inside a 2-gram inside a 3-gram), a full
+    64-entry table and a 10-symbol vocabulary: every tile is dense with overlapping, nested and
+    tile-straddling matches, and spans of neighbouring anchors pile up."""
+    rng = np.random.default_rng(7)
+    rows = [[5], [7, 5], [9, 7, 5], [1, 2, 3, 4], [4], [2, 2], [2, 2, 2, 2], [0, 0, 0]]
+    while len(rows) < 64:                                   # fill up with random 4-grams (rarely matched)
+        rows.append(rng.integers(0, 10, size=4).tolist())
+    tab = np.full((64, 4), -1, np.int32)
+    lens = np.zeros(64, np.int32)
+    for e, r in enumerate(rows):
+        tab[e, :len(r)] = r
+        lens[e] = len(r)
+    n, batch = 5000, 3
+    tok = rng.integers(0, 10, size=(batch, n)).astype(np.int32)
+    seq_len = np.array([5000, 2049, 3], np.int32)           # one sequence shorter than the longest n-gram
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], n=n, batch=batch, span_L=L)
+    prm = _prm(w, span_L=L)
+    anchor, spons, vouch = ta.ta_match_anchors(_dev(tok), tab, lens, prm, seq_len=_dev(seq_len))
+    torch.cuda.synchronize()
+    hits = 0
+    for b in range(batch):
+        nb = int(seq_len[b])
+        a, s, v = ora.evict_sequence(tok[b, :nb], tab, lens, L=L)
+        assert np.array_equal(anchor[b, :nb].cpu().numpy(), a)
+        assert np.array_equal(spons[b, :nb].cpu().numpy(), s)
+        assert np.array_equal(vouch[b, :nb].cpu().numpy().view(np.uint32), v.view(np.uint32))
+        assert not anchor[b, nb:].any() and not vouch[b, nb:].any()
+        hits += int(a.sum())
+    assert hits > 1000                                       # roughly one position in five is an anchor
+
+
 # --------------------------------------------------------------------------
 # step 3
 # --------------------------------------------------------------------------
