@@ -130,3 +130,13 @@ def test_decode_attention_free_and_partly_filled_cache():
     assert td.seq_len.min() < 256 < td.seq_len.max()
     ev, _ = _run_decode(w, K=256, steps=70, p_anchor=0.1, check_every=10)
     assert 0 < ev < 70 * 2 * 2
+
+
+def test_decode_dense_anchors_overlapping_decayed_spans():
+    # one-token anchors emitted at every other step: the spans of several anchors with
+    # different (decayed) budgets overlap on most cached rows, so the voucher sums and the
+    # ranking must reproduce the specified order of fp32 operations exactly
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=2, n=600, hq=8, hkv=2, ragged=(300, 600),
+                  gram_min=1, gram_max=1, table_entries=8, planted=8)
+    ev, anc = _run_decode(w, K=48, steps=40, p_anchor=0.5)
+    assert ev == 40 * 2 * 2 and anc >= 20
