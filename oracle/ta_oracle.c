@@ -13,8 +13,9 @@
  * Parity pins live in tests/ (printed voucher values, the budget-partition
  * example, softmax row sums, closed forms, brute force on tiny inputs,
  * numpy/torch library routines; the incremental form: sliding-window reduction,
- * decay closed form, softmax sums, tuple-order arg-min).  Unpinned: nothing in
- * this file; the values
+ * decay closed form, softmax sums, tuple-order arg-min; the learned detector:
+ * GELU and logistic closed forms, a linear special case, torch's float64 ops).
+ * Unpinned: nothing in this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
 #include <math.h>
@@ -423,4 +424,53 @@ int32_t ta_oracle_decode_unit(uint16_t *Kc, uint16_t *Vc, int32_t *pos, float *A
         return -1;
     pos[worst_slot] = -1;
     return worst_slot;
+}
+
+
+/* ======================================================================
+ * Learned anchor detection and confidence-weighted sponsorship
+ * (Sec. 5.1 "Learned Anchor Detection": the detector equation and the
+ * TA-Learned / TA-LearnRank rules).
+ * ====================================================================== */
+
+/*
+ * Detector f(h) = sigmoid(W2 . GELU(W1 . h)) on one sequence of hidden states
+ * (Sec. 5.1, detector equation).  h is [n][dm], W1 is [m][dm], W2 is [m], all bf16
+ * bit patterns; no bias terms (the equation has none); GELU is the exact form
+ * x * Phi(x) of the cited definition.  Everything is evaluated in double and the
+ * confidence is returned rounded to fp32.
+ */
+void ta_oracle_detect(const uint16_t *h, const uint16_t *W1, const uint16_t *W2,
+                      int32_t n, int32_t dm, int32_t m, float *conf)
+{
+    for (int32_t p = 0; p < n; ++p) {
+        double out = 0.0;
+        for (int32_t j = 0; j < m; ++j) {
+            double z = 0.0;
+            for (int32_t c = 0; c < dm; ++c)
+                z += bf16_to_double(h[(size_t)p * dm + c]) * bf16_to_double(W1[(size_t)j * dm + c]);
+            const double gelu = 0.5 * z * (1.0 + erf(z / sqrt(2.0)));
+            out += bf16_to_double(W2[j]) * gelu;
+        }
+        conf[p] = (float)(1.0 / (1.0 + exp(-out)));
+    }
+}
+
+/*
+ * Anchors and their budgets from confidences (Sec. 5.1).  A position is an
+ * anchor iff conf > thr (strictly; 0.5 for TA-Learned, 0.3 for TA-LearnRank).
+ * rank == 0: every anchor gets the fixed budget B (TA-Learned: the sponsorship of
+ * Eq. 2 applied after confident predictions).  rank != 0: the budget is the
+ * confidence itself times `scale` (TA-LearnRank equation: V_j sums f(h_i) rho^(j-i);
+ * scale = 1 is the printed form).  The product is one fp32 multiplication.
+ * Vouchers then follow from ta_oracle_expand with these per-anchor budgets.
+ */
+void ta_oracle_confidence_anchors(const float *conf, int32_t n, float thr, int32_t rank,
+                                  float B, float scale, uint8_t *anchor, float *anchor_B)
+{
+    for (int32_t p = 0; p < n; ++p) {
+        const int is_anchor = conf[p] > thr;
+        anchor[p] = (uint8_t)is_anchor;
+        anchor_B[p] = is_anchor ? (rank ? scale * conf[p] : B) : 0.0f;
+    }
 }

@@ -55,6 +55,10 @@ def _load():
         lib.ta_oracle_decode_unit.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, vp, vp, i32,
                                               i32, i32, i32, f64, f32, f32, f32, vp, vp]
         lib.ta_oracle_decode_unit.restype = i32
+        lib.ta_oracle_detect.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+        lib.ta_oracle_detect.restype = None
+        lib.ta_oracle_confidence_anchors.argtypes = [vp, i32, f32, i32, f32, f32, vp, vp]
+        lib.ta_oracle_confidence_anchors.restype = None
         _lib = lib
     return _lib
 
@@ -139,6 +143,30 @@ def compact(rows, idx):
     out = np.zeros((idx.shape[0], rows.shape[1]), np.uint16)
     _load().ta_oracle_compact(_p(rows), _p(idx), idx.shape[0], rows.shape[1], _p(out))
     return out
+
+
+def detect(h, W1, W2):
+    """Detector confidence sigmoid(W2 . GELU(W1 . h)) per position (Sec. 5.1).
+    h uint16 [n][dm], W1 uint16 [m][dm], W2 uint16 [m] (bf16 bit patterns).  Returns f32 [n]."""
+    h, W1, W2 = _c(h, np.uint16), _c(W1, np.uint16), _c(W2, np.uint16)
+    n, dm = h.shape
+    m = W1.shape[0]
+    assert W1.shape == (m, dm) and W2.shape == (m,)
+    conf = np.zeros(n, np.float32)
+    _load().ta_oracle_detect(_p(h), _p(W1), _p(W2), n, dm, m, _p(conf))
+    return conf
+
+
+def confidence_anchors(conf, thr, rank, B=15.0, scale=1.0):
+    """Anchor flags (conf > thr) and per-anchor budgets: B when rank is false (TA-Learned), else
+    scale * conf (TA-LearnRank).  Returns (anchor u8 [n], anchor_B f32 [n])."""
+    conf = _c(conf, np.float32)
+    n = conf.shape[0]
+    anchor = np.zeros(n, np.uint8)
+    ab = np.zeros(n, np.float32)
+    _load().ta_oracle_confidence_anchors(_p(conf), n, float(thr), int(bool(rank)), float(B), float(scale),
+                                         _p(anchor), _p(ab))
+    return anchor, ab
 
 
 def evict_sequence(tok, tab_ids, tab_len, L=6, B=15.0, rho=0.8, anchor_B=None):
