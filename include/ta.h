@@ -8,6 +8,8 @@
  *   2. ta_score          attention column sums of an observation window
  *   3. ta_select         protected top-K under the (class, utility, position) order
  *   4. ta_compact        gather of the retained K/V rows
+ *      ta_detect_anchors /  anchors from a learned detector on hidden states instead of the
+ *      ta_expand_vouchers   table match, with confidence-weighted budgets (Sec. 5.1)
  *      ta_evict          all of the above in one call
  *      ta_decode_init /  the same policy applied after every generation step
  *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
@@ -119,6 +121,44 @@ int32_t ta_match_anchors(const int32_t *tok, const int32_t *seq_len, int32_t B, 
                          const int32_t *tab_ids, const int32_t *tab_len, int32_t E,
                          const float *anchor_B, const ta_params *prm,
                          uint8_t *anchor, uint8_t *spons, float *vouch, void *stream);
+
+/*
+ * Learned anchor detection (Sec. 5.1 "Learned Anchor Detection": detector
+ * f(h) = sigmoid(W2 . GELU(W1 . h)) on the hidden state of each position, and
+ * the two ways the paper feeds it into the policy).
+ *   conf[b][p]     = f(h[b][p])  (bf16 inputs, fp32 accumulation, exact-erf GELU, no biases)
+ *   anchor[b][p]   = 1 iff conf > thr  (strict; TA-Learned uses 0.5, TA-LearnRank 0.3)
+ *   anchor_B[b][p] = at anchors: prm->sponsor_B when rank == 0 (TA-Learned, fixed budget),
+ *                    scale * conf when rank != 0 (TA-LearnRank, budget proportional to the
+ *                    confidence; scale = 1 gives vouchers conf * rho^k); 0 elsewhere
+ * Positions >= seq_len[b] get 0 in all three outputs.  The outputs feed
+ * ta_expand_vouchers (then ta_select) in place of the table match.
+ *
+ *   h        DEVICE bf16 [B][n][d_model], rows h_row_stride elements apart (>= d_model,
+ *            multiple of 8), sequences n * h_row_stride apart; 16-byte aligned
+ *   W1       DEVICE bf16 [m][d_model] contiguous, 16-byte aligned;  W2 DEVICE bf16 [m]
+ *   d_model  multiple of 32, 32..32768;  m one of 32, 64, 128, 256
+ *   conf, anchor_B DEVICE float [B][n] (out);  anchor DEVICE uint8 [B][n] (out)
+ * Errors: NULL, SHAPE (sizes outside the ranges above, thr or scale not finite,
+ *         256 * h_row_stride * 2 bytes >= 2^31), ALIGN.
+ */
+int32_t ta_detect_anchors(const void *h, int64_t h_row_stride, const void *W1, const void *W2,
+                          const int32_t *seq_len, int32_t B, int32_t n, int32_t d_model, int32_t m,
+                          float thr, int32_t rank, float scale, const ta_params *prm,
+                          float *conf, uint8_t *anchor, float *anchor_B, void *stream);
+
+/*
+ * Step 2 alone - voucher allocation (Eq. 2; Alg. 1, voucher loops) from anchor
+ * flags that were not produced by the table match (learned detection, Sec. 5.1).
+ * vouch and spons exactly as defined under ta_match_anchors, with
+ * anchor[b][i] != 0 marking the anchors (flags at positions >= seq_len are ignored).
+ *   anchor    DEVICE uint8 [B][n] (in);  anchor_B DEVICE float [B][n] or NULL (= prm->sponsor_B)
+ *   spons     DEVICE uint8 [B][n] (out); vouch DEVICE float [B][n] (out)
+ * Errors: NULL, SHAPE (B, n < 1; span_L out of range).
+ */
+int32_t ta_expand_vouchers(const uint8_t *anchor, const float *anchor_B, const int32_t *seq_len,
+                           int32_t B, int32_t n, const ta_params *prm,
+                           uint8_t *spons, float *vouch, void *stream);
 
 /*
  * Step 3 - attention term A_i of Eq. 1 (cumulative attention over heads and

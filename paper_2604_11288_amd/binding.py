@@ -24,7 +24,7 @@ TA_MAX_ROWS = 512
 TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
 TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
-EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_score", "ta_select", "ta_compact",
+EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_score", "ta_select", "ta_compact",
            "ta_evict", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
@@ -95,6 +95,11 @@ def lib():
         L.ta_workspace_bytes.restype = sz
         L.ta_match_anchors.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.ta_match_anchors.restype = i32
+        L.ta_detect_anchors.argtypes = [vp, ctypes.c_int64, vp, vp, vp, i32, i32, i32, i32,
+                                        ctypes.c_float, i32, ctypes.c_float, vp, vp, vp, vp, vp]
+        L.ta_detect_anchors.restype = i32
+        L.ta_expand_vouchers.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        L.ta_expand_vouchers.restype = i32
         L.ta_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ta_score.restype = i32
         L.ta_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -182,6 +187,46 @@ def ta_match_anchors(tok, tab_ids, tab_len, params: Params, seq_len=None, anchor
                                 _stream(stream))
     _check(rc, "ta_match_anchors")
     return anchor, spons, vouch
+
+
+def ta_detect_anchors(h, W1, W2, params: Params, thr: float, rank: bool, scale: float = 1.0, seq_len=None,
+                      out=None, stream=None):
+    """Learned detector.  h bf16 [B][n][d_model] (rows may be strided), W1 bf16 [m][d_model], W2 bf16 [m].
+    Returns (conf f32, anchor u8, anchor_B f32), each [B][n]."""
+    assert h.dtype == torch.bfloat16 and h.dim() == 3 and h.stride(2) == 1
+    B, n, dm = h.shape
+    assert B == 1 or h.stride(0) == n * h.stride(1), "sequences must follow each other row after row"
+    assert W1.dtype == torch.bfloat16 and W1.dim() == 2 and W1.is_contiguous() and W1.shape[1] == dm
+    m = W1.shape[0]
+    assert W2.dtype == torch.bfloat16 and W2.is_contiguous() and W2.numel() == m
+    if out is None:
+        conf = torch.empty((B, n), dtype=torch.float32, device=h.device)
+        anchor = torch.empty((B, n), dtype=torch.uint8, device=h.device)
+        anchor_B = torch.empty((B, n), dtype=torch.float32, device=h.device)
+    else:
+        conf, anchor, anchor_B = out
+    cp = params.c()
+    rc = lib().ta_detect_anchors(_ptr(h), h.stride(1), _ptr(W1), _ptr(W2), _ptr(seq_len), B, n, dm, m,
+                                 float(thr), int(bool(rank)), float(scale), ctypes.byref(cp),
+                                 _ptr(conf), _ptr(anchor), _ptr(anchor_B), _stream(stream))
+    _check(rc, "ta_detect_anchors")
+    return conf, anchor, anchor_B
+
+
+def ta_expand_vouchers(anchor, params: Params, anchor_B=None, seq_len=None, out=None, stream=None):
+    """Step 2 from given anchor flags u8 [B][n].  Returns (spons u8, vouch f32), each [B][n]."""
+    assert anchor.dtype == torch.uint8 and anchor.dim() == 2 and anchor.is_contiguous()
+    B, n = anchor.shape
+    if out is None:
+        spons = torch.empty((B, n), dtype=torch.uint8, device=anchor.device)
+        vouch = torch.empty((B, n), dtype=torch.float32, device=anchor.device)
+    else:
+        spons, vouch = out
+    cp = params.c()
+    rc = lib().ta_expand_vouchers(_ptr(anchor), _ptr(anchor_B), _ptr(seq_len), B, n, ctypes.byref(cp),
+                                  _ptr(spons), _ptr(vouch), _stream(stream))
+    _check(rc, "ta_expand_vouchers")
+    return spons, vouch
 
 
 def ta_score(Q, K, params: Params, seq_len=None, A=None, ws=None, stream=None):

@@ -6,7 +6,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libta.so")
-SOURCES = ["ta_api.hip", "ta_match.hip", "ta_score.hip", "ta_select.hip", "ta_compact.hip", "ta_decode.hip"]
+SOURCES = ["ta_api.hip", "ta_match.hip", "ta_score.hip", "ta_select.hip", "ta_compact.hip", "ta_decode.hip",
+           "ta_detect.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: the utility, voucher and ranking arithmetic is specified operation by
 # operation in fp32 (the rounded-operation intrinsics of the HIP headers are plain * and +, which

@@ -185,6 +185,40 @@ int32_t ta_match_anchors(const int32_t* tok, const int32_t* seq_len, int32_t B, 
                                        (hipStream_t)stream));
 }
 
+int32_t ta_detect_anchors(const void* h, int64_t h_row_stride, const void* W1, const void* W2,
+                          const int32_t* seq_len, int32_t B, int32_t n, int32_t d_model, int32_t m,
+                          float thr, int32_t rank, float scale, const ta_params* prm,
+                          float* conf, uint8_t* anchor, float* anchor_B, void* stream)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    if (!h || !W1 || !W2 || !conf || !anchor || !anchor_B) return TA_ERR_NULL;
+    if (B < 1 || n < 1) return TA_ERR_SHAPE;
+    if (d_model < 32 || d_model > 32768 || d_model % 32 != 0) return TA_ERR_SHAPE;
+    if (m != 32 && m != 64 && m != 128 && m != 256) return TA_ERR_SHAPE;
+    if (h_row_stride < d_model) return TA_ERR_SHAPE;
+    if (256 * h_row_stride * 2 >= 0x7FFFFFFFll) return TA_ERR_SHAPE;      // 32-bit offsets inside a tile
+    if (((int64_t)B * n + 255) / 256 > 0x7FFFFFFFll) return TA_ERR_SHAPE;
+    if (!isfinite(thr) || !isfinite(scale)) return TA_ERR_SHAPE;
+    if (h_row_stride % 8 != 0 || !aligned16(h) || !aligned16(W1)) return TA_ERR_ALIGN;
+    return hip_status(ta::launch_detect(h, h_row_stride, W1, W2, seq_len, B, n, d_model, m, thr, rank,
+                                        prm->sponsor_B, scale, conf, anchor, anchor_B, (hipStream_t)stream));
+}
+
+int32_t ta_expand_vouchers(const uint8_t* anchor, const float* anchor_B, const int32_t* seq_len,
+                           int32_t B, int32_t n, const ta_params* prm,
+                           uint8_t* spons, float* vouch, void* stream)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    if (!anchor || !spons || !vouch) return TA_ERR_NULL;
+    if (B < 1 || n < 1 || B > 65535) return TA_ERR_SHAPE;
+    ta::MatchTable tab;
+    rc = build_table(nullptr, nullptr, 0, prm, &tab);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_expand(anchor, anchor_B, seq_len, B, n, tab, spons, vouch, (hipStream_t)stream));
+}
+
 int32_t ta_score(const void* Q, const void* K, const ta_layout* lay, const int32_t* seq_len,
                  const ta_params* prm, float* A, void* ws, size_t ws_bytes, void* stream)
 {

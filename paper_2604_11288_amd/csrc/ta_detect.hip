@@ -1,0 +1,276 @@
+// Learned anchor detection (Sec. 5.1 "Learned Anchor Detection"): per position the confidence
+//   f(h) = sigmoid(W2 . GELU(W1 . h))
+// of a small two-layer perceptron on the hidden state, the anchor flag f(h) > thr and the
+// per-anchor sponsor budget of TA-Learned (fixed B) or TA-LearnRank (scale * f(h)).
+//
+// The first layer is a [positions x d_model] x [d_model x m] contraction: bf16 MFMA
+// (v_mfma_f32_32x32x16_bf16), fp32 accumulation.  It is computed as W1 . h^T so that a lane
+// owns ONE position (a column of the accumulator tile) and 16 hidden units of each tile: GELU,
+// the product with W2 and the sum over the hidden units are then register arithmetic, followed
+// by one half-wave exchange.  A workgroup owns 256 consecutive positions and all m hidden
+// units; a wavefront owns 64 positions x (32 * HT) hidden units.  h and W1 stream through LDS
+// in slices of 32 input features (64 bytes per row), a ring of three buffers filled by direct
+// global->LDS loads two slices ahead, 16-byte chunks XOR-swizzled by row for conflict-free
+// fragment reads.  W1 is re-read by every workgroup (from the L2: it is at most 4 MB); with 256
+// positions per workgroup that traffic equals the traffic of h itself.
+#include <math.h>
+
+#include "ta_internal.h"
+#include "ta_score_common.h"
+
+namespace ta {
+
+namespace {
+
+constexpr int DT_TOKENS = 256;                   // positions per workgroup
+constexpr int DT_KS = 32;                        // input features per slice
+constexpr int DT_RING = 3;
+
+struct DetectArgs {
+    const uint4* h;
+    const uint4* W1;
+    const uint16_t* W2;
+    const int32_t* seq_len;
+    float* conf;
+    uint8_t* anchor;
+    float* anchor_B;
+    int64_t total;                               // batch * n positions
+    int32_t n, dm, m;
+    int32_t h_row_bytes;                         // bytes between consecutive positions
+    float thr, B, scale;
+    int32_t rank;
+};
+
+__device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_base)
+{
+    // direct global->LDS load, 16 bytes per lane, lane i lands at lds_base + 16 i (inline assembly
+    // so that the compiler does not wait for all of them before every LDS read)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(off), "s"(base)
+                 : "memory", "m0");
+}
+
+constexpr int vm_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// HT: 32-unit hidden tiles per wavefront; MH: wavefront columns over the hidden units (m = 32 HT MH)
+template <int HT, int MH>
+__global__ void __launch_bounds__(256 * MH, 2)
+detect_kernel(DetectArgs a)
+{
+    constexpr int M = 32 * HT * MH;
+    constexpr int WAVES = 4 * MH;
+    constexpr int NI_H = DT_TOKENS / 16;                   // 1 KB loads per slice: h (16 rows each)
+    constexpr int NI_W = M / 16;                           //                      W1
+    constexpr int LH = NI_H / WAVES;                       // per wavefront
+    constexpr int LW = (NI_W + WAVES - 1) / WAVES;         // (wraps: a few duplicate loads when M is small)
+    constexpr int LPS = LH + LW;
+    constexpr int H_BYTES = DT_TOKENS * 64;                // bytes of the h part of a buffer
+    constexpr int BUF_BYTES = H_BYTES + M * 64;
+
+    extern __shared__ uint4 s_buf[];                       // DT_RING buffers, then W2 as floats
+    float* s_w2 = reinterpret_cast<float*>(reinterpret_cast<char*>(s_buf) + DT_RING * BUF_BYTES);
+    float* s_part = s_w2 + M;                              // [MH][DT_TOKENS] partial sums over hidden units
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c32 = lane & 31, hf = lane >> 5;
+    const int tw = wave & 3, mh = wave >> 2;               // position block of 64, hidden column
+    const int64_t tile0 = (int64_t)blockIdx.x * DT_TOKENS;
+    const int nstages = a.dm / DT_KS;
+
+    for (int j = tid; j < M; j += 256 * MH) s_w2[j] = bf16_bits_to_float(a.W2[j]);
+
+    // per-lane byte offsets of this wavefront's loads inside a slice (loop invariant)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)s_buf;
+    uint32_t off_h[LH], off_w[LW];
+    int ins_h[LH], ins_w[LW];
+#pragma unroll
+    for (int j = 0; j < LH; ++j) {
+        const int ins = wave + WAVES * j;
+        const int row = ins * 16 + (lane >> 2);
+        int64_t t = tile0 + row;
+        t = t < a.total ? t : a.total - 1;                 // stay inside the tensor; never stored
+        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        off_h[j] = (uint32_t)((t - tile0) * a.h_row_bytes + chunk * 16);
+        ins_h[j] = ins;
+    }
+#pragma unroll
+    for (int j = 0; j < LW; ++j) {
+        const int ins = (wave + WAVES * j) % NI_W;
+        const int row = ins * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        off_w[j] = (uint32_t)(row * a.dm * 2 + chunk * 16);
+        ins_w[j] = ins;
+    }
+    const char* hbase = reinterpret_cast<const char*>(a.h) + tile0 * a.h_row_bytes;
+    const char* wbase = reinterpret_cast<const char*>(a.W1);
+    const auto issue = [&](int s) {
+        const uint32_t dst = lds0 + (uint32_t)(s % DT_RING) * BUF_BYTES;
+        const char* hs = hbase + (size_t)s * (DT_KS * 2);
+        const char* ws = wbase + (size_t)s * (DT_KS * 2);
+#pragma unroll
+        for (int j = 0; j < LH; ++j) dma16(hs, off_h[j], __builtin_amdgcn_readfirstlane(dst + ins_h[j] * 1024));
+#pragma unroll
+        for (int j = 0; j < LW; ++j)
+            dma16(ws, off_w[j], __builtin_amdgcn_readfirstlane(dst + H_BYTES + ins_w[j] * 1024));
+    };
+    const auto wait_but = [](int k) {                      // at most k later slices outstanding
+        switch (k) {
+            case 0: __builtin_amdgcn_s_waitcnt(vm_imm(0)); break;
+            case 1: __builtin_amdgcn_s_waitcnt(vm_imm(LPS)); break;
+            default: __builtin_amdgcn_s_waitcnt(vm_imm(2 * LPS)); break;
+        }
+    };
+    static_assert(2 * LPS <= 63, "vmcnt range");
+
+#pragma unroll
+    for (int s = 0; s < DT_RING - 1; ++s)
+        if (s < nstages) issue(s);
+
+    // fragment slots of this lane inside a buffer (16-byte units), for the two MFMA steps of a slice
+    int slot_h[2][2], slot_w[HT][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const int row = 64 * tw + 32 * tt + c32;
+            slot_h[tt][ks] = row * 4 + ((2 * ks + hf) ^ ((row >> 2) & 3));
+        }
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) {
+            const int row = 32 * (mh * HT + ht) + c32;
+            slot_w[ht][ks] = H_BYTES / 16 + row * 4 + ((2 * ks + hf) ^ ((row >> 2) & 3));
+        }
+    }
+
+    f32x16 acc[2][HT];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tt][ht][i] = 0.0f;
+
+    for (int s = 0; s < nstages; ++s) {
+        const int later = nstages - 1 - s;
+        wait_but(later < DT_RING - 2 ? later : DT_RING - 2);
+        __syncthreads();                                   // slice s landed everywhere, slice s-1 consumed
+        if (s + DT_RING - 1 < nstages) issue(s + DT_RING - 1);
+        const uint4* buf = s_buf + (size_t)(s % DT_RING) * (BUF_BYTES / 16);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 hfrag[2], wfrag[HT];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) hfrag[tt] = as_frag(buf[slot_h[tt][ks]]);
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht) wfrag[ht] = as_frag(buf[slot_w[ht][ks]]);
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt)   // rows: hidden units of the tile, columns: positions
+                    acc[tt][ht] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[ht], hfrag[tt], acc[tt][ht], 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue: GELU, weights of the output unit, sum over the hidden units -----------
+    // acc[tt][ht][i] is hidden unit 32 (mh HT + ht) + 8 (i / 4) + 4 hf + i % 4 of position 64 tw + 32 tt + c32
+    float part[2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) {
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                asm volatile("" ::: "memory");             // the weights are read where they are used, not all up front
+                const float4 w = *reinterpret_cast<const float4*>(&s_w2[32 * (mh * HT + ht) + 8 * i4 + 4 * hf]);
+                const float wv[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float z = acc[tt][ht][4 * i4 + c];
+                    const float gelu = 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+                    sum = fmaf(wv[c], gelu, sum);
+                    asm volatile("" : "+v"(sum));          // consume each value now: no pile-up of live erf results
+                }
+            }
+        }
+        sum += __shfl_xor(sum, 32);                        // the two half-waves hold disjoint hidden units
+        part[tt] = sum;
+    }
+    if (hf == 0) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) s_part[mh * DT_TOKENS + 64 * tw + 32 * tt + c32] = part[tt];
+    }
+    __syncthreads();
+    if (tid < DT_TOKENS) {
+        const int64_t t = tile0 + tid;
+        if (t < a.total) {
+            float out = s_part[tid];
+#pragma unroll
+            for (int c = 1; c < MH; ++c) out += s_part[c * DT_TOKENS + tid];
+            float conf = 1.0f / (1.0f + expf(-out));
+            if (a.seq_len) {
+                const int64_t b = t / a.n;
+                if ((int32_t)(t - b * a.n) >= a.seq_len[b]) conf = 0.0f;   // past the end of its sequence
+            }
+            const bool is_anchor = conf > a.thr;
+            a.conf[t] = conf;
+            a.anchor[t] = is_anchor ? 1 : 0;
+            a.anchor_B[t] = is_anchor ? (a.rank ? a.scale * conf : a.B) : 0.0f;
+        }
+    }
+}
+
+template <int HT, int MH>
+hipError_t launch_one(const DetectArgs& a, hipStream_t st)
+{
+    constexpr int M = 32 * HT * MH;
+    const size_t lds = (size_t)DT_RING * (DT_TOKENS * 64 + M * 64) + (size_t)M * 4 + (size_t)MH * DT_TOKENS * 4;
+    static bool attr_set = false;                          // dynamic LDS above 64 KB needs the attribute once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&detect_kernel<HT, MH>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const unsigned blocks = (unsigned)((a.total + DT_TOKENS - 1) / DT_TOKENS);
+    hipLaunchKernelGGL((detect_kernel<HT, MH>), dim3(blocks), dim3(256 * MH), lds, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_detect(const void* h, int64_t h_row_stride, const void* W1, const void* W2,
+                         const int32_t* seq_len, int32_t batch, int32_t n, int32_t dm, int32_t m,
+                         float thr, int32_t rank, float B, float scale,
+                         float* conf, uint8_t* anchor, float* anchor_B, hipStream_t st)
+{
+    DetectArgs a;
+    a.h = (const uint4*)h;
+    a.W1 = (const uint4*)W1;
+    a.W2 = (const uint16_t*)W2;
+    a.seq_len = seq_len;
+    a.conf = conf;
+    a.anchor = anchor;
+    a.anchor_B = anchor_B;
+    a.total = (int64_t)batch * n;
+    a.n = n;
+    a.dm = dm;
+    a.m = m;
+    a.h_row_bytes = (int32_t)(h_row_stride * 2);
+    a.thr = thr;
+    a.B = B;
+    a.scale = scale;
+    a.rank = rank;
+    switch (m) {
+        case 32: return launch_one<1, 1>(a, st);
+        case 64: return launch_one<2, 1>(a, st);
+        case 128: return launch_one<4, 1>(a, st);
+        default: return launch_one<4, 2>(a, st);           // 256
+    }
+}
+
+}  // namespace ta

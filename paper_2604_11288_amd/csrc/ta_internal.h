@@ -22,6 +22,18 @@ hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, i
                         const MatchTable& tab, const float* anchor_B,
                         uint8_t* anchor, uint8_t* spons, float* vouch, hipStream_t st);
 
+// Step 2 alone from given anchor flags (read, not written); tab supplies L, B and the powers only.
+hipError_t launch_expand(const uint8_t* anchor, const float* anchor_B, const int32_t* seq_len, int32_t B, int32_t n,
+                         const MatchTable& tab, uint8_t* spons, float* vouch, hipStream_t st);
+
+// ---- learned anchor detection -------------------------------------------------
+// conf = sigmoid(W2 . GELU(W1 . h)) per position, anchor = conf > thr, budget B or scale * conf.
+// m is one of 32, 64, 128, 256; dm a multiple of 32; h rows h_row_stride elements apart.
+hipError_t launch_detect(const void* h, int64_t h_row_stride, const void* W1, const void* W2,
+                         const int32_t* seq_len, int32_t batch, int32_t n, int32_t dm, int32_t m,
+                         float thr, int32_t rank, float B, float scale,
+                         float* conf, uint8_t* anchor, float* anchor_B, hipStream_t st);
+
 // Arguments of a match that rides along with the first sweep of the score step.
 struct MatchRider {
     const int32_t* tok;

@@ -15,6 +15,42 @@ match_expand_kernel(MatchArgs a, MatchTable tab)
     match_expand_tile(a, tab, (int32_t)blockIdx.x, (int32_t)blockIdx.y, (int)threadIdx.x, lds);
 }
 
+// Step 2 alone, for anchors that do not come from the n-gram table (learned detection,
+// Sec. 5.1): the anchor flags are an input; their bytes for [tile0 - MATCH_MARGIN, tile end)
+// become the bit string the expansion reads.
+__global__ void __launch_bounds__(MATCH_THREADS)
+expand_mask_kernel(MatchArgs a, MatchTable tab)
+{
+    constexpr int WORDS = (MATCH_TILE + MATCH_MARGIN) / 32 + 2;
+    __shared__ uint32_t s_bits[WORDS];
+    const int tid = (int)threadIdx.x;
+    const int32_t tile = (int32_t)blockIdx.x, b = (int32_t)blockIdx.y;
+    const int32_t n = a.n;
+    int32_t nb = a.seq_len ? a.seq_len[b] : n;
+    nb = nb < 0 ? 0 : (nb > n ? n : nb);
+    const int32_t first = tile * MATCH_TILE - MATCH_MARGIN;
+    const uint8_t* flags = a.anchor + (size_t)b * (size_t)n;
+    if (tid < WORDS) s_bits[tid] = 0u;
+    __syncthreads();
+    for (int g = tid; g < (MATCH_TILE + MATCH_MARGIN) / 4; g += MATCH_THREADS) {
+        const int32_t q0 = first + 4 * g;
+        uint32_t nib = 0u;
+        if (q0 >= 0 && q0 + 3 < nb && a.vec_ok) {
+            const uchar4 f = *reinterpret_cast<const uchar4*>(flags + q0);
+            nib = (f.x ? 1u : 0u) | (f.y ? 2u : 0u) | (f.z ? 4u : 0u) | (f.w ? 8u : 0u);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int32_t q = q0 + c;
+                if (q >= 0 && q < nb && flags[q]) nib |= 1u << c;
+            }
+        }
+        if (nib) atomicOr(&s_bits[(4 * g) >> 5], nib << ((4 * g) & 31));
+    }
+    __syncthreads();
+    expand_tile(a, tab, tile, b, tid, s_bits, false);
+}
+
 }  // namespace
 
 MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
@@ -42,6 +78,15 @@ hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, i
     const MatchArgs a = make_match_args(tok, seq_len, B, n, anchor_B, anchor, spons, vouch);
     dim3 grid((unsigned)a.tiles, (unsigned)B);
     hipLaunchKernelGGL(match_expand_kernel, grid, dim3(MATCH_THREADS), 0, st, a, tab);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand(const uint8_t* anchor, const float* anchor_B, const int32_t* seq_len, int32_t B, int32_t n,
+                         const MatchTable& tab, uint8_t* spons, float* vouch, hipStream_t st)
+{
+    const MatchArgs a = make_match_args(nullptr, seq_len, B, n, anchor_B, const_cast<uint8_t*>(anchor), spons, vouch);
+    dim3 grid((unsigned)a.tiles, (unsigned)B);
+    hipLaunchKernelGGL(expand_mask_kernel, grid, dim3(MATCH_THREADS), 0, st, a, tab);
     return hipGetLastError();
 }
 

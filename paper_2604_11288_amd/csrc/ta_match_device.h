@@ -54,10 +54,11 @@ MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B,
 
 __device__ __forceinline__ uint32_t filter_slot(int32_t t) { return (uint32_t)t & (FILTER_BITS - 1); }
 
+// Phases 0-2: anchor flags of [tile0 - MATCH_MARGIN, tile0 + MATCH_TILE) as bits in lds.bits.
 // Called by exactly MATCH_THREADS threads (tid = 0 .. MATCH_THREADS-1) of a workgroup whose
-// other wavefronts, if any, have already returned.
-__device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const MatchTable& tab, int32_t tile,
-                                                  int32_t b, int tid, MatchLds& lds)
+// other wavefronts, if any, have already returned; ends with a workgroup barrier.
+__device__ __forceinline__ void match_flags_tile(const MatchArgs& a, const MatchTable& tab, int32_t tile,
+                                                 int32_t b, int tid, MatchLds& lds)
 {
     uint32_t* s_filter = lds.filter;
     int32_t* s_tok = lds.tok;
@@ -67,7 +68,6 @@ __device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const Matc
     int32_t nb = a.seq_len ? a.seq_len[b] : n;
     nb = nb < 0 ? 0 : (nb > n ? n : nb);
     const int32_t tile0 = tile * MATCH_TILE;
-    const int32_t L = tab.L;
     const size_t row = (size_t)b * (size_t)n;
 
     // phase 1 first: the tokens of [tile0 - HALO, tile0 + TILE) are requested before the filter is
@@ -131,6 +131,20 @@ __device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const Matc
         }
     }
     __syncthreads();
+}
+
+// Phase 3: vouchers and sponsor flags of the tile from the flag bits in `s_bits` (bit j: anchor
+// at position tile0 - MATCH_MARGIN + j; bits of positions outside [0, seq_len) must be clear).
+// The anchor flags themselves are stored too when `store_anchor` is set.
+__device__ __forceinline__ void expand_tile(const MatchArgs& a, const MatchTable& tab, int32_t tile, int32_t b,
+                                            int tid, const uint32_t* s_bits, bool store_anchor)
+{
+    const int32_t n = a.n;
+    int32_t nb = a.seq_len ? a.seq_len[b] : n;
+    nb = nb < 0 ? 0 : (nb > n ? n : nb);
+    const int32_t tile0 = tile * MATCH_TILE;
+    const int32_t L = tab.L;
+    const size_t row = (size_t)b * (size_t)n;
 
     // phase 3: vouchers and sponsor flags, 4 consecutive positions per lane
     const int32_t p0 = tile0 + 4 * tid;
@@ -169,19 +183,27 @@ __device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const Matc
     if (a.vec_ok && p0 + 3 < n) {
         uchar4 au = make_uchar4(anc4[0], anc4[1], anc4[2], anc4[3]);
         uchar4 su = make_uchar4(sp4[0], sp4[1], sp4[2], sp4[3]);
-        *reinterpret_cast<uchar4*>(a.anchor + row + p0) = au;
+        if (store_anchor) *reinterpret_cast<uchar4*>(a.anchor + row + p0) = au;
         *reinterpret_cast<uchar4*>(a.spons + row + p0) = su;
         *reinterpret_cast<float4*>(a.vouch + row + p0) = make_float4(v4[0], v4[1], v4[2], v4[3]);
     } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (p0 + c < n) {
-                a.anchor[row + p0 + c] = anc4[c];
+                if (store_anchor) a.anchor[row + p0 + c] = anc4[c];
                 a.spons[row + p0 + c] = sp4[c];
                 a.vouch[row + p0 + c] = v4[c];
             }
         }
     }
+}
+
+// Steps 1+2 for one tile: flags by n-gram match, then the expansion.
+__device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const MatchTable& tab, int32_t tile,
+                                                  int32_t b, int tid, MatchLds& lds)
+{
+    match_flags_tile(a, tab, tile, b, tid, lds);
+    expand_tile(a, tab, tile, b, tid, lds.bits, true);
 }
 
 }  // namespace ta

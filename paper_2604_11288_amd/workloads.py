@@ -195,3 +195,42 @@ def make_decode_qkv(w: Workload, step: int, device="cpu", layers: Optional[int] 
     def draw(shape):
         return torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
     return draw((lyr, w.batch, w.hq, w.d)), draw((lyr, w.batch, w.hkv, w.d)), draw((lyr, w.batch, w.hkv, w.d))
+
+
+def make_detector_inputs(batch: int, n: int, d_model: int, m: int, seed: int = BASE_SEED + 11, p_anchor: float = 0.05,
+                         device="cpu", row_stride: Optional[int] = None):
+    """Inputs of the learned anchor detector (Sec. 5.1): hidden states h bf16 [B][n][d_model]
+    (rows row_stride elements apart), first-layer weights W1 bf16 [m][d_model], output weights
+    W2 bf16 [m].
+
+    No trained detector or model is involved.  The weights are built so that the confidences
+    spread over (0, 1) the way a trained detector's do: half of the hidden units look along one
+    random direction u, the other half are random background units with negative output weight
+    (the detector has no bias, so they supply the negative resting logit).  h is N(0,1) noise;
+    a fraction p_anchor of the positions gets a component along u whose strength is uniform, so
+    their confidences land on both sides of the 0.3 and 0.5 thresholds and the rest stay near 0.
+    """
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    stride = d_model if row_stride is None else row_stride
+    u = torch.randn(d_model, generator=g, device=device, dtype=torch.float32)
+    u = u / u.norm()
+    half = m // 2
+    W1 = torch.randn((m, d_model), generator=g, device=device, dtype=torch.float32) / d_model ** 0.5
+    W1[:half] = 0.25 * u + 0.02 * W1[:half]
+    W2 = torch.empty(m, device=device, dtype=torch.float32)
+    W2[:half] = 0.25 * 64.0 / half
+    W2[half:] = -0.5 * 64.0 / (m - half)
+    hbuf = torch.empty((batch * n, stride), dtype=torch.bfloat16, device=device)
+    step = max(1, (1 << 26) // stride)
+    for s in range(0, batch * n, step):
+        e = min(s + step, batch * n)
+        x = torch.randn((e - s, d_model), generator=g, device=device, dtype=torch.float32)
+        is_anchor = torch.rand(e - s, generator=g, device=device) < p_anchor
+        strength = torch.rand(e - s, generator=g, device=device) * 7.2
+        x += (is_anchor * strength)[:, None] * u[None, :]
+        hbuf[s:e, :d_model] = x.to(torch.bfloat16)
+        if stride > d_model:
+            hbuf[s:e, d_model:] = 7.0                      # padding a correct kernel never reads
+    h = hbuf.view(batch, n, stride)[:, :, :d_model]
+    return h, W1.to(torch.bfloat16), W2.to(torch.bfloat16)
