@@ -73,6 +73,12 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="also time this many generation steps of the incremental form after the pass "
                          "(needs a scored workload; reported as decode_step)")
+    ap.add_argument("--detect-positions", type=int, default=0,
+                    help="also time the learned anchor detector + voucher expansion on about this many positions "
+                         "of synthetic last-layer hidden states (sequences of the workload's length; reported as "
+                         "learned_detect)")
+    ap.add_argument("--detect-dmodel", type=int, default=4096)
+    ap.add_argument("--detect-hidden", type=int, default=128)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy kernel (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -214,6 +220,43 @@ def main():
                   "key_rows_GB/s": round(row_bytes / step_us / 1e3, 1),
                   "hbm_frac": round(row_bytes / step_us / 1e3 / HBM_PEAK_GBS, 4)}
 
+    # ---- learned anchor detection (the confidence-weighted variant of steps 1+2) ----------------
+    detect = None
+    if args.detect_positions > 0:
+        dB = max(1, args.detect_positions // w.n)
+        dm, m = args.detect_dmodel, args.detect_hidden
+        h, W1, W2 = wl.make_detector_inputs(dB, w.n, dm, m, device=dev)
+        outs = ta.ta_detect_anchors(h, W1, W2, prm, 0.3, True, stream=stream)
+        exp = ta.ta_expand_vouchers(outs[1], prm, anchor_B=outs[2], stream=stream)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        reps = 20
+        ev[0].record(stream)
+        for _ in range(reps):
+            ta.ta_detect_anchors(h, W1, W2, prm, 0.3, True, out=outs, stream=stream)
+        ev[1].record(stream)
+        for _ in range(reps):
+            ta.ta_expand_vouchers(outs[1], prm, anchor_B=outs[2], out=exp, stream=stream)
+        ev[2].record(stream)
+        torch.cuda.synchronize()
+        det_us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
+        exp_us = ev[1].elapsed_time(ev[2]) * 1e3 / reps
+        h_bytes = dB * w.n * dm * 2
+        detect = {"positions": dB * w.n, "d_model": dm, "hidden": m, "rule": "TA-LearnRank (conf > 0.3, budget = conf)",
+                  "detect_us": round(det_us, 1), "expand_us": round(exp_us, 1),
+                  "h_GB/s": round(h_bytes / det_us / 1e3, 1), "hbm_frac": round(h_bytes / det_us / 1e3 / HBM_PEAK_GBS, 4),
+                  "TFLOP/s": round(2.0 * dB * w.n * dm * m / det_us / 1e6, 1),
+                  "anchors": int(outs[1].sum())}
+        if not args.no_cpu_baseline:
+            from oracle import ta_oracle as ora
+            ora.build()
+            rows = 256
+            hb, w1b, w2b = wl.bf16_bits(h[0, :rows]), wl.bf16_bits(W1), wl.bf16_bits(W2)
+            c0 = time.perf_counter()
+            ora.detect(hb, w1b, w2b)
+            detect["cpu_oracle_us_per_position"] = round((time.perf_counter() - c0) * 1e6 / rows, 1)
+        del h, outs, exp
+
     # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample --------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -275,6 +318,7 @@ def main():
         "kernels_us": {k: round(v, 2) for k, v in kern_us.items()},
         "budget_sweep": sweep,
         "decode_step": decode,
+        "learned_detect": detect,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

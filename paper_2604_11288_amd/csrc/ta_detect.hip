@@ -11,8 +11,8 @@
 // units; a wavefront owns 64 positions x (32 * HT) hidden units.  h and W1 stream through LDS
 // in slices of 32 input features (64 bytes per row), a ring of three buffers filled by direct
 // global->LDS loads two slices ahead, 16-byte chunks XOR-swizzled by row for conflict-free
-// fragment reads.  W1 is re-read by every workgroup (from the L2: it is at most 4 MB); with 256
-// positions per workgroup that traffic equals the traffic of h itself.
+// fragment reads.  W1 is re-read by every workgroup (from the L2: it is at most 16 MB, 1 MB for the usual
+// d_model = 4096, m = 128); per workgroup that is m / positions of the bytes of h.
 #include <math.h>
 
 #include "ta_internal.h"
@@ -22,7 +22,6 @@ namespace ta {
 
 namespace {
 
-constexpr int DT_TOKENS = 256;                   // positions per workgroup
 constexpr int DT_KS = 32;                        // input features per slice
 constexpr int DT_RING = 3;
 
@@ -55,13 +54,16 @@ constexpr int vm_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// HT: 32-unit hidden tiles per wavefront; MH: wavefront columns over the hidden units (m = 32 HT MH)
-template <int HT, int MH>
-__global__ void __launch_bounds__(256 * MH, 2)
+// TW: wavefront rows over the positions (64 TW positions per workgroup); HT: 32-unit hidden tiles
+// per wavefront; MH: wavefront columns over the hidden units (m = 32 HT MH)
+template <int TW, int HT, int MH>
+__global__ void __launch_bounds__(64 * TW * MH, 2)
 detect_kernel(DetectArgs a)
 {
+    constexpr int DT_TOKENS = 64 * TW;
+    constexpr int THREADS = 64 * TW * MH;
     constexpr int M = 32 * HT * MH;
-    constexpr int WAVES = 4 * MH;
+    constexpr int WAVES = TW * MH;
     constexpr int NI_H = DT_TOKENS / 16;                   // 1 KB loads per slice: h (16 rows each)
     constexpr int NI_W = M / 16;                           //                      W1
     constexpr int LH = NI_H / WAVES;                       // per wavefront
@@ -77,11 +79,11 @@ detect_kernel(DetectArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, hf = lane >> 5;
-    const int tw = wave & 3, mh = wave >> 2;               // position block of 64, hidden column
+    const int tw = wave % TW, mh = wave / TW;              // position block of 64, hidden column
     const int64_t tile0 = (int64_t)blockIdx.x * DT_TOKENS;
     const int nstages = a.dm / DT_KS;
 
-    for (int j = tid; j < M; j += 256 * MH) s_w2[j] = bf16_bits_to_float(a.W2[j]);
+    for (int j = tid; j < M; j += THREADS) s_w2[j] = bf16_bits_to_float(a.W2[j]);
 
     // per-lane byte offsets of this wavefront's loads inside a slice (loop invariant)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)s_buf;
@@ -205,7 +207,7 @@ detect_kernel(DetectArgs a)
         for (int tt = 0; tt < 2; ++tt) s_part[mh * DT_TOKENS + 64 * tw + 32 * tt + c32] = part[tt];
     }
     __syncthreads();
-    if (tid < DT_TOKENS) {
+    if (tid < DT_TOKENS) {                                 // THREADS >= DT_TOKENS
         const int64_t t = tile0 + tid;
         if (t < a.total) {
             float out = s_part[tid];
@@ -224,20 +226,21 @@ detect_kernel(DetectArgs a)
     }
 }
 
-template <int HT, int MH>
+template <int TW, int HT, int MH>
 hipError_t launch_one(const DetectArgs& a, hipStream_t st)
 {
     constexpr int M = 32 * HT * MH;
+    constexpr int DT_TOKENS = 64 * TW;
     const size_t lds = (size_t)DT_RING * (DT_TOKENS * 64 + M * 64) + (size_t)M * 4 + (size_t)MH * DT_TOKENS * 4;
     static bool attr_set = false;                          // dynamic LDS above 64 KB needs the attribute once
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&detect_kernel<HT, MH>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&detect_kernel<TW, HT, MH>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const unsigned blocks = (unsigned)((a.total + DT_TOKENS - 1) / DT_TOKENS);
-    hipLaunchKernelGGL((detect_kernel<HT, MH>), dim3(blocks), dim3(256 * MH), lds, st, a);
+    hipLaunchKernelGGL((detect_kernel<TW, HT, MH>), dim3(blocks), dim3(64 * TW * MH), lds, st, a);
     return hipGetLastError();
 }
 
@@ -266,10 +269,10 @@ hipError_t launch_detect(const void* h, int64_t h_row_stride, const void* W1, co
     a.scale = scale;
     a.rank = rank;
     switch (m) {
-        case 32: return launch_one<1, 1>(a, st);
-        case 64: return launch_one<2, 1>(a, st);
-        case 128: return launch_one<4, 1>(a, st);
-        default: return launch_one<4, 2>(a, st);           // 256
+        case 32: return launch_one<4, 1, 1>(a, st);
+        case 64: return launch_one<4, 2, 1>(a, st);
+        case 128: return launch_one<4, 4, 1>(a, st);
+        default: return launch_one<4, 2, 4>(a, st);        // 256: sixteen wavefronts of 64 x 64
     }
 }
 
