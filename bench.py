@@ -37,11 +37,11 @@ def kv_bytes_per_pass(w, budget, seq_len=None):
 # sources still hash to what was profiled, and is null otherwise.
 SCORE_TRAFFIC = {
     "workload": "c2_full_model",
-    "bytes_per_step": 564.2e6,
+    "bytes_per_step": 559.4e6,
     "sources": {
-        "ta_score.hip": "d3da90c86ada77aa966458dcf3f202dc10d53455bae7104dc946a829f26405e2",
-        "ta_score_common.h": "a5b19090cb7b621ee55fb63227fecd9b95bbd6aef7344737e826d7e480caf31d",
-        "ta_match_device.h": "4f84fb2d69d2fbeeecfa969531451986c9e9342e7ccc822bb80070460680ac64",
+        "ta_score.hip": "c90c08e729bea18101596b7501bba9f123ab92cb100d0c6cd2cb1f4fa9735a6d",
+        "ta_score_common.h": "fbbe78be7b8be5f520bfb3b45e5ed4bd9b5567d7968503bec942999d6176d6bd",
+        "ta_match_device.h": "65f3540c6956f0ab39262b2c72213fd330f5fd3f13388ec689522f4ddc94e0c0",
     },
 }
 
