@@ -14,7 +14,9 @@
  * example, softmax row sums, closed forms, brute force on tiny inputs,
  * numpy/torch library routines; the incremental form: sliding-window reduction,
  * decay closed form, softmax sums, tuple-order arg-min; the learned detector:
- * GELU and logistic closed forms, a linear special case, torch's float64 ops).
+ * GELU and logistic closed forms, a linear special case, torch's float64 ops;
+ * embedding cosine: identical / orthogonal / opposite vectors, scale invariance,
+ * numpy float64).
  * Unpinned: nothing in this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
@@ -474,3 +476,55 @@ void ta_oracle_confidence_anchors(const float *conf, int32_t n, float thr, int32
         anchor_B[p] = is_anchor ? (rank ? scale * conf[p] : B) : 0.0f;
     }
 }
+
+/*
+ * Embedding-based anchor detection (Sec. 3.2 "Anchor detection", third instantiation;
+ * TA-Fast-Embedding of Sec. 3.4 and of the multilingual experiment): the similarity of
+ * an input embedding x to a set of anchor-concept embeddings c_0 .. c_{E-1} is the
+ * largest cosine
+ *     sim = max_e  (x . c_e) / (|x| |c_e|),
+ * a cosine with a zero vector on either side counting as 0.  x is [n][dm], C is
+ * [E][dm], bf16 bit patterns, E >= 1; evaluated in double, returned rounded to fp32.
+ * The paper gives no threshold: a position is an anchor iff sim > tau (strictly),
+ * tau a parameter.  Budgets are the fixed B of Eq. 2, so the flags feed
+ * ta_oracle_expand unchanged.
+ */
+void ta_oracle_cosine_sim(const uint16_t *x, const uint16_t *C, int32_t n, int32_t dm, int32_t E, float *sim)
+{
+    for (int32_t p = 0; p < n; ++p) {
+        double xx = 0.0;
+        for (int32_t c = 0; c < dm; ++c) {
+            const double v = bf16_to_double(x[(size_t)p * dm + c]);
+            xx += v * v;
+        }
+        double best = 0.0;
+        for (int32_t e = 0; e < E; ++e) {
+            double dot = 0.0, cc = 0.0;
+            for (int32_t c = 0; c < dm; ++c) {
+                const double v = bf16_to_double(C[(size_t)e * dm + c]);
+                dot += bf16_to_double(x[(size_t)p * dm + c]) * v;
+                cc += v * v;
+            }
+            const double cosine = (xx > 0.0 && cc > 0.0) ? dot / (sqrt(xx) * sqrt(cc)) : 0.0;
+            if (e == 0 || cosine > best) best = cosine;
+        }
+        sim[p] = (float)best;
+    }
+}
+
+void ta_oracle_threshold_anchors(const float *sim, int32_t n, float tau, uint8_t *anchor)
+{
+    for (int32_t p = 0; p < n; ++p) anchor[p] = (uint8_t)(sim[p] > tau);
+}
+
+/*
+ * Input embeddings depend on the token ID only, so embedding-based detection can be run
+ * over the vocabulary once and looked up per position: anchor[p] = vocab_anchor[tok[p]].
+ * IDs outside [0, V) are never anchors.
+ */
+void ta_oracle_lookup_anchors(const int32_t *tok, int32_t n, const uint8_t *vocab_anchor, int32_t V, uint8_t *anchor)
+{
+    for (int32_t p = 0; p < n; ++p)
+        anchor[p] = (uint8_t)((tok[p] >= 0 && tok[p] < V) ? (vocab_anchor[tok[p]] != 0) : 0);
+}
+

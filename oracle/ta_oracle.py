@@ -59,6 +59,12 @@ def _load():
         lib.ta_oracle_detect.restype = None
         lib.ta_oracle_confidence_anchors.argtypes = [vp, i32, f32, i32, f32, f32, vp, vp]
         lib.ta_oracle_confidence_anchors.restype = None
+        lib.ta_oracle_cosine_sim.argtypes = [vp, vp, i32, i32, i32, vp]
+        lib.ta_oracle_cosine_sim.restype = None
+        lib.ta_oracle_threshold_anchors.argtypes = [vp, i32, f32, vp]
+        lib.ta_oracle_threshold_anchors.restype = None
+        lib.ta_oracle_lookup_anchors.argtypes = [vp, i32, vp, i32, vp]
+        lib.ta_oracle_lookup_anchors.restype = None
         _lib = lib
     return _lib
 
@@ -167,6 +173,35 @@ def confidence_anchors(conf, thr, rank, B=15.0, scale=1.0):
     _load().ta_oracle_confidence_anchors(_p(conf), n, float(thr), int(bool(rank)), float(B), float(scale),
                                          _p(anchor), _p(ab))
     return anchor, ab
+
+
+def cosine_sim(x, C):
+    """Largest cosine between each row of x and the concept rows of C (embedding-based anchor
+    detection, Sec. 3.2).  x uint16 [n][dm], C uint16 [E][dm] (bf16 bit patterns).  Returns f32 [n]."""
+    x, C = _c(x, np.uint16), _c(C, np.uint16)
+    n, dm = x.shape
+    E = C.shape[0]
+    assert C.shape == (E, dm) and E >= 1
+    sim = np.zeros(n, np.float32)
+    _load().ta_oracle_cosine_sim(_p(x), _p(C), n, dm, E, _p(sim))
+    return sim
+
+
+def threshold_anchors(sim, tau):
+    """anchor[p] = sim[p] > tau."""
+    sim = _c(sim, np.float32)
+    anchor = np.zeros(sim.shape[0], np.uint8)
+    _load().ta_oracle_threshold_anchors(_p(sim), sim.shape[0], float(tau), _p(anchor))
+    return anchor
+
+
+def lookup_anchors(tok, vocab_anchor):
+    """anchor[p] = vocab_anchor[tok[p]] (0 for IDs outside the vocabulary)."""
+    tok = _c(tok, np.int32)
+    va = _c(vocab_anchor, np.uint8)
+    anchor = np.zeros(tok.shape[0], np.uint8)
+    _load().ta_oracle_lookup_anchors(_p(tok), tok.shape[0], _p(va), va.shape[0], _p(anchor))
+    return anchor
 
 
 def evict_sequence(tok, tab_ids, tab_len, L=6, B=15.0, rho=0.8, anchor_B=None):
