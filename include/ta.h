@@ -10,6 +10,8 @@
  *   4. ta_compact        gather of the retained K/V rows
  *      ta_detect_anchors /  anchors from a learned detector on hidden states instead of the
  *      ta_expand_vouchers   table match, with confidence-weighted budgets (Sec. 5.1)
+ *      ta_embed_anchors /   anchors from cosine similarity to anchor-concept embeddings
+ *      ta_lookup_anchors    (Sec. 3.2), per position or once per vocabulary entry
  *      ta_evict          all of the above in one call
  *      ta_decode_init /  the same policy applied after every generation step
  *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
@@ -146,6 +148,38 @@ int32_t ta_detect_anchors(const void *h, int64_t h_row_stride, const void *W1, c
                           const int32_t *seq_len, int32_t B, int32_t n, int32_t d_model, int32_t m,
                           float thr, int32_t rank, float scale, const ta_params *prm,
                           float *conf, uint8_t *anchor, float *anchor_B, void *stream);
+
+/*
+ * Embedding-based anchor detection (Sec. 3.2 "Anchor detection", third
+ * instantiation; TA-Fast-Embedding of Sec. 3.4 and Sec. 5.3): similarity of an
+ * input embedding to a set of anchor-concept embeddings,
+ *   sim[b][p]    = max over e < E of  (x . c_e) / (|x| |c_e|)   (a cosine with a zero
+ *                  vector on either side counts as 0; bf16 inputs, fp32 accumulation)
+ *   anchor[b][p] = 1 iff sim > tau  (strict; the paper gives no value for tau)
+ * Positions >= seq_len[b] get 0 in both outputs.  Input embeddings depend on the
+ * token ID only: run this over the embedding table once (B = 1, n = vocabulary
+ * size) and use ta_lookup_anchors per sequence, or run it per position.
+ *
+ *   x        DEVICE bf16 [B][n][d_model], rows x_row_stride elements apart (>= d_model,
+ *            multiple of 8), sequences n * x_row_stride apart; 16-byte aligned
+ *   C        DEVICE bf16 [E][d_model] contiguous, 16-byte aligned;  1 <= E <= 256
+ *   d_model  multiple of 32, 32..32768
+ *   sim      DEVICE float [B][n] (out);  anchor DEVICE uint8 [B][n] (out)
+ * Errors: NULL, SHAPE (as ta_detect_anchors; E out of range; tau not finite), ALIGN.
+ */
+int32_t ta_embed_anchors(const void *x, int64_t x_row_stride, const void *C, int32_t E,
+                         const int32_t *seq_len, int32_t B, int32_t n, int32_t d_model, float tau,
+                         float *sim, uint8_t *anchor, void *stream);
+
+/*
+ * Anchor flags of token IDs from per-vocabulary flags (the output of
+ * ta_embed_anchors over the embedding table):
+ *   anchor[b][p] = 1 iff p < seq_len[b], 0 <= tok[b][p] < V and vocab_anchor[tok[b][p]] != 0.
+ *   tok DEVICE int32 [B][n]; vocab_anchor DEVICE uint8 [V]; anchor DEVICE uint8 [B][n] (out)
+ * Errors: NULL, SHAPE (B, n, V < 1).
+ */
+int32_t ta_lookup_anchors(const int32_t *tok, const int32_t *seq_len, int32_t B, int32_t n,
+                          const uint8_t *vocab_anchor, int32_t V, uint8_t *anchor, void *stream);
 
 /*
  * Step 2 alone - voucher allocation (Eq. 2; Alg. 1, voucher loops) from anchor

@@ -24,7 +24,8 @@ TA_MAX_ROWS = 512
 TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
 TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
-EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_score", "ta_select", "ta_compact",
+EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
+           "ta_lookup_anchors", "ta_score", "ta_select", "ta_compact",
            "ta_evict", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
@@ -98,6 +99,10 @@ def lib():
         L.ta_detect_anchors.argtypes = [vp, ctypes.c_int64, vp, vp, vp, i32, i32, i32, i32,
                                         ctypes.c_float, i32, ctypes.c_float, vp, vp, vp, vp, vp]
         L.ta_detect_anchors.restype = i32
+        L.ta_embed_anchors.argtypes = [vp, ctypes.c_int64, vp, i32, vp, i32, i32, i32, ctypes.c_float, vp, vp, vp]
+        L.ta_embed_anchors.restype = i32
+        L.ta_lookup_anchors.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
+        L.ta_lookup_anchors.restype = i32
         L.ta_expand_vouchers.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.ta_expand_vouchers.restype = i32
         L.ta_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -211,6 +216,36 @@ def ta_detect_anchors(h, W1, W2, params: Params, thr: float, rank: bool, scale: 
                                  _ptr(conf), _ptr(anchor), _ptr(anchor_B), _stream(stream))
     _check(rc, "ta_detect_anchors")
     return conf, anchor, anchor_B
+
+
+def ta_embed_anchors(x, C, tau: float, seq_len=None, out=None, stream=None):
+    """Embedding-based detection.  x bf16 [B][n][d_model] (rows may be strided; the embedding table is
+    B = 1, n = vocabulary size), C bf16 [E][d_model].  Returns (sim f32, anchor u8), each [B][n]."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 3 and x.stride(2) == 1
+    B, n, dm = x.shape
+    assert B == 1 or x.stride(0) == n * x.stride(1), "sequences must follow each other row after row"
+    assert C.dtype == torch.bfloat16 and C.dim() == 2 and C.is_contiguous() and C.shape[1] == dm
+    if out is None:
+        sim = torch.empty((B, n), dtype=torch.float32, device=x.device)
+        anchor = torch.empty((B, n), dtype=torch.uint8, device=x.device)
+    else:
+        sim, anchor = out
+    rc = lib().ta_embed_anchors(_ptr(x), x.stride(1), _ptr(C), C.shape[0], _ptr(seq_len), B, n, dm, float(tau),
+                                _ptr(sim), _ptr(anchor), _stream(stream))
+    _check(rc, "ta_embed_anchors")
+    return sim, anchor
+
+
+def ta_lookup_anchors(tok, vocab_anchor, seq_len=None, out=None, stream=None):
+    """anchor[b][p] = vocab_anchor[tok[b][p]] != 0.  tok int32 [B][n], vocab_anchor u8 [V].  Returns u8 [B][n]."""
+    assert tok.dtype == torch.int32 and tok.dim() == 2 and tok.is_contiguous()
+    assert vocab_anchor.dtype == torch.uint8 and vocab_anchor.dim() == 1 and vocab_anchor.is_contiguous()
+    B, n = tok.shape
+    anchor = torch.empty((B, n), dtype=torch.uint8, device=tok.device) if out is None else out
+    rc = lib().ta_lookup_anchors(_ptr(tok), _ptr(seq_len), B, n, _ptr(vocab_anchor), vocab_anchor.numel(),
+                                 _ptr(anchor), _stream(stream))
+    _check(rc, "ta_lookup_anchors")
+    return anchor
 
 
 def ta_expand_vouchers(anchor, params: Params, anchor_B=None, seq_len=None, out=None, stream=None):

@@ -205,6 +205,31 @@ int32_t ta_detect_anchors(const void* h, int64_t h_row_stride, const void* W1, c
                                         prm->sponsor_B, scale, conf, anchor, anchor_B, (hipStream_t)stream));
 }
 
+int32_t ta_embed_anchors(const void* x, int64_t x_row_stride, const void* C, int32_t E,
+                         const int32_t* seq_len, int32_t B, int32_t n, int32_t d_model, float tau,
+                         float* sim, uint8_t* anchor, void* stream)
+{
+    if (!x || !C || !sim || !anchor) return TA_ERR_NULL;
+    if (B < 1 || n < 1) return TA_ERR_SHAPE;
+    if (d_model < 32 || d_model > 32768 || d_model % 32 != 0) return TA_ERR_SHAPE;
+    if (E < 1 || E > 256) return TA_ERR_SHAPE;
+    if (x_row_stride < d_model) return TA_ERR_SHAPE;
+    if (256 * x_row_stride * 2 >= 0x7FFFFFFFll) return TA_ERR_SHAPE;      // 32-bit offsets inside a tile
+    if (((int64_t)B * n + 255) / 256 > 0x7FFFFFFFll) return TA_ERR_SHAPE;
+    if (!isfinite(tau)) return TA_ERR_SHAPE;
+    if (x_row_stride % 8 != 0 || !aligned16(x) || !aligned16(C)) return TA_ERR_ALIGN;
+    return hip_status(ta::launch_cosine(x, x_row_stride, C, E, (int64_t)B * n, d_model, seq_len, n, tau, sim, anchor,
+                                        (hipStream_t)stream));
+}
+
+int32_t ta_lookup_anchors(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
+                          const uint8_t* vocab_anchor, int32_t V, uint8_t* anchor, void* stream)
+{
+    if (!tok || !vocab_anchor || !anchor) return TA_ERR_NULL;
+    if (B < 1 || n < 1 || V < 1 || B > 65535) return TA_ERR_SHAPE;
+    return hip_status(ta::launch_lookup(tok, seq_len, B, n, vocab_anchor, V, anchor, (hipStream_t)stream));
+}
+
 int32_t ta_expand_vouchers(const uint8_t* anchor, const float* anchor_B, const int32_t* seq_len,
                            int32_t B, int32_t n, const ta_params* prm,
                            uint8_t* spons, float* vouch, void* stream)

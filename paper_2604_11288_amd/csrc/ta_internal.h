@@ -34,6 +34,13 @@ hipError_t launch_detect(const void* h, int64_t h_row_stride, const void* W1, co
                          float thr, int32_t rank, float B, float scale,
                          float* conf, uint8_t* anchor, float* anchor_B, hipStream_t st);
 
+// sim = largest cosine between a row of x and the E rows of C; anchor = sim > tau.
+hipError_t launch_cosine(const void* x, int64_t x_row_stride, const void* C, int32_t E, int64_t rows, int32_t dm,
+                         const int32_t* seq_len, int32_t n, float tau, float* sim, uint8_t* anchor, hipStream_t st);
+// anchor[b][p] = vocab_anchor[tok[b][p]] != 0 for valid positions and IDs.
+hipError_t launch_lookup(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
+                         const uint8_t* vocab_anchor, int32_t V, uint8_t* anchor, hipStream_t st);
+
 // Arguments of a match that rides along with the first sweep of the score step.
 struct MatchRider {
     const int32_t* tok;

@@ -51,6 +51,25 @@ expand_mask_kernel(MatchArgs a, MatchTable tab)
     expand_tile(a, tab, tile, b, tid, s_bits, false);
 }
 
+// Anchor flags by token ID (embedding-based detection evaluated once per vocabulary entry).
+__global__ void __launch_bounds__(256)
+lookup_kernel(const int32_t* tok, const int32_t* seq_len, int32_t n, const uint8_t* vocab_anchor, int32_t V,
+              uint8_t* anchor)
+{
+    const int32_t b = (int32_t)blockIdx.y;
+    const int32_t p = (int32_t)(blockIdx.x * 256 + threadIdx.x);
+    if (p >= n) return;
+    int32_t nb = seq_len ? seq_len[b] : n;
+    nb = nb < 0 ? 0 : (nb > n ? n : nb);
+    const size_t at = (size_t)b * (size_t)n + (size_t)p;
+    uint8_t f = 0;
+    if (p < nb) {
+        const int32_t t = tok[at];
+        if (t >= 0 && t < V) f = vocab_anchor[t] ? 1 : 0;
+    }
+    anchor[at] = f;
+}
+
 }  // namespace
 
 MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
@@ -87,6 +106,14 @@ hipError_t launch_expand(const uint8_t* anchor, const float* anchor_B, const int
     const MatchArgs a = make_match_args(nullptr, seq_len, B, n, anchor_B, const_cast<uint8_t*>(anchor), spons, vouch);
     dim3 grid((unsigned)a.tiles, (unsigned)B);
     hipLaunchKernelGGL(expand_mask_kernel, grid, dim3(MATCH_THREADS), 0, st, a, tab);
+    return hipGetLastError();
+}
+
+hipError_t launch_lookup(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
+                         const uint8_t* vocab_anchor, int32_t V, uint8_t* anchor, hipStream_t st)
+{
+    dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(lookup_kernel, grid, dim3(256), 0, st, tok, seq_len, n, vocab_anchor, V, anchor);
     return hipGetLastError();
 }
 

@@ -234,3 +234,35 @@ def make_detector_inputs(batch: int, n: int, d_model: int, m: int, seed: int = B
             hbuf[s:e, d_model:] = 7.0                      # padding a correct kernel never reads
     h = hbuf.view(batch, n, stride)[:, :, :d_model]
     return h, W1.to(torch.bfloat16), W2.to(torch.bfloat16)
+
+
+def make_embedding_inputs(V: int, d_model: int, E: int, seed: int = BASE_SEED + 13, p_near: float = 0.05,
+                          device="cpu", row_stride: Optional[int] = None):
+    """Inputs of embedding-based anchor detection (Sec. 3.2): an input-embedding table bf16
+    [V][d_model] (rows row_stride elements apart) and E anchor-concept embeddings bf16 [E][d_model].
+
+    No model's embedding table is involved.  Rows are N(0, 0.02^2) noise; a fraction p_near of
+    them is a mix t * c_e / |c_e| + (1 - t) * noise / |noise| with a random concept e and t uniform
+    on (0, 1), so their largest cosine spreads over (0, 1); the other rows have cosines of order
+    1 / sqrt(d_model).  Concepts are N(0,1) scaled by random factors (norms must divide out).
+    """
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    stride = d_model if row_stride is None else row_stride
+    C = torch.randn((E, d_model), generator=g, device=device, dtype=torch.float32)
+    C *= torch.rand((E, 1), generator=g, device=device) * 3.0 + 0.25
+    buf = torch.empty((V, stride), dtype=torch.bfloat16, device=device)
+    step = max(1, (1 << 26) // stride)
+    Cn = C / C.norm(dim=1, keepdim=True)
+    for s in range(0, V, step):
+        e = min(s + step, V)
+        noise = torch.randn((e - s, d_model), generator=g, device=device, dtype=torch.float32)
+        near = torch.rand(e - s, generator=g, device=device) < p_near
+        which = torch.randint(0, E, (e - s,), generator=g, device=device)
+        t = torch.rand(e - s, generator=g, device=device)[:, None]
+        mixed = t * Cn[which] + (1.0 - t) * noise / noise.norm(dim=1, keepdim=True)
+        rows = torch.where(near[:, None], mixed * 0.5, noise * 0.02)
+        buf[s:e, :d_model] = rows.to(torch.bfloat16)
+        if stride > d_model:
+            buf[s:e, d_model:] = 7.0                       # padding a correct kernel never reads
+    return buf[:, :d_model], C.to(torch.bfloat16)
