@@ -77,6 +77,11 @@ def main():
                     help="also time the learned anchor detector + voucher expansion on about this many positions "
                          "of synthetic last-layer hidden states (sequences of the workload's length; reported as "
                          "learned_detect)")
+    ap.add_argument("--embed-rows", type=int, default=0,
+                    help="also time embedding-based anchor detection (largest cosine to --embed-concepts concept "
+                         "embeddings) over an embedding table of this many rows, and the per-token lookup of the "
+                         "workload's token IDs (reported as embedding_detect)")
+    ap.add_argument("--embed-concepts", type=int, default=16)
     ap.add_argument("--detect-dmodel", type=int, default=4096)
     ap.add_argument("--detect-hidden", type=int, default=128)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -257,6 +262,41 @@ def main():
             detect["cpu_oracle_us_per_position"] = round((time.perf_counter() - c0) * 1e6 / rows, 1)
         del h, outs, exp
 
+    # ---- embedding-based detection: the embedding table once, then a lookup per token -------------
+    embed = None
+    if args.embed_rows > 0:
+        dm, E, V = args.detect_dmodel, args.embed_concepts, args.embed_rows
+        emb, C = wl.make_embedding_inputs(V, dm, E, device=dev)
+        outs = ta.ta_embed_anchors(emb[None], C, 0.5, stream=stream)
+        tokv = tok % V
+        lk = ta.ta_lookup_anchors(tokv, outs[1].view(-1), seq_len=seq, stream=stream)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        reps = 20
+        ev[0].record(stream)
+        for _ in range(reps):
+            ta.ta_embed_anchors(emb[None], C, 0.5, out=outs, stream=stream)
+        ev[1].record(stream)
+        for _ in range(reps):
+            ta.ta_lookup_anchors(tokv, outs[1].view(-1), seq_len=seq, out=lk, stream=stream)
+        ev[2].record(stream)
+        torch.cuda.synchronize()
+        e_us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
+        l_us = ev[1].elapsed_time(ev[2]) * 1e3 / reps
+        e_bytes = V * dm * 2
+        embed = {"rows": V, "d_model": dm, "concepts": E, "tau": 0.5,
+                 "embed_us": round(e_us, 1), "lookup_us": round(l_us, 1),
+                 "x_GB/s": round(e_bytes / e_us / 1e3, 1), "hbm_frac": round(e_bytes / e_us / 1e3 / HBM_PEAK_GBS, 4),
+                 "anchor_rows": int(outs[1].sum())}
+        if not args.no_cpu_baseline:
+            from oracle import ta_oracle as ora
+            ora.build()
+            rows = 256
+            c0 = time.perf_counter()
+            ora.cosine_sim(wl.bf16_bits(emb[:rows]), wl.bf16_bits(C))
+            embed["cpu_oracle_us_per_row"] = round((time.perf_counter() - c0) * 1e6 / rows, 1)
+        del emb, outs, lk
+
     # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample --------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -319,6 +359,7 @@ def main():
         "budget_sweep": sweep,
         "decode_step": decode,
         "learned_detect": detect,
+        "embedding_detect": embed,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
