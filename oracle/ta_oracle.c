@@ -16,7 +16,9 @@
  * decay closed form, softmax sums, tuple-order arg-min; the learned detector:
  * GELU and logistic closed forms, a linear special case, torch's float64 ops;
  * embedding cosine: identical / orthogonal / opposite vectors, scale invariance,
- * numpy float64).
+ * numpy float64; policy options: torch max_pool1d, the partition against the
+ * elastic selection, a plain top-K and brute force, the budget-partition table,
+ * sum / endpoints / monotonicity of the layer budgets).
  * Unpinned: nothing in this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
@@ -526,5 +528,118 @@ void ta_oracle_lookup_anchors(const int32_t *tok, int32_t n, const uint8_t *voca
 {
     for (int32_t p = 0; p < n; ++p)
         anchor[p] = (uint8_t)((tok[p] >= 0 && tok[p] < V) ? (vocab_anchor[tok[p]] != 0) : 0);
+}
+
+/* ======================================================================
+ * Policy options around the same selection (Sec. 3.3 budget partition; Sec. 2 /
+ * Sec. 4 baselines as settings; Sec. 5.2 robustness).
+ * ====================================================================== */
+
+/*
+ * Max-pooling of the attention scores before the selection, the clustering step
+ * of the SnapKV baseline (Sec. 2 "clusters attention patterns"): window of k
+ * positions (k odd) centred on p, clipped to the sequence:
+ *   out[p] = max { A[q] : |q - p| <= (k-1)/2, 0 <= q < n }.
+ */
+void ta_oracle_maxpool(const float *A, int32_t n, int32_t k, float *out)
+{
+    const int32_t r = (k - 1) / 2;
+    for (int32_t p = 0; p < n; ++p) {
+        float m = A[p];
+        for (int32_t q = p - r; q <= p + r; ++q)
+            if (q >= 0 && q < n && A[q] > m)
+                m = A[q];
+        out[p] = m;
+    }
+}
+
+/*
+ * Selection with a fixed budget partition (Sec. 3.3): K = K_main + K_protected.
+ * The protected pool holds the k_protected sponsored tokens that rank first under
+ * (u, position) - all of them if there are fewer; the main pool holds the mandatory
+ * tokens (sinks, recent window) and fills its remaining K - mandatory - protected
+ * slots with the best of ALL other tokens under (u, position), sponsored or not
+ * ("selected by utility score").  Unused protected slots return to the main pool.
+ * k_protected = 0 is the strict configuration of the ablation (K_main = K);
+ * k_protected >= number of sponsored tokens is the elastic reading of
+ * ta_oracle_select whenever the sponsored tokens fit.
+ */
+int32_t ta_oracle_select_partition(const float *A, const uint8_t *anchor,
+                                   const uint8_t *spons, const float *V,
+                                   int32_t n, int32_t K, int32_t k_protected,
+                                   int32_t n_sink, int32_t n_recent,
+                                   float alpha, float beta, float gamma, int32_t *idx)
+{
+    int32_t cnt = K < n ? K : n;
+    if (cnt <= 0)
+        return 0;
+    float *u = (float *)malloc(sizeof(float) * (size_t)n);
+    ta_oracle_key *keys = (ta_oracle_key *)malloc(sizeof(ta_oracle_key) * (size_t)n);
+    ta_oracle_utility(A, anchor, V, n, alpha, beta, gamma, u);
+    /* pass 1: mandatory tokens first, then sponsored by (u, position), then the rest */
+    int32_t mandatory = 0;
+    for (int32_t p = 0; p < n; ++p) {
+        int32_t cls = 0;
+        if (p < n_sink || p >= n - n_recent) {
+            cls = 2;
+            ++mandatory;
+        } else if (spons[p])
+            cls = 1;
+        keys[p].cls = cls;
+        keys[p].u = u[p];
+        keys[p].pos = p;
+    }
+    qsort(keys, (size_t)n, sizeof(ta_oracle_key), key_before);
+    int32_t sponsored = 0;
+    for (int32_t r = mandatory; r < n && keys[r].cls == 1; ++r)
+        ++sponsored;
+    int32_t prot = k_protected < sponsored ? k_protected : sponsored;
+    if (prot > cnt - mandatory)
+        prot = cnt - mandatory > 0 ? cnt - mandatory : 0;
+    /* pass 2: everything after the mandatory and protected tokens competes by (u, position) alone */
+    for (int32_t r = mandatory + prot; r < n; ++r)
+        keys[r].cls = 0;
+    if (mandatory + prot < n)
+        qsort(keys + mandatory + prot, (size_t)(n - mandatory - prot), sizeof(ta_oracle_key), key_before);
+    for (int32_t r = 0; r < cnt; ++r)
+        idx[r] = keys[r].pos;
+    qsort(idx, (size_t)cnt, sizeof(int32_t), int_ascending);
+    free(keys);
+    free(u);
+    return cnt;
+}
+
+/*
+ * Per-layer budgets of the PyramidKV baseline (Sec. 2 "allocates budgets pyramidally
+ * across transformer layers"): an arithmetic progression that falls from the first
+ * layer to the last, ends at k_min and has mean K, i.e. starts at 2K - k_min:
+ *   K_l = round-to-nearest( (2K - k_min) - l * (2K - 2 k_min) / (layers - 1) ),
+ * with the rounding residue added to layer 0 so that the budgets sum to layers * K.
+ * One layer: K.  Requires 1 <= k_min <= K.
+ */
+void ta_oracle_layer_budgets(int32_t layers, int32_t K, int32_t k_min, int32_t *out)
+{
+    if (layers == 1) {
+        out[0] = K;
+        return;
+    }
+    const double top = 2.0 * K - k_min, step = (2.0 * K - 2.0 * k_min) / (layers - 1);
+    int64_t sum = 0;
+    for (int32_t l = 0; l < layers; ++l) {
+        out[l] = (int32_t)floor(top - l * step + 0.5);
+        sum += out[l];
+    }
+    out[0] += (int32_t)((int64_t)layers * K - sum);
+}
+
+/*
+ * Allowlist filtering (Sec. 5.2: adversarial anchor injection is answered by an
+ * allowlist): an anchor only counts where allow[p] != 0 - positions of untrusted
+ * spans can neither be anchors nor sponsor anything.
+ */
+void ta_oracle_allow_filter(const uint8_t *anchor, const uint8_t *allow, int32_t n, uint8_t *out)
+{
+    for (int32_t p = 0; p < n; ++p)
+        out[p] = (uint8_t)(anchor[p] != 0 && allow[p] != 0);
 }
 

@@ -59,6 +59,14 @@ def _load():
         lib.ta_oracle_detect.restype = None
         lib.ta_oracle_confidence_anchors.argtypes = [vp, i32, f32, i32, f32, f32, vp, vp]
         lib.ta_oracle_confidence_anchors.restype = None
+        lib.ta_oracle_maxpool.argtypes = [vp, i32, i32, vp]
+        lib.ta_oracle_maxpool.restype = None
+        lib.ta_oracle_select_partition.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, f32, vp]
+        lib.ta_oracle_select_partition.restype = i32
+        lib.ta_oracle_layer_budgets.argtypes = [i32, i32, i32, vp]
+        lib.ta_oracle_layer_budgets.restype = None
+        lib.ta_oracle_allow_filter.argtypes = [vp, vp, i32, vp]
+        lib.ta_oracle_allow_filter.restype = None
         lib.ta_oracle_cosine_sim.argtypes = [vp, vp, i32, i32, i32, vp]
         lib.ta_oracle_cosine_sim.restype = None
         lib.ta_oracle_threshold_anchors.argtypes = [vp, i32, f32, vp]
@@ -202,6 +210,46 @@ def lookup_anchors(tok, vocab_anchor):
     anchor = np.zeros(tok.shape[0], np.uint8)
     _load().ta_oracle_lookup_anchors(_p(tok), tok.shape[0], _p(va), va.shape[0], _p(anchor))
     return anchor
+
+
+def maxpool(A, k):
+    """out[p] = max of A over the k positions centred on p (clipped to the sequence); k odd."""
+    A = _c(A, np.float32)
+    assert k >= 1 and k % 2 == 1
+    out = np.zeros_like(A)
+    _load().ta_oracle_maxpool(_p(A), A.shape[0], int(k), _p(out))
+    return out
+
+
+def select_partition(A, anchor, spons, V, K, k_protected, n_sink, n_recent, alpha=1.0, beta=0.5, gamma=0.3):
+    """Retained positions (ascending) under the fixed partition K = K_main + K_protected (Sec. 3.3)."""
+    anchor = _c(anchor, np.uint8)
+    spons = _c(spons, np.uint8)
+    V = _c(V, np.float32)
+    n = anchor.shape[0]
+    a = None if A is None else _c(A, np.float32)
+    if a is None:
+        assert alpha == 0.0
+    idx = np.zeros(max(min(K, n), 1), np.int32)
+    cnt = _load().ta_oracle_select_partition(_p(a), _p(anchor), _p(spons), _p(V), n, int(K), int(k_protected),
+                                             int(n_sink), int(n_recent), float(alpha), float(beta), float(gamma),
+                                             _p(idx))
+    return idx[:cnt].copy()
+
+
+def layer_budgets(layers, K, k_min):
+    """Per-layer budgets falling arithmetically from 2K - k_min to k_min with mean K."""
+    out = np.zeros(layers, np.int32)
+    _load().ta_oracle_layer_budgets(int(layers), int(K), int(k_min), _p(out))
+    return out
+
+
+def allow_filter(anchor, allow):
+    """Anchors that lie on allowed positions."""
+    anchor, allow = _c(anchor, np.uint8), _c(allow, np.uint8)
+    out = np.zeros_like(anchor)
+    _load().ta_oracle_allow_filter(_p(anchor), _p(allow), anchor.shape[0], _p(out))
+    return out
 
 
 def evict_sequence(tok, tab_ids, tab_len, L=6, B=15.0, rho=0.8, anchor_B=None):
