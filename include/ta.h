@@ -73,7 +73,34 @@ typedef struct ta_params {
     float gamma;        /* weight of the anchor indicator S_i (0.3)                       */
     int32_t causal;     /* 1: window query w sees keys 0..n-W+w; 0: every key             */
     float budget_decay; /* per-step decay of sponsor budgets (paper: 0.9); decode steps   */
+    /* Options around the same selection (baselines of Sec. 2 / Sec. 4 and the partition of
+     * Sec. 3.3 as settings).  Defaults: 1, -1, NULL, NULL.  The per-step form accepts only the
+     * defaults of pool_k and k_protected and ignores layer_K and allow. */
+    int32_t pool_k;      /* odd window (1, 3, 5, 7 or 9) of a max-pool applied to A along the sequence
+                            before the utility - the clustering step of SnapKV; 1 = none            */
+    int32_t k_protected; /* K_protected of Sec. 3.3: the protected pool holds the k_protected best
+                            sponsored tokens under (u, position); all other tokens that are not
+                            mandatory compete for the K_main = K - k_protected slots by (u, position)
+                            alone, mandatory tokens count against K_main, unused protected slots
+                            return to the main pool.  Negative: the elastic pool (every sponsored
+                            token outranks every plain one).  0: the strict configuration           */
+    const int32_t *layer_K; /* DEVICE int32 [layers] or NULL: budget of each layer (PyramidKV-style
+                            schedules, see ta_layer_budgets), clamped on the device to
+                            [max(1, n_sink + n_recent), K]; idx rows keep K entries, cnt says how
+                            many are valid                                                         */
+    const uint8_t *allow;   /* DEVICE uint8 [B][n] or NULL: allowlist of positions (Sec. 5.2): an
+                            anchor only counts where allow != 0                                    */
 } ta_params;
+
+/*
+ * Per-layer budgets of a pyramidal schedule (the PyramidKV baseline, Sec. 2): an arithmetic
+ * progression falling from layer 0 to the last layer, ending at k_min, with mean K:
+ *   K_l = round((2K - k_min) - l (2K - 2 k_min) / (layers - 1)), the rounding residue added
+ *   to layer 0 so that the budgets sum to layers * K.  One layer: K.
+ *   out HOST int32 [layers].  Pass max_l K_l (= out[0]) as K and a DEVICE copy as layer_K.
+ * Errors: NULL, SHAPE (layers < 1, k_min < 1, k_min > K).
+ */
+int32_t ta_layer_budgets(int32_t layers, int32_t K, int32_t k_min, int32_t *out);
 
 /*
  * Shapes and strides of the cache tensors.  Strides are in ELEMENTS (bf16).
@@ -108,7 +135,8 @@ size_t ta_workspace_bytes(const ta_layout *lay, const ta_params *prm);
  *                each term B_i * (float)rho^k rounded to fp32 and added in fp32
  *                in order of increasing k = j - i; spans are clipped at seq_len.
  * spons[b][j]  = 1 iff an anchor lies in [j-L, j-1]  (<=> vouch > 0 for B > 0).
- * Positions >= seq_len[b] get 0 in all three outputs.
+ * Positions >= seq_len[b] get 0 in all three outputs.  With prm->allow set, a
+ * match only counts where allow[b][p] != 0.
  *
  *   tok       DEVICE int32 [B][n]
  *   seq_len   DEVICE int32 [B] or NULL
@@ -227,7 +255,9 @@ int32_t ta_score(const void *Q, const void *K, const ta_layout *lay, const int32
  *   cnt     DEVICE int32 [layers][batch][hkv]    (out; = min(K, len))
  * The retained set of TA-Fast does not depend on layer or head: call with
  * layers = hkv = 1 and share idx across units (see ta_compact).
- * Errors: NULL, SHAPE, BUDGET.
+ * prm->pool_k, prm->k_protected and prm->layer_K modify the selection as described
+ * at ta_params.
+ * Errors: NULL, SHAPE (also pool_k not in {1,3,5,7,9}), BUDGET.
  */
 int32_t ta_select(const float *A, const uint8_t *anchor, const uint8_t *spons, const float *vouch,
                   const int32_t *seq_len, int32_t layers, int32_t batch, int32_t hkv, int32_t n,

@@ -25,7 +25,7 @@ TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
 TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
-           "ta_lookup_anchors", "ta_score", "ta_select", "ta_compact",
+           "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_select", "ta_compact",
            "ta_evict", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
@@ -42,7 +42,9 @@ class CParams(ctypes.Structure):
     _fields_ = [("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32), ("span_L", ctypes.c_int32),
                 ("sponsor_B", ctypes.c_float), ("rho", ctypes.c_double),
                 ("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("gamma", ctypes.c_float),
-                ("causal", ctypes.c_int32), ("budget_decay", ctypes.c_float)]
+                ("causal", ctypes.c_int32), ("budget_decay", ctypes.c_float),
+                ("pool_k", ctypes.c_int32), ("k_protected", ctypes.c_int32),
+                ("layer_K", ctypes.c_void_p), ("allow", ctypes.c_void_p)]
 
 
 class CDecodeState(ctypes.Structure):
@@ -74,10 +76,19 @@ class Params:
     gamma: float = 0.3
     causal: bool = True
     budget_decay: float = 0.9
+    pool_k: int = 1                              # max-pool window over A (SnapKV clustering), 1 = none
+    k_protected: int = -1                        # K_protected of Sec. 3.3, negative = elastic pool
+    layer_K: Optional[torch.Tensor] = None       # device int32 [layers]: per-layer budgets
+    allow: Optional[torch.Tensor] = None         # device uint8 [B][n]: allowlist of positions
 
     def c(self) -> CParams:
+        for t, dt in ((self.layer_K, torch.int32), (self.allow, torch.uint8)):
+            assert t is None or (t.dtype == dt and t.is_contiguous())
         return CParams(self.n_sink, self.n_recent, self.span_L, self.sponsor_B, self.rho,
-                       self.alpha, self.beta, self.gamma, 1 if self.causal else 0, self.budget_decay)
+                       self.alpha, self.beta, self.gamma, 1 if self.causal else 0, self.budget_decay,
+                       self.pool_k, self.k_protected,
+                       None if self.layer_K is None else self.layer_K.data_ptr(),
+                       None if self.allow is None else self.allow.data_ptr())
 
 
 _lib = None
@@ -99,6 +110,8 @@ def lib():
         L.ta_detect_anchors.argtypes = [vp, ctypes.c_int64, vp, vp, vp, i32, i32, i32, i32,
                                         ctypes.c_float, i32, ctypes.c_float, vp, vp, vp, vp, vp]
         L.ta_detect_anchors.restype = i32
+        L.ta_layer_budgets.argtypes = [i32, i32, i32, vp]
+        L.ta_layer_budgets.restype = i32
         L.ta_embed_anchors.argtypes = [vp, ctypes.c_int64, vp, i32, vp, i32, i32, i32, ctypes.c_float, vp, vp, vp]
         L.ta_embed_anchors.restype = i32
         L.ta_lookup_anchors.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
@@ -216,6 +229,13 @@ def ta_detect_anchors(h, W1, W2, params: Params, thr: float, rank: bool, scale: 
                                  _ptr(conf), _ptr(anchor), _ptr(anchor_B), _stream(stream))
     _check(rc, "ta_detect_anchors")
     return conf, anchor, anchor_B
+
+
+def ta_layer_budgets(layers: int, K: int, k_min: int) -> np.ndarray:
+    """Pyramidal per-layer budgets (host int32 [layers]) with mean K that fall to k_min."""
+    out = np.zeros(layers, np.int32)
+    _check(lib().ta_layer_budgets(layers, K, k_min, out.ctypes.data), "ta_layer_budgets")
+    return out
 
 
 def ta_embed_anchors(x, C, tau: float, seq_len=None, out=None, stream=None):

@@ -28,6 +28,9 @@ int32_t check_params(const ta_params* prm)
     if (!isfinite(prm->alpha) || !isfinite(prm->beta) || !isfinite(prm->gamma) ||
         !isfinite(prm->sponsor_B))
         return TA_ERR_SHAPE;
+    if (prm->pool_k != 0 && prm->pool_k != 1 && prm->pool_k != 3 && prm->pool_k != 5 && prm->pool_k != 7 &&
+        prm->pool_k != 9)
+        return TA_ERR_SHAPE;
     return TA_OK;
 }
 
@@ -171,6 +174,24 @@ size_t ta_workspace_bytes(const ta_layout* lay, const ta_params* prm)
     return workspace_bytes(lay);
 }
 
+int32_t ta_layer_budgets(int32_t layers, int32_t K, int32_t k_min, int32_t* out)
+{
+    if (!out) return TA_ERR_NULL;
+    if (layers < 1 || k_min < 1 || k_min > K) return TA_ERR_SHAPE;
+    if (layers == 1) {
+        out[0] = K;
+        return TA_OK;
+    }
+    const double first = 2.0 * K - k_min, fall = (2.0 * K - 2.0 * k_min) / (layers - 1);
+    int64_t total = 0;
+    for (int32_t l = 0; l < layers; ++l) {
+        out[l] = (int32_t)floor(first - fall * l + 0.5);
+        total += out[l];
+    }
+    out[0] += (int32_t)((int64_t)layers * K - total);        // rounding residue
+    return TA_OK;
+}
+
 int32_t ta_match_anchors(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
                          const int32_t* tab_ids, const int32_t* tab_len, int32_t E,
                          const float* anchor_B, const ta_params* prm,
@@ -181,7 +202,7 @@ int32_t ta_match_anchors(const int32_t* tok, const int32_t* seq_len, int32_t B, 
     ta::MatchTable tab;
     rc = build_table(tab_ids, tab_len, E, prm, &tab);
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_match(tok, seq_len, B, n, tab, anchor_B, anchor, spons, vouch,
+    return hip_status(ta::launch_match(tok, seq_len, B, n, tab, anchor_B, prm->allow, anchor, spons, vouch,
                                        (hipStream_t)stream));
 }
 
@@ -241,7 +262,7 @@ int32_t ta_expand_vouchers(const uint8_t* anchor, const float* anchor_B, const i
     ta::MatchTable tab;
     rc = build_table(nullptr, nullptr, 0, prm, &tab);
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_expand(anchor, anchor_B, seq_len, B, n, tab, spons, vouch, (hipStream_t)stream));
+    return hip_status(ta::launch_expand(anchor, anchor_B, prm->allow, seq_len, B, n, tab, spons, vouch, (hipStream_t)stream));
 }
 
 int32_t ta_score(const void* Q, const void* K, const ta_layout* lay, const int32_t* seq_len,
@@ -295,6 +316,7 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
         rc = check_score(Q, Kin, lay, prm, A, ws, ws_bytes);
         if (rc != TA_OK) return rc;
     }
+    if (!scored && prm->layer_K) return TA_ERR_SHAPE;       // one shared retained set cannot have per-layer sizes
     const int32_t sel_layers = scored ? lay->layers : 1;
     const int32_t sel_hkv = scored ? lay->hkv : 1;
     rc = check_select(A, anchor, spons, vouch, sel_layers, lay->batch, sel_hkv, lay->n, K, prm, idx, cnt);
@@ -305,11 +327,11 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
     hipStream_t st = (hipStream_t)stream;
     if (scored) {
         // the match rides along with the first sweep of the scores (one launch fewer in front of them)
-        const ta::MatchRider rider = {tok, anchor_B, anchor, spons, vouch, &tab};
+        const ta::MatchRider rider = {tok, anchor_B, prm->allow, anchor, spons, vouch, &tab};
         rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, &rider, st));
         if (rc != TA_OK) return rc;
     } else {
-        rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, anchor, spons, vouch, st));
+        rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, prm->allow, anchor, spons, vouch, st));
         if (rc != TA_OK) return rc;
     }
     rc = hip_status(ta::launch_select(A, anchor, spons, vouch, seq_len, sel_layers, lay->batch, sel_hkv,
@@ -346,6 +368,7 @@ int32_t ta_decode_step(const ta_decode_state* st, const int32_t* new_tok, const 
     if (!new_tok || !k_new || !v_new) return TA_ERR_NULL;
     if (prm->alpha != 0.0f && !q_new) return TA_ERR_NULL;
     if (!isfinite(prm->budget_decay)) return TA_ERR_SHAPE;
+    if (prm->pool_k > 1 || prm->k_protected >= 0) return TA_ERR_SHAPE;   // options of the one-shot selection only
     if (!aligned16(k_new) || !aligned16(v_new) || (q_new && !aligned16(q_new))) return TA_ERR_ALIGN;
     rc = check_budget(prm, st->K);
     if (rc != TA_OK) return rc;

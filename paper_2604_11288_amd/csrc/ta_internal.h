@@ -19,12 +19,12 @@ struct MatchTable {
 };
 
 hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
-                        const MatchTable& tab, const float* anchor_B,
+                        const MatchTable& tab, const float* anchor_B, const uint8_t* allow,
                         uint8_t* anchor, uint8_t* spons, float* vouch, hipStream_t st);
 
 // Step 2 alone from given anchor flags (read, not written); tab supplies L, B and the powers only.
-hipError_t launch_expand(const uint8_t* anchor, const float* anchor_B, const int32_t* seq_len, int32_t B, int32_t n,
-                         const MatchTable& tab, uint8_t* spons, float* vouch, hipStream_t st);
+hipError_t launch_expand(const uint8_t* anchor, const float* anchor_B, const uint8_t* allow, const int32_t* seq_len,
+                         int32_t B, int32_t n, const MatchTable& tab, uint8_t* spons, float* vouch, hipStream_t st);
 
 // ---- learned anchor detection -------------------------------------------------
 // conf = sigmoid(W2 . GELU(W1 . h)) per position, anchor = conf > thr, budget B or scale * conf.
@@ -45,6 +45,7 @@ hipError_t launch_lookup(const int32_t* tok, const int32_t* seq_len, int32_t B, 
 struct MatchRider {
     const int32_t* tok;
     const float* anchor_B;
+    const uint8_t* allow;
     uint8_t* anchor;
     uint8_t* spons;
     float* vouch;

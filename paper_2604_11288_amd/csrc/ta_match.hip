@@ -30,6 +30,7 @@ expand_mask_kernel(MatchArgs a, MatchTable tab)
     nb = nb < 0 ? 0 : (nb > n ? n : nb);
     const int32_t first = tile * MATCH_TILE - MATCH_MARGIN;
     const uint8_t* flags = a.anchor + (size_t)b * (size_t)n;
+    const uint8_t* allow = a.allow ? a.allow + (size_t)b * (size_t)n : nullptr;
     if (tid < WORDS) s_bits[tid] = 0u;
     __syncthreads();
     for (int g = tid; g < (MATCH_TILE + MATCH_MARGIN) / 4; g += MATCH_THREADS) {
@@ -44,6 +45,11 @@ expand_mask_kernel(MatchArgs a, MatchTable tab)
                 const int32_t q = q0 + c;
                 if (q >= 0 && q < nb && flags[q]) nib |= 1u << c;
             }
+        }
+        if (nib && allow) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if ((nib >> c) & 1u) nib &= ~((allow[q0 + c] ? 0u : 1u) << c);   // set bits are inside [0, nb)
         }
         if (nib) atomicOr(&s_bits[(4 * g) >> 5], nib << ((4 * g) & 31));
     }
@@ -73,12 +79,13 @@ lookup_kernel(const int32_t* tok, const int32_t* seq_len, int32_t n, const uint8
 }  // namespace
 
 MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
-                          const float* anchor_B, uint8_t* anchor, uint8_t* spons, float* vouch)
+                          const float* anchor_B, const uint8_t* allow, uint8_t* anchor, uint8_t* spons, float* vouch)
 {
     MatchArgs a;
     a.tok = tok;
     a.seq_len = seq_len;
     a.anchor_B = anchor_B;
+    a.allow = allow;
     a.anchor = anchor;
     a.spons = spons;
     a.vouch = vouch;
@@ -91,19 +98,19 @@ MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B,
 }
 
 hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
-                        const MatchTable& tab, const float* anchor_B,
+                        const MatchTable& tab, const float* anchor_B, const uint8_t* allow,
                         uint8_t* anchor, uint8_t* spons, float* vouch, hipStream_t st)
 {
-    const MatchArgs a = make_match_args(tok, seq_len, B, n, anchor_B, anchor, spons, vouch);
+    const MatchArgs a = make_match_args(tok, seq_len, B, n, anchor_B, allow, anchor, spons, vouch);
     dim3 grid((unsigned)a.tiles, (unsigned)B);
     hipLaunchKernelGGL(match_expand_kernel, grid, dim3(MATCH_THREADS), 0, st, a, tab);
     return hipGetLastError();
 }
 
-hipError_t launch_expand(const uint8_t* anchor, const float* anchor_B, const int32_t* seq_len, int32_t B, int32_t n,
-                         const MatchTable& tab, uint8_t* spons, float* vouch, hipStream_t st)
+hipError_t launch_expand(const uint8_t* anchor, const float* anchor_B, const uint8_t* allow, const int32_t* seq_len,
+                         int32_t B, int32_t n, const MatchTable& tab, uint8_t* spons, float* vouch, hipStream_t st)
 {
-    const MatchArgs a = make_match_args(nullptr, seq_len, B, n, anchor_B, const_cast<uint8_t*>(anchor), spons, vouch);
+    const MatchArgs a = make_match_args(nullptr, seq_len, B, n, anchor_B, allow, const_cast<uint8_t*>(anchor), spons, vouch);
     dim3 grid((unsigned)a.tiles, (unsigned)B);
     hipLaunchKernelGGL(expand_mask_kernel, grid, dim3(MATCH_THREADS), 0, st, a, tab);
     return hipGetLastError();

@@ -31,6 +31,7 @@ struct MatchArgs {
     const int32_t* tok;
     const int32_t* seq_len;
     const float* anchor_B;
+    const uint8_t* allow;                        // allowlist of positions, or null
     uint8_t* anchor;
     uint8_t* spons;
     float* vouch;
@@ -50,7 +51,7 @@ struct MatchLds {
 static_assert(MATCH_MARGIN >= TA_MAX_SPAN && MATCH_MARGIN % 64 == 0, "flag margin");
 
 MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B, int32_t n,
-                          const float* anchor_B, uint8_t* anchor, uint8_t* spons, float* vouch);
+                          const float* anchor_B, const uint8_t* allow, uint8_t* anchor, uint8_t* spons, float* vouch);
 
 __device__ __forceinline__ uint32_t filter_slot(int32_t t) { return (uint32_t)t & (FILTER_BITS - 1); }
 
@@ -114,6 +115,7 @@ __device__ __forceinline__ void match_flags_tile(const MatchArgs& a, const Match
         if (q >= 0 && q < nb) {
             const uint32_t h = filter_slot(s_tok[q - base]);
             cand = ((s_filter[h >> 5] >> (h & 31)) & 1u) != 0u;
+            if (cand && a.allow) cand = a.allow[row + (size_t)q] != 0;     // a match counts on allowed positions only
         }
         unsigned long long todo = __ballot(cand), m = 0ull;
         while (todo) {

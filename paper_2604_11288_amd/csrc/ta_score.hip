@@ -529,7 +529,7 @@ void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t 
     const unsigned blocks = (unsigned)(8ll * a.units_per_xcd * a.nchunks);
     if (rider) {
         RiderArgs r;
-        r.m = make_match_args(rider->tok, a.seq_len, a.batch, a.n, rider->anchor_B, rider->anchor, rider->spons,
+        r.m = make_match_args(rider->tok, a.seq_len, a.batch, a.n, rider->anchor_B, rider->allow, rider->anchor, rider->spons,
                               rider->vouch);
         r.tab = *rider->tab;
         r.score_blocks = blocks;

@@ -13,6 +13,15 @@
 // in LDS, followed - only if several positions tie with the threshold u - by a
 // radix select over their positions.  The retained positions are then written
 // in ascending order with a ballot/popcount stream compaction.
+//
+// Options around the same selection (baselines and Sec. 3.3 as settings):
+//   pool_r       the scores are max-pooled over 2 pool_r + 1 positions before the utility
+//                (the clustering step of SnapKV)
+//   layer_K      per-layer budgets (PyramidKV); idx rows keep the common capacity K
+//   k_protected  fixed partition K = K_main + K_protected (template CAPPED): the protected pool
+//                takes the k_protected best sponsored tokens, everything else that is not
+//                mandatory competes for the main pool by (u, position) alone - two threshold
+//                searches instead of one
 #include <mutex>
 
 #include "ta_internal.h"
@@ -33,9 +42,11 @@ struct SelectArgs {
     const uint8_t* spons;
     const float* vouch;
     const int32_t* seq_len;
+    const int32_t* layer_K;
     int32_t* idx;
     int32_t* cnt;
     int32_t batch, hkv, n, K;
+    int32_t pool_r, k_protected;
     int32_t units, units_per_xcd;
     int32_t vec_ok;
     int32_t n_sink, n_recent;
@@ -131,7 +142,7 @@ struct Quad {
     uint8_t an[4];
 };
 
-template <bool CACHED>
+template <bool CACHED, bool CAPPED>
 __global__ void __launch_bounds__(SEL_THREADS)
 select_kernel(SelectArgs a)
 {
@@ -149,10 +160,17 @@ select_kernel(SelectArgs a)
     const int32_t unit = (int32_t)(blockIdx.x & 7u) * a.units_per_xcd + (int32_t)(blockIdx.x >> 3);
     if (unit >= a.units) return;
     const int32_t b = (unit / a.hkv) % a.batch;
-    const int32_t n = a.n, K = a.K;
+    const int32_t n = a.n;
+    int32_t K = a.K;                                         // capacity of an idx row; the budget unless a layer has its own
+    if (a.layer_K) {
+        int32_t lo = a.n_sink + a.n_recent;                  // the mandatory tokens must fit (validated: <= a.K)
+        lo = lo < 1 ? 1 : lo;
+        const int32_t kl = a.layer_K[unit / (a.batch * a.hkv)];
+        K = kl < lo ? lo : (kl > K ? K : kl);
+    }
     int32_t nb = a.seq_len ? a.seq_len[b] : n;
     nb = nb < 0 ? 0 : (nb > n ? n : nb);
-    int32_t* idx = a.idx + (size_t)unit * (size_t)K;
+    int32_t* idx = a.idx + (size_t)unit * (size_t)a.K;
 
     if (nb <= K) {                                           // nothing to evict
         for (int32_t p = tid; p < nb; p += SEL_THREADS) idx[p] = p;
@@ -194,10 +212,40 @@ select_kernel(SelectArgs a)
             for (int c = 0; c < 4; ++c) out[c] = (4 * q + c < nb) ? src[4 * q + c] : 0.0f;
         }
     };
+    // scores of a quad, max-pooled over [p - r, p + r] clipped to the sequence (r <= 4: the quad and its neighbours)
+    auto load_pooled = [&](int32_t q, float (&out)[4]) {
+        float w[12];
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            const int32_t qq = q - 1 + j;
+            if (vec && qq >= 0 && 4 * qq + 3 < n) {
+                const float4 f = *reinterpret_cast<const float4*>(A + 4 * qq);
+                w[4 * j + 0] = f.x; w[4 * j + 1] = f.y; w[4 * j + 2] = f.z; w[4 * j + 3] = f.w;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (4 * qq + c >= nb) w[4 * j + c] = -INFINITY;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int32_t p = 4 * qq + c;
+                    w[4 * j + c] = (p >= 0 && p < nb) ? A[p] : -INFINITY;
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float m = w[4 + c];
+#pragma unroll
+            for (int d = 1; d <= 4; ++d)
+                if (d <= a.pool_r) m = fmaxf(m, fmaxf(w[4 + c - d], w[4 + c + d]));
+            out[c] = (4 * q + c < nb) ? m : 0.0f;
+        }
+    };
     auto load_rest = [&](int32_t q, Quad& x) {               // everything but the sponsor flags
         load_flags(anchor, q, x.an);
         load_floats(vouch, q, x.v);
-        if (use_A) load_floats(A, q, x.A);
+        if (use_A && a.pool_r > 0) load_pooled(q, x.A);
+        else if (use_A) load_floats(A, q, x.A);
         else {
 #pragma unroll
             for (int c = 0; c < 4; ++c) x.A[c] = 0.0f;
@@ -227,11 +275,19 @@ select_kernel(SelectArgs a)
     const int bclass = (c2 + c1 <= K) ? 0 : 1;
     const int32_t R = bclass == 0 ? K - c2 - c1 : K - c2;    // slots for the boundary class
     const float nf = (float)nb;
+    // fixed partition: P sponsored tokens are protected, M more slots go to the best of everything else
+    int32_t P = 0;
+    if (CAPPED) {
+        P = a.k_protected < c1 ? a.k_protected : c1;
+        P = P < K - c2 ? P : K - c2;
+    }
+    const int32_t M = K - c2 - P;
 
-    // order-preserving key of position p if it belongs to the boundary class, else 0
+    // order-preserving key of position p if it belongs to the boundary class (fixed partition:
+    // if it is not mandatory), else 0
     auto key_of = [&](int32_t p, float Ap, uint8_t an, uint8_t sp, float v) -> uint32_t {
         if (p < ns || p >= rs) return 0u;
-        if ((sp != 0) != (bclass == 1)) return 0u;
+        if (!CAPPED && (sp != 0) != (bclass == 1)) return 0u;
         float r = __fdiv_rn((float)(p + 1), nf);
         float t = use_A ? __fmul_rn(a.alpha, Ap) : 0.0f;
         t = __fadd_rn(t, __fmul_rn(a.beta, r));
@@ -272,16 +328,18 @@ select_kernel(SelectArgs a)
     __syncthreads();
 
     // ---- threshold search ------------------------------------------------
-    uint32_t T = 0xFFFFFFFFu;     // boundary-class position p is kept iff key > T, or key == T and p >= Pt
-    int32_t Pt = 0x7FFFFFFF;
-    if (R > 0) {
-        uint32_t prefix = 0, need = (uint32_t)R;
+    // Among the positions `member` admits (it gets a quad, its keys, and clears the keys of the
+    // others), finds the `want`-th largest (key, position): a member is in the top `want` iff
+    // key > T, or key == T and position >= Pt.
+    auto find_threshold = [&](auto&& member, uint32_t want, uint32_t& T, int32_t& Pt) {
+        uint32_t prefix = 0, need = want;
         bool done = false;
         for (int pass = 0; pass < 4 && !done; ++pass) {
             const int shift = 24 - 8 * pass;
             for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
                 uint32_t k4[4];
                 keys_at(q, k4);
+                member(q, k4);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const uint32_t k = k4[c];
@@ -308,6 +366,7 @@ select_kernel(SelectArgs a)
                     for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
                         uint32_t k4[4];
                         keys_at(q, k4);
+                        member(q, k4);
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
                             const uint32_t p = (uint32_t)(4 * q + c);
@@ -324,6 +383,38 @@ select_kernel(SelectArgs a)
                 done = true;
             }
         }
+    };
+
+    uint32_t T = 0xFFFFFFFFu;     // boundary-class position p is kept iff key > T, or key == T and p >= Pt
+    int32_t Pt = 0x7FFFFFFF;
+    uint32_t T1 = 0xFFFFFFFFu;    // fixed partition: a sponsored position is protected iff key > T1, or key == T1 and p >= Pt1
+    int32_t Pt1 = 0x7FFFFFFF;
+    if (!CAPPED) {
+        if (R > 0) find_threshold([](int32_t, uint32_t (&)[4]) {}, (uint32_t)R, T, Pt);
+    } else {
+        if (P == c1) {                                       // every sponsored token is protected
+            T1 = 0u;
+            Pt1 = 0;
+        } else if (P > 0) {
+            find_threshold([&](int32_t q, uint32_t (&k4)[4]) {
+                uint8_t sp[4];
+                load_flags(spons, q, sp);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (!sp[c]) k4[c] = 0u;
+            }, (uint32_t)P, T1, Pt1);
+        }
+        if (M > 0) {                                         // more candidates than M remain: nb > K
+            find_threshold([&](int32_t q, uint32_t (&k4)[4]) {
+                uint8_t sp[4];
+                load_flags(spons, q, sp);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int32_t p = 4 * q + c;
+                    if (sp[c] && (k4[c] > T1 || (k4[c] == T1 && p >= Pt1))) k4[c] = 0u;   // protected: not a candidate
+                }
+            }, (uint32_t)M, T, Pt);
+        }
     }
 
     // ---- ascending write-out: one scan over per-quad counts per round of 4096 positions ----
@@ -339,7 +430,7 @@ select_kernel(SelectArgs a)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int32_t p = 4 * q + c;
-                need_keys = need_keys || (p >= ns && p < rs && ((sp[c] != 0) == (bclass == 1)));
+                need_keys = need_keys || (p >= ns && p < rs && (CAPPED || (sp[c] != 0) == (bclass == 1)));
             }
             if (need_keys) keys_at(q, k4);
 #pragma unroll
@@ -348,6 +439,9 @@ select_kernel(SelectArgs a)
                 bool kp = false;
                 if (p < nb) {
                     if (p < ns || p >= rs) kp = true;
+                    else if (CAPPED)
+                        kp = (sp[c] && (k4[c] > T1 || (k4[c] == T1 && p >= Pt1))) ||     // protected pool
+                             (k4[c] > T) || (k4[c] == T && p >= Pt);                     // main pool
                     else if ((sp[c] != 0) != (bclass == 1)) kp = sp[c] != 0;   // class 1 above the boundary class, class 0 below it
                     else kp = (k4[c] > T) || (k4[c] == T && p >= Pt);
                 }
@@ -398,6 +492,9 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
     a.spons = spons;
     a.vouch = vouch;
     a.seq_len = seq_len;
+    a.layer_K = prm.layer_K;
+    a.pool_r = (prm.alpha != 0.0f && prm.pool_k > 1) ? (prm.pool_k - 1) / 2 : 0;
+    a.k_protected = prm.k_protected;
     a.idx = idx;
     a.cnt = cnt;
     a.batch = batch;
@@ -415,18 +512,25 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
     a.vec_ok = (n % 4 == 0) && ((uintptr_t)anchor % 4 == 0) && ((uintptr_t)spons % 4 == 0) &&
                ((uintptr_t)vouch % 16 == 0) && (a.A == nullptr || (uintptr_t)a.A % 16 == 0);
     const unsigned blocks = 8u * (unsigned)a.units_per_xcd;
+    const bool capped = prm.k_protected >= 0;
     if (n <= SEL_CACHE_MAX_N) {
         hipError_t attr_err = hipSuccess;
         std::call_once(g_attr_once, [&]() {
-            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true>),
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
+            if (attr_err == hipSuccess)
+                attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
         });
         if (attr_err != hipSuccess) return attr_err;
-        hipLaunchKernelGGL(select_kernel<true>, dim3(blocks), dim3(SEL_THREADS),
-                           (size_t)((n + 3) / 4 * 4) * sizeof(uint32_t), st, a);
+        const size_t lds = (size_t)((n + 3) / 4 * 4) * sizeof(uint32_t);
+        if (capped) hipLaunchKernelGGL((select_kernel<true, true>), dim3(blocks), dim3(SEL_THREADS), lds, st, a);
+        else hipLaunchKernelGGL((select_kernel<true, false>), dim3(blocks), dim3(SEL_THREADS), lds, st, a);
     } else {
-        hipLaunchKernelGGL(select_kernel<false>, dim3(blocks), dim3(SEL_THREADS), 0, st, a);
+        if (capped) hipLaunchKernelGGL((select_kernel<false, true>), dim3(blocks), dim3(SEL_THREADS), 0, st, a);
+        else hipLaunchKernelGGL((select_kernel<false, false>), dim3(blocks), dim3(SEL_THREADS), 0, st, a);
     }
     return hipGetLastError();
 }

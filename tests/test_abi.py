@@ -191,3 +191,13 @@ def test_decode_error_paths(L):
     assert L.ta_decode_step(*a) == tb.TA_ERR_ALIGN
     a = step(); a[1] = None
     assert L.ta_decode_step(*a) == tb.TA_ERR_NULL
+
+
+def test_layer_budgets_host_function_matches_oracle(L):
+    from oracle import ta_oracle as ora
+    for layers, K, kmin in ((32, 1024, 64), (32, 16, 4), (5, 100, 1), (1, 50, 10), (28, 333, 17), (2, 7, 7)):
+        assert np.array_equal(tb.ta_layer_budgets(layers, K, kmin), ora.layer_budgets(layers, K, kmin))
+    out = np.zeros(4, np.int32)
+    assert L.ta_layer_budgets(4, 10, 11, out.ctypes.data) == tb.TA_ERR_SHAPE       # k_min > K
+    assert L.ta_layer_budgets(0, 10, 1, out.ctypes.data) == tb.TA_ERR_SHAPE
+    assert L.ta_layer_budgets(4, 10, 1, None) == tb.TA_ERR_NULL

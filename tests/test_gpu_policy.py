@@ -1,0 +1,222 @@
+"""GPU parity of the policy options around the selection: max-pooled scores (SnapKV clustering
+step), the fixed budget partition K_main + K_protected of Sec. 3.3, per-layer budgets
+(PyramidKV), the allowlist of Sec. 5.2, and the baselines of Sec. 4 as settings.  Everything
+here is index / flag work given the same scores: bit-exact against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_11288_amd as ta
+from oracle import ta_oracle as ora
+from paper_2604_11288_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _prm(w, **kw):
+    base = dict(n_sink=w.n_sink, n_recent=w.n_recent, span_L=w.span_L, sponsor_B=w.sponsor_B,
+                rho=w.rho, alpha=w.alpha, beta=w.beta, gamma=w.gamma)
+    base.update(kw)
+    return ta.Params(**base)
+
+
+def _scores(rng, shape, mode):
+    if mode == "ties":
+        return np.round(rng.random(shape) * 4, 1).astype(np.float32)
+    if mode == "heavy":                       # attention far above any voucher: plain tokens outrank sponsored ones
+        return (rng.random(shape) * 200).astype(np.float32)
+    return (rng.random(shape) * 4).astype(np.float32)
+
+
+@pytest.mark.parametrize("n,ragged,pool_k,mode", [
+    (4096, None, 3, "uniform"), (4096, None, 5, "ties"), (4096, None, 7, "uniform"), (4096, None, 9, "uniform"),
+    (4099, (900, 4099), 5, "uniform"),        # rows not 16-byte aligned, ragged: scalar loads
+    (40000, (33000, 40000), 7, "uniform"),    # keys recomputed per pass
+])
+def test_select_with_max_pooled_scores(n, ragged, pool_k, mode):
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], n=n, batch=2, planted=6, ragged=ragged)
+    td = wl.make_tokens(w, clean=False)
+    rng = np.random.default_rng(n + pool_k)
+    layers, hkv, K = 2, 2, 200
+    A = _scores(rng, (layers, w.batch, hkv, n), mode)
+    prm = _prm(w, pool_k=pool_k)
+    seq = _dev(td.seq_len)
+    anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, prm, seq_len=seq)
+    idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, layers, hkv, seq_len=seq)
+    torch.cuda.synchronize()
+    idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    differs = 0
+    for b in range(w.batch):
+        nb = int(td.seq_len[b])
+        a, s, v = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len)
+        for l in range(layers):
+            for h in range(hkv):
+                ref = ora.select(ora.maxpool(A[l, b, h, :nb], pool_k), a, s, v, K, w.n_sink, w.n_recent)
+                assert cnt[l, b, h] == len(ref)
+                assert np.array_equal(idx[l, b, h, :len(ref)], ref), (l, b, h)
+                differs += not np.array_equal(ref, ora.select(A[l, b, h, :nb], a, s, v, K, w.n_sink, w.n_recent))
+    assert differs > 0                        # the pooling does change the selection
+
+
+@pytest.mark.parametrize("n,K,planted,mode,ragged", [
+    (4096, 16, 4, "heavy", None),             # the paper's K = 16: 24 sponsored tokens, pools of 0..8
+    (4096, 64, 8, "heavy", None),
+    (5000, 300, 8, "ties", (2000, 5000)),
+    (4096, 256, 8, "uniform", None),
+    (40000, 512, 40, "heavy", (35000, 40000)),
+])
+def test_select_with_fixed_partition(n, K, planted, mode, ragged):
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], n=n, batch=2, planted=planted, ragged=ragged)
+    td = wl.make_tokens(w, clean=False)
+    rng = np.random.default_rng(n + K)
+    layers, hkv = 1, 3
+    A = _scores(rng, (layers, w.batch, hkv, n), mode)
+    seq = _dev(td.seq_len)
+    base = _prm(w)
+    anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, base, seq_len=seq)
+    sets = {}
+    for kp in (0, 1, 4, K // 4, K - w.n_sink - w.n_recent, 10 ** 6):
+        prm = _prm(w, k_protected=kp)
+        idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, layers, hkv, seq_len=seq)
+        torch.cuda.synchronize()
+        idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+        for b in range(w.batch):
+            nb = int(td.seq_len[b])
+            a, s, v = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len)
+            for h in range(hkv):
+                ref = ora.select_partition(A[0, b, h, :nb], a, s, v, K, kp, w.n_sink, w.n_recent)
+                assert cnt[0, b, h] == len(ref)
+                assert np.array_equal(idx[0, b, h, :len(ref)], ref), (kp, b, h)
+        sets[kp] = idx.copy()
+    if mode == "heavy":
+        assert not np.array_equal(sets[0], sets[10 ** 6])        # the pool size matters under heavy attention
+
+
+def test_select_with_per_layer_budgets_and_schedule():
+    layers, K_mean, k_min = 6, 120, 24
+    budgets = ta.ta_layer_budgets(layers, K_mean, k_min)
+    assert np.array_equal(budgets, ora.layer_budgets(layers, K_mean, k_min)) and budgets.sum() == layers * K_mean
+    K = int(budgets.max())
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], n=3000, batch=2, planted=6, ragged=(100, 3000))
+    td = wl.make_tokens(w, clean=False)
+    td.seq_len[0] = 100                        # shorter than most layers' budgets
+    rng = np.random.default_rng(4)
+    hkv = 2
+    A = _scores(rng, (layers, w.batch, hkv, w.n), "uniform")
+    seq = _dev(td.seq_len)
+    lk = budgets.copy()
+    lk[1], lk[2] = 10 ** 6, 1                  # out-of-range entries are clamped to [n_sink + n_recent, K]
+    prm = _prm(w, layer_K=_dev(lk))
+    anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, prm, seq_len=seq)
+    idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, layers, hkv, seq_len=seq)
+    torch.cuda.synchronize()
+    idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    assert idx.shape == (layers, w.batch, hkv, K)
+    for l in range(layers):
+        Kl = int(min(max(lk[l], w.n_sink + w.n_recent), K))
+        for b in range(w.batch):
+            nb = int(td.seq_len[b])
+            a, s, v = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len)
+            for h in range(hkv):
+                ref = ora.select(A[l, b, h, :nb], a, s, v, Kl, w.n_sink, w.n_recent)
+                assert cnt[l, b, h] == len(ref) == min(Kl, nb)
+                assert np.array_equal(idx[l, b, h, :len(ref)], ref), (l, b, h)
+
+
+def test_allowlist_in_match_and_expansion():
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=3, n=5000, ragged=(1200, 5000), planted=12)
+    td = wl.make_tokens(w, clean=False)
+    rng = np.random.default_rng(6)
+    allow = (rng.random((w.batch, w.n)) < 0.5).astype(np.uint8) * rng.integers(1, 256, (w.batch, w.n)).astype(np.uint8)
+    allow[:, 2000:2600] = 0                    # an untrusted span
+    seq = _dev(td.seq_len)
+    plain = _prm(w)
+    filt = _prm(w, allow=_dev(allow))
+    a0, s0, v0 = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, plain, seq_len=seq)
+    a1, s1, v1 = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, filt, seq_len=seq)
+    s2, v2 = ta.ta_expand_vouchers(a0, filt, seq_len=seq)      # the same filter applied to given flags
+    torch.cuda.synchronize()
+    a0, a1, s1, v1, s2, v2 = (t.cpu().numpy() for t in (a0, a1, s1, v1, s2, v2))
+    removed = 0
+    for b in range(w.batch):
+        nb = int(td.seq_len[b])
+        a = ora.match(td.tok[b, :nb], td.tab_ids, td.tab_len)
+        fa = ora.allow_filter(a, allow[b, :nb])
+        s_ref, v_ref = ora.expand(fa)
+        assert np.array_equal(a1[b, :nb], fa)
+        assert np.array_equal(s1[b, :nb], s_ref) and np.array_equal(v1[b, :nb].view(np.uint32), v_ref.view(np.uint32))
+        assert np.array_equal(s2[b, :nb], s_ref) and np.array_equal(v2[b, :nb].view(np.uint32), v_ref.view(np.uint32))
+        removed += int(a.sum() - fa.sum())
+    assert removed > 5
+
+
+def test_evict_with_all_options_against_the_oracle_chain():
+    # whole pass with pooled scores, a fixed partition, per-layer budgets and an allowlist: the
+    # selection of every unit from the GPU's own scores, the compacted rows bit for bit
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=3, batch=2, n=2100, hq=8, hkv=2, planted=6, ragged=(900, 2100))
+    td = wl.make_tokens(w, clean=False)
+    Q, K_, V_ = wl.make_qkv(w, device=DEV)
+    budgets = ta.ta_layer_budgets(w.layers, 96, 32)
+    K = int(budgets.max())
+    allow = np.ones((w.batch, w.n), np.uint8)
+    allow[:, 700:1000] = 0
+    prm = _prm(w, pool_k=5, k_protected=6, layer_K=_dev(budgets), allow=_dev(allow))
+    seq = _dev(td.seq_len)
+    out = ta.ta_evict(_dev(td.tok), td.tab_ids, td.tab_len, Q, K_, V_, K, prm, seq_len=seq)
+    torch.cuda.synchronize()
+    A, idx, cnt = out.A.cpu().numpy(), out.idx.cpu().numpy(), out.cnt.cpu().numpy()
+    Kb, Vb, Ko, Vo = wl.bf16_bits(K_), wl.bf16_bits(V_), wl.bf16_bits(out.Kout), wl.bf16_bits(out.Vout)
+    for b in range(w.batch):
+        nb = int(td.seq_len[b])
+        fa = ora.allow_filter(ora.match(td.tok[b, :nb], td.tab_ids, td.tab_len), allow[b, :nb])
+        s, v = ora.expand(fa)
+        for l in range(w.layers):
+            for g in range(w.hkv):
+                ref = ora.select_partition(ora.maxpool(A[l, b, g, :nb], 5), fa, s, v, int(budgets[l]), 6,
+                                           w.n_sink, w.n_recent)
+                c = len(ref)
+                assert cnt[l, b, g] == c and np.array_equal(idx[l, b, g, :c], ref), (l, b, g)
+                assert np.array_equal(Ko[l, b, g, :c], Kb[l, b, g][ref]) and np.array_equal(Vo[l, b, g, :c], Vb[l, b, g][ref])
+
+
+def test_baselines_as_settings_of_the_same_kernels():
+    n, K = 3000, 64
+    rng = np.random.default_rng(12)
+    tok = _dev(rng.integers(0, 1000, (1, n)).astype(np.int32))
+    A = rng.random((1, 1, 1, n)).astype(np.float32)
+    none_ids, none_len = np.zeros((0, 4), np.int32), np.zeros(0, np.int32)
+    # StreamingLLM / TOVA window: empty table, no attention term
+    prm = ta.Params(n_sink=4, n_recent=0, alpha=0.0, beta=0.5, gamma=0.0)
+    anchor, spons, vouch = ta.ta_match_anchors(tok, none_ids, none_len, prm)
+    idx, cnt = ta.ta_select(None, anchor, spons, vouch, K, prm, 1, 1)
+    torch.cuda.synchronize()
+    assert not anchor.any() and idx[0, 0, 0].cpu().tolist() == [0, 1, 2, 3] + list(range(n - (K - 4), n))
+    # H2O: heavy hitters by attention plus a recent window of K / 2
+    prm = ta.Params(n_sink=0, n_recent=K // 2, alpha=1.0, beta=0.0, gamma=0.0)
+    idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, 1, 1)
+    torch.cuda.synchronize()
+    z8, zf = np.zeros(n, np.uint8), np.zeros(n, np.float32)
+    assert np.array_equal(idx[0, 0, 0].cpu().numpy(), ora.select(A[0, 0, 0], z8, z8, zf, K, 0, K // 2, 1.0, 0.0, 0.0))
+    # SnapKV: observation window kept, prefix ranked by max-pooled attention (kernel 7)
+    prm = ta.Params(n_sink=0, n_recent=32, alpha=1.0, beta=0.0, gamma=0.0, pool_k=7)
+    idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, 1, 1)
+    torch.cuda.synchronize()
+    ref = ora.select(ora.maxpool(A[0, 0, 0], 7), z8, z8, zf, K, 0, 32, 1.0, 0.0, 0.0)
+    assert np.array_equal(idx[0, 0, 0].cpu().numpy(), ref)
+
+
+def test_options_rejected_where_they_do_not_apply():
+    w = wl.scaled(wl.CONFIGS["c3_ta_fast"], layers=2, batch=1, n=600, hq=4, hkv=2)
+    td = wl.make_tokens(w)
+    _, K_, V_ = wl.make_qkv(w, device=DEV)
+    prm = _prm(w, layer_K=_dev(np.array([40, 20], np.int32)))
+    with pytest.raises(ta.TaError):            # one shared retained set cannot have per-layer sizes
+        ta.ta_evict(_dev(td.tok), td.tab_ids, td.tab_len, None, K_, V_, 40, prm)
+    with pytest.raises(ta.TaError):            # pool window outside {1, 3, 5, 7, 9}
+        ta.ta_select(None, *ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, _prm(w)), 40,
+                     _prm(w, pool_k=4), 1, 1)
