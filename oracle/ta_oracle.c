@@ -18,7 +18,8 @@
  * embedding cosine: identical / orthogonal / opposite vectors, scale invariance,
  * numpy float64; policy options: torch max_pool1d, the partition against the
  * elastic selection, a plain top-K and brute force, the budget-partition table,
- * sum / endpoints / monotonicity of the layer budgets).
+ * sum / endpoints / monotonicity of the layer budgets; scores from a given
+ * log-sum-exp: torch.logsumexp, agreement with the two-pass scores, row sums).
  * Unpinned: nothing in this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
@@ -641,5 +642,65 @@ void ta_oracle_allow_filter(const uint8_t *anchor, const uint8_t *allow, int32_t
 {
     for (int32_t p = 0; p < n; ++p)
         out[p] = (uint8_t)(anchor[p] != 0 && allow[p] != 0);
+}
+
+/*
+ * Scoring fused with the prefill attention (Sec. 3.4 / Sec. 4.7: TA must live with
+ * SDPA / FlashAttention backends that never materialise the attention matrix).  Such a
+ * kernel already sweeps the keys for the window's queries and leaves, per query row, the
+ * log-sum-exp of its scaled logits,
+ *     lse[h][w] = log sum_{i visible} exp(q_{h,w} . k_i / sqrt(d)),
+ * from which the attention weight of a key is exp(s - lse) without a second reduction:
+ *     A[i] = sum_{h,w : i visible} exp(q_{h,w} . k_i / sqrt(d) - lse[h][w]).
+ * ta_oracle_row_lse is the definition of that by-product (double, rounded to fp32; -inf
+ * for a row that sees no key); ta_oracle_score_lse evaluates the sum above in double from
+ * the fp32 lse it is given.
+ */
+void ta_oracle_row_lse(const uint16_t *Q, const uint16_t *K, int32_t n, int32_t G, int32_t W, int32_t d,
+                       int32_t causal, float *lse)
+{
+    const double scale = 1.0 / sqrt((double)d);
+    double *s = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    for (int32_t h = 0; h < G; ++h)
+        for (int32_t w = 0; w < W; ++w) {
+            const uint16_t *qrow = Q + ((size_t)h * W + w) * d;
+            const int32_t last = causal ? (n - W + w) : (n - 1);
+            double m = -INFINITY;
+            for (int32_t i = 0; i <= last; ++i) {
+                double dot = 0.0;
+                for (int32_t c = 0; c < d; ++c)
+                    dot += bf16_to_double(qrow[c]) * bf16_to_double(K[(size_t)i * d + c]);
+                s[i] = dot * scale;
+                if (s[i] > m)
+                    m = s[i];
+            }
+            double Z = 0.0;
+            for (int32_t i = 0; i <= last; ++i)
+                Z += exp(s[i] - m);
+            lse[(size_t)h * W + w] = last < 0 ? -INFINITY : (float)(m + log(Z));
+        }
+    free(s);
+}
+
+void ta_oracle_score_lse(const uint16_t *Q, const uint16_t *K, const float *lse,
+                         int32_t n, int32_t G, int32_t W, int32_t d, int32_t causal, float *A)
+{
+    const double scale = 1.0 / sqrt((double)d);
+    double *acc = (double *)calloc((size_t)(n > 0 ? n : 1), sizeof(double));
+    for (int32_t h = 0; h < G; ++h)
+        for (int32_t w = 0; w < W; ++w) {
+            const uint16_t *qrow = Q + ((size_t)h * W + w) * d;
+            const int32_t last = causal ? (n - W + w) : (n - 1);
+            const double l = (double)lse[(size_t)h * W + w];
+            for (int32_t i = 0; i <= last; ++i) {
+                double dot = 0.0;
+                for (int32_t c = 0; c < d; ++c)
+                    dot += bf16_to_double(qrow[c]) * bf16_to_double(K[(size_t)i * d + c]);
+                acc[i] += exp(dot * scale - l);
+            }
+        }
+    for (int32_t i = 0; i < n; ++i)
+        A[i] = (float)acc[i];
+    free(acc);
 }
 

@@ -59,6 +59,10 @@ def _load():
         lib.ta_oracle_detect.restype = None
         lib.ta_oracle_confidence_anchors.argtypes = [vp, i32, f32, i32, f32, f32, vp, vp]
         lib.ta_oracle_confidence_anchors.restype = None
+        lib.ta_oracle_row_lse.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+        lib.ta_oracle_row_lse.restype = None
+        lib.ta_oracle_score_lse.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        lib.ta_oracle_score_lse.restype = None
         lib.ta_oracle_maxpool.argtypes = [vp, i32, i32, vp]
         lib.ta_oracle_maxpool.restype = None
         lib.ta_oracle_select_partition.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, f32, vp]
@@ -119,6 +123,28 @@ def score(Q, K, causal=True):
     assert K.shape[1] == d
     A = np.zeros(n, np.float32)
     _load().ta_oracle_score(_p(Q), _p(K), n, G, W, d, 1 if causal else 0, _p(A))
+    return A
+
+
+def row_lse(Q, K, causal=True):
+    """Log-sum-exp of the scaled logits of every window row: the by-product of a flash-style
+    prefill attention kernel.  Q uint16 [G][W][d], K uint16 [n][d].  Returns f32 [G][W]."""
+    Q, K = _c(Q, np.uint16), _c(K, np.uint16)
+    G, W, d = Q.shape
+    n = K.shape[0]
+    lse = np.zeros((G, W), np.float32)
+    _load().ta_oracle_row_lse(_p(Q), _p(K), n, G, W, d, int(bool(causal)), _p(lse))
+    return lse
+
+
+def score_lse(Q, K, lse, causal=True):
+    """Attention column sums from given row log-sum-exps (one sweep over the keys)."""
+    Q, K, lse = _c(Q, np.uint16), _c(K, np.uint16), _c(lse, np.float32)
+    G, W, d = Q.shape
+    n = K.shape[0]
+    assert lse.shape == (G, W)
+    A = np.zeros(n, np.float32)
+    _load().ta_oracle_score_lse(_p(Q), _p(K), _p(lse), n, G, W, d, int(bool(causal)), _p(A))
     return A
 
 
