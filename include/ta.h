@@ -240,6 +240,20 @@ int32_t ta_score(const void *Q, const void *K, const ta_layout *lay, const int32
                  const ta_params *prm, float *A, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Step 3 fused with the prefill attention (Sec. 3.4, Sec. 4.7: SDPA / FlashAttention
+ * backends never materialise the attention matrix).  Such a kernel already sweeps the keys
+ * for the window's queries and leaves the log-sum-exp of every row's scaled logits,
+ *   lse[l][b][h][w] = log sum over the keys visible to row w of exp(q_{h,w} . k_i / sqrt(d))
+ * (natural logarithm; -inf for a row that sees no key).  Given it, the attention weight of
+ * a key is exp(s - lse) and A needs ONE sweep over K instead of two:
+ *   A[i] = sum over the group's heads h and rows w of exp(q_{h,w} . k_i / sqrt(d) - lse).
+ * Same inputs, output, masking and errors as ta_score; no workspace.
+ *   lse  DEVICE float [layers][batch][hq][window], contiguous
+ */
+int32_t ta_score_lse(const void *Q, const void *K, const ta_layout *lay, const int32_t *seq_len,
+                     const ta_params *prm, const float *lse, float *A, void *stream);
+
+/*
  * Step 4 - utility and protected top-K (Eq. 1 / Eq. 3; Alg. 1, utility and
  * top-K steps; Sec. 3.3; Thm. 2-4; budget-partition table, App. D).
  *   u_p   = alpha*A_p + beta*(p+1)/len + gamma*anchor_p + vouch_p   (fp32, each product

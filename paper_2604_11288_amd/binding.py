@@ -25,7 +25,7 @@ TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
 TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
-           "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_select", "ta_compact",
+           "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_select", "ta_compact",
            "ta_evict", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
@@ -120,6 +120,8 @@ def lib():
         L.ta_expand_vouchers.restype = i32
         L.ta_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ta_score.restype = i32
+        L.ta_score_lse.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ta_score_lse.restype = i32
         L.ta_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         L.ta_select.restype = i32
         L.ta_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
@@ -296,6 +298,21 @@ def ta_score(Q, K, params: Params, seq_len=None, A=None, ws=None, stream=None):
     rc = lib().ta_score(_ptr(Q), _ptr(K), ctypes.byref(lay), _ptr(seq_len), ctypes.byref(cp),
                         _ptr(A), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
     _check(rc, "ta_score")
+    return A
+
+
+def ta_score_lse(Q, K, lse, params: Params, seq_len=None, A=None, stream=None):
+    """Step 3 in one sweep from the row log-sum-exps of a prefill attention kernel.
+    lse f32 [Lyr][B][Hq][W].  Returns A f32 [Lyr][B][Hkv][n]."""
+    lay = layout_of(K, Q)
+    assert lse.dtype == torch.float32 and lse.is_contiguous()
+    assert tuple(lse.shape) == (lay.layers, lay.batch, lay.hq, lay.window)
+    if A is None:
+        A = torch.empty((lay.layers, lay.batch, lay.hkv, lay.n), dtype=torch.float32, device=K.device)
+    cp = params.c()
+    rc = lib().ta_score_lse(_ptr(Q), _ptr(K), ctypes.byref(lay), _ptr(seq_len), ctypes.byref(cp),
+                            _ptr(lse), _ptr(A), _stream(stream))
+    _check(rc, "ta_score_lse")
     return A
 
 

@@ -270,7 +270,21 @@ int32_t ta_score(const void* Q, const void* K, const ta_layout* lay, const int32
 {
     int32_t rc = check_score(Q, K, lay, prm, A, ws, ws_bytes);
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws, nullptr,
+    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws, nullptr, nullptr,
+                                       (hipStream_t)stream));
+}
+
+int32_t ta_score_lse(const void* Q, const void* K, const ta_layout* lay, const int32_t* seq_len,
+                     const ta_params* prm, const float* lse, float* A, void* stream)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    rc = check_layout(lay, true);
+    if (rc != TA_OK) return rc;
+    if (!Q || !K || !A || !lse) return TA_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K)) return TA_ERR_ALIGN;
+    if (ta::score_grid_blocks(*lay) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
+    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, nullptr, lse, nullptr,
                                        (hipStream_t)stream));
 }
 
@@ -328,7 +342,7 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
     if (scored) {
         // the match rides along with the first sweep of the scores (one launch fewer in front of them)
         const ta::MatchRider rider = {tok, anchor_B, prm->allow, anchor, spons, vouch, &tab};
-        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, &rider, st));
+        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, nullptr, &rider, st));
         if (rc != TA_OK) return rc;
     } else {
         rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, prm->allow, anchor, spons, vouch, st));

@@ -58,8 +58,10 @@ size_t score_workspace_bytes(const ta_layout& lay);
 int64_t score_grid_blocks(const ta_layout& lay);
 // With `rider` set, the match + voucher expansion of all sequences runs as trailing workgroups
 // of the first sweep's launch (it depends on the tokens only and is needed after the score).
+// With `lse` set (row log-sum-exps from a prefill attention kernel, [layers][batch][hq][W]) only the
+// column-sum sweep runs and ws is not used.
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
-                        int causal, float* A, float* ws, const MatchRider* rider, hipStream_t st);
+                        int causal, float* A, float* ws, const float* lse, const MatchRider* rider, hipStream_t st);
 
 // ---- select -----------------------------------------------------------------
 hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* spons,

@@ -244,7 +244,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         for (int r = tid; r < GROUP_ROWS * RG; r += THREADS) {
             float c = INFINITY;
             int32_t lim = -1;
-            if (r < a.rows) {
+            if (r < a.rows && a.lse) {
+                // the row's normaliser comes from the prefill attention kernel: c = lse * log2(e)
+                const int32_t h = r / W, w = r - h * W;
+                const float v = a.lse[(((size_t)l * a.batch + b) * ((size_t)a.hkv * a.G) + (size_t)(g * a.G + h)) * W + w];
+                if (v > -INFINITY) c = v * 1.4426950408889634f;
+                lim = a.causal ? nb - W + w : nb - 1;
+            } else if (r < a.rows) {
                 const float2* st = reinterpret_cast<const float2*>(a.ws) + ((size_t)unit * a.nchunks * a.rows_pad + r);
                 const size_t step = (size_t)a.rows_pad;
                 const int last_ch = a.nchunks - 1;
@@ -541,6 +547,16 @@ void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t 
     hipLaunchKernelGGL((score_kernel<RG, RT, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
 }
 
+// Column-sum sweep alone: the row normalisers are given (a.lse).
+template <int RG, int RT>
+void launch_colsum(ScoreArgs a, int64_t units, hipStream_t st)
+{
+    a.units = (int32_t)units;
+    a.units_per_xcd = (int32_t)((units + 7) / 8);
+    const unsigned blocks = (unsigned)(8ll * a.units_per_xcd * a.nchunks);
+    hipLaunchKernelGGL((score_kernel<RG, RT, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
+}
+
 }  // namespace
 
 namespace {
@@ -606,10 +622,11 @@ int64_t score_grid_blocks(const ta_layout& lay)
 }
 
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
-                        int causal, float* A, float* ws, const MatchRider* rider, hipStream_t st)
+                        int causal, float* A, float* ws, const float* lse, const MatchRider* rider, hipStream_t st)
 {
     const ScorePlan p = make_plan(lay);
     ScoreArgs a;
+    a.lse = lse;
     a.Q = (const uint4*)Q;
     a.K = (const uint4*)K;
     a.seq_len = seq_len;
@@ -633,6 +650,14 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.nchunks = p.nchunks;
     a.causal = causal;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
+    if (lse) {                                             // one sweep: the normalisers are given
+        switch (a.rows_pad) {
+            case 128: launch_colsum<2, 2>(a, p.units, st); break;
+            case 256: launch_colsum<4, 2>(a, p.units, st); break;
+            default: launch_colsum<8, 2>(a, p.units, st); break;
+        }
+        return hipGetLastError();
+    }
     switch (a.rows_pad) {
         // two 32-row tiles per wavefront (one tile per wavefront with twice the wavefronts - four
         // per SIMD instead of two - was measured: same time at 128 rows, 5 % slower at 256)

@@ -14,6 +14,7 @@ struct ScoreArgs {
     const int32_t* seq_len;
     float* A;
     float* ws;
+    const float* lse;                  // given row log-sum-exps [layers][batch][hq][W] (natural log), or null
     int64_t q_sl, q_sb, q_sh;          // Q strides (layer, batch, head) in 16-byte units
     int64_t k_sl, k_sb, k_sh;          // K strides (layer, batch, head) in 16-byte units
     int32_t k_sp;                      // K position stride in 16-byte units (n * k_sp < 2^31)

@@ -1,0 +1,91 @@
+"""GPU parity of the one-sweep scores from given row log-sum-exps (scoring fused with a
+flash-style prefill attention kernel, Sec. 3.4 / Sec. 4.7) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_11288_amd as ta
+from oracle import ta_oracle as ora
+from paper_2604_11288_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _close(got, ref):
+    return np.all(np.abs(got - ref) <= 1e-3 * np.abs(ref) + 1e-7)
+
+
+def _oracle_lse(w, Q, K, seq_len, causal):
+    G = w.hq // w.hkv
+    lse = np.full((w.layers, w.batch, w.hq, w.window), -np.inf, np.float32)
+    for l in range(w.layers):
+        for b in range(w.batch):
+            nb = int(seq_len[b])
+            for g in range(w.hkv):
+                lse[l, b, g * G:(g + 1) * G] = ora.row_lse(wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]),
+                                                           wl.bf16_bits(K[l, b, g, :nb]), causal)
+    return lse
+
+
+@pytest.mark.parametrize("n,hq,hkv,window,causal,ragged", [
+    (4096, 32, 8, 32, True, None),            # the shape of one layer of the full-model workload
+    (3000, 8, 2, 64, True, (40, 3000)),       # 256 rows per unit; one sequence shorter than the window
+    (2500, 8, 8, 16, False, None),
+    (9000, 4, 1, 128, True, (5000, 9000)),    # 512 rows per unit, several chunks
+])
+def test_scores_from_given_lse_match_oracle(n, hq, hkv, window, causal, ragged):
+    w = wl.scaled(wl.CONFIGS["c1_single_layer"], layers=2, batch=2, n=n, hq=hq, hkv=hkv, window=window, ragged=ragged)
+    td = wl.make_tokens(w)
+    if ragged:
+        td.seq_len[1] = ragged[0]
+    Q, K, _ = wl.make_qkv(w, device=DEV, with_v=False)
+    prm = ta.Params(causal=causal)
+    lse = _oracle_lse(w, Q, K, td.seq_len, causal)
+    seq = _dev(td.seq_len)
+    A = ta.ta_score_lse(Q, K, _dev(lse), prm, seq_len=seq)
+    A2 = ta.ta_score(Q, K, prm, seq_len=seq)
+    torch.cuda.synchronize()
+    A, A2 = A.cpu().numpy(), A2.cpu().numpy()
+    G = hq // hkv
+    for l in range(w.layers):
+        for b in range(w.batch):
+            nb = int(td.seq_len[b])
+            for g in range(hkv):
+                Qb, Kb = wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]), wl.bf16_bits(K[l, b, g, :nb])
+                ref = ora.score_lse(Qb, Kb, lse[l, b, g * G:(g + 1) * G], causal)
+                assert _close(A[l, b, g, :nb], ref), (l, b, g)
+                assert not A[l, b, g, nb:].any()
+                assert _close(A[l, b, g, :nb], ora.score(Qb, Kb, causal))       # and the two-pass definition
+                assert _close(A[l, b, g, :nb], A2[l, b, g, :nb])                # and the two-sweep kernel
+
+
+def test_lse_from_a_device_attention_pass_and_selection_behind_it():
+    # the log-sum-exp as an fp32 prefill kernel would leave it (torch on the device), then the
+    # selection from these scores against the oracle's selection from the same scores
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=2, batch=1, n=4096, planted=6)
+    td = wl.make_tokens(w)
+    Q, K, _ = wl.make_qkv(w, device=DEV, with_v=False)
+    G, W, n = w.hq // w.hkv, w.window, w.n
+    Kx = K.float().repeat_interleave(G, dim=2)                                   # [Lyr][B][Hq][n][d]
+    S = torch.einsum("lbhwd,lbhnd->lbhwn", Q.float(), Kx) / w.d ** 0.5
+    mask = torch.arange(n, device=DEV)[None, :] > (n - W + torch.arange(W, device=DEV))[:, None]
+    S = S.masked_fill(mask, float("-inf"))
+    lse = torch.logsumexp(S, dim=-1).contiguous()
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent)
+    A = ta.ta_score_lse(Q, K, lse, prm)
+    anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, prm)
+    idx, cnt = ta.ta_select(A, anchor, spons, vouch, 64, prm, w.layers, w.hkv)
+    torch.cuda.synchronize()
+    A_h = A.cpu().numpy()
+    a, s, v = ora.evict_sequence(td.tok[0], td.tab_ids, td.tab_len)
+    for l in range(w.layers):
+        for g in range(w.hkv):
+            ref = ora.score(wl.bf16_bits(Q[l, 0, g * G:(g + 1) * G]), wl.bf16_bits(K[l, 0, g]))
+            assert _close(A_h[l, 0, g], ref), (l, g)
+            sel = ora.select(A_h[l, 0, g], a, s, v, 64, w.n_sink, w.n_recent)
+            assert np.array_equal(idx[l, 0, g].cpu().numpy(), sel)
