@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="also time this many generation steps of the incremental form after the pass "
                          "(needs a scored workload; reported as decode_step)")
+    ap.add_argument("--score-lse", action="store_true",
+                    help="also time the one-sweep score from given row log-sum-exps (what a flash-style prefill "
+                         "kernel leaves behind; computed here with torch, outside the timing; reported as score_one_sweep)")
     ap.add_argument("--detect-positions", type=int, default=0,
                     help="also time the learned anchor detector + voucher expansion on about this many positions "
                          "of synthetic last-layer hidden states (sequences of the workload's length; reported as "
@@ -180,6 +183,48 @@ def main():
         roofline = {"kernel": "compact", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                     "avg_launch_us": round(kern_us["compact"], 2)}
+
+    # ---- one-sweep score: row normalisers taken from the prefill attention kernel ----------------
+    one_sweep = None
+    if args.score_lse and scored:
+        lse = torch.empty((w.layers, w.batch, w.hq, w.window), dtype=torch.float32, device=dev)
+        lens = torch.from_numpy(td.seq_len).to(dev)
+        for l in range(w.layers):
+            for b in range(w.batch):
+                nb = int(td.seq_len[b])
+                S = torch.einsum("hwd,hnd->hwn", Q[l, b].float(), K[l, b, :, :nb].float().repeat_interleave(G, dim=0))
+                S = S / w.d ** 0.5
+                vis = torch.arange(nb, device=dev)[None, :] <= (nb - w.window + torch.arange(w.window, device=dev))[:, None]
+                lse[l, b] = torch.logsumexp(S.masked_fill(~vis[None], float("-inf")), dim=-1)
+        A2 = torch.empty_like(plan.A)
+        for _ in range(10):
+            ta.ta_score_lse(Q, K, lse, prm, seq_len=seq, A=A2, stream=stream)
+        pairs = []
+        for _ in range(max(args.steps, 20)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            ta.ta_score_lse(Q, K, lse, prm, seq_len=seq, A=A2, stream=stream)
+            e1.record(stream)
+            pairs.append((e0, e1))
+        torch.cuda.synchronize()
+        us1 = 1e3 * float(np.median([a.elapsed_time(b) for a, b in pairs]))
+        rel = float(((A2 - plan.A).abs() / (plan.A.abs() + 1e-7)).max())
+        # the whole pass with the one-sweep score (the match tiles ride with the column-sum sweep)
+        plan1 = ta.EvictPlan(tok, td.tab_ids, td.tab_len, Q, K, V, budget, prm, seq_len=seq, lse=lse)
+        for _ in range(args.warmup):
+            plan1.run(stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            plan1.run(stream)
+        torch.cuda.synchronize()
+        pass1_us = (time.perf_counter() - t0) * 1e6 / args.steps
+        one_sweep = {"entry_point": "ta_score_lse / ta_evict_lse", "score_us": round(us1, 2),
+                     "score_GB/s": round(alg_bytes / us1 / 1e3, 1),
+                     "score_hbm_frac": round(alg_bytes / us1 / 1e3 / HBM_PEAK_GBS, 4),
+                     "max_rel_diff_to_two_sweep": float("%.2e" % rel),
+                     "pass_us": round(pass1_us, 1), "pass_GB/s": round((score_b + compact_b) / pass1_us / 1e3, 1)}
+        del lse, A2, plan1
 
     # ---- budget sweep of the same workload (context, outside the headline timing) ----------
     sweep = {}
@@ -357,6 +402,7 @@ def main():
         "hbm_frac": round(value / HBM_PEAK_GBS, 4),
         "kernels_us": {k: round(v, 2) for k, v in kern_us.items()},
         "budget_sweep": sweep,
+        "score_one_sweep": one_sweep,
         "decode_step": decode,
         "learned_detect": detect,
         "embedding_detect": embed,

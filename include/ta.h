@@ -312,6 +312,18 @@ int32_t ta_evict(const int32_t *tok, const int32_t *seq_len,
                  void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The whole pass with the one-sweep score of ta_score_lse: as ta_evict for prm->alpha != 0,
+ * with the row log-sum-exps of the prefill attention kernel in place of the workspace.
+ * Errors: as ta_evict; SHAPE when prm->alpha == 0.
+ */
+int32_t ta_evict_lse(const int32_t *tok, const int32_t *seq_len,
+                     const int32_t *tab_ids, const int32_t *tab_len, int32_t E, const float *anchor_B,
+                     const void *Q, const void *Kin, const void *Vin, const float *lse,
+                     const ta_layout *lay, const ta_params *prm, int32_t K,
+                     uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
+                     int32_t *idx, int32_t *cnt, void *Kout, void *Vout, void *stream);
+
+/*
  * Incremental form: the same retention policy applied after every generation
  * step (Sec. 3.1 "after each generation step"; Alg. 1 including its last step,
  * the budget decay B_i <- decay * B_i of Sec. 3.2 "Token selection").

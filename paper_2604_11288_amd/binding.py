@@ -26,7 +26,7 @@ TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
            "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_select", "ta_compact",
-           "ta_evict", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
+           "ta_evict", "ta_evict_lse", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
 class TaError(RuntimeError):
@@ -129,6 +129,9 @@ def lib():
         L.ta_evict.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32,
                                vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ta_evict.restype = i32
+        L.ta_evict_lse.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, i32,
+                                   vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ta_evict_lse.restype = i32
         L.ta_decode_init.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ta_decode_init.restype = i32
         L.ta_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
@@ -355,9 +358,10 @@ class EvictPlan:
     """
 
     def __init__(self, tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params,
-                 seq_len=None, anchor_B=None):
+                 seq_len=None, anchor_B=None, lse=None):
         dev = Kin.device
         self.params, self.K = params, int(K)
+        self.lse = lse                     # row log-sum-exps of the prefill attention kernel: ta_evict_lse
         self.scored = params.alpha != 0.0
         self.lay = layout_of(Kin, Q if self.scored else None)
         lay = self.lay
@@ -372,8 +376,11 @@ class EvictPlan:
             self.A = torch.empty((lay.layers, B, lay.hkv, n), dtype=torch.float32, device=dev)
             self.idx = torch.full((lay.layers, B, lay.hkv, self.K), -1, dtype=torch.int32, device=dev)
             self.cnt = torch.zeros((lay.layers, B, lay.hkv), dtype=torch.int32, device=dev)
-            nbytes = ta_workspace_bytes(lay, params)
+            nbytes = ta_workspace_bytes(lay, params) if lse is None else 0
             self.ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+            if lse is not None:
+                assert lse.dtype == torch.float32 and lse.is_contiguous()
+                assert tuple(lse.shape) == (lay.layers, B, lay.hq, lay.window)
         else:
             self.A, self.ws = None, None
             self.idx = torch.full((B, self.K), -1, dtype=torch.int32, device=dev)
@@ -385,6 +392,14 @@ class EvictPlan:
 
     def run(self, stream=None):
         ws_bytes = 0 if self.ws is None else self.ws.numel()
+        if self.lse is not None:
+            rc = lib().ta_evict_lse(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
+                                    self.E, _ptr(self.anchor_B), _ptr(self.Q), _ptr(self.Kin), _ptr(self.Vin),
+                                    _ptr(self.lse), ctypes.byref(self.lay), ctypes.byref(self._cp), self.K,
+                                    _ptr(self.anchor), _ptr(self.spons), _ptr(self.vouch), _ptr(self.A),
+                                    _ptr(self.idx), _ptr(self.cnt), _ptr(self.Kout), _ptr(self.Vout), _stream(stream))
+            _check(rc, "ta_evict_lse")
+            return self
         rc = lib().ta_evict(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
                             self.E, _ptr(self.anchor_B), _ptr(self.Q), _ptr(self.Kin), _ptr(self.Vin),
                             ctypes.byref(self.lay), ctypes.byref(self._cp), self.K,
@@ -399,6 +414,12 @@ def ta_evict(tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params, seq_len
              stream=None) -> EvictPlan:
     """The whole pass in one call; returns the plan object holding every output tensor."""
     return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B).run(stream)
+
+
+def ta_evict_lse(tok, tab_ids, tab_len, Q, Kin, Vin, lse, K: int, params: Params, seq_len=None, anchor_B=None,
+                 stream=None) -> EvictPlan:
+    """The whole pass with the one-sweep score from given row log-sum-exps (f32 [Lyr][B][Hq][W])."""
+    return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B, lse=lse).run(stream)
 
 
 class DecodeState:

@@ -308,13 +308,16 @@ int32_t ta_compact(const void* Kin, const void* Vin, const int32_t* idx, const i
                                          (hipStream_t)stream));
 }
 
-int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
-                 const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
-                 const void* Q, const void* Kin, const void* Vin,
-                 const ta_layout* lay, const ta_params* prm, int32_t K,
-                 uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
-                 int32_t* idx, int32_t* cnt, void* Kout, void* Vout,
-                 void* ws, size_t ws_bytes, void* stream)
+namespace {
+
+// The whole pass; `lse` != NULL selects the one-sweep score (then ws is not used).
+int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
+                   const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                   const void* Q, const void* Kin, const void* Vin,
+                   const ta_layout* lay, const ta_params* prm, int32_t K,
+                   uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                   int32_t* idx, int32_t* cnt, void* Kout, void* Vout,
+                   void* ws, size_t ws_bytes, const float* lse, void* stream)
 {
     // validate every stage first: nothing runs unless all of them can
     int32_t rc = check_params(prm);
@@ -326,7 +329,13 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
     ta::MatchTable tab;
     rc = build_table(tab_ids, tab_len, E, prm, &tab);
     if (rc != TA_OK) return rc;
-    if (scored) {
+    if (scored && lse) {
+        rc = check_layout(lay, true);
+        if (rc != TA_OK) return rc;
+        if (!Q || !Kin || !A) return TA_ERR_NULL;
+        if (!aligned16(Q) || !aligned16(Kin)) return TA_ERR_ALIGN;
+        if (ta::score_grid_blocks(*lay) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
+    } else if (scored) {
         rc = check_score(Q, Kin, lay, prm, A, ws, ws_bytes);
         if (rc != TA_OK) return rc;
     }
@@ -340,9 +349,9 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
 
     hipStream_t st = (hipStream_t)stream;
     if (scored) {
-        // the match rides along with the first sweep of the scores (one launch fewer in front of them)
+        // the match rides along with the first sweep over the keys (one launch fewer in front of them)
         const ta::MatchRider rider = {tok, anchor_B, prm->allow, anchor, spons, vouch, &tab};
-        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, nullptr, &rider, st));
+        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, lse, &rider, st));
         if (rc != TA_OK) return rc;
     } else {
         rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, prm->allow, anchor, spons, vouch, st));
@@ -352,6 +361,33 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
                                       lay->n, K, *prm, idx, cnt, st));
     if (rc != TA_OK) return rc;
     return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, st));
+}
+
+}  // namespace
+
+int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
+                 const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                 const void* Q, const void* Kin, const void* Vin,
+                 const ta_layout* lay, const ta_params* prm, int32_t K,
+                 uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                 int32_t* idx, int32_t* cnt, void* Kout, void* Vout,
+                 void* ws, size_t ws_bytes, void* stream)
+{
+    return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
+                      idx, cnt, Kout, Vout, ws, ws_bytes, nullptr, stream);
+}
+
+int32_t ta_evict_lse(const int32_t* tok, const int32_t* seq_len,
+                     const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                     const void* Q, const void* Kin, const void* Vin, const float* lse,
+                     const ta_layout* lay, const ta_params* prm, int32_t K,
+                     uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                     int32_t* idx, int32_t* cnt, void* Kout, void* Vout, void* stream)
+{
+    if (!prm || !lse) return TA_ERR_NULL;
+    if (prm->alpha == 0.0f) return TA_ERR_SHAPE;            // nothing to fuse in the attention-free setting
+    return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
+                      idx, cnt, Kout, Vout, nullptr, 0, lse, stream);
 }
 
 int32_t ta_decode_init(const ta_decode_state* st, const int32_t* tok, const int32_t* seq_len, int32_t n,

@@ -63,8 +63,9 @@ __device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, u
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
-// Statistics sweep that also carries the match tiles: workgroups past the score grid each run
-// one tile of the anchor match (they start as the first score workgroups retire).
+// A sweep that also carries the match tiles: workgroups past the score grid each run one tile
+// of the anchor match (they start as the first score workgroups retire).  The statistics sweep
+// carries them in the two-sweep step, the column-sum sweep when the normalisers are given.
 struct RiderArgs {
     MatchArgs m;
     MatchTable tab;
@@ -84,9 +85,9 @@ score_kernel(ScoreArgs a)
     score_body<RG, RT, COLSUM>(a, s_k);
 }
 
-template <int RG, int RT>
+template <int RG, int RT, bool COLSUM>
 __global__ void __launch_bounds__(128 * RG, RT == 1 ? 4 : 2)
-score_stats_match_kernel(ScoreArgs a, RiderArgs r)
+score_match_kernel(ScoreArgs a, RiderArgs r)
 {
     __shared__ uint4 s_k[ring_of(RG)][STAGE_UNITS];
     static_assert(sizeof(MatchLds) <= sizeof(uint4) * ring_of(RG) * STAGE_UNITS, "match tile must fit the stage ring");
@@ -97,7 +98,7 @@ score_stats_match_kernel(ScoreArgs a, RiderArgs r)
                           (int)threadIdx.x, *reinterpret_cast<MatchLds*>(&s_k[0][0]));
         return;
     }
-    score_body<RG, RT, false>(a, s_k);
+    score_body<RG, RT, COLSUM>(a, s_k);
 }
 
 template <int RG, int RT, bool COLSUM>
@@ -525,6 +526,22 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     }
 }
 
+template <int RG, int RT, bool COLSUM>
+void launch_sweep(const ScoreArgs& a, unsigned blocks, const MatchRider* rider, hipStream_t st)
+{
+    if (rider) {
+        RiderArgs r;
+        r.m = make_match_args(rider->tok, a.seq_len, a.batch, a.n, rider->anchor_B, rider->allow, rider->anchor, rider->spons,
+                              rider->vouch);
+        r.tab = *rider->tab;
+        r.score_blocks = blocks;
+        const unsigned extra = (unsigned)r.m.tiles * (unsigned)r.m.batch;
+        hipLaunchKernelGGL((score_match_kernel<RG, RT, COLSUM>), dim3(blocks + extra), dim3(128 * RG), 0, st, a, r);
+    } else {
+        hipLaunchKernelGGL((score_kernel<RG, RT, COLSUM>), dim3(blocks), dim3(128 * RG), 0, st, a);
+    }
+}
+
 template <int RG, int RT>
 void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t st)
 {
@@ -533,28 +550,12 @@ void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t 
     a.units = (int32_t)units;
     a.units_per_xcd = (int32_t)((units + 7) / 8);
     const unsigned blocks = (unsigned)(8ll * a.units_per_xcd * a.nchunks);
-    if (rider) {
-        RiderArgs r;
-        r.m = make_match_args(rider->tok, a.seq_len, a.batch, a.n, rider->anchor_B, rider->allow, rider->anchor, rider->spons,
-                              rider->vouch);
-        r.tab = *rider->tab;
-        r.score_blocks = blocks;
-        const unsigned extra = (unsigned)r.m.tiles * (unsigned)r.m.batch;
-        hipLaunchKernelGGL((score_stats_match_kernel<RG, RT>), dim3(blocks + extra), dim3(128 * RG), 0, st, a, r);
-    } else {
-        hipLaunchKernelGGL((score_kernel<RG, RT, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
+    if (a.lse) {                                           // the row normalisers are given: column sums alone
+        launch_sweep<RG, RT, true>(a, blocks, rider, st);
+        return;
     }
-    hipLaunchKernelGGL((score_kernel<RG, RT, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
-}
-
-// Column-sum sweep alone: the row normalisers are given (a.lse).
-template <int RG, int RT>
-void launch_colsum(ScoreArgs a, int64_t units, hipStream_t st)
-{
-    a.units = (int32_t)units;
-    a.units_per_xcd = (int32_t)((units + 7) / 8);
-    const unsigned blocks = (unsigned)(8ll * a.units_per_xcd * a.nchunks);
-    hipLaunchKernelGGL((score_kernel<RG, RT, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
+    launch_sweep<RG, RT, false>(a, blocks, rider, st);
+    launch_sweep<RG, RT, true>(a, blocks, nullptr, st);
 }
 
 }  // namespace
@@ -650,14 +651,6 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.nchunks = p.nchunks;
     a.causal = causal;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)lay.d));
-    if (lse) {                                             // one sweep: the normalisers are given
-        switch (a.rows_pad) {
-            case 128: launch_colsum<2, 2>(a, p.units, st); break;
-            case 256: launch_colsum<4, 2>(a, p.units, st); break;
-            default: launch_colsum<8, 2>(a, p.units, st); break;
-        }
-        return hipGetLastError();
-    }
     switch (a.rows_pad) {
         // two 32-row tiles per wavefront (one tile per wavefront with twice the wavefronts - four
         // per SIMD instead of two - was measured: same time at 128 rows, 5 % slower at 256)

@@ -89,3 +89,36 @@ def test_lse_from_a_device_attention_pass_and_selection_behind_it():
             assert _close(A_h[l, 0, g], ref), (l, g)
             sel = ora.select(A_h[l, 0, g], a, s, v, 64, w.n_sink, w.n_recent)
             assert np.array_equal(idx[l, 0, g].cpu().numpy(), sel)
+
+
+def test_whole_pass_with_given_lse():
+    # ta_evict_lse: flags and vouchers as the table match gives them, scores within tolerance of the
+    # oracle, the selection of every unit from the pass's own scores and the compacted rows bit-exact
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=2, batch=2, n=3000, planted=6, ragged=(1000, 3000))
+    td = wl.make_tokens(w, clean=False)
+    Q, K, V = wl.make_qkv(w, device=DEV)
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent)
+    lse = _oracle_lse(w, Q, K, td.seq_len, True)
+    seq = _dev(td.seq_len)
+    Kb = 96
+    out = ta.ta_evict_lse(_dev(td.tok), td.tab_ids, td.tab_len, Q, K, V, _dev(lse), Kb, prm, seq_len=seq)
+    torch.cuda.synchronize()
+    A, idx, cnt = out.A.cpu().numpy(), out.idx.cpu().numpy(), out.cnt.cpu().numpy()
+    Kbits, Vbits, Ko, Vo = wl.bf16_bits(K), wl.bf16_bits(V), wl.bf16_bits(out.Kout), wl.bf16_bits(out.Vout)
+    G = w.hq // w.hkv
+    for b in range(w.batch):
+        nb = int(td.seq_len[b])
+        a, s, v = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len)
+        assert np.array_equal(out.anchor[b, :nb].cpu().numpy(), a) and np.array_equal(out.spons[b, :nb].cpu().numpy(), s)
+        assert np.array_equal(out.vouch[b, :nb].cpu().numpy().view(np.uint32), v.view(np.uint32))
+        for l in range(w.layers):
+            for g in range(w.hkv):
+                ref = ora.score(wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]), wl.bf16_bits(K[l, b, g, :nb]))
+                assert _close(A[l, b, g, :nb], ref), (l, b, g)
+                sel = ora.select(A[l, b, g, :nb], a, s, v, Kb, w.n_sink, w.n_recent)
+                c = len(sel)
+                assert cnt[l, b, g] == c and np.array_equal(idx[l, b, g, :c], sel)
+                assert np.array_equal(Ko[l, b, g, :c], Kbits[l, b, g][sel]) and np.array_equal(Vo[l, b, g, :c], Vbits[l, b, g][sel])
+    with pytest.raises(ta.TaError):            # nothing to fuse without an attention term
+        ta.ta_evict_lse(_dev(td.tok), td.tab_ids, td.tab_len, Q, K, V, _dev(lse), Kb,
+                        ta.Params(n_sink=4, n_recent=4, alpha=0.0), seq_len=seq)
