@@ -19,7 +19,8 @@
  * numpy float64; policy options: torch max_pool1d, the partition against the
  * elastic selection, a plain top-K and brute force, the budget-partition table,
  * sum / endpoints / monotonicity of the layer budgets; scores from a given
- * log-sum-exp: torch.logsumexp, agreement with the two-pass scores, row sums).
+ * log-sum-exp: torch.logsumexp, agreement with the two-pass scores, row sums;
+ * paged gather: numpy fancy indexing on both common page layouts).
  * Unpinned: nothing in this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
@@ -702,5 +703,25 @@ void ta_oracle_score_lse(const uint16_t *Q, const uint16_t *K, const float *lse,
     for (int32_t i = 0; i < n; ++i)
         A[i] = (float)acc[i];
     free(acc);
+}
+
+/*
+ * Paged (block-table) caches, the layout of serving engines: the rows of one sequence live in
+ * pages of page_size positions scattered over a pool; table[j] is the page that holds
+ * positions [j * page_size, (j + 1) * page_size).  Row p of head `head` starts at element
+ *     table[p / page_size] * stride_page + (p % page_size) * stride_pos + head * stride_head
+ * of the pool (one layer).  This function is the whole of the oracle's paged support: it
+ * lays the n rows of a (sequence, head) out densely, [n][d], after which every other
+ * function of this file applies unchanged.
+ */
+void ta_oracle_paged_gather(const uint16_t *pool, const int32_t *table, int32_t n, int32_t page_size,
+                            int64_t stride_page, int64_t stride_pos, int64_t stride_head, int32_t head,
+                            int32_t d, uint16_t *out)
+{
+    for (int32_t p = 0; p < n; ++p) {
+        const uint16_t *row = pool + (int64_t)table[p / page_size] * stride_page +
+                              (int64_t)(p % page_size) * stride_pos + (int64_t)head * stride_head;
+        memcpy(out + (size_t)p * d, row, sizeof(uint16_t) * (size_t)d);
+    }
 }
 

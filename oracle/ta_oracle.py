@@ -59,6 +59,9 @@ def _load():
         lib.ta_oracle_detect.restype = None
         lib.ta_oracle_confidence_anchors.argtypes = [vp, i32, f32, i32, f32, f32, vp, vp]
         lib.ta_oracle_confidence_anchors.restype = None
+        i64 = ctypes.c_int64
+        lib.ta_oracle_paged_gather.argtypes = [vp, vp, i32, i32, i64, i64, i64, i32, i32, vp]
+        lib.ta_oracle_paged_gather.restype = None
         lib.ta_oracle_row_lse.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
         lib.ta_oracle_row_lse.restype = None
         lib.ta_oracle_score_lse.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
@@ -124,6 +127,18 @@ def score(Q, K, causal=True):
     A = np.zeros(n, np.float32)
     _load().ta_oracle_score(_p(Q), _p(K), n, G, W, d, 1 if causal else 0, _p(A))
     return A
+
+
+def paged_gather(pool, table, n, page_size, stride_page, stride_pos, stride_head, head, d):
+    """Dense [n][d] rows (uint16) of one (sequence, head) of a paged cache pool of one layer.
+    pool: flat uint16 array; table int32 [pages of the sequence]; strides in elements."""
+    pool = _c(pool, np.uint16).reshape(-1)
+    table = _c(table, np.int32)
+    assert table.shape[0] * page_size >= n
+    out = np.zeros((n, d), np.uint16)
+    _load().ta_oracle_paged_gather(_p(pool), _p(table), int(n), int(page_size), int(stride_page), int(stride_pos),
+                                   int(stride_head), int(head), int(d), _p(out))
+    return out
 
 
 def row_lse(Q, K, causal=True):
