@@ -12,6 +12,10 @@
  *      ta_expand_vouchers   table match, with confidence-weighted budgets (Sec. 5.1)
  *      ta_embed_anchors /   anchors from cosine similarity to anchor-concept embeddings
  *      ta_lookup_anchors    (Sec. 3.2), per position or once per vocabulary entry
+ *      ta_score_lse /    scores in one sweep from the prefill attention's row log-sum-exps
+ *      ta_evict_lse
+ *      ta_score_paged /  steps 3 and 5 over paged (block-table) caches
+ *      ta_compact_paged
  *      ta_evict          all of the above in one call
  *      ta_decode_init /  the same policy applied after every generation step
  *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
@@ -310,6 +314,40 @@ int32_t ta_evict(const int32_t *tok, const int32_t *seq_len,
                  uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
                  int32_t *idx, int32_t *cnt, void *Kout, void *Vout,
                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Paged (block-table) caches, the layout of serving engines: K and V rows of a sequence
+ * live in pages of page_size positions scattered over a pool; entry j of a sequence's row
+ * of the block table is the page that holds its positions [j*page_size, (j+1)*page_size).
+ * Row p of KV head g of sequence b in layer l starts at element
+ *   l*stride[0] + block_table[b][p / page_size]*stride[1] + (p % page_size)*stride[2] + g*stride[3]
+ * of the pool ([pages][page_size][heads][d] and [pages][heads][page_size][d] are both
+ * expressible).  Table entries are clamped to [0, num_pages - 1] on the device, so a
+ * corrupt table cannot fault.  With a paged cache, ta_layout gives the sizes and the query
+ * strides; its kv_stride is not used.
+ */
+typedef struct ta_paged_kv {
+    int32_t page_size;          /* positions per page; scoring needs a multiple of 64           */
+    int32_t max_pages;          /* block-table entries per sequence; max_pages*page_size >= n   */
+    int32_t num_pages;          /* pages in the pool                                            */
+    const int32_t *block_table; /* DEVICE int32 [batch][max_pages]                              */
+    int64_t stride[4];          /* ELEMENTS: {layer, page, position, head}; multiples of 8      */
+} ta_paged_kv;
+
+/*
+ * Steps 3 and 5 over a paged cache: ta_score / ta_score_lse (lse != NULL: one sweep, ws
+ * not used) and ta_compact with the rows addressed through the block table.  Outputs as in
+ * the dense calls (A [layers][batch][hkv][n]; Kout, Vout dense [layers][batch][hkv][K][d]).
+ * Errors: as the dense calls; SHAPE also for page_size < 1 (scoring: not a multiple of 64),
+ * max_pages*page_size < n, num_pages < 1, negative strides; ALIGN for strides that are
+ * not multiples of 8 or pools that are not 16-byte aligned; NULL for a missing table.
+ */
+int32_t ta_score_paged(const void *Q, const void *Kpool, const ta_paged_kv *pg, const ta_layout *lay,
+                       const int32_t *seq_len, const ta_params *prm, const float *lse,
+                       float *A, void *ws, size_t ws_bytes, void *stream);
+int32_t ta_compact_paged(const void *Kpool, const void *Vpool, const ta_paged_kv *pg,
+                         const int32_t *idx, const int32_t *cnt, const ta_layout *lay, int32_t K,
+                         int32_t idx_shared, void *Kout, void *Vout, void *stream);
 
 /*
  * The whole pass with the one-sweep score of ta_score_lse: as ta_evict for prm->alpha != 0,

@@ -25,7 +25,7 @@ TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
 TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
-           "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_select", "ta_compact",
+           "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged",
            "ta_evict", "ta_evict_lse", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
@@ -61,6 +61,11 @@ class CLayout(ctypes.Structure):
                 ("hkv", ctypes.c_int32), ("n", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("d", ctypes.c_int32),
                 ("kv_stride", ctypes.c_int64 * 4), ("q_stride", ctypes.c_int64 * 3)]
+
+
+class CPaged(ctypes.Structure):
+    _fields_ = [("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32), ("num_pages", ctypes.c_int32),
+                ("block_table", ctypes.c_void_p), ("stride", ctypes.c_int64 * 4)]
 
 
 @dataclass
@@ -122,6 +127,10 @@ def lib():
         L.ta_score.restype = i32
         L.ta_score_lse.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
         L.ta_score_lse.restype = i32
+        L.ta_score_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ta_score_paged.restype = i32
+        L.ta_compact_paged.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.ta_compact_paged.restype = i32
         L.ta_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         L.ta_select.restype = i32
         L.ta_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
@@ -317,6 +326,71 @@ def ta_score_lse(Q, K, lse, params: Params, seq_len=None, A=None, stream=None):
                             _ptr(lse), _ptr(A), _stream(stream))
     _check(rc, "ta_score_lse")
     return A
+
+
+class PagedKV:
+    """A paged (block-table) cache: pools of pages, the block table and the element strides
+    {layer, page, position, head} of ta_paged_kv.  Kpool / Vpool: bf16 tensors of any shape whose
+    storage the strides index; table: device int32 [batch][max_pages]."""
+
+    def __init__(self, Kpool, Vpool, table, page_size, num_pages, strides, layers, batch, hkv, n, d=TA_HEAD_DIM):
+        assert table.dtype == torch.int32 and table.dim() == 2 and table.is_contiguous() and table.shape[0] == batch
+        self.Kpool, self.Vpool, self.table = Kpool, Vpool, table
+        self.page_size, self.num_pages, self.strides = int(page_size), int(num_pages), tuple(int(x) for x in strides)
+        self.layers, self.batch, self.hkv, self.n, self.d = layers, batch, hkv, n, d
+
+    def c(self) -> CPaged:
+        pg = CPaged()
+        pg.page_size, pg.max_pages, pg.num_pages = self.page_size, self.table.shape[1], self.num_pages
+        pg.block_table = self.table.data_ptr()
+        for i in range(4):
+            pg.stride[i] = self.strides[i]
+        return pg
+
+    def layout(self, Q=None) -> CLayout:
+        lay = CLayout()
+        lay.layers, lay.batch, lay.hkv, lay.n, lay.d = self.layers, self.batch, self.hkv, self.n, self.d
+        if Q is not None:
+            assert Q.dim() == 5 and Q.dtype == torch.bfloat16 and Q.stride(4) == 1 and Q.stride(3) == Q.shape[4]
+            lay.hq, lay.window = Q.shape[2], Q.shape[3]
+            for i in range(3):
+                lay.q_stride[i] = Q.stride(i)
+        else:
+            lay.hq, lay.window = self.hkv, 0
+        return lay
+
+
+def ta_score_paged(Q, paged: PagedKV, params: Params, seq_len=None, lse=None, A=None, ws=None, stream=None):
+    """Step 3 over a paged cache (two sweeps, or one with lse).  Returns A f32 [Lyr][B][Hkv][n]."""
+    lay, pg = paged.layout(Q), paged.c()
+    if A is None:
+        A = torch.empty((lay.layers, lay.batch, lay.hkv, lay.n), dtype=torch.float32, device=Q.device)
+    if ws is None and lse is None:
+        dense = CLayout.from_buffer_copy(lay)
+        dense.kv_stride[3] = lay.d
+        need = ta_workspace_bytes(dense, replace(params, alpha=1.0))
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    cp = params.c()
+    rc = lib().ta_score_paged(_ptr(Q), _ptr(paged.Kpool), ctypes.byref(pg), ctypes.byref(lay), _ptr(seq_len),
+                              ctypes.byref(cp), _ptr(lse), _ptr(A), _ptr(ws),
+                              0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "ta_score_paged")
+    return A
+
+
+def ta_compact_paged(paged: PagedKV, idx, cnt, K: int, idx_shared: bool = False, out=None, stream=None):
+    """Step 5 over a paged cache.  Returns dense (Kout, Vout) bf16 [Lyr][B][Hkv][K][d]."""
+    lay, pg = paged.layout(), paged.c()
+    if out is None:
+        shape = (lay.layers, lay.batch, lay.hkv, K, lay.d)
+        Kout = torch.zeros(shape, dtype=torch.bfloat16, device=paged.Kpool.device)
+        Vout = torch.zeros(shape, dtype=torch.bfloat16, device=paged.Kpool.device)
+    else:
+        Kout, Vout = out
+    rc = lib().ta_compact_paged(_ptr(paged.Kpool), _ptr(paged.Vpool), ctypes.byref(pg), _ptr(idx), _ptr(cnt),
+                                ctypes.byref(lay), K, 1 if idx_shared else 0, _ptr(Kout), _ptr(Vout), _stream(stream))
+    _check(rc, "ta_compact_paged")
+    return Kout, Vout
 
 
 def ta_select(A, anchor, spons, vouch, K: int, params: Params, layers: int, hkv: int,

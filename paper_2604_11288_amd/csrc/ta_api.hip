@@ -270,7 +270,7 @@ int32_t ta_score(const void* Q, const void* K, const ta_layout* lay, const int32
 {
     int32_t rc = check_score(Q, K, lay, prm, A, ws, ws_bytes);
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws, nullptr, nullptr,
+    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws, nullptr, nullptr, nullptr,
                                        (hipStream_t)stream));
 }
 
@@ -284,7 +284,7 @@ int32_t ta_score_lse(const void* Q, const void* K, const ta_layout* lay, const i
     if (!Q || !K || !A || !lse) return TA_ERR_NULL;
     if (!aligned16(Q) || !aligned16(K)) return TA_ERR_ALIGN;
     if (ta::score_grid_blocks(*lay) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
-    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, nullptr, lse, nullptr,
+    return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, nullptr, lse, nullptr, nullptr,
                                        (hipStream_t)stream));
 }
 
@@ -304,11 +304,31 @@ int32_t ta_compact(const void* Kin, const void* Vin, const int32_t* idx, const i
 {
     int32_t rc = check_compact(Kin, Vin, idx, cnt, lay, K, Kout, Vout);
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, idx_shared, Kout, Vout,
+    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, idx_shared, Kout, Vout, nullptr,
                                          (hipStream_t)stream));
 }
 
 namespace {
+
+// A dense layout whose kv strides pass the shared checks; the real addressing of a paged cache is in `pg`.
+int32_t check_paged(const ta_paged_kv* pg, const ta_layout* lay, ta_layout* dense, bool scoring)
+{
+    if (!pg || !lay) return TA_ERR_NULL;
+    if (!pg->block_table) return TA_ERR_NULL;
+    if (pg->page_size < 1 || pg->max_pages < 1 || pg->num_pages < 1) return TA_ERR_SHAPE;
+    if (scoring && pg->page_size % 64 != 0) return TA_ERR_SHAPE;
+    if ((int64_t)pg->max_pages * pg->page_size < lay->n) return TA_ERR_SHAPE;
+    for (int i = 0; i < 4; ++i) {
+        if (pg->stride[i] < 0) return TA_ERR_SHAPE;
+        if (pg->stride[i] % 8 != 0) return TA_ERR_ALIGN;
+    }
+    if (pg->stride[2] < lay->d) return TA_ERR_SHAPE;
+    if ((pg->stride[2] / 8) * (int64_t)pg->page_size >= 0x7FFFFFFFll) return TA_ERR_SHAPE;   // 32-bit offsets in a page
+    *dense = *lay;
+    dense->kv_stride[0] = dense->kv_stride[1] = dense->kv_stride[2] = 0;
+    dense->kv_stride[3] = lay->d;
+    return TA_OK;
+}
 
 // The whole pass; `lse` != NULL selects the one-sweep score (then ws is not used).
 int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
@@ -351,7 +371,7 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
     if (scored) {
         // the match rides along with the first sweep over the keys (one launch fewer in front of them)
         const ta::MatchRider rider = {tok, anchor_B, prm->allow, anchor, spons, vouch, &tab};
-        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, lse, &rider, st));
+        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, lse, &rider, nullptr, st));
         if (rc != TA_OK) return rc;
     } else {
         rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, prm->allow, anchor, spons, vouch, st));
@@ -360,10 +380,46 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
     rc = hip_status(ta::launch_select(A, anchor, spons, vouch, seq_len, sel_layers, lay->batch, sel_hkv,
                                       lay->n, K, *prm, idx, cnt, st));
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, st));
+    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, nullptr, st));
 }
 
 }  // namespace
+
+int32_t ta_score_paged(const void* Q, const void* Kpool, const ta_paged_kv* pg, const ta_layout* lay,
+                       const int32_t* seq_len, const ta_params* prm, const float* lse,
+                       float* A, void* ws, size_t ws_bytes, void* stream)
+{
+    int32_t rc = check_params(prm);
+    if (rc != TA_OK) return rc;
+    ta_layout dense;
+    rc = check_paged(pg, lay, &dense, true);
+    if (rc != TA_OK) return rc;
+    if (lse) {
+        rc = check_layout(&dense, true);
+        if (rc != TA_OK) return rc;
+        if (!Q || !Kpool || !A) return TA_ERR_NULL;
+        if (!aligned16(Q) || !aligned16(Kpool)) return TA_ERR_ALIGN;
+        if (ta::score_grid_blocks(dense) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
+    } else {
+        rc = check_score(Q, Kpool, &dense, prm, A, ws, ws_bytes);
+        if (rc != TA_OK) return rc;
+    }
+    return hip_status(ta::launch_score(Q, Kpool, dense, seq_len, prm->causal, A, (float*)ws, lse, nullptr, pg,
+                                       (hipStream_t)stream));
+}
+
+int32_t ta_compact_paged(const void* Kpool, const void* Vpool, const ta_paged_kv* pg,
+                         const int32_t* idx, const int32_t* cnt, const ta_layout* lay, int32_t K,
+                         int32_t idx_shared, void* Kout, void* Vout, void* stream)
+{
+    ta_layout dense;
+    int32_t rc = check_paged(pg, lay, &dense, false);
+    if (rc != TA_OK) return rc;
+    rc = check_compact(Kpool, Vpool, idx, cnt, &dense, K, Kout, Vout);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_compact(Kpool, Vpool, idx, cnt, dense, K, idx_shared, Kout, Vout, pg,
+                                         (hipStream_t)stream));
+}
 
 int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
                  const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,

@@ -31,8 +31,13 @@ struct CompactArgs {
     int32_t batch, hkv, n, K;
     int32_t idx_shared;
     int32_t blocks_per_unit;
+    // paged input: rows are addressed through the block table (s_batch unused, s_page per page)
+    const int32_t* table;
+    int64_t s_page;
+    int32_t page_size, max_pages, num_pages;
 };
 
+template <bool PAGED>
 __global__ void __launch_bounds__(COMPACT_THREADS)
 compact_kernel(CompactArgs a)
 {
@@ -45,7 +50,7 @@ compact_kernel(CompactArgs a)
     int32_t cnt = a.cnt[sel];
     cnt = cnt > a.K ? a.K : cnt;
     const int32_t* idx = a.idx + (size_t)sel * (size_t)a.K;
-    const int64_t in_base = l * a.s_layer + b * a.s_batch + h * a.s_head;
+    const int64_t in_base = l * a.s_layer + (PAGED ? 0 : b * a.s_batch) + h * a.s_head;
     const int64_t out_base = (int64_t)unit * a.K * 16;
 
     const int lane16 = threadIdx.x & 15;
@@ -57,6 +62,12 @@ compact_kernel(CompactArgs a)
         r = r < cnt ? r : cnt - 1;                          // tail lanes re-read the last row, store nothing
         int32_t p = idx[r];
         p = p < 0 ? 0 : (p >= a.n ? a.n - 1 : p);
+        if (PAGED) {
+            const int32_t slot = p / a.page_size;
+            int32_t page = a.table[(size_t)b * a.max_pages + slot];
+            page = page < 0 ? 0 : (page >= a.num_pages ? a.num_pages - 1 : page);
+            return in_base + (int64_t)page * a.s_page + (int64_t)(p - slot * a.page_size) * a.s_pos + lane16;
+        }
         return in_base + (int64_t)p * a.s_pos + lane16;
     };
     static_assert(COMPACT_ITERS == 4, "loads below are written out four times");
@@ -89,7 +100,7 @@ compact_kernel(CompactArgs a)
 
 hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
                           const ta_layout& lay, int32_t K, int32_t idx_shared,
-                          void* Kout, void* Vout, hipStream_t st)
+                          void* Kout, void* Vout, const ta_paged_kv* pg, hipStream_t st)
 {
     CompactArgs a;
     a.Kin = (const uint4*)Kin;
@@ -98,10 +109,25 @@ hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, 
     a.cnt = cnt;
     a.Kout = (uint4*)Kout;
     a.Vout = (uint4*)Vout;
-    a.s_layer = lay.kv_stride[0] / 8;
-    a.s_batch = lay.kv_stride[1] / 8;
-    a.s_head = lay.kv_stride[2] / 8;
-    a.s_pos = lay.kv_stride[3] / 8;
+    if (pg) {
+        a.s_layer = pg->stride[0] / 8;
+        a.s_page = pg->stride[1] / 8;
+        a.s_pos = pg->stride[2] / 8;
+        a.s_head = pg->stride[3] / 8;
+        a.s_batch = 0;
+        a.table = pg->block_table;
+        a.page_size = pg->page_size;
+        a.max_pages = pg->max_pages;
+        a.num_pages = pg->num_pages;
+    } else {
+        a.s_layer = lay.kv_stride[0] / 8;
+        a.s_batch = lay.kv_stride[1] / 8;
+        a.s_head = lay.kv_stride[2] / 8;
+        a.s_pos = lay.kv_stride[3] / 8;
+        a.table = nullptr;
+        a.s_page = 0;
+        a.page_size = a.max_pages = a.num_pages = 0;
+    }
     a.batch = lay.batch;
     a.hkv = lay.hkv;
     a.n = lay.n;
@@ -110,7 +136,8 @@ hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, 
     a.blocks_per_unit = (K + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
     int64_t blocks = units * a.blocks_per_unit;
-    hipLaunchKernelGGL(compact_kernel, dim3((unsigned)blocks), dim3(COMPACT_THREADS), 0, st, a);
+    if (pg) hipLaunchKernelGGL(compact_kernel<true>, dim3((unsigned)blocks), dim3(COMPACT_THREADS), 0, st, a);
+    else hipLaunchKernelGGL(compact_kernel<false>, dim3((unsigned)blocks), dim3(COMPACT_THREADS), 0, st, a);
     return hipGetLastError();
 }
 

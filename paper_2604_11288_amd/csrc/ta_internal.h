@@ -60,8 +60,10 @@ int64_t score_grid_blocks(const ta_layout& lay);
 // of the first sweep's launch (it depends on the tokens only and is needed after the score).
 // With `lse` set (row log-sum-exps from a prefill attention kernel, [layers][batch][hq][W]) only the
 // column-sum sweep runs and ws is not used.
+// `pg` != null: K is a paged pool addressed through pg->block_table (lay.kv_stride unused).
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
-                        int causal, float* A, float* ws, const float* lse, const MatchRider* rider, hipStream_t st);
+                        int causal, float* A, float* ws, const float* lse, const MatchRider* rider,
+                        const ta_paged_kv* pg, hipStream_t st);
 
 // ---- select -----------------------------------------------------------------
 hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* spons,
@@ -72,7 +74,7 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
 // ---- compact ----------------------------------------------------------------
 hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
                           const ta_layout& lay, int32_t K, int32_t idx_shared,
-                          void* Kout, void* Vout, hipStream_t st);
+                          void* Kout, void* Vout, const ta_paged_kv* pg, hipStream_t st);
 
 // ---- incremental (decode) form ------------------------------------------------
 hipError_t launch_decode_init(const ta_decode_state& st, const int32_t* tok, const int32_t* seq_len, int32_t n,

@@ -73,16 +73,16 @@ struct RiderArgs {
 };
 
 // RG row groups of RT 32-row MFMA tiles each per workgroup; 2 * RG wavefronts.
-template <int RG, int RT, bool COLSUM>
+template <int RG, int RT, bool COLSUM, bool PAGED>
 __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS]);
 
 // one tile per wavefront: four wavefronts per SIMD (at most 128 registers each)
-template <int RG, int RT, bool COLSUM>
+template <int RG, int RT, bool COLSUM, bool PAGED>
 __global__ void __launch_bounds__(128 * RG, RT == 1 ? 4 : 2)
 score_kernel(ScoreArgs a)
 {
     __shared__ uint4 s_k[ring_of(RG)][STAGE_UNITS];        // 16 KB per stage
-    score_body<RG, RT, COLSUM>(a, s_k);
+    score_body<RG, RT, COLSUM, PAGED>(a, s_k);
 }
 
 template <int RG, int RT, bool COLSUM>
@@ -98,10 +98,10 @@ score_match_kernel(ScoreArgs a, RiderArgs r)
                           (int)threadIdx.x, *reinterpret_cast<MatchLds*>(&s_k[0][0]));
         return;
     }
-    score_body<RG, RT, COLSUM>(a, s_k);
+    score_body<RG, RT, COLSUM, false>(a, s_k);
 }
 
-template <int RG, int RT, bool COLSUM>
+template <int RG, int RT, bool COLSUM, bool PAGED>
 __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS])
 {
     constexpr int ROW_TILES = RT;
@@ -192,7 +192,28 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     // 16-byte chunk c' ^ (row & 15) of key row `row`.
     // The byte offset of a lane's 16 bytes inside a stage does not depend on the stage, so a
     // stage costs one scalar base address and no vector arithmetic (except the ragged last one).
-    const uint4* kbase = a.K + l * a.k_sl + b * a.k_sb + g * a.k_sh;
+    // Paged K: the keys of a stage (64 positions, page_size is a multiple of 64) lie in one page; lane j
+    // keeps the page of the j-th page slot of this chunk, so a stage costs a lane read, not a load.
+    const uint4* kbase = a.K + l * a.k_sl + (PAGED ? 0 : b * a.k_sb) + g * a.k_sh;
+    const int32_t slot_lo = PAGED ? key_lo / a.page_size : 0;
+    int32_t my_page = 0;
+    if constexpr (PAGED) {
+        const int32_t slot = slot_lo + lane;
+        if (slot < a.max_pages) my_page = a.table[(size_t)b * a.max_pages + slot];
+        my_page = my_page < 0 ? 0 : (my_page >= a.num_pages ? a.num_pages - 1 : my_page);
+    }
+    const auto stage_base = [&](int32_t key0) -> const uint4* {
+        if constexpr (!PAGED) return kbase + (int64_t)key0 * a.k_sp;
+        const int32_t slot = key0 / a.page_size;
+        const int32_t rel = __builtin_amdgcn_readfirstlane(slot - slot_lo);
+        int32_t page;
+        if (rel < 64) page = __builtin_amdgcn_readlane(my_page, rel);
+        else {                                             // chunks longer than 64 pages: read the table
+            page = a.table[(size_t)b * a.max_pages + slot];
+            page = page < 0 ? 0 : (page >= a.num_pages ? a.num_pages - 1 : page);
+        }
+        return kbase + (int64_t)page * a.k_spage + (int64_t)(key0 - slot * a.page_size) * a.k_sp;
+    };
     const uint32_t lds_ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)&s_k[0][0];
     const uint32_t lds_wave = lds_ring + 1024u * (uint32_t)__builtin_amdgcn_readfirstlane(wave);
     uint32_t lane_off[LPS];
@@ -203,7 +224,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     }
     auto stage_issue = [&](int s) {
         const int32_t key0 = key_lo + stage_pos(s) * STAGE_KEYS;
-        const uint4* sbase = kbase + (int64_t)key0 * a.k_sp;
+        const uint4* sbase = stage_base(key0);
         const uint32_t dst = lds_wave + (uint32_t)(s % RING) * (STAGE_UNITS * 16u);
         if (key0 + STAGE_KEYS <= n) {
 #pragma unroll
@@ -292,6 +313,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     // The compiler waits for ordinary loads with a count that knows nothing of the direct loads
     // below: a wait placed after them would also wait for every stage in flight.  Using the
     // fragments here puts that wait before the first direct load is issued.
+    if constexpr (PAGED) asm volatile("" ::"v"(my_page) : "memory");
 #pragma unroll
     for (int t = 0; t < ROW_TILES; ++t)
         asm volatile("" ::"v"(qf[t][0]), "v"(qf[t][1]), "v"(qf[t][2]), "v"(qf[t][3]), "v"(qf[t][4]), "v"(qf[t][5]),
@@ -537,8 +559,10 @@ void launch_sweep(const ScoreArgs& a, unsigned blocks, const MatchRider* rider, 
         r.score_blocks = blocks;
         const unsigned extra = (unsigned)r.m.tiles * (unsigned)r.m.batch;
         hipLaunchKernelGGL((score_match_kernel<RG, RT, COLSUM>), dim3(blocks + extra), dim3(128 * RG), 0, st, a, r);
+    } else if (a.table) {
+        hipLaunchKernelGGL((score_kernel<RG, RT, COLSUM, true>), dim3(blocks), dim3(128 * RG), 0, st, a);
     } else {
-        hipLaunchKernelGGL((score_kernel<RG, RT, COLSUM>), dim3(blocks), dim3(128 * RG), 0, st, a);
+        hipLaunchKernelGGL((score_kernel<RG, RT, COLSUM, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
     }
 }
 
@@ -623,11 +647,17 @@ int64_t score_grid_blocks(const ta_layout& lay)
 }
 
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
-                        int causal, float* A, float* ws, const float* lse, const MatchRider* rider, hipStream_t st)
+                        int causal, float* A, float* ws, const float* lse, const MatchRider* rider,
+                        const ta_paged_kv* pg, hipStream_t st)
 {
     const ScorePlan p = make_plan(lay);
     ScoreArgs a;
     a.lse = lse;
+    a.table = pg ? pg->block_table : nullptr;
+    a.k_spage = pg ? pg->stride[1] / 8 : 0;
+    a.page_size = pg ? pg->page_size : 0;
+    a.max_pages = pg ? pg->max_pages : 0;
+    a.num_pages = pg ? pg->num_pages : 0;
     a.Q = (const uint4*)Q;
     a.K = (const uint4*)K;
     a.seq_len = seq_len;
@@ -636,10 +666,17 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.q_sl = lay.q_stride[0] / 8;
     a.q_sb = lay.q_stride[1] / 8;
     a.q_sh = lay.q_stride[2] / 8;
-    a.k_sl = lay.kv_stride[0] / 8;
-    a.k_sb = lay.kv_stride[1] / 8;
-    a.k_sh = lay.kv_stride[2] / 8;
-    a.k_sp = (int32_t)(lay.kv_stride[3] / 8);
+    if (pg) {
+        a.k_sl = pg->stride[0] / 8;
+        a.k_sb = 0;
+        a.k_sp = (int32_t)(pg->stride[2] / 8);
+        a.k_sh = pg->stride[3] / 8;
+    } else {
+        a.k_sl = lay.kv_stride[0] / 8;
+        a.k_sb = lay.kv_stride[1] / 8;
+        a.k_sh = lay.kv_stride[2] / 8;
+        a.k_sp = (int32_t)(lay.kv_stride[3] / 8);
+    }
     a.batch = lay.batch;
     a.hkv = lay.hkv;
     a.G = lay.hq / lay.hkv;

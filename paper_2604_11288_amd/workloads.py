@@ -266,3 +266,35 @@ def make_embedding_inputs(V: int, d_model: int, E: int, seed: int = BASE_SEED + 
         if stride > d_model:
             buf[s:e, d_model:] = 7.0                       # padding a correct kernel never reads
     return buf[:, :d_model], C.to(torch.bfloat16)
+
+
+def make_paged(K: torch.Tensor, V: torch.Tensor, page_size: int, heads_first: bool = False, spare_pages: int = 3,
+               seed: int = BASE_SEED + 17):
+    """Scatters dense caches [Lyr][B][Hkv][n][d] into paged pools the way a serving engine's
+    allocator leaves them: every sequence's pages sit at random places of a pool that also holds
+    a few unused pages.  Pools are [Lyr][pages][page_size][Hkv][d], or [Lyr][pages][Hkv][page_size][d]
+    with heads_first.  Returns (Kpool, Vpool, table int32 [B][max_pages] on the device, num_pages,
+    element strides (layer, page, position, head)).  Pure data movement."""
+    lyr, B, H, n, d = K.shape
+    max_pages = (n + page_size - 1) // page_size
+    num_pages = B * max_pages + spare_pages
+    rng = np.random.default_rng(seed)
+    table = rng.permutation(num_pages)[: B * max_pages].astype(np.int32).reshape(B, max_pages)
+    shape = (lyr, num_pages, H, page_size, d) if heads_first else (lyr, num_pages, page_size, H, d)
+    pools = []
+    for src in (K, V):
+        pool = torch.full(shape, 3.0, dtype=torch.bfloat16, device=K.device)   # unused pages and tails hold junk
+        for b in range(B):
+            for j in range(max_pages):
+                lo, hi = j * page_size, min((j + 1) * page_size, n)
+                rows = src[:, b, :, lo:hi]                                      # [Lyr][H][rows][d]
+                if heads_first:
+                    pool[:, table[b, j], :, : hi - lo] = rows
+                else:
+                    pool[:, table[b, j], : hi - lo] = rows.transpose(1, 2)
+        pools.append(pool)
+    if heads_first:
+        strides = (num_pages * H * page_size * d, H * page_size * d, d, page_size * d)
+    else:
+        strides = (num_pages * page_size * H * d, page_size * H * d, H * d, d)
+    return pools[0], pools[1], torch.from_numpy(table).to(K.device), num_pages, strides
