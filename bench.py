@@ -76,6 +76,11 @@ def main():
     ap.add_argument("--score-lse", action="store_true",
                     help="also time the one-sweep score from given row log-sum-exps (what a flash-style prefill "
                          "kernel leaves behind; computed here with torch, outside the timing; reported as score_one_sweep)")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_SIZE",
+                    help="also time scoring and compaction over a paged (block-table) copy of the same cache with "
+                         "pages of this many positions (a multiple of 64; reported as paged)")
+    ap.add_argument("--paged-heads-first", action="store_true",
+                    help="pages laid out [heads][page_size][d] instead of [page_size][heads][d]")
     ap.add_argument("--detect-positions", type=int, default=0,
                     help="also time the learned anchor detector + voucher expansion on about this many positions "
                          "of synthetic last-layer hidden states (sequences of the workload's length; reported as "
@@ -225,6 +230,40 @@ def main():
                      "max_rel_diff_to_two_sweep": float("%.2e" % rel),
                      "pass_us": round(pass1_us, 1), "pass_GB/s": round((score_b + compact_b) / pass1_us / 1e3, 1)}
         del lse, A2, plan1
+
+    # ---- the same cache behind a block table -----------------------------------------------------
+    paged_out = None
+    if args.paged > 0 and scored:
+        Kp, Vp, table, num_pages, strides = wl.make_paged(K, V, args.paged, heads_first=args.paged_heads_first)
+        pk = ta.PagedKV(Kp, Vp, table, args.paged, num_pages, strides, w.layers, w.batch, w.hkv, w.n)
+        Ap = torch.empty_like(plan.A)
+        outp = (torch.zeros_like(plan.Kout), torch.zeros_like(plan.Vout))
+        evp = {"score": [], "compact": []}
+        for it in range(10 + max(args.steps, 20)):
+            if it == 10:
+                evp = {"score": [], "compact": []}
+            # the same sequence of launches as the stage-by-stage timing of the dense cache above
+            for name, fn in (("match", lambda: ta.ta_match_anchors(tok, td.tab_ids, td.tab_len, prm, seq_len=seq,
+                                                                   out=(plan.anchor, plan.spons, plan.vouch), stream=stream)),
+                             ("score", lambda: ta.ta_score_paged(Q, pk, prm, seq_len=seq, A=Ap, ws=plan.ws, stream=stream)),
+                             ("select", lambda: ta.ta_select(Ap, plan.anchor, plan.spons, plan.vouch, budget, prm,
+                                                             sel_layers, sel_hkv, seq_len=seq, out=(plan.idx, plan.cnt),
+                                                             stream=stream)),
+                             ("compact", lambda: ta.ta_compact_paged(pk, plan.idx, plan.cnt, budget, out=outp, stream=stream))):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                fn()
+                e1.record(stream)
+                if name in evp:
+                    evp[name].append((e0, e1))
+        torch.cuda.synchronize()
+        pus = {k: 1e3 * float(np.median([a.elapsed_time(b) for a, b in v])) for k, v in evp.items()}
+        paged_out = {"page_size": args.paged, "pages": num_pages,
+                     "page_layout": "[heads][page_size][d]" if args.paged_heads_first else "[page_size][heads][d]", "score_us": round(pus["score"], 2),
+                     "compact_us": round(pus["compact"], 2),
+                     "same_scores_as_dense": bool(torch.equal(Ap, plan.A)),
+                     "same_rows_as_dense": bool(torch.equal(outp[0], plan.Kout) and torch.equal(outp[1], plan.Vout))}
+        del Kp, Vp, pk, Ap, outp
 
     # ---- budget sweep of the same workload (context, outside the headline timing) ----------
     sweep = {}
@@ -403,6 +442,7 @@ def main():
         "kernels_us": {k: round(v, 2) for k, v in kern_us.items()},
         "budget_sweep": sweep,
         "score_one_sweep": one_sweep,
+        "paged": paged_out,
         "decode_step": decode,
         "learned_detect": detect,
         "embedding_detect": embed,

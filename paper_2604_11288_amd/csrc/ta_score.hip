@@ -195,7 +195,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     // Paged K: the keys of a stage (64 positions, page_size is a multiple of 64) lie in one page; lane j
     // keeps the page of the j-th page slot of this chunk, so a stage costs a lane read, not a load.
     const uint4* kbase = a.K + l * a.k_sl + (PAGED ? 0 : b * a.k_sb) + g * a.k_sh;
-    const int32_t slot_lo = PAGED ? key_lo / a.page_size : 0;
+    const auto slot_of = [&](int32_t key) { return a.page_shift >= 0 ? key >> a.page_shift : key / a.page_size; };
+    const int32_t slot_lo = PAGED ? slot_of(key_lo) : 0;
     int32_t my_page = 0;
     if constexpr (PAGED) {
         const int32_t slot = slot_lo + lane;
@@ -204,7 +205,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     }
     const auto stage_base = [&](int32_t key0) -> const uint4* {
         if constexpr (!PAGED) return kbase + (int64_t)key0 * a.k_sp;
-        const int32_t slot = key0 / a.page_size;
+        const int32_t slot = slot_of(key0);
         const int32_t rel = __builtin_amdgcn_readfirstlane(slot - slot_lo);
         int32_t page;
         if (rel < 64) page = __builtin_amdgcn_readlane(my_page, rel);
@@ -658,6 +659,11 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     a.page_size = pg ? pg->page_size : 0;
     a.max_pages = pg ? pg->max_pages : 0;
     a.num_pages = pg ? pg->num_pages : 0;
+    a.page_shift = -1;
+    if (pg && (pg->page_size & (pg->page_size - 1)) == 0) {
+        a.page_shift = 0;
+        while ((1 << a.page_shift) < pg->page_size) ++a.page_shift;
+    }
     a.Q = (const uint4*)Q;
     a.K = (const uint4*)K;
     a.seq_len = seq_len;

@@ -17,6 +17,7 @@ struct ScoreArgs {
     const int32_t* table;              // paged K: block table [batch][max_pages], or null (dense K)
     int64_t k_spage;                   // paged K: page stride in 16-byte units
     int32_t page_size, max_pages, num_pages;
+    int32_t page_shift;                // log2(page_size) when it is a power of two, else -1
     const float* lse;                  // given row log-sum-exps [layers][batch][hq][W] (natural log), or null
     int64_t q_sl, q_sb, q_sh;          // Q strides (layer, batch, head) in 16-byte units
     int64_t k_sl, k_sb, k_sh;          // K strides (layer, batch, head) in 16-byte units
