@@ -39,9 +39,9 @@ SCORE_TRAFFIC = {
     "workload": "c2_full_model",
     "bytes_per_step": 559.4e6,
     "sources": {
-        "ta_score.hip": "c90c08e729bea18101596b7501bba9f123ab92cb100d0c6cd2cb1f4fa9735a6d",
-        "ta_score_common.h": "fbbe78be7b8be5f520bfb3b45e5ed4bd9b5567d7968503bec942999d6176d6bd",
-        "ta_match_device.h": "65f3540c6956f0ab39262b2c72213fd330f5fd3f13388ec689522f4ddc94e0c0",
+        "ta_score.hip": "4d15422174543c740d79d74b74f4f0d0c93b0d61880bb55b79c9112d8431ec76",
+        "ta_score_common.h": "14e66dcdc4dc6f17f6869341ad61b1a751102228fa6b741a7ac8e73ca6c74618",
+        "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
     },
 }
 
