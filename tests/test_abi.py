@@ -201,3 +201,85 @@ def test_layer_budgets_host_function_matches_oracle(L):
     assert L.ta_layer_budgets(4, 10, 11, out.ctypes.data) == tb.TA_ERR_SHAPE       # k_min > K
     assert L.ta_layer_budgets(0, 10, 1, out.ctypes.data) == tb.TA_ERR_SHAPE
     assert L.ta_layer_budgets(4, 10, 1, None) == tb.TA_ERR_NULL
+
+
+def test_detector_and_embedding_error_paths(L):
+    cp = tb.Params().c()
+    f32 = ctypes.c_float
+    det = lambda h=FAKE, stride=4096, m=128, dm=4096, thr=0.5, scale=1.0: [
+        h, stride, FAKE, FAKE, None, 2, 100, dm, m, f32(thr), 0, f32(scale), ctypes.byref(cp), FAKE, FAKE, FAKE, None]
+    assert L.ta_detect_anchors(*det(h=None)) == tb.TA_ERR_NULL
+    assert L.ta_detect_anchors(*det(m=96)) == tb.TA_ERR_SHAPE                     # hidden width not 32/64/128/256
+    assert L.ta_detect_anchors(*det(dm=4080, stride=4080)) == tb.TA_ERR_SHAPE     # d_model not a multiple of 32
+    assert L.ta_detect_anchors(*det(stride=4095)) == tb.TA_ERR_SHAPE              # rows overlap
+    assert L.ta_detect_anchors(*det(stride=4100)) == tb.TA_ERR_ALIGN              # rows not 16-byte aligned
+    assert L.ta_detect_anchors(*det(thr=float("nan"))) == tb.TA_ERR_SHAPE
+    assert L.ta_detect_anchors(*det(scale=float("inf"))) == tb.TA_ERR_SHAPE
+    assert L.ta_detect_anchors(*det(h=ctypes.c_void_p(0x7f0000001008))) == tb.TA_ERR_ALIGN
+    a = det(); a[12] = None
+    assert L.ta_detect_anchors(*a) == tb.TA_ERR_NULL
+    emb = lambda E=16, dm=4096, tau=0.5, x=FAKE: [x, dm, FAKE, E, None, 1, 1000, dm, f32(tau), FAKE, FAKE, None]
+    assert L.ta_embed_anchors(*emb(x=None)) == tb.TA_ERR_NULL
+    assert L.ta_embed_anchors(*emb(E=0)) == tb.TA_ERR_SHAPE
+    assert L.ta_embed_anchors(*emb(E=257)) == tb.TA_ERR_SHAPE
+    assert L.ta_embed_anchors(*emb(dm=48)) == tb.TA_ERR_SHAPE
+    assert L.ta_embed_anchors(*emb(tau=float("nan"))) == tb.TA_ERR_SHAPE
+    assert L.ta_lookup_anchors(FAKE, None, 1, 100, None, 10, FAKE, None) == tb.TA_ERR_NULL
+    assert L.ta_lookup_anchors(FAKE, None, 1, 100, FAKE, 0, FAKE, None) == tb.TA_ERR_SHAPE
+    assert L.ta_expand_vouchers(None, None, None, 1, 100, ctypes.byref(cp), FAKE, FAKE, None) == tb.TA_ERR_NULL
+    assert L.ta_expand_vouchers(FAKE, None, None, 0, 100, ctypes.byref(cp), FAKE, FAKE, None) == tb.TA_ERR_SHAPE
+    cp_bad = tb.Params(pool_k=4).c()
+    assert L.ta_expand_vouchers(FAKE, None, None, 1, 100, ctypes.byref(cp_bad), FAKE, FAKE, None) == tb.TA_ERR_SHAPE
+
+
+def test_lse_and_paged_error_paths(L):
+    cp = tb.Params().c()
+    lay = _lay()
+    lse = lambda lay_=lay, l=FAKE, K=FAKE: [FAKE, K, ctypes.byref(lay_), None, ctypes.byref(cp), l, FAKE, None]
+    assert L.ta_score_lse(*lse(l=None)) == tb.TA_ERR_NULL
+    assert L.ta_score_lse(*lse(_lay(d=64))) == tb.TA_ERR_SHAPE
+    assert L.ta_score_lse(*lse(K=ctypes.c_void_p(0x7f0000001008))) == tb.TA_ERR_ALIGN
+
+    def pg(page_size=64, max_pages=64, num_pages=70, table=FAKE, stride=(70 * 64 * 8 * 128, 64 * 8 * 128, 8 * 128, 128)):
+        p = tb.CPaged()
+        p.page_size, p.max_pages, p.num_pages = page_size, max_pages, num_pages
+        p.block_table = table.value if table is not None else None
+        for i in range(4):
+            p.stride[i] = stride[i]
+        return p
+    need = L.ta_workspace_bytes(ctypes.byref(lay), ctypes.byref(cp))
+    sc = lambda p, lay_=lay: [FAKE, FAKE, ctypes.byref(p), ctypes.byref(lay_), None, ctypes.byref(cp), None,
+                              FAKE, FAKE, need, None]
+    assert L.ta_score_paged(*sc(pg(page_size=48))) == tb.TA_ERR_SHAPE             # not a multiple of 64
+    assert L.ta_score_paged(*sc(pg(max_pages=63))) == tb.TA_ERR_SHAPE             # table too short for n = 4096
+    assert L.ta_score_paged(*sc(pg(table=None))) == tb.TA_ERR_NULL
+    assert L.ta_score_paged(*sc(pg(stride=(0, 64 * 8 * 128, 8 * 128 + 4, 128)))) == tb.TA_ERR_ALIGN
+    assert L.ta_score_paged(*sc(pg(num_pages=0))) == tb.TA_ERR_SHAPE
+    a = sc(pg()); a[9] = need - 1
+    assert L.ta_score_paged(*a) == tb.TA_ERR_WORKSPACE
+    cm = lambda p, K=16: [FAKE, FAKE, ctypes.byref(p), FAKE, FAKE, ctypes.byref(lay), K, 0, FAKE, FAKE, None]
+    assert L.ta_compact_paged(*cm(pg(page_size=0))) == tb.TA_ERR_SHAPE
+    assert L.ta_compact_paged(*cm(pg(page_size=16, max_pages=255))) == tb.TA_ERR_SHAPE
+    assert L.ta_compact_paged(*cm(pg(), K=0)) == tb.TA_ERR_SHAPE
+    a = cm(pg()); a[8] = None
+    assert L.ta_compact_paged(*a) == tb.TA_ERR_NULL
+    # ta_evict_lse: needs an attention term and the log-sum-exps
+    ids, lens = _table()
+    cp0 = tb.Params(alpha=0.0).c()
+    ev = lambda prm, l=FAKE: [FAKE, None, ids.ctypes.data, lens.ctypes.data, 2, None, FAKE, FAKE, FAKE, l,
+                              ctypes.byref(lay), ctypes.byref(prm), 16, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None]
+    assert L.ta_evict_lse(*ev(cp0)) == tb.TA_ERR_SHAPE
+    assert L.ta_evict_lse(*ev(cp, l=None)) == tb.TA_ERR_NULL
+
+
+def test_decode_rejects_one_shot_options(L):
+    st = tb.CDecodeState()
+    st.layers, st.batch, st.hq, st.hkv, st.d, st.K, st.cap = 1, 1, 8, 2, 128, 16, 64
+    for name in ("tok", "len", "anchor", "budget", "vouch", "spons", "Kc", "Vc", "pos", "A"):
+        setattr(st, name, FAKE.value)
+    ids, lens = _table()
+    call = lambda prm: L.ta_decode_step(ctypes.byref(st), FAKE, FAKE, FAKE, FAKE, ids.ctypes.data, lens.ctypes.data, 2,
+                                        ctypes.byref(prm), None, None)
+    assert call(tb.Params(n_sink=4, n_recent=4, pool_k=5).c()) == tb.TA_ERR_SHAPE
+    assert call(tb.Params(n_sink=4, n_recent=4, k_protected=4).c()) == tb.TA_ERR_SHAPE
+    assert call(tb.Params(n_sink=10, n_recent=10).c()) == tb.TA_ERR_BUDGET
