@@ -14,8 +14,8 @@
  *      ta_lookup_anchors    (Sec. 3.2), per position or once per vocabulary entry
  *      ta_score_lse /    scores in one sweep from the prefill attention's row log-sum-exps
  *      ta_evict_lse
- *      ta_score_paged /  steps 3 and 5 over paged (block-table) caches
- *      ta_compact_paged
+ *      ta_score_paged /  steps 3 and 5, and the whole pass, over paged (block-table) caches
+ *      ta_compact_paged / ta_evict_paged
  *      ta_evict          all of the above in one call
  *      ta_decode_init /  the same policy applied after every generation step
  *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
@@ -360,6 +360,19 @@ int32_t ta_evict_lse(const int32_t *tok, const int32_t *seq_len,
                      const ta_layout *lay, const ta_params *prm, int32_t K,
                      uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
                      int32_t *idx, int32_t *cnt, void *Kout, void *Vout, void *stream);
+
+/*
+ * The whole pass over a paged cache: as ta_evict (lse == NULL; ws as there) or ta_evict_lse
+ * (lse != NULL; ws unused), with K and V addressed through the block table of `pg`.
+ * Outputs as in the dense calls.  Errors: as ta_evict / ta_score_paged / ta_compact_paged.
+ */
+int32_t ta_evict_paged(const int32_t *tok, const int32_t *seq_len,
+                       const int32_t *tab_ids, const int32_t *tab_len, int32_t E, const float *anchor_B,
+                       const void *Q, const void *Kpool, const void *Vpool, const ta_paged_kv *pg,
+                       const float *lse, const ta_layout *lay, const ta_params *prm, int32_t K,
+                       uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
+                       int32_t *idx, int32_t *cnt, void *Kout, void *Vout,
+                       void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Incremental form: the same retention policy applied after every generation

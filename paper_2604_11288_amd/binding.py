@@ -26,7 +26,7 @@ TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
            "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged",
-           "ta_evict", "ta_evict_lse", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
+           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
 class TaError(RuntimeError):
@@ -141,6 +141,9 @@ def lib():
         L.ta_evict_lse.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, i32,
                                    vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ta_evict_lse.restype = i32
+        L.ta_evict_paged.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                     vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ta_evict_paged.restype = i32
         L.ta_decode_init.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ta_decode_init.restype = i32
         L.ta_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
@@ -432,12 +435,19 @@ class EvictPlan:
     """
 
     def __init__(self, tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params,
-                 seq_len=None, anchor_B=None, lse=None):
+                 seq_len=None, anchor_B=None, lse=None, paged=None):
+        self.paged = paged                 # PagedKV: Kin / Vin are then its pools (pass None for both)
+        if paged is not None:
+            Kin, Vin = paged.Kpool, paged.Vpool
         dev = Kin.device
         self.params, self.K = params, int(K)
         self.lse = lse                     # row log-sum-exps of the prefill attention kernel: ta_evict_lse
         self.scored = params.alpha != 0.0
-        self.lay = layout_of(Kin, Q if self.scored else None)
+        if paged is not None:
+            self.lay = paged.layout(Q if self.scored else None)
+            self._pg = paged.c()
+        else:
+            self.lay = layout_of(Kin, Q if self.scored else None)
         lay = self.lay
         self.tok, self.seq_len, self.anchor_B = tok, seq_len, anchor_B
         self.Q, self.Kin, self.Vin = (Q if self.scored else None), Kin, Vin
@@ -450,7 +460,11 @@ class EvictPlan:
             self.A = torch.empty((lay.layers, B, lay.hkv, n), dtype=torch.float32, device=dev)
             self.idx = torch.full((lay.layers, B, lay.hkv, self.K), -1, dtype=torch.int32, device=dev)
             self.cnt = torch.zeros((lay.layers, B, lay.hkv), dtype=torch.int32, device=dev)
-            nbytes = ta_workspace_bytes(lay, params) if lse is None else 0
+            sized = lay
+            if paged is not None:                                # workspace size depends on the sizes only
+                sized = CLayout.from_buffer_copy(lay)
+                sized.kv_stride[3] = lay.d
+            nbytes = ta_workspace_bytes(sized, params) if lse is None else 0
             self.ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
             if lse is not None:
                 assert lse.dtype == torch.float32 and lse.is_contiguous()
@@ -466,6 +480,16 @@ class EvictPlan:
 
     def run(self, stream=None):
         ws_bytes = 0 if self.ws is None else self.ws.numel()
+        if self.paged is not None:
+            rc = lib().ta_evict_paged(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
+                                      self.E, _ptr(self.anchor_B), _ptr(self.Q), _ptr(self.Kin), _ptr(self.Vin),
+                                      ctypes.byref(self._pg), _ptr(self.lse), ctypes.byref(self.lay),
+                                      ctypes.byref(self._cp), self.K,
+                                      _ptr(self.anchor), _ptr(self.spons), _ptr(self.vouch), _ptr(self.A),
+                                      _ptr(self.idx), _ptr(self.cnt), _ptr(self.Kout), _ptr(self.Vout),
+                                      _ptr(self.ws), ws_bytes, _stream(stream))
+            _check(rc, "ta_evict_paged")
+            return self
         if self.lse is not None:
             rc = lib().ta_evict_lse(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
                                     self.E, _ptr(self.anchor_B), _ptr(self.Q), _ptr(self.Kin), _ptr(self.Vin),
@@ -488,6 +512,12 @@ def ta_evict(tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params, seq_len
              stream=None) -> EvictPlan:
     """The whole pass in one call; returns the plan object holding every output tensor."""
     return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B).run(stream)
+
+
+def ta_evict_paged(tok, tab_ids, tab_len, Q, paged: "PagedKV", K: int, params: Params, seq_len=None, anchor_B=None,
+                   lse=None, stream=None) -> EvictPlan:
+    """The whole pass over a paged cache (two sweeps, or one with lse)."""
+    return EvictPlan(tok, tab_ids, tab_len, Q, None, None, K, params, seq_len, anchor_B, lse=lse, paged=paged).run(stream)
 
 
 def ta_evict_lse(tok, tab_ids, tab_len, Q, Kin, Vin, lse, K: int, params: Params, seq_len=None, anchor_B=None,

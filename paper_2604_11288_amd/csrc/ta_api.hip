@@ -337,8 +337,14 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
                    const ta_layout* lay, const ta_params* prm, int32_t K,
                    uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
                    int32_t* idx, int32_t* cnt, void* Kout, void* Vout,
-                   void* ws, size_t ws_bytes, const float* lse, void* stream)
+                   void* ws, size_t ws_bytes, const float* lse, const ta_paged_kv* pg, void* stream)
 {
+    ta_layout dense_of_paged;
+    if (pg) {                                              // sizes from lay, addressing from pg
+        int32_t prc = check_paged(pg, lay, &dense_of_paged, prm && prm->alpha != 0.0f);
+        if (prc != TA_OK) return prc;
+        lay = &dense_of_paged;
+    }
     // validate every stage first: nothing runs unless all of them can
     int32_t rc = check_params(prm);
     if (rc != TA_OK) return rc;
@@ -371,7 +377,7 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
     if (scored) {
         // the match rides along with the first sweep over the keys (one launch fewer in front of them)
         const ta::MatchRider rider = {tok, anchor_B, prm->allow, anchor, spons, vouch, &tab};
-        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, lse, &rider, nullptr, st));
+        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, lse, &rider, pg, st));
         if (rc != TA_OK) return rc;
     } else {
         rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, prm->allow, anchor, spons, vouch, st));
@@ -380,7 +386,7 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
     rc = hip_status(ta::launch_select(A, anchor, spons, vouch, seq_len, sel_layers, lay->batch, sel_hkv,
                                       lay->n, K, *prm, idx, cnt, st));
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, nullptr, st));
+    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, pg, st));
 }
 
 }  // namespace
@@ -430,7 +436,7 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
                  void* ws, size_t ws_bytes, void* stream)
 {
     return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
-                      idx, cnt, Kout, Vout, ws, ws_bytes, nullptr, stream);
+                      idx, cnt, Kout, Vout, ws, ws_bytes, nullptr, nullptr, stream);
 }
 
 int32_t ta_evict_lse(const int32_t* tok, const int32_t* seq_len,
@@ -443,7 +449,20 @@ int32_t ta_evict_lse(const int32_t* tok, const int32_t* seq_len,
     if (!prm || !lse) return TA_ERR_NULL;
     if (prm->alpha == 0.0f) return TA_ERR_SHAPE;            // nothing to fuse in the attention-free setting
     return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
-                      idx, cnt, Kout, Vout, nullptr, 0, lse, stream);
+                      idx, cnt, Kout, Vout, nullptr, 0, lse, nullptr, stream);
+}
+
+int32_t ta_evict_paged(const int32_t* tok, const int32_t* seq_len,
+                       const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                       const void* Q, const void* Kpool, const void* Vpool, const ta_paged_kv* pg, const float* lse,
+                       const ta_layout* lay, const ta_params* prm, int32_t K,
+                       uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                       int32_t* idx, int32_t* cnt, void* Kout, void* Vout,
+                       void* ws, size_t ws_bytes, void* stream)
+{
+    if (!pg) return TA_ERR_NULL;
+    return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kpool, Vpool, lay, prm, K, anchor, spons, vouch, A,
+                      idx, cnt, Kout, Vout, ws, ws_bytes, lse, pg, stream);
 }
 
 int32_t ta_decode_init(const ta_decode_state* st, const int32_t* tok, const int32_t* seq_len, int32_t n,

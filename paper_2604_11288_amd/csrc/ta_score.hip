@@ -552,6 +552,12 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
 template <int RG, int RT, bool COLSUM>
 void launch_sweep(const ScoreArgs& a, unsigned blocks, const MatchRider* rider, hipStream_t st)
 {
+    if (rider && a.table) {
+        // paged keys: the match runs as a launch of its own in front of the sweep
+        launch_match(rider->tok, a.seq_len, a.batch, a.n, *rider->tab, rider->anchor_B, rider->allow, rider->anchor,
+                     rider->spons, rider->vouch, st);
+        rider = nullptr;
+    }
     if (rider) {
         RiderArgs r;
         r.m = make_match_args(rider->tok, a.seq_len, a.batch, a.n, rider->anchor_B, rider->allow, rider->anchor, rider->spons,

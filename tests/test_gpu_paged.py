@@ -97,3 +97,40 @@ def test_corrupt_block_table_cannot_fault():
     A = ta.ta_score_paged(Q, paged, ta.Params())
     torch.cuda.synchronize()
     assert torch.isfinite(A).all()
+
+
+@pytest.mark.parametrize("with_lse,alpha", [(False, 1.0), (True, 1.0), (False, 0.0)])
+def test_whole_pass_over_a_paged_cache_equals_the_dense_pass(with_lse, alpha):
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=2, batch=2, n=2600, hq=8, hkv=2, planted=6, ragged=(900, 2600),
+                  alpha=alpha)
+    td = wl.make_tokens(w, clean=False)
+    Q, K, V = wl.make_qkv(w, device=DEV)
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent, alpha=alpha)
+    seq = _dev(td.seq_len)
+    lse = None
+    if with_lse:
+        G = w.hq // w.hkv
+        lse_h = np.full((w.layers, w.batch, w.hq, w.window), -np.inf, np.float32)
+        for l in range(w.layers):
+            for b in range(w.batch):
+                nb = int(td.seq_len[b])
+                for g in range(w.hkv):
+                    lse_h[l, b, g * G:(g + 1) * G] = ora.row_lse(wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]),
+                                                                 wl.bf16_bits(K[l, b, g, :nb]), True)
+        lse = _dev(lse_h)
+    Kp, Vp, table, num_pages, strides = wl.make_paged(K, V, 128)
+    paged = ta.PagedKV(Kp, Vp, table, 128, num_pages, strides, w.layers, w.batch, w.hkv, w.n)
+    Kb = 150
+    tok = _dev(td.tok)
+    Qa = Q if alpha != 0.0 else None
+    if with_lse:
+        dense = ta.ta_evict_lse(tok, td.tab_ids, td.tab_len, Q, K, V, lse, Kb, prm, seq_len=seq)
+    else:
+        dense = ta.ta_evict(tok, td.tab_ids, td.tab_len, Qa, K, V, Kb, prm, seq_len=seq)
+    pg = ta.ta_evict_paged(tok, td.tab_ids, td.tab_len, Qa, paged, Kb, prm, seq_len=seq, lse=lse)
+    torch.cuda.synchronize()
+    for name in ("anchor", "spons", "vouch", "idx", "cnt", "Kout", "Vout"):
+        assert torch.equal(getattr(dense, name), getattr(pg, name)), name
+    if alpha != 0.0:
+        assert torch.equal(dense.A, pg.A)
+    assert int(pg.cnt.min()) > 0 and pg.Kout.abs().sum() > 0
