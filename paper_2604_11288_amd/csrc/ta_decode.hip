@@ -12,11 +12,13 @@
 //                        (class, u, position) order
 //   decode_decay_kernel  B_i <- decay * B_i for every position
 // The unit kernel is the hot one: it reads the unit's K slots once (HBM bound,
-// (K+1) * 256 B per unit per step).  With 4 query heads per group the
-// contraction is a 4-row GEMV, so it runs on the vector ALUs: 16 lanes share a
-// 256-byte key row (one 16-byte load each) and reduce their partial dot
-// products with four cross-lane adds.
+// (K+1) * 256 B per unit per step).  The logits of the group's query heads over the
+// slots are a thin contraction that runs on the matrix cores (16-row key tiles x 16
+// head columns), fed with whole key rows that are turned into operand fragments
+// through a small LDS tile.
 #include <math.h>
+
+#include <mutex>
 
 #include "ta_internal.h"
 
@@ -162,53 +164,6 @@ struct UnitArgs {
     float scale_log2;
 };
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
-{
-    union { uint32_t u; bf16x2 v; } x, y;
-    x.u = a;
-    y.u = b;
-    return __builtin_amdgcn_fdot2_f32_bf16(x.v, y.v, c, false);   // a.lo*b.lo + a.hi*b.hi + c in fp32
-}
-
-// dot product of eight bf16 pairs, fp32 accumulation
-__device__ __forceinline__ float dot8(const uint4& a, const uint4& b)
-{
-    float s = dot2(a.x, b.x, 0.0f);
-    s = dot2(a.y, b.y, s);
-    s = dot2(a.z, b.z, s);
-    s = dot2(a.w, b.w, s);
-    return s;
-}
-
-// v + (v of another lane of the same row of 16), through the data-parallel-primitive path of
-// the vector ALU (no LDS traffic).  After the four steps below every lane of a 16-lane group
-// holds the group's sum.
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v)
-{
-    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true);
-    return v + __int_as_float(o);
-}
-
-// keep + (send of the lane selected by CTRL)
-template <int CTRL>
-__device__ __forceinline__ float dpp_add_other(float keep, float send)
-{
-    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(send), CTRL, 0xF, 0xF, true);
-    return keep + __int_as_float(o);
-}
-
-__device__ __forceinline__ float sum16(float d)
-{
-    d = dpp_add<0xB1>(d);      // quad_perm [1,0,3,2]: lane ^ 1
-    d = dpp_add<0x4E>(d);      // quad_perm [2,3,0,1]: lane ^ 2
-    d = dpp_add<0x141>(d);     // row_half_mirror: the other quad of each 8
-    d = dpp_add<0x140>(d);     // row_mirror: the other half of the 16
-    return d;
-}
-
 __device__ __forceinline__ uint32_t ordered_bits(float u)
 {
     uint32_t b = __float_as_uint(u);
@@ -230,7 +185,7 @@ __device__ __forceinline__ T block_reduce(T v, T* s_red, Op op)
     return r;
 }
 
-constexpr int DW_ROWS = 6;                                 // key rows in flight per 16-lane group
+constexpr int DT_RING = 4;                                 // 16-row key tiles held per wavefront: one multiplied, the others in flight
 
 __device__ __forceinline__ float wave_max(float v)
 {
@@ -244,6 +199,23 @@ __device__ __forceinline__ float wave_sum(float v)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     return v;
+}
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// the two 8-byte halves of a 16-byte load as MFMA operand fragments (four bf16 each)
+__device__ __forceinline__ s16x4 lo_half(const uint4& v)
+{
+    union { uint2 u; s16x4 s; } c;
+    c.u = make_uint2(v.x, v.y);
+    return c.s;
+}
+__device__ __forceinline__ s16x4 hi_half(const uint4& v)
+{
+    union { uint2 u; s16x4 s; } c;
+    c.u = make_uint2(v.z, v.w);
+    return c.s;
 }
 
 // One wavefront per unit, no workgroup barriers: the step of a unit is a chain of short
@@ -272,31 +244,39 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
     const bool scored = a.alpha != 0.0f;
     int32_t* s_pos = reinterpret_cast<int32_t*>(s_dyn);
     float* s_A = s_dyn + slots;
-    float* s_w = s_dyn + 2 * slots;
+    const int wstride = (slots + 3) & ~3;                  // logits of a head: padded to whole 16-byte groups
+    uint4* s_t = reinterpret_cast<uint4*>(s_dyn + ((2 * slots + 3) & ~3));   // one 16-row key tile, 4 KB (scored only)
+    float* s_w = reinterpret_cast<float*>(s_t + 256);
 
-    // first key rows and the queries are requested before anything else.  A lane's rows of one
-    // batch are 1 KB apart, so they share one address register; only the batch that runs past
-    // the last slot clamps its rows.
-    uint4 qv[GH];
-    uint4 krow[DW_ROWS];
-    const uint4* lane_rows = Kc + grp * 16 + sub;          // row grp, this lane's 16 bytes
-    const auto load_rows = [&](int s0, uint4 (&dst)[DW_ROWS]) {
-        if (s0 + 4 * DW_ROWS <= slots) {
+    // The logits of the group's decode queries over the cached rows are a [slots x d] x [d x G]
+    // contraction: v_mfma_f32_16x16x16_bf16 with 16 key rows as the rows of a tile and the heads
+    // as its columns (G <= 8 of the 16 are used; the matrix pipe is idle otherwise).
+    // Key rows are loaded the way memory likes them - a wavefront instruction takes four whole
+    // consecutive rows, 16 lanes x 16 bytes each - and turned into operand fragments through a
+    // 4 KB tile in LDS: lane (i16, kq) of the matrix layout needs 16 bytes of row i16 at chunk
+    // kq + 4 t, t = 0..3, and uses their two halves as two k-steps.  (Loading the fragments
+    // straight from global memory - 16 rows x 64 bytes per instruction - streams at 4.6 TB/s,
+    // whole rows at 5.8.)  The query fragments are loaded with the fragment addressing, so both
+    // operands see the features in the same (permuted) order, which a contraction does not
+    // care about.  The first tiles and the queries are requested before anything else.
+    const int i16 = sub, kq = grp;
+    const int ntiles = (slots + 15) >> 4;
+    uint4 qf[4], tiles[DT_RING][4];                        // DT_RING - 1 tiles in flight while one is multiplied
+    const auto load_tile = [&](int tile, uint4 (&dst)[4]) {
 #pragma unroll
-            for (int r = 0; r < DW_ROWS; ++r) dst[r] = lane_rows[(s0 + 4 * r) * 16];
-        } else {
-#pragma unroll
-            for (int r = 0; r < DW_ROWS; ++r) {
-                const int s = s0 + 4 * r + grp;
-                dst[r] = Kc[(s < slots ? s : slots - 1) * 16 + sub];
-            }
+        for (int t = 0; t < 4; ++t) {
+            int row = tile * 16 + 4 * t + grp;
+            row = row < slots ? row : slots - 1;           // past the last slot: a valid row, masked at the store
+            dst[t] = Kc[row * 16 + sub];
         }
     };
     if (scored) {
+        const uint4* qrow = a.q_new + ((size_t)(l * st.batch + b) * st.hq + g * G + (i16 < G ? i16 : 0)) * 16;
 #pragma unroll
-        for (int h = 0; h < GH; ++h)
-            qv[h] = h < G ? a.q_new[((size_t)(l * st.batch + b) * st.hq + g * G + h) * 16 + sub] : make_uint4(0, 0, 0, 0);
-        load_rows(0, krow);
+        for (int t = 0; t < 4; ++t) qf[t] = i16 < G ? qrow[kq + 4 * t] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < DT_RING - 1; ++j)
+            if (j < ntiles) load_tile(j, tiles[j]);
     }
     int first_free = 0x7FFFFFFF;                           // lowest-numbered free slot
     for (int s0 = lane; s0 < slots; s0 += 4 * 64) {        // four slots per lane and round trip
@@ -330,64 +310,72 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
     }
     const uint4* kn = a.k_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
     const uint4* vn = a.v_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
-    const uint4 kn_sub = kn[sub];
-    if (lane < 16) Kc[f * 16 + lane] = kn_sub;
+    if (lane < 16) Kc[f * 16 + lane] = kn[lane];
     else if (lane < 32) Vc[f * 16 + lane - 16] = vn[lane - 16];
     __builtin_amdgcn_wave_barrier();                       // the slot table is in LDS for every lane
 
     // ---- attention of the group's decode queries over the occupied slots ----------
     if (scored) {
-        // Logits of one key row for all heads.  The 16 partial dot products of a head are summed
-        // across the group's lanes; with four heads the first two exchange steps also halve the
-        // number of heads a lane carries (lane keeps heads {0,1} or {2,3}, then one of them), so a
-        // row costs 5 cross-lane adds instead of 16.  Lanes 0..3 of the group end up with heads
-        // 0, 2, 1, 3 and store them.
-        const bool odd1 = (sub & 1) != 0, odd2 = (sub & 2) != 0;
-        const int my_head = GH == 4 ? 2 * (sub & 1) + ((sub >> 1) & 1) : sub;
-        const auto row_logits = [&](const uint4& kv, int s, bool occ) {
-            float mine;
-            if constexpr (GH == 4) {
-                const float d0 = dot8(qv[0], kv), d1 = dot8(qv[1], kv), d2 = dot8(qv[2], kv), d3 = dot8(qv[3], kv);
-                // lane ^ 1: even lanes keep heads 0 and 1, odd lanes heads 2 and 3
-                const float ka = odd1 ? d2 : d0, sa = odd1 ? d0 : d2;
-                const float kb = odd1 ? d3 : d1, sb = odd1 ? d1 : d3;
-                const float a2 = dpp_add_other<0xB1>(ka, sa);
-                const float b2 = dpp_add_other<0xB1>(kb, sb);
-                // lane ^ 2: keep one of the two
-                const float kc = odd2 ? b2 : a2, scn = odd2 ? a2 : b2;
-                float v = dpp_add_other<0x4E>(kc, scn);
-                v = dpp_add<0x124>(v);     // row_ror:4 and row_ror:8 keep the low two lane bits,
-                v = dpp_add<0x128>(v);     // i.e. the head: sum over lanes i, i+4, i+8, i+12
-                mine = v;
-            } else {
-                mine = 0.0f;
+        const auto frag_logits = [&](const uint4 (&frag)[4]) -> f32x4 {
+            f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                for (int h = 0; h < GH; ++h) {
-                    const float d = sum16(dot8(qv[h], kv));
-                    mine = sub == h ? d : mine;
+            for (int t = 0; t < 4; ++t) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(lo_half(frag[t]), lo_half(qf[t]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(hi_half(frag[t]), hi_half(qf[t]), acc, 0, 0, 0);
+            }
+            return acc;                                    // rows 4 kq .. 4 kq + 3 of the tile, head i16
+        };
+        // whole rows -> fragments through the LDS tile: row r chunk c sits at r * 16 + (c ^ r), which
+        // keeps both the row-wise writes and the column-wise reads free of bank conflicts.  LDS
+        // operations of a wavefront execute in order, so the tile needs no barrier (a wave-barrier
+        // builtin here would also keep the staging registers in scratch memory).
+        const auto tile_logits = [&](const uint4 (&rows)[4]) -> f32x4 {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int r = 4 * t + grp;
+                s_t[r * 16 + (sub ^ r)] = make_uint4(rows[t].x, rows[t].y, rows[t].z, rows[t].w);   // by components: a struct copy keeps `rows` in scratch memory
+            }
+            uint4 frag[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint4 v = s_t[i16 * 16 + ((kq + 4 * t) ^ i16)];
+                frag[t] = make_uint4(v.x, v.y, v.z, v.w);
+            }
+            return frag_logits(frag);
+        };
+        const auto store_tile = [&](int tile, const f32x4& acc) {
+            const int s = tile * 16 + 4 * kq;
+            if (i16 < G && s < wstride) {
+                const int4 p4 = *reinterpret_cast<const int4*>(&s_pos[s]);   // past `slots`: other LDS of this wavefront, masked
+                float4 o;
+                o.x = (s + 0 < slots && p4.x >= 0) ? acc[0] * a.scale_log2 : -INFINITY;
+                o.y = (s + 1 < slots && p4.y >= 0) ? acc[1] * a.scale_log2 : -INFINITY;
+                o.z = (s + 2 < slots && p4.z >= 0) ? acc[2] * a.scale_log2 : -INFINITY;
+                o.w = (s + 3 < slots && p4.w >= 0) ? acc[3] * a.scale_log2 : -INFINITY;
+                *reinterpret_cast<float4*>(&s_w[i16 * wstride + s]) = o;
+            }
+        };
+        // the tiles rotate through the registers (constant indices once unrolled)
+        for (int tb = 0; tb < ntiles; tb += DT_RING) {
+#pragma unroll
+            for (int j = 0; j < DT_RING; ++j) {
+                if (tb + j < ntiles) {
+                    if (tb + j + DT_RING - 1 < ntiles) load_tile(tb + j + DT_RING - 1, tiles[(j + DT_RING - 1) % DT_RING]);
+                    store_tile(tb + j, tile_logits(tiles[j]));
                 }
             }
-            if (sub < GH && my_head < G) s_w[my_head * slots + s] = occ ? mine * a.scale_log2 : -INFINITY;
-        };
-        for (int s0 = 0; s0 < slots; s0 += 4 * DW_ROWS) {
-            uint4 knext[DW_ROWS];
-            const bool more = s0 + 4 * DW_ROWS < slots;
-            if (more) load_rows(s0 + 4 * DW_ROWS, knext);  // next rows in flight while these are reduced
-#pragma unroll
-            for (int r = 0; r < DW_ROWS; ++r) {
-                const int s = s0 + 4 * r + grp;
-                if (s < slots) row_logits(krow[r], s, s_pos[s] >= 0);
-            }
-            if (more) {
-#pragma unroll
-                for (int r = 0; r < DW_ROWS; ++r) krow[r] = knext[r];
-            }
         }
-        // the row that has just been written is not read back: its logits come from the
-        // registers (whatever the loop stored for that slot is replaced here)
-        __builtin_amdgcn_wave_barrier();
-        if (grp == 0) row_logits(kn_sub, f, true);
-        __builtin_amdgcn_wave_barrier();
+        // the row that has just been written is not read back: its logits come from the new key
+        // itself (whatever the loop stored for that slot is replaced here)
+        {
+            uint4 knf[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) knf[t] = kn[kq + 4 * t];          // every row of this tile is the new key
+            const f32x4 acc = frag_logits(knf);
+            __builtin_amdgcn_wave_barrier();
+            if (i16 < G && kq == 0) s_w[i16 * wstride + f] = acc[0] * a.scale_log2;
+            __builtin_amdgcn_wave_barrier();
+        }
         // softmax statistics of every head, then the weights are added per slot in head order
         // (H2O-style cumulative attention)
         float m_h[GH], inv_h[GH];
@@ -396,7 +384,7 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
             m_h[h] = 0.0f;
             inv_h[h] = 0.0f;
             if (h < G) {
-                const float* sh = s_w + h * slots;
+                const float* sh = s_w + h * wstride;
                 float m = -INFINITY;
                 for (int s = lane; s < slots; s += 64) m = fmaxf(m, sh[s]);
                 m = wave_max(m);
@@ -412,7 +400,7 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
                 float add = 0.0f;
 #pragma unroll
                 for (int h = 0; h < GH; ++h)
-                    if (h < G) add += __builtin_amdgcn_exp2f(s_w[h * slots + s] - m_h[h]) * inv_h[h];
+                    if (h < G) add += __builtin_amdgcn_exp2f(s_w[h * wstride + s] - m_h[h]) * inv_h[h];
                 const float v = (s == f ? 0.0f : s_A[s]) + add;
                 s_A[s] = v;
                 A[s] = v;
@@ -526,7 +514,21 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)st.d));
     const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
     const int G = st.hq / st.hkv;
-    const size_t lds = (size_t)((prm.alpha != 0.0f ? G : 0) + 2) * (st.K + 1) * sizeof(float);
+    const int slots = st.K + 1;
+    // slot table and accumulated attention; with an attention term also one key tile and the logits
+    const size_t lds = (prm.alpha != 0.0f ? (size_t)((2 * slots + 3) & ~3) + 1024 + (size_t)G * ((slots + 3) & ~3) : (size_t)2 * slots) *
+                       sizeof(float);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    static std::once_flag once;                            // dynamic LDS above 64 KB (large budgets) needs the attribute
+    hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&]() {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<MAX_GROUP>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    });
+    if (attr_err != hipSuccess) return attr_err;
     if (G <= 4) hipLaunchKernelGGL(decode_unit_kernel<4>, dim3(units), dim3(64), lds, s, st, a);
     else hipLaunchKernelGGL(decode_unit_kernel<MAX_GROUP>, dim3(units), dim3(64), lds, s, st, a);
 

@@ -140,3 +140,10 @@ def test_decode_dense_anchors_overlapping_decayed_spans():
                   gram_min=1, gram_max=1, table_entries=8, planted=8)
     ev, anc = _run_decode(w, K=48, steps=40, p_anchor=0.5)
     assert ev == 40 * 2 * 2 and anc >= 20
+
+
+def test_decode_large_budget_eight_heads_per_group():
+    # 1501 slots x 8 query heads: the logits of a unit need more than 64 KB of LDS
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=1, n=1700, hq=8, hkv=1, ragged=None)
+    ev, _ = _run_decode(w, K=1500, steps=5, p_anchor=0.2, check_every=2)
+    assert ev == 5
