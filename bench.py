@@ -39,7 +39,7 @@ SCORE_TRAFFIC = {
     "workload": "c2_full_model",
     "bytes_per_step": 559.4e6,
     "sources": {
-        "ta_score.hip": "4d15422174543c740d79d74b74f4f0d0c93b0d61880bb55b79c9112d8431ec76",
+        "ta_score.hip": "f9fc43beb2eb861d15aefc1aabe3c57741883aa27b9276ea64782d04aedfc2a2",
         "ta_score_common.h": "14e66dcdc4dc6f17f6869341ad61b1a751102228fa6b741a7ac8e73ca6c74618",
         "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
     },
