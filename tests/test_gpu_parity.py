@@ -169,6 +169,9 @@ def test_score_c1_shape():
     (600, 16, 2, 64, True),       # 512 rows: four row tiles per wavefront
     (64, 4, 1, 64, True),         # window as long as the context
     (33, 4, 4, 1, True),          # one query row per head
+    (8192, 4, 1, 32, True),       # 128 rows, 4 chunks of 2048 keys
+    (8300, 4, 1, 32, True),       # ragged last chunk and last stage
+    (4096, 4, 1, 32, False),      # no mask at the headline context length
 ])
 def test_score_shapes(n, hq, hkv, window, causal):
     w = wl.scaled(wl.CONFIGS["c1_single_layer"], layers=2, batch=2, n=n, hq=hq, hkv=hkv, window=window)
@@ -179,6 +182,13 @@ def test_score_ragged_lengths_and_large_logits():
     w = wl.scaled(wl.CONFIGS["c1_single_layer"], layers=1, batch=4, n=900, hq=8, hkv=2, window=16)
     _check_score(w, seq_len=[900, 517, 16, 5])          # 5 < W: some window rows see nothing
     _check_score(w, scale=12.0)                         # sharp softmax: max subtraction must hold
+
+
+def test_score_chunks_past_the_sequence_end():
+    # chunks and stages that lie wholly past a sequence's end contribute empty statistics and zero
+    # scores; an empty sequence has only such chunks
+    w = wl.scaled(wl.CONFIGS["c1_single_layer"], layers=2, batch=4, n=2000, hq=8, hkv=2, window=32)
+    _check_score(w, seq_len=[2000, 130, 0, 1025])
 
 
 def test_score_long_context_chunking():
