@@ -39,8 +39,8 @@ SCORE_TRAFFIC = {
     "workload": "c2_full_model",
     "bytes_per_step": 559.4e6,
     "sources": {
-        "ta_score.hip": "f9fc43beb2eb861d15aefc1aabe3c57741883aa27b9276ea64782d04aedfc2a2",
-        "ta_score_common.h": "14e66dcdc4dc6f17f6869341ad61b1a751102228fa6b741a7ac8e73ca6c74618",
+        "ta_score.hip": "c3729cb05e7556b7b8f2be62f13900d3a5362f89ecda413358ec32a89dd64b6c",
+        "ta_score_common.h": "3e4b78495a5669b06b80090303e2ac50ab9622f4b9ead1de520e8aee81424db4",
         "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
     },
 }
@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_SIZE",
                     help="also time scoring and compaction over a paged (block-table) copy of the same cache with "
                          "pages of this many positions (a multiple of 64; reported as paged)")
+    ap.add_argument("--layer-tensors", action="store_true",
+                    help="also time the pass over the same cache kept as one tensor per layer (ta_evict_layers), "
+                         "and the same work issued as one ta_evict call per layer (reported as layer_tensors)")
     ap.add_argument("--paged-heads-first", action="store_true",
                     help="pages laid out [heads][page_size][d] instead of [page_size][heads][d]")
     ap.add_argument("--detect-positions", type=int, default=0,
@@ -265,6 +268,36 @@ def main():
                      "same_rows_as_dense": bool(torch.equal(outp[0], plan.Kout) and torch.equal(outp[1], plan.Vout))}
         del Kp, Vp, pk, Ap, outp
 
+    # ---- the same cache as one tensor per layer ---------------------------------------------------
+    layers_out = None
+    if args.layer_tensors:
+        Ql = [Q[l].clone() for l in range(w.layers)] if scored else None
+        Kl = [K[l].clone() for l in range(w.layers)]
+        Vl = [V[l].clone() for l in range(w.layers)]
+        lplan = ta.LayerEvictPlan(tok, td.tab_ids, td.tab_len, Ql, Kl, Vl, budget, prm, seq_len=seq)
+        # one call per layer: what a caller without the pointer tables would issue
+        singles = [ta.EvictPlan(tok, td.tab_ids, td.tab_len, Ql[l][None] if scored else None, Kl[l][None], Vl[l][None],
+                                budget, prm, seq_len=seq) for l in range(w.layers)]
+
+        def wall(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e6 / args.steps
+
+        lus = wall(lambda: lplan.run(stream))
+        sus = wall(lambda: [p.run(stream) for p in singles])
+        same = all(torch.equal(lplan.Kout[l], plan.Kout[l]) and torch.equal(lplan.Vout[l], plan.Vout[l])
+                   for l in range(w.layers)) and torch.equal(lplan.idx, plan.idx)
+        layers_out = {"entry_point": "ta_evict_layers", "pass_us": round(lus, 1),
+                      "pass_GB/s": round((score_b + compact_b) / lus / 1e3, 1),
+                      "one_ta_evict_call_per_layer_us": round(sus, 1), "same_output_as_stacked": bool(same)}
+        del Ql, Kl, Vl, lplan, singles
+
     # ---- budget sweep of the same workload (context, outside the headline timing) ----------
     sweep = {}
     if args.calibrate_copy:
@@ -442,7 +475,7 @@ def main():
         "kernels_us": {k: round(v, 2) for k, v in kern_us.items()},
         "budget_sweep": sweep,
         "score_one_sweep": one_sweep,
-        "paged": paged_out,
+        "paged": paged_out, "layer_tensors": layers_out,
         "decode_step": decode,
         "learned_detect": detect,
         "embedding_detect": embed,

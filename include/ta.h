@@ -17,13 +17,15 @@
  *      ta_score_paged /  steps 3 and 5, and the whole pass, over paged (block-table) caches
  *      ta_compact_paged / ta_evict_paged
  *      ta_evict          all of the above in one call
+ *      ta_evict_layers   the same over caches that are one tensor per layer
  *      ta_decode_init /  the same policy applied after every generation step
  *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
  *
  * Conventions shared by every entry point
  *   - Pointers marked DEVICE are GPU global memory owned by the caller;
  *     pointers marked HOST are ordinary host memory read during the call.
- *     Inputs are never written; outputs must not alias inputs.
+ *     Inputs are never written; outputs must not alias inputs (ta_compact and the passes
+ *     built on it refuse K/V outputs whose address equals an input's or each other's: SHAPE).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls only enqueue work on it: they never synchronise, allocate or free.
  *   - Positions are 0-based; the paper's token i is position p = i - 1.
@@ -48,6 +50,8 @@ extern "C" {
 #define TA_MAX_TABLE 64   /* anchor-table entries                       */
 #define TA_MAX_GRAM 4     /* tokens per anchor n-gram                   */
 #define TA_MAX_SPAN 64    /* sponsor span L                             */
+#define TA_MAX_LAYER_PTRS 96 /* layers of a per-layer pointer table       */
+#define TA_LAYER_WS_BYTES 4096 /* workspace share of such a table         */
 #define TA_HEAD_DIM 128   /* the only supported head dimension          */
 #define TA_MAX_ROWS 512   /* (query heads per KV head) * window rows    */
 
@@ -373,6 +377,39 @@ int32_t ta_evict_paged(const int32_t *tok, const int32_t *seq_len,
                        uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
                        int32_t *idx, int32_t *cnt, void *Kout, void *Vout,
                        void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Caches kept as one tensor per layer (the `past_key_values` order that Sec. 3.2 "Token
+ * selection" applies index_select to is a list of per-layer K and V tensors): HOST arrays of
+ * lay->layers DEVICE pointers, read during the call.  Layer l of K and V is a
+ * [batch][hkv][n][d] tensor with the strides kv_stride[1..3] of `lay`, layer l of Q a
+ * [batch][hq][window][d] tensor with q_stride[1..2]; Kout[l], Vout[l] are dense
+ * [batch][hkv][K][d].  kv_stride[0] and q_stride[0] are not used.
+ */
+typedef struct ta_layer_ptrs {
+    const void *const *Q;     /* HOST [layers] of DEVICE bf16; may be NULL when prm->alpha == 0 */
+    const void *const *K;     /* HOST [layers] of DEVICE bf16 */
+    const void *const *V;     /* HOST [layers] of DEVICE bf16 */
+    void *const *Kout;        /* HOST [layers] of DEVICE bf16 */
+    void *const *Vout;        /* HOST [layers] of DEVICE bf16 */
+} ta_layer_ptrs;
+
+/*
+ * ta_evict over per-layer tensors: the same kernels in the same launches (one pass over all
+ * layers, not one per layer), each layer's base address taken from `lp` instead of
+ * base + l * layer stride.  Every other argument and output as in ta_evict, except
+ *   ws   DEVICE, at least ta_workspace_bytes(lay, prm) rounded up to a multiple of 256, plus
+ *        TA_LAYER_WS_BYTES (needed when prm->alpha == 0 too): the table is validated on the
+ *        host and then kept there for the kernels.
+ * Errors: as ta_evict; SHAPE also for lay->layers > TA_MAX_LAYER_PTRS; NULL for a missing
+ * array or entry; ALIGN for an entry that is not 16-byte aligned; SHAPE for an output entry
+ * equal to an input entry of the same layer.
+ */
+int32_t ta_evict_layers(const int32_t *tok, const int32_t *seq_len,
+                        const int32_t *tab_ids, const int32_t *tab_len, int32_t E, const float *anchor_B,
+                        const ta_layer_ptrs *lp, const ta_layout *lay, const ta_params *prm, int32_t K,
+                        uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
+                        int32_t *idx, int32_t *cnt, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Incremental form: the same retention policy applied after every generation

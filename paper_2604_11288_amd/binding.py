@@ -20,13 +20,15 @@ TA_MAX_GRAM = 4
 TA_MAX_SPAN = 64
 TA_HEAD_DIM = 128
 TA_MAX_ROWS = 512
+TA_MAX_LAYER_PTRS = 96
+TA_LAYER_WS_BYTES = 4096
 
 TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
 TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
            "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged",
-           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
+           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
 class TaError(RuntimeError):
@@ -144,6 +146,9 @@ def lib():
         L.ta_evict_paged.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ta_evict_paged.restype = i32
+        L.ta_evict_layers.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, i32,
+                                      vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ta_evict_layers.restype = i32
         L.ta_decode_init.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ta_decode_init.restype = i32
         L.ta_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
@@ -524,6 +529,93 @@ def ta_evict_lse(tok, tab_ids, tab_len, Q, Kin, Vin, lse, K: int, params: Params
                  stream=None) -> EvictPlan:
     """The whole pass with the one-sweep score from given row log-sum-exps (f32 [Lyr][B][Hq][W])."""
     return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B, lse=lse).run(stream)
+
+
+class CLayerPtrs(ctypes.Structure):
+    _fields_ = [("Q", ctypes.c_void_p), ("K", ctypes.c_void_p), ("V", ctypes.c_void_p),
+                ("Kout", ctypes.c_void_p), ("Vout", ctypes.c_void_p)]
+
+
+class LayerEvictPlan:
+    """ta_evict_layers on caches kept as one tensor per layer.
+
+    Q_layers: list of bf16 [B][Hq][W][d] (or None when params.alpha == 0); K_layers, V_layers: lists
+    of bf16 [B][Hkv][n][d] with the same strides in every layer.  Kout / Vout are lists of dense
+    [B][Hkv][K][d] tensors; the other outputs are as in EvictPlan.  run() only performs the C call.
+    """
+
+    def __init__(self, tok, tab_ids, tab_len, Q_layers, K_layers, V_layers, K: int, params: Params,
+                 seq_len=None, anchor_B=None):
+        layers = len(K_layers)
+        assert layers >= 1 and len(V_layers) == layers
+        K0 = K_layers[0]
+        dev = K0.device
+        self.params, self.K = params, int(K)
+        self.scored = params.alpha != 0.0
+        for t in list(K_layers) + list(V_layers):
+            assert t.dim() == 4 and t.dtype == torch.bfloat16 and t.shape == K0.shape and t.stride() == K0.stride()
+        assert K0.stride(3) == 1
+        lay = CLayout()
+        lay.layers = layers
+        lay.batch, lay.hkv, lay.n, lay.d = K0.shape
+        lay.kv_stride[0] = 0
+        for i in range(3):
+            lay.kv_stride[i + 1] = K0.stride(i)
+        if self.scored:
+            assert len(Q_layers) == layers
+            Q0 = Q_layers[0]
+            for t in Q_layers:
+                assert t.dim() == 4 and t.dtype == torch.bfloat16 and t.shape == Q0.shape and t.stride() == Q0.stride()
+            assert Q0.stride(3) == 1 and Q0.stride(2) == Q0.shape[3], "rows of a query head must be contiguous"
+            lay.hq, lay.window = Q0.shape[1], Q0.shape[2]
+            lay.q_stride[0] = 0
+            lay.q_stride[1], lay.q_stride[2] = Q0.stride(0), Q0.stride(1)
+        else:
+            lay.hq, lay.window = lay.hkv, 0
+        self.lay = lay
+        self.tok, self.seq_len, self.anchor_B = tok, seq_len, anchor_B
+        self.Q_layers = list(Q_layers) if self.scored else None
+        self.K_layers, self.V_layers = list(K_layers), list(V_layers)
+        self.ids, self.lens, self.E = _table(tab_ids, tab_len)
+        B, n = lay.batch, lay.n
+        self.anchor = torch.empty((B, n), dtype=torch.uint8, device=dev)
+        self.spons = torch.empty((B, n), dtype=torch.uint8, device=dev)
+        self.vouch = torch.empty((B, n), dtype=torch.float32, device=dev)
+        if self.scored:
+            self.A = torch.empty((layers, B, lay.hkv, n), dtype=torch.float32, device=dev)
+            self.idx = torch.full((layers, B, lay.hkv, self.K), -1, dtype=torch.int32, device=dev)
+            self.cnt = torch.zeros((layers, B, lay.hkv), dtype=torch.int32, device=dev)
+            nbytes = (ta_workspace_bytes(lay, params) + 255) // 256 * 256 + TA_LAYER_WS_BYTES
+        else:
+            self.A = None
+            nbytes = TA_LAYER_WS_BYTES
+            self.idx = torch.full((B, self.K), -1, dtype=torch.int32, device=dev)
+            self.cnt = torch.zeros((B,), dtype=torch.int32, device=dev)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)      # score scratch + the address table
+        self.Kout = [torch.zeros((B, lay.hkv, self.K, lay.d), dtype=torch.bfloat16, device=dev) for _ in range(layers)]
+        self.Vout = [torch.zeros((B, lay.hkv, self.K, lay.d), dtype=torch.bfloat16, device=dev) for _ in range(layers)]
+        table = lambda ts: (ctypes.c_void_p * layers)(*[t.data_ptr() for t in ts])
+        self._tables = [table(self.Q_layers) if self.scored else None, table(self.K_layers), table(self.V_layers),
+                        table(self.Kout), table(self.Vout)]     # host arrays, kept alive with the plan
+        addr = lambda a: None if a is None else ctypes.cast(a, ctypes.c_void_p)
+        self._lp = CLayerPtrs(*[addr(a) for a in self._tables])
+        self._cp = params.c()
+
+    def run(self, stream=None):
+        ws_bytes = self.ws.numel()
+        rc = lib().ta_evict_layers(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
+                                   self.E, _ptr(self.anchor_B), ctypes.byref(self._lp), ctypes.byref(self.lay),
+                                   ctypes.byref(self._cp), self.K,
+                                   _ptr(self.anchor), _ptr(self.spons), _ptr(self.vouch), _ptr(self.A),
+                                   _ptr(self.idx), _ptr(self.cnt), _ptr(self.ws), ws_bytes, _stream(stream))
+        _check(rc, "ta_evict_layers")
+        return self
+
+
+def ta_evict_layers(tok, tab_ids, tab_len, Q_layers, K_layers, V_layers, K: int, params: Params, seq_len=None,
+                    anchor_B=None, stream=None) -> LayerEvictPlan:
+    """The whole pass over per-layer cache tensors; returns the plan object holding every output."""
+    return LayerEvictPlan(tok, tab_ids, tab_len, Q_layers, K_layers, V_layers, K, params, seq_len, anchor_B).run(stream)
 
 
 class DecodeState:

@@ -140,6 +140,8 @@ int32_t check_compact(const void* Kin, const void* Vin, const int32_t* idx, cons
     if (!Kin || !Vin || !idx || !cnt || !Kout || !Vout) return TA_ERR_NULL;
     if (K < 1) return TA_ERR_SHAPE;
     if (!aligned16(Kin) || !aligned16(Vin) || !aligned16(Kout) || !aligned16(Vout)) return TA_ERR_ALIGN;
+    // outputs must not alias the inputs or each other: workgroups read and write rows in no fixed order
+    if (Kout == Kin || Kout == Vin || Vout == Kin || Vout == Vin || Kout == Vout) return TA_ERR_SHAPE;
     const int64_t units = (int64_t)lay->layers * lay->batch * lay->hkv;
     if (units * ((K + 63) / 64) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
     return TA_OK;
@@ -271,7 +273,7 @@ int32_t ta_score(const void* Q, const void* K, const ta_layout* lay, const int32
     int32_t rc = check_score(Q, K, lay, prm, A, ws, ws_bytes);
     if (rc != TA_OK) return rc;
     return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, (float*)ws, nullptr, nullptr, nullptr,
-                                       (hipStream_t)stream));
+                                       nullptr, (hipStream_t)stream));
 }
 
 int32_t ta_score_lse(const void* Q, const void* K, const ta_layout* lay, const int32_t* seq_len,
@@ -285,7 +287,7 @@ int32_t ta_score_lse(const void* Q, const void* K, const ta_layout* lay, const i
     if (!aligned16(Q) || !aligned16(K)) return TA_ERR_ALIGN;
     if (ta::score_grid_blocks(*lay) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
     return hip_status(ta::launch_score(Q, K, *lay, seq_len, prm->causal, A, nullptr, lse, nullptr, nullptr,
-                                       (hipStream_t)stream));
+                                       nullptr, (hipStream_t)stream));
 }
 
 int32_t ta_select(const float* A, const uint8_t* anchor, const uint8_t* spons, const float* vouch,
@@ -305,7 +307,7 @@ int32_t ta_compact(const void* Kin, const void* Vin, const int32_t* idx, const i
     int32_t rc = check_compact(Kin, Vin, idx, cnt, lay, K, Kout, Vout);
     if (rc != TA_OK) return rc;
     return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, idx_shared, Kout, Vout, nullptr,
-                                         (hipStream_t)stream));
+                                         nullptr, (hipStream_t)stream));
 }
 
 namespace {
@@ -330,6 +332,28 @@ int32_t check_paged(const ta_paged_kv* pg, const ta_layout* lay, ta_layout* dens
     return TA_OK;
 }
 
+// Copies a per-layer pointer table after checking every entry that the pass will use.
+int32_t check_layer_ptrs(const ta_layer_ptrs* lp, const ta_layout* lay, bool scored, ta::LayerPtrs* out)
+{
+    if (lay->layers < 1 || lay->layers > TA_MAX_LAYER_PTRS) return TA_ERR_SHAPE;
+    if (!lp->K || !lp->V || !lp->Kout || !lp->Vout || (scored && !lp->Q)) return TA_ERR_NULL;
+    memset(out, 0, sizeof(*out));
+    for (int32_t l = 0; l < lay->layers; ++l) {
+        const void* q = scored ? lp->Q[l] : nullptr;
+        const void *k = lp->K[l], *v = lp->V[l];
+        void *ko = lp->Kout[l], *vo = lp->Vout[l];
+        if (!k || !v || !ko || !vo || (scored && !q)) return TA_ERR_NULL;
+        if (!aligned16(k) || !aligned16(v) || !aligned16(ko) || !aligned16(vo) || !aligned16(q)) return TA_ERR_ALIGN;
+        if (ko == k || ko == v || vo == k || vo == v || ko == vo) return TA_ERR_SHAPE;
+        out->Q[l] = q;
+        out->K[l] = k;
+        out->V[l] = v;
+        out->Kout[l] = ko;
+        out->Vout[l] = vo;
+    }
+    return TA_OK;
+}
+
 // The whole pass; `lse` != NULL selects the one-sweep score (then ws is not used).
 int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
                    const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
@@ -337,8 +361,25 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
                    const ta_layout* lay, const ta_params* prm, int32_t K,
                    uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
                    int32_t* idx, int32_t* cnt, void* Kout, void* Vout,
-                   void* ws, size_t ws_bytes, const float* lse, const ta_paged_kv* pg, void* stream)
+                   void* ws, size_t ws_bytes, const float* lse, const ta_paged_kv* pg, const ta_layer_ptrs* lp,
+                   void* stream)
 {
+    // one tensor per layer: the shared checks see layer 0's addresses and no layer stride
+    ta::LayerPtrs layer_ptrs;
+    ta_layout lay_of_layers;
+    if (lp) {
+        if (!lay || !prm) return TA_ERR_NULL;
+        const int32_t prc = check_layer_ptrs(lp, lay, prm->alpha != 0.0f, &layer_ptrs);
+        if (prc != TA_OK) return prc;
+        lay_of_layers = *lay;
+        lay_of_layers.kv_stride[0] = lay_of_layers.q_stride[0] = 0;
+        lay = &lay_of_layers;
+        Q = layer_ptrs.Q[0];
+        Kin = layer_ptrs.K[0];
+        Vin = layer_ptrs.V[0];
+        Kout = layer_ptrs.Kout[0];
+        Vout = layer_ptrs.Vout[0];
+    }
     ta_layout dense_of_paged;
     if (pg) {                                              // sizes from lay, addressing from pg
         int32_t prc = check_paged(pg, lay, &dense_of_paged, prm && prm->alpha != 0.0f);
@@ -372,12 +413,25 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
     if (rc != TA_OK) return rc;
     rc = check_compact(Kin, Vin, idx, cnt, lay, K, Kout, Vout);
     if (rc != TA_OK) return rc;
+    // the table of per-layer addresses goes to the workspace, behind what the score step uses of it
+    ta::LayerPtrs* lptr = nullptr;
+    if (lp) {
+        static_assert(sizeof(ta::LayerPtrs) <= TA_LAYER_WS_BYTES, "table must fit its share of the workspace");
+        const size_t table_off = ((scored ? workspace_bytes(lay) : 0) + 255) & ~(size_t)255;
+        if (!ws || ws_bytes < table_off + TA_LAYER_WS_BYTES) return TA_ERR_WORKSPACE;
+        if (!aligned16(ws)) return TA_ERR_ALIGN;
+        lptr = reinterpret_cast<ta::LayerPtrs*>(static_cast<char*>(ws) + table_off);
+    }
 
     hipStream_t st = (hipStream_t)stream;
+    if (lp) {
+        rc = hip_status(ta::launch_layer_table(layer_ptrs, lptr, st));
+        if (rc != TA_OK) return rc;
+    }
     if (scored) {
         // the match rides along with the first sweep over the keys (one launch fewer in front of them)
         const ta::MatchRider rider = {tok, anchor_B, prm->allow, anchor, spons, vouch, &tab};
-        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, lse, &rider, pg, st));
+        rc = hip_status(ta::launch_score(Q, Kin, *lay, seq_len, prm->causal, A, (float*)ws, lse, &rider, pg, lptr, st));
         if (rc != TA_OK) return rc;
     } else {
         rc = hip_status(ta::launch_match(tok, seq_len, lay->batch, lay->n, tab, anchor_B, prm->allow, anchor, spons, vouch, st));
@@ -386,7 +440,7 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
     rc = hip_status(ta::launch_select(A, anchor, spons, vouch, seq_len, sel_layers, lay->batch, sel_hkv,
                                       lay->n, K, *prm, idx, cnt, st));
     if (rc != TA_OK) return rc;
-    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, pg, st));
+    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, *lay, K, scored ? 0 : 1, Kout, Vout, pg, lptr, st));
 }
 
 }  // namespace
@@ -411,7 +465,7 @@ int32_t ta_score_paged(const void* Q, const void* Kpool, const ta_paged_kv* pg, 
         if (rc != TA_OK) return rc;
     }
     return hip_status(ta::launch_score(Q, Kpool, dense, seq_len, prm->causal, A, (float*)ws, lse, nullptr, pg,
-                                       (hipStream_t)stream));
+                                       nullptr, (hipStream_t)stream));
 }
 
 int32_t ta_compact_paged(const void* Kpool, const void* Vpool, const ta_paged_kv* pg,
@@ -424,7 +478,7 @@ int32_t ta_compact_paged(const void* Kpool, const void* Vpool, const ta_paged_kv
     rc = check_compact(Kpool, Vpool, idx, cnt, &dense, K, Kout, Vout);
     if (rc != TA_OK) return rc;
     return hip_status(ta::launch_compact(Kpool, Vpool, idx, cnt, dense, K, idx_shared, Kout, Vout, pg,
-                                         (hipStream_t)stream));
+                                         nullptr, (hipStream_t)stream));
 }
 
 int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
@@ -436,7 +490,7 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
                  void* ws, size_t ws_bytes, void* stream)
 {
     return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
-                      idx, cnt, Kout, Vout, ws, ws_bytes, nullptr, nullptr, stream);
+                      idx, cnt, Kout, Vout, ws, ws_bytes, nullptr, nullptr, nullptr, stream);
 }
 
 int32_t ta_evict_lse(const int32_t* tok, const int32_t* seq_len,
@@ -449,7 +503,7 @@ int32_t ta_evict_lse(const int32_t* tok, const int32_t* seq_len,
     if (!prm || !lse) return TA_ERR_NULL;
     if (prm->alpha == 0.0f) return TA_ERR_SHAPE;            // nothing to fuse in the attention-free setting
     return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
-                      idx, cnt, Kout, Vout, nullptr, 0, lse, nullptr, stream);
+                      idx, cnt, Kout, Vout, nullptr, 0, lse, nullptr, nullptr, stream);
 }
 
 int32_t ta_evict_paged(const int32_t* tok, const int32_t* seq_len,
@@ -462,7 +516,18 @@ int32_t ta_evict_paged(const int32_t* tok, const int32_t* seq_len,
 {
     if (!pg) return TA_ERR_NULL;
     return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kpool, Vpool, lay, prm, K, anchor, spons, vouch, A,
-                      idx, cnt, Kout, Vout, ws, ws_bytes, lse, pg, stream);
+                      idx, cnt, Kout, Vout, ws, ws_bytes, lse, pg, nullptr, stream);
+}
+
+int32_t ta_evict_layers(const int32_t* tok, const int32_t* seq_len,
+                        const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                        const ta_layer_ptrs* lp, const ta_layout* lay, const ta_params* prm, int32_t K,
+                        uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                        int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!lp) return TA_ERR_NULL;
+    return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, nullptr, nullptr, nullptr, lay, prm, K, anchor, spons,
+                      vouch, A, idx, cnt, nullptr, nullptr, ws, ws_bytes, nullptr, nullptr, lp, stream);
 }
 
 int32_t ta_decode_init(const ta_decode_state* st, const int32_t* tok, const int32_t* seq_len, int32_t n,

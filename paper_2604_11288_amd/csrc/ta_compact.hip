@@ -35,9 +35,22 @@ struct CompactArgs {
     const int32_t* table;
     int64_t s_page;
     int32_t page_size, max_pages, num_pages;
+    // one tensor per layer: DEVICE tables; layer l reads Kin_l[l], Vin_l[l] and writes Kout_l[l], Vout_l[l]
+    const uint4* const* Kin_l;
+    const uint4* const* Vin_l;
+    uint4* const* Kout_l;
+    uint4* const* Vout_l;
 };
 
-template <bool PAGED>
+// marks a pointer read from a device table as a global address (else it is accessed with flat instructions)
+template <typename T>
+__device__ __forceinline__ T* global_ptr(T* p)
+{
+    typedef __attribute__((address_space(1))) T* gp;
+    return (T*)(gp)(uintptr_t)p;
+}
+
+template <bool PAGED, bool LAYERED>
 __global__ void __launch_bounds__(COMPACT_THREADS)
 compact_kernel(CompactArgs a)
 {
@@ -50,8 +63,8 @@ compact_kernel(CompactArgs a)
     int32_t cnt = a.cnt[sel];
     cnt = cnt > a.K ? a.K : cnt;
     const int32_t* idx = a.idx + (size_t)sel * (size_t)a.K;
-    const int64_t in_base = l * a.s_layer + (PAGED ? 0 : b * a.s_batch) + h * a.s_head;
-    const int64_t out_base = (int64_t)unit * a.K * 16;
+    const int64_t in_base = (LAYERED ? 0 : l * a.s_layer) + (PAGED ? 0 : b * a.s_batch) + h * a.s_head;
+    const int64_t out_base = (int64_t)(LAYERED ? unit - l * a.hkv * a.batch : unit) * a.K * 16;
 
     const int lane16 = threadIdx.x & 15;
     const int rsub = threadIdx.x >> 4;
@@ -75,10 +88,10 @@ compact_kernel(CompactArgs a)
     const int64_t o2 = src(row0 + 2 * ROWS_PER_ITER), o3 = src(row0 + 3 * ROWS_PER_ITER);
     // The compacted rows are not read again by this pass: streaming stores keep them from
     // lingering in the caches as dirty lines that the next kernel's reads would have to evict.
-    const u32x4* Kin = reinterpret_cast<const u32x4*>(a.Kin);
-    const u32x4* Vin = reinterpret_cast<const u32x4*>(a.Vin);
-    u32x4* Kout = reinterpret_cast<u32x4*>(a.Kout);
-    u32x4* Vout = reinterpret_cast<u32x4*>(a.Vout);
+    const u32x4* Kin = reinterpret_cast<const u32x4*>(LAYERED ? global_ptr(a.Kin_l[l]) : a.Kin);
+    const u32x4* Vin = reinterpret_cast<const u32x4*>(LAYERED ? global_ptr(a.Vin_l[l]) : a.Vin);
+    u32x4* Kout = reinterpret_cast<u32x4*>(LAYERED ? global_ptr(a.Kout_l[l]) : a.Kout);
+    u32x4* Vout = reinterpret_cast<u32x4*>(LAYERED ? global_ptr(a.Vout_l[l]) : a.Vout);
     const u32x4 k0 = __builtin_nontemporal_load(&Kin[o0]), k1 = __builtin_nontemporal_load(&Kin[o1]);
     const u32x4 k2 = __builtin_nontemporal_load(&Kin[o2]), k3 = __builtin_nontemporal_load(&Kin[o3]);
     const u32x4 v0 = __builtin_nontemporal_load(&Vin[o0]), v1 = __builtin_nontemporal_load(&Vin[o1]);
@@ -96,13 +109,35 @@ compact_kernel(CompactArgs a)
     put(row0 + 3 * ROWS_PER_ITER, k3, v3);
 }
 
+// Writes a table of per-layer addresses, handed over by value, to device memory: the kernels of the
+// pass then read their layer's entries from there.  (Handing the table to those kernels by value
+// was measured: with argument blocks of a few KB every scalar load of an argument becomes slow, and
+// the compaction took 690 us instead of 42.)
+__global__ void layer_table_kernel(LayerPtrs t, LayerPtrs* dst)
+{
+    constexpr int WORDS = (int)(sizeof(LayerPtrs) / sizeof(uint64_t));
+    const uint64_t* src = reinterpret_cast<const uint64_t*>(&t);
+    uint64_t* out = reinterpret_cast<uint64_t*>(dst);
+    for (int i = (int)threadIdx.x; i < WORDS; i += (int)blockDim.x) out[i] = src[i];
+}
+
 }  // namespace
+
+hipError_t launch_layer_table(const LayerPtrs& host_table, LayerPtrs* dev_table, hipStream_t st)
+{
+    hipLaunchKernelGGL(layer_table_kernel, dim3(1), dim3(512), 0, st, host_table, dev_table);
+    return hipGetLastError();
+}
 
 hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
                           const ta_layout& lay, int32_t K, int32_t idx_shared,
-                          void* Kout, void* Vout, const ta_paged_kv* pg, hipStream_t st)
+                          void* Kout, void* Vout, const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st)
 {
     CompactArgs a;
+    a.Kin_l = lp ? reinterpret_cast<const uint4* const*>(&lp->K[0]) : nullptr;
+    a.Vin_l = lp ? reinterpret_cast<const uint4* const*>(&lp->V[0]) : nullptr;
+    a.Kout_l = lp ? reinterpret_cast<uint4* const*>(&lp->Kout[0]) : nullptr;
+    a.Vout_l = lp ? reinterpret_cast<uint4* const*>(&lp->Vout[0]) : nullptr;
     a.Kin = (const uint4*)Kin;
     a.Vin = (const uint4*)Vin;
     a.idx = idx;
@@ -136,8 +171,10 @@ hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, 
     a.blocks_per_unit = (K + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
     int64_t blocks = units * a.blocks_per_unit;
-    if (pg) hipLaunchKernelGGL(compact_kernel<true>, dim3((unsigned)blocks), dim3(COMPACT_THREADS), 0, st, a);
-    else hipLaunchKernelGGL(compact_kernel<false>, dim3((unsigned)blocks), dim3(COMPACT_THREADS), 0, st, a);
+    const dim3 grid((unsigned)blocks), block(COMPACT_THREADS);
+    if (pg) hipLaunchKernelGGL((compact_kernel<true, false>), grid, block, 0, st, a);
+    else if (lp) hipLaunchKernelGGL((compact_kernel<false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((compact_kernel<false, false>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 

@@ -52,6 +52,18 @@ struct MatchRider {
     const MatchTable* tab;
 };
 
+// Per-layer base addresses in place of base + l * layer stride (entries past the layer count unused).
+// The launchers below take such a table in DEVICE memory (written there by launch_layer_table).
+struct LayerPtrs {
+    const void* Q[TA_MAX_LAYER_PTRS];
+    const void* K[TA_MAX_LAYER_PTRS];
+    const void* V[TA_MAX_LAYER_PTRS];
+    void* Kout[TA_MAX_LAYER_PTRS];
+    void* Vout[TA_MAX_LAYER_PTRS];
+};
+
+hipError_t launch_layer_table(const LayerPtrs& host_table, LayerPtrs* dev_table, hipStream_t st);
+
 // ---- score ------------------------------------------------------------------
 // Scratch bytes and grid size of the score step for a validated layout.
 size_t score_workspace_bytes(const ta_layout& lay);
@@ -61,9 +73,10 @@ int64_t score_grid_blocks(const ta_layout& lay);
 // With `lse` set (row log-sum-exps from a prefill attention kernel, [layers][batch][hq][W]) only the
 // column-sum sweep runs and ws is not used.
 // `pg` != null: K is a paged pool addressed through pg->block_table (lay.kv_stride unused).
+// `lp` != null: Q and K of layer l start at lp->Q[l], lp->K[l] (Q, K and the layer strides unused).
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
                         int causal, float* A, float* ws, const float* lse, const MatchRider* rider,
-                        const ta_paged_kv* pg, hipStream_t st);
+                        const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st);
 
 // ---- select -----------------------------------------------------------------
 hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* spons,
@@ -72,9 +85,10 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
                          const ta_params& prm, int32_t* idx, int32_t* cnt, hipStream_t st);
 
 // ---- compact ----------------------------------------------------------------
+// `lp` != null: layer l reads lp->K[l], lp->V[l] and writes lp->Kout[l], lp->Vout[l].
 hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
                           const ta_layout& lay, int32_t K, int32_t idx_shared,
-                          void* Kout, void* Vout, const ta_paged_kv* pg, hipStream_t st);
+                          void* Kout, void* Vout, const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st);
 
 // ---- incremental (decode) form ------------------------------------------------
 hipError_t launch_decode_init(const ta_decode_state& st, const int32_t* tok, const int32_t* seq_len, int32_t n,

@@ -194,7 +194,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     // stage costs one scalar base address and no vector arithmetic (except the ragged last one).
     // Paged K: the keys of a stage (64 positions, page_size is a multiple of 64) lie in one page; lane j
     // keeps the page of the j-th page slot of this chunk, so a stage costs a lane read, not a load.
-    const uint4* kbase = a.K + l * a.k_sl + (PAGED ? 0 : b * a.k_sb) + g * a.k_sh;
+    const uint4* kbase = (a.Kl ? uniform_global_ptr(a.Kl[l]) : a.K + l * a.k_sl) + (PAGED ? 0 : b * a.k_sb) + g * a.k_sh;
     const auto slot_of = [&](int32_t key) { return a.page_shift >= 0 ? key >> a.page_shift : key / a.page_size; };
     const int32_t slot_lo = PAGED ? slot_of(key_lo) : 0;
     int32_t my_page = 0;
@@ -242,6 +242,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         }
     };
     // ---- Q fragments of this wavefront's 64 rows (registers, whole chunk) -----------
+    const uint4* qlayer = a.Ql ? uniform_global_ptr(a.Ql[l]) : a.Q + l * a.q_sl;
     bf16x8 qf[ROW_TILES][8];
     int32_t my_lim[ROW_TILES];                             // sweep 1: last visible key of this lane's row
 #pragma unroll
@@ -250,7 +251,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         int32_t lim = -1;
         if (r < a.rows) {
             const int32_t h = r / W, w = r - h * W;
-            const uint4* qrow = a.Q + l * a.q_sl + b * a.q_sb + (int64_t)(g * a.G + h) * a.q_sh + (int64_t)w * 16;
+            const uint4* qrow = qlayer + b * a.q_sb + (int64_t)(g * a.G + h) * a.q_sh + (int64_t)w * 16;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) qf[t][ks] = as_frag(qrow[2 * ks + hf]);
             lim = a.causal ? nb - W + w : nb - 1;
@@ -554,7 +555,7 @@ void launch_sweep(const ScoreArgs& a, unsigned blocks, const MatchRider* rider, 
 {
     if (rider && a.table) {
         // paged keys: the match runs as a launch of its own in front of the sweep
-        launch_match(rider->tok, a.seq_len, a.batch, a.n, *rider->tab, rider->anchor_B, rider->allow, rider->anchor,
+        (void)launch_match(rider->tok, a.seq_len, a.batch, a.n, *rider->tab, rider->anchor_B, rider->allow, rider->anchor,
                      rider->spons, rider->vouch, st);
         rider = nullptr;
     }
@@ -655,10 +656,12 @@ int64_t score_grid_blocks(const ta_layout& lay)
 
 hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, const int32_t* seq_len,
                         int causal, float* A, float* ws, const float* lse, const MatchRider* rider,
-                        const ta_paged_kv* pg, hipStream_t st)
+                        const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st)
 {
     const ScorePlan p = make_plan(lay);
     ScoreArgs a;
+    a.Ql = lp ? reinterpret_cast<const uint4* const*>(&lp->Q[0]) : nullptr;
+    a.Kl = lp ? reinterpret_cast<const uint4* const*>(&lp->K[0]) : nullptr;
     a.lse = lse;
     a.table = pg ? pg->block_table : nullptr;
     a.k_spage = pg ? pg->stride[1] / 8 : 0;

@@ -28,6 +28,10 @@ struct ScoreArgs {
     int32_t units, units_per_xcd;      // units in total and per XCD (block -> unit mapping)
     int32_t causal;
     float scale_log2;                  // log2(e) / sqrt(d)
+    // one tensor per layer: DEVICE tables of per-layer base addresses (layer l starts at Ql[l], Kl[l]
+    // instead of Q + l*q_sl, K + l*k_sl), or null
+    const uint4* const* Ql;
+    const uint4* const* Kl;
 };
 
 __device__ __forceinline__ bf16x8 as_frag(uint4 v)
@@ -35,6 +39,19 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v)
     union { uint4 u; bf16x8 b; } c;
     c.u = v;
     return c.b;
+}
+
+// A pointer to global memory that is the same in every lane, moved to scalar registers (a value
+// loaded from device memory sits in vector registers even when its address is uniform) and marked
+// as a global address (a pointer read from memory is otherwise accessed with flat instructions).
+template <typename T>
+__device__ __forceinline__ T* uniform_global_ptr(T* p)
+{
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    typedef __attribute__((address_space(1))) T* global_ptr;
+    return (T*)(global_ptr)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

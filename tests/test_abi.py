@@ -138,6 +138,9 @@ def test_select_and_compact_error_paths(L):
     assert L.ta_compact(*cmp_(_lay(d=96))) == tb.TA_ERR_SHAPE
     a = cmp_(); a[0] = ctypes.c_void_p(0x7f0000001004)
     assert L.ta_compact(*a) == tb.TA_ERR_ALIGN
+    # outputs that alias an input or each other are refused (distinct addresses pass this check:
+    # with the same fake address everywhere the call above got as far as the alias test)
+    assert L.ta_compact(*cmp_()) == tb.TA_ERR_SHAPE
 
 
 def test_evict_validates_every_stage_before_launching(L):
@@ -157,6 +160,47 @@ def test_evict_validates_every_stage_before_launching(L):
     # TA-Fast needs neither Q nor a workspace, but still a sane budget
     cp0 = tb.Params(alpha=0.0).c()
     assert L.ta_evict(*args(K=3, Q=None, ws=None, nbytes=0, prm=cp0)) == tb.TA_ERR_BUDGET
+
+
+def test_evict_layers_checks_every_table_entry(L):
+    ids, lens = _table()
+    cp = tb.Params().c()
+    lay = _lay()
+    need = L.ta_workspace_bytes(ctypes.byref(lay), ctypes.byref(cp))
+    base = 0x7f0000001000
+
+    def table(vals):
+        return (ctypes.c_void_p * len(vals))(*vals)
+
+    def lp(layers=2, **kw):
+        # distinct fake addresses per array and layer (never dereferenced)
+        arrs = {name: [base + 0x100000 * (5 * l + i) for l in range(layers)]
+                for i, name in enumerate(("Q", "K", "V", "Kout", "Vout"))}
+        for k, v in kw.items():
+            arrs[k] = v
+        keep = {k: (None if v is None else table(v)) for k, v in arrs.items()}
+        c = tb.CLayerPtrs(*[None if keep[k] is None else ctypes.cast(keep[k], ctypes.c_void_p)
+                            for k in ("Q", "K", "V", "Kout", "Vout")])
+        c._keep = keep
+        return c
+
+    def args(p, lay_=lay, prm=cp, K=16, ws=FAKE, nbytes=need):
+        return [FAKE, None, ids.ctypes.data, lens.ctypes.data, 2, None, None if p is None else ctypes.byref(p),
+                ctypes.byref(lay_), ctypes.byref(prm), K, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws, nbytes, None]
+    assert L.ta_evict_layers(*args(None)) == tb.TA_ERR_NULL
+    assert L.ta_evict_layers(*args(lp(V=None))) == tb.TA_ERR_NULL                     # a missing array
+    assert L.ta_evict_layers(*args(lp(Q=None))) == tb.TA_ERR_NULL                     # alpha != 0 needs queries
+    assert L.ta_evict_layers(*args(lp(K=[base, None]))) == tb.TA_ERR_NULL             # a missing entry
+    assert L.ta_evict_layers(*args(lp(Vout=[base + 0x10, base + 0x24]))) == tb.TA_ERR_ALIGN
+    k_tab = [base + 0x100000, base + 0x200000]
+    assert L.ta_evict_layers(*args(lp(K=k_tab, Kout=[base + 0x300000, k_tab[1]]))) == tb.TA_ERR_SHAPE   # output on its input
+    big = _lay(layers=97)
+    assert L.ta_evict_layers(*args(lp(layers=97), lay_=big)) == tb.TA_ERR_SHAPE       # more layers than a table holds
+    # the stages behind the table are validated as in ta_evict
+    assert L.ta_evict_layers(*args(lp(), K=3)) == tb.TA_ERR_BUDGET
+    assert L.ta_evict_layers(*args(lp(), ws=None)) == tb.TA_ERR_WORKSPACE
+    cp0 = tb.Params(alpha=0.0).c()
+    assert L.ta_evict_layers(*args(lp(Q=None), prm=cp0, K=3, ws=None, nbytes=0)) == tb.TA_ERR_BUDGET
 
 
 def _decode_state(**kw):
