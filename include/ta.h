@@ -17,7 +17,8 @@
  *      ta_score_paged /  steps 3 and 5, and the whole pass, over paged (block-table) caches
  *      ta_compact_paged / ta_evict_paged
  *      ta_evict          all of the above in one call
- *      ta_evict_layers   the same over caches that are one tensor per layer
+ *      ta_evict_layers / the same over caches that are one tensor (or one page pool)
+ *      ta_evict_layers_paged  per layer
  *      ta_decode_init /  the same policy applied after every generation step
  *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
  *
@@ -410,6 +411,22 @@ int32_t ta_evict_layers(const int32_t *tok, const int32_t *seq_len,
                         const ta_layer_ptrs *lp, const ta_layout *lay, const ta_params *prm, int32_t K,
                         uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
                         int32_t *idx, int32_t *cnt, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * ta_evict_paged over one page pool per layer (serving engines allocate the pools of a layer
+ * on their own and share the block table between the layers): lp->K[l], lp->V[l] are the
+ * pools of layer l, addressed through pg->block_table with the strides pg->stride[1..3]
+ * (pg->stride[0] is not used: pass 0); lp->Q, lp->Kout, lp->Vout as in ta_evict_layers; lse as in
+ * ta_evict_paged (NULL: two sweeps).  ws as in ta_evict_layers (with lse != NULL only the
+ * TA_LAYER_WS_BYTES of the table are needed).
+ * Errors: as ta_evict_paged and ta_evict_layers.
+ */
+int32_t ta_evict_layers_paged(const int32_t *tok, const int32_t *seq_len,
+                              const int32_t *tab_ids, const int32_t *tab_len, int32_t E, const float *anchor_B,
+                              const ta_layer_ptrs *lp, const ta_paged_kv *pg, const float *lse,
+                              const ta_layout *lay, const ta_params *prm, int32_t K,
+                              uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
+                              int32_t *idx, int32_t *cnt, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Incremental form: the same retention policy applied after every generation

@@ -28,7 +28,7 @@ TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
            "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged",
-           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
+           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_evict_layers_paged", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
 
 
 class TaError(RuntimeError):
@@ -149,6 +149,9 @@ def lib():
         L.ta_evict_layers.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, i32,
                                       vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ta_evict_layers.restype = i32
+        L.ta_evict_layers_paged.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32,
+                                            vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ta_evict_layers_paged.restype = i32
         L.ta_decode_init.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ta_decode_init.restype = i32
         L.ta_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
@@ -545,22 +548,31 @@ class LayerEvictPlan:
     """
 
     def __init__(self, tok, tab_ids, tab_len, Q_layers, K_layers, V_layers, K: int, params: Params,
-                 seq_len=None, anchor_B=None):
+                 seq_len=None, anchor_B=None, paged: Optional["PagedKV"] = None, lse=None):
         layers = len(K_layers)
         assert layers >= 1 and len(V_layers) == layers
         K0 = K_layers[0]
         dev = K0.device
         self.params, self.K = params, int(K)
         self.scored = params.alpha != 0.0
+        self.paged, self.lse = paged, lse
         for t in list(K_layers) + list(V_layers):
-            assert t.dim() == 4 and t.dtype == torch.bfloat16 and t.shape == K0.shape and t.stride() == K0.stride()
-        assert K0.stride(3) == 1
+            assert t.dtype == torch.bfloat16 and t.shape == K0.shape and t.stride() == K0.stride()
         lay = CLayout()
         lay.layers = layers
-        lay.batch, lay.hkv, lay.n, lay.d = K0.shape
-        lay.kv_stride[0] = 0
-        for i in range(3):
-            lay.kv_stride[i + 1] = K0.stride(i)
+        if paged is not None:
+            # K_layers / V_layers are the page pools of the layers; sizes and addressing come from `paged`
+            # (a PagedKV whose own pools may be None and whose layer stride is not used)
+            assert paged.layers == layers
+            lay.batch, lay.hkv, lay.n, lay.d = paged.batch, paged.hkv, paged.n, paged.d
+            self._pg = paged.c()
+            self._pg.stride[0] = 0
+        else:
+            assert K0.dim() == 4 and K0.stride(3) == 1
+            lay.batch, lay.hkv, lay.n, lay.d = K0.shape
+            lay.kv_stride[0] = 0
+            for i in range(3):
+                lay.kv_stride[i + 1] = K0.stride(i)
         if self.scored:
             assert len(Q_layers) == layers
             Q0 = Q_layers[0]
@@ -585,7 +597,14 @@ class LayerEvictPlan:
             self.A = torch.empty((layers, B, lay.hkv, n), dtype=torch.float32, device=dev)
             self.idx = torch.full((layers, B, lay.hkv, self.K), -1, dtype=torch.int32, device=dev)
             self.cnt = torch.zeros((layers, B, lay.hkv), dtype=torch.int32, device=dev)
-            nbytes = (ta_workspace_bytes(lay, params) + 255) // 256 * 256 + TA_LAYER_WS_BYTES
+            sized = lay
+            if paged is not None:                                # workspace size depends on the sizes only
+                sized = CLayout.from_buffer_copy(lay)
+                sized.kv_stride[3] = lay.d
+            nbytes = (0 if lse is not None else (ta_workspace_bytes(sized, params) + 255) // 256 * 256) + TA_LAYER_WS_BYTES
+            if lse is not None:
+                assert lse.dtype == torch.float32 and lse.is_contiguous()
+                assert tuple(lse.shape) == (layers, B, lay.hq, lay.window)
         else:
             self.A = None
             nbytes = TA_LAYER_WS_BYTES
@@ -603,6 +622,16 @@ class LayerEvictPlan:
 
     def run(self, stream=None):
         ws_bytes = self.ws.numel()
+        if self.paged is not None:
+            rc = lib().ta_evict_layers_paged(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data,
+                                             self.lens.ctypes.data, self.E, _ptr(self.anchor_B), ctypes.byref(self._lp),
+                                             ctypes.byref(self._pg), _ptr(self.lse), ctypes.byref(self.lay),
+                                             ctypes.byref(self._cp), self.K,
+                                             _ptr(self.anchor), _ptr(self.spons), _ptr(self.vouch), _ptr(self.A),
+                                             _ptr(self.idx), _ptr(self.cnt), _ptr(self.ws), ws_bytes, _stream(stream))
+            _check(rc, "ta_evict_layers_paged")
+            return self
+        assert self.lse is None, "row log-sum-exps are taken by the paged form only"
         rc = lib().ta_evict_layers(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
                                    self.E, _ptr(self.anchor_B), ctypes.byref(self._lp), ctypes.byref(self.lay),
                                    ctypes.byref(self._cp), self.K,
@@ -610,6 +639,14 @@ class LayerEvictPlan:
                                    _ptr(self.idx), _ptr(self.cnt), _ptr(self.ws), ws_bytes, _stream(stream))
         _check(rc, "ta_evict_layers")
         return self
+
+
+def ta_evict_layers_paged(tok, tab_ids, tab_len, Q_layers, Kpool_layers, Vpool_layers, paged: "PagedKV", K: int,
+                          params: Params, seq_len=None, anchor_B=None, lse=None, stream=None) -> LayerEvictPlan:
+    """The whole pass over one page pool per layer behind a shared block table (`paged` describes
+    the table, the page geometry and the sizes; its own pools are not used)."""
+    return LayerEvictPlan(tok, tab_ids, tab_len, Q_layers, Kpool_layers, Vpool_layers, K, params, seq_len, anchor_B,
+                          paged=paged, lse=lse).run(stream)
 
 
 def ta_evict_layers(tok, tab_ids, tab_len, Q_layers, K_layers, V_layers, K: int, params: Params, seq_len=None,

@@ -417,7 +417,7 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
     ta::LayerPtrs* lptr = nullptr;
     if (lp) {
         static_assert(sizeof(ta::LayerPtrs) <= TA_LAYER_WS_BYTES, "table must fit its share of the workspace");
-        const size_t table_off = ((scored ? workspace_bytes(lay) : 0) + 255) & ~(size_t)255;
+        const size_t table_off = ((scored && !lse ? workspace_bytes(lay) : 0) + 255) & ~(size_t)255;
         if (!ws || ws_bytes < table_off + TA_LAYER_WS_BYTES) return TA_ERR_WORKSPACE;
         if (!aligned16(ws)) return TA_ERR_ALIGN;
         lptr = reinterpret_cast<ta::LayerPtrs*>(static_cast<char*>(ws) + table_off);
@@ -528,6 +528,18 @@ int32_t ta_evict_layers(const int32_t* tok, const int32_t* seq_len,
     if (!lp) return TA_ERR_NULL;
     return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, nullptr, nullptr, nullptr, lay, prm, K, anchor, spons,
                       vouch, A, idx, cnt, nullptr, nullptr, ws, ws_bytes, nullptr, nullptr, lp, stream);
+}
+
+int32_t ta_evict_layers_paged(const int32_t* tok, const int32_t* seq_len,
+                              const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                              const ta_layer_ptrs* lp, const ta_paged_kv* pg, const float* lse,
+                              const ta_layout* lay, const ta_params* prm, int32_t K,
+                              uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                              int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!lp || !pg) return TA_ERR_NULL;
+    return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, nullptr, nullptr, nullptr, lay, prm, K, anchor, spons,
+                      vouch, A, idx, cnt, nullptr, nullptr, ws, ws_bytes, lse, pg, lp, stream);
 }
 
 int32_t ta_decode_init(const ta_decode_state* st, const int32_t* tok, const int32_t* seq_len, int32_t n,

@@ -172,7 +172,8 @@ hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, 
     int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
     int64_t blocks = units * a.blocks_per_unit;
     const dim3 grid((unsigned)blocks), block(COMPACT_THREADS);
-    if (pg) hipLaunchKernelGGL((compact_kernel<true, false>), grid, block, 0, st, a);
+    if (pg && lp) hipLaunchKernelGGL((compact_kernel<true, true>), grid, block, 0, st, a);
+    else if (pg) hipLaunchKernelGGL((compact_kernel<true, false>), grid, block, 0, st, a);
     else if (lp) hipLaunchKernelGGL((compact_kernel<false, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((compact_kernel<false, false>), grid, block, 0, st, a);
     return hipGetLastError();

@@ -201,6 +201,25 @@ def test_evict_layers_checks_every_table_entry(L):
     assert L.ta_evict_layers(*args(lp(), ws=None)) == tb.TA_ERR_WORKSPACE
     cp0 = tb.Params(alpha=0.0).c()
     assert L.ta_evict_layers(*args(lp(Q=None), prm=cp0, K=3, ws=None, nbytes=0)) == tb.TA_ERR_BUDGET
+    # the table itself needs room in the workspace, also when nothing is scored
+    assert L.ta_evict_layers(*args(lp(Q=None), prm=cp0, ws=None, nbytes=0)) == tb.TA_ERR_WORKSPACE
+    assert L.ta_evict_layers(*args(lp(), nbytes=need)) == tb.TA_ERR_WORKSPACE
+    # one page pool per layer
+    pg = tb.CPaged()
+    pg.page_size, pg.max_pages, pg.num_pages, pg.block_table = 64, 64, 70, 0x7f0000001000
+    for i, x in enumerate((0, 64 * 8 * 128, 8 * 128, 128)):
+        pg.stride[i] = x
+
+    def pargs(p, pg_=pg, nbytes=need + 4096 + 256):
+        a = args(p, nbytes=nbytes)
+        return a[:7] + [None if pg_ is None else ctypes.byref(pg_), None] + a[7:]
+    assert L.ta_evict_layers_paged(*pargs(lp(), pg_=None)) == tb.TA_ERR_NULL
+    assert L.ta_evict_layers_paged(*pargs(None)) == tb.TA_ERR_NULL
+    bad = tb.CPaged.from_buffer_copy(pg)
+    bad.page_size = 48
+    assert L.ta_evict_layers_paged(*pargs(lp(), pg_=bad)) == tb.TA_ERR_SHAPE          # scoring wants multiples of 64
+    assert L.ta_evict_layers_paged(*pargs(lp(K=[base, None]))) == tb.TA_ERR_NULL
+    assert L.ta_evict_layers_paged(*pargs(lp(), nbytes=need)) == tb.TA_ERR_WORKSPACE
 
 
 def _decode_state(**kw):

@@ -89,3 +89,54 @@ def test_layers_attention_free_pass_shares_one_retained_set():
     a, s, v = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len)
     idx_ref = ora.select(None, a, s, v, K, w.n_sink, w.n_recent, alpha=0.0)
     assert np.array_equal(got.idx[b, :int(got.cnt[b])].cpu().numpy(), idx_ref)
+
+
+@pytest.mark.parametrize("page_size,heads_first,alpha,with_lse", [
+    (64, False, 1.0, False),
+    (128, True, 1.0, True),        # one sweep from given row log-sum-exps
+    (16, False, 0.0, False),       # nothing scored: any page size
+])
+def test_layers_paged_pass_equals_the_paged_pass_on_a_stacked_pool(page_size, heads_first, alpha, with_lse):
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=3, batch=2, n=2000, hq=8, hkv=2, window=32,
+                  ragged=(300, 2000), planted=6)
+    td = wl.make_tokens(w, clean=False)
+    Q, Kc, Vc = wl.make_qkv(w, device=DEV)
+    Kp, Vp, table, num_pages, strides = wl.make_paged(Kc, Vc, page_size, heads_first=heads_first)
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent, alpha=alpha)
+    tok, seq = _dev(td.tok), _dev(td.seq_len)
+    K = 150
+    lse = None
+    if with_lse:
+        # natural-log normalisers of the window rows, by torch on the device (inputs of the call, not a reference)
+        lse = torch.empty((w.layers, w.batch, w.hq, w.window), dtype=torch.float32, device=DEV)
+        G = w.hq // w.hkv
+        for l in range(w.layers):
+            for b in range(w.batch):
+                nb = int(td.seq_len[b])
+                S = torch.einsum("hwd,hnd->hwn", Q[l, b].float(), Kc[l, b, :, :nb].float().repeat_interleave(G, dim=0))
+                S = S / w.d ** 0.5
+                vis = torch.arange(nb, device=DEV)[None, :] <= (nb - w.window + torch.arange(w.window, device=DEV))[:, None]
+                lse[l, b] = torch.logsumexp(S.masked_fill(~vis[None], float("-inf")), dim=-1)
+    stacked = ta.PagedKV(Kp, Vp, table, page_size, num_pages, strides, w.layers, w.batch, w.hkv, w.n)
+    Qs = Q if alpha != 0.0 else None
+    ref = ta.ta_evict_paged(tok, td.tab_ids, td.tab_len, Qs, stacked, K, prm, seq_len=seq, lse=lse)
+    # the same pools, one allocation per layer
+    Kl = [Kp[l].clone() for l in range(w.layers)]
+    Vl = [Vp[l].clone() for l in range(w.layers)]
+    Ql = _scatter(Q) if alpha != 0.0 else None
+    desc = ta.PagedKV(None, None, table, page_size, num_pages, strides, w.layers, w.batch, w.hkv, w.n)
+    got = ta.ta_evict_layers_paged(tok, td.tab_ids, td.tab_len, Ql, Kl, Vl, desc, K, prm, seq_len=seq, lse=lse)
+    torch.cuda.synchronize()
+    assert torch.equal(got.idx, ref.idx) and torch.equal(got.cnt, ref.cnt)
+    if alpha != 0.0:
+        assert torch.equal(got.A, ref.A)
+    for l in range(w.layers):
+        assert torch.equal(got.Kout[l], ref.Kout[l]) and torch.equal(got.Vout[l], ref.Vout[l]), l
+    # one unit against the oracle's paged gather and compaction
+    l, b, g = 2, 1, 1
+    nb = int(td.seq_len[b])
+    rows_k = ora.paged_gather(wl.bf16_bits(Kl[l]), table.cpu().numpy()[b], nb, page_size, strides[1], strides[2], strides[3], g, w.d)
+    sel = (b,) if alpha == 0.0 else (l, b, g)
+    c = int(got.cnt[sel])
+    idx_h = got.idx[sel][:c].cpu().numpy()
+    assert np.array_equal(wl.bf16_bits(got.Kout[l][b, g, :c]), ora.compact(rows_k, idx_h))
