@@ -39,7 +39,7 @@ SCORE_TRAFFIC = {
     "workload": "c2_full_model",
     "bytes_per_step": 559.4e6,
     "sources": {
-        "ta_score.hip": "c3729cb05e7556b7b8f2be62f13900d3a5362f89ecda413358ec32a89dd64b6c",
+        "ta_score.hip": "3d4c1d0d73c0a6bcc86fbff7ae068b3f33b1357248de3595f22667017ae339f7",
         "ta_score_common.h": "3e4b78495a5669b06b80090303e2ac50ab9622f4b9ead1de520e8aee81424db4",
         "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
     },

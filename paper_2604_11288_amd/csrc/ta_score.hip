@@ -31,6 +31,7 @@
 //           the column sum is a register accumulation plus one half-wave swap.
 #include <math.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "ta_match_device.h"
@@ -45,6 +46,8 @@ constexpr int STAGE_UNITS = STAGE_KEYS * 16;     // 16-byte units per stage (256
 // Stage buffers per workgroup; loads run that many minus one stages ahead.  (Eight buffers for
 // the wider workgroups, which have a compute unit to themselves, were measured: no gain.)
 constexpr int ring_of(int) { return 4; }
+// the widest workgroup: 64 * MAX_RG rows at a time (more row groups leave too few registers per lane)
+constexpr int MAX_RG = 4;
 
 // Direct global->LDS load of 16 bytes per lane: lane i reads 16 bytes at base + off (base
 // wave-uniform, off per lane) and its data lands at lds_base + 16*i (lds_base wave-uniform,
@@ -73,8 +76,9 @@ struct RiderArgs {
 };
 
 // RG row groups of RT 32-row MFMA tiles each per workgroup; 2 * RG wavefronts.
+// row_base: first of the 64 * RG rows this call works on (units with more rows take several calls)
 template <int RG, int RT, bool COLSUM, bool PAGED>
-__device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS]);
+__device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS], int32_t row_base);
 
 // one tile per wavefront: four wavefronts per SIMD (at most 128 registers each)
 template <int RG, int RT, bool COLSUM, bool PAGED>
@@ -82,7 +86,16 @@ __global__ void __launch_bounds__(128 * RG, RT == 1 ? 4 : 2)
 score_kernel(ScoreArgs a)
 {
     __shared__ uint4 s_k[ring_of(RG)][STAGE_UNITS];        // 16 KB per stage
-    score_body<RG, RT, COLSUM, PAGED>(a, s_k);
+    // a workgroup holds 64 * RG rows at a time; a unit with more rows is done in passes over its chunk
+    // (the keys of the later passes come from the L2; their column sums are added to the first pass's)
+    if constexpr (RG < MAX_RG) {
+        score_body<RG, RT, COLSUM, PAGED>(a, s_k, 0);      // these kernels only get units that fit one pass
+    } else {
+        for (int32_t row_base = 0; row_base < a.rows_pad; row_base += 64 * RG) {
+            if (row_base > 0) __syncthreads();             // the previous pass is done with the LDS
+            score_body<RG, RT, COLSUM, PAGED>(a, s_k, row_base);
+        }
+    }
 }
 
 template <int RG, int RT, bool COLSUM>
@@ -98,11 +111,18 @@ score_match_kernel(ScoreArgs a, RiderArgs r)
                           (int)threadIdx.x, *reinterpret_cast<MatchLds*>(&s_k[0][0]));
         return;
     }
-    score_body<RG, RT, COLSUM, false>(a, s_k);
+    if constexpr (RG < MAX_RG) {
+        score_body<RG, RT, COLSUM, false>(a, s_k, 0);
+    } else {
+        for (int32_t row_base = 0; row_base < a.rows_pad; row_base += 64 * RG) {
+            if (row_base > 0) __syncthreads();
+            score_body<RG, RT, COLSUM, false>(a, s_k, row_base);
+        }
+    }
 }
 
 template <int RG, int RT, bool COLSUM, bool PAGED>
-__device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS])
+__device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAGE_UNITS], const int32_t row_base)
 {
     constexpr int ROW_TILES = RT;
     constexpr int GROUP_ROWS = 32 * RT;                    // rows of one wavefront
@@ -247,7 +267,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     int32_t my_lim[ROW_TILES];                             // sweep 1: last visible key of this lane's row
 #pragma unroll
     for (int t = 0; t < ROW_TILES; ++t) {
-        const int32_t r = GROUP_ROWS * rg + 32 * t + c32;
+        const int32_t r = row_base + GROUP_ROWS * rg + 32 * t + c32;
         int32_t lim = -1;
         if (r < a.rows) {
             const int32_t h = r / W, w = r - h * W;
@@ -265,7 +285,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     // load is issued: these are ordinary loads, and waiting for them later would also wait for
     // every direct load issued in between).  Chunks are added in index order, four loads in flight.
     if constexpr (COLSUM) {
-        for (int r = tid; r < GROUP_ROWS * RG; r += THREADS) {
+        for (int lr = tid; lr < GROUP_ROWS * RG; lr += THREADS) {
+            const int32_t r = row_base + lr;
             float c = INFINITY;
             int32_t lim = -1;
             if (r < a.rows && a.lse) {
@@ -307,8 +328,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
                 const int32_t h = r / W, w = r - h * W;
                 lim = a.causal ? nb - W + w : nb - 1;
             }
-            s_c[r] = c;
-            s_lim[r] = lim;
+            s_c[lr] = c;
+            s_lim[lr] = lim;
         }
     }
 
@@ -441,7 +462,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
                     float v = s_part[s & 1][0][tid];
 #pragma unroll
                     for (int w = 1; w < RG; ++w) v += s_part[s & 1][w][tid];
-                    a.A[(size_t)unit * n + key] = v;
+                    float* dst = &a.A[(size_t)unit * n + key];
+                    *dst = row_base > 0 ? *dst + v : v;    // the same thread wrote it in the pass before
                 }
             }
         }
@@ -453,6 +475,41 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
     const auto flush_pending = [&]() {
         for (; flushed < reduced; ++flushed) flush(flushed);
     };
+    // The same in two halves for the pipelined loop: the LDS reads of the partial sums are issued
+    // right behind the barrier and their sum is stored after the stage's MFMAs and reduction.  Done
+    // in one piece at the top of the stage, the wavefront that flushes waits for its reads behind
+    // the fragment reads of every other wavefront (all issued at the barrier), falls behind by that
+    // wait in every stage, and the whole workgroup waits for it at the next barrier.
+    float fl_v[RG];
+    int32_t fl_key = -1;
+    const auto flush_begin = [&]() {
+        fl_key = -1;
+        if constexpr (COLSUM) {
+            if (flushed < reduced) {
+                if (tid < STAGE_KEYS) {
+                    const int32_t key = key_lo + stage_pos(flushed) * STAGE_KEYS + tid;
+                    if (key < key_hi) {
+                        fl_key = key;
+#pragma unroll
+                        for (int w = 0; w < RG; ++w) fl_v[w] = s_part[flushed & 1][w][tid];
+                    }
+                }
+                ++flushed;
+            }
+            flush_pending();                               // (the pipelined loop never has a second stage pending)
+        }
+    };
+    const auto flush_end = [&]() {
+        if constexpr (COLSUM) {
+            if (fl_key >= 0) {
+                float v = fl_v[0];
+#pragma unroll
+                for (int w = 1; w < RG; ++w) v += fl_v[w];
+                float* dst = &a.A[(size_t)unit * n + fl_key];
+                *dst = row_base > 0 ? *dst + v : v;
+            }
+        }
+    };
 
     // (A) fully visible stages: MFMAs of stage s and the reduction of stage s-1 in one block.
     // Two accumulator sets alternate (loop unrolled by two) so that no registers are copied.
@@ -463,14 +520,16 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
         int s = 1;
         for (; s + 1 < nfast; s += 2) {
             stage_sync(s);
-            flush_pending();                               // reductions before this barrier are complete
+            flush_begin();                                 // reductions before this barrier are complete
             mma(s, acc_odd);
             reduce(s - 1, acc_even, fast_tag{});
+            flush_end();
             reduced = s;
             stage_sync(s + 1);
-            flush_pending();
+            flush_begin();
             mma(s + 1, acc_even);
             reduce(s, acc_odd, fast_tag{});
+            flush_end();
             reduced = s + 1;
         }
         const bool odd_left = s < nfast;                   // one more stage, into the odd set
@@ -543,8 +602,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
                 const float mf = fmaxf(m_run[t], mo);
                 float zf = 0.0f;
                 if (mf > -INFINITY) zf = z_run[t] * fast_exp2(m_run[t] - mf) + zo * fast_exp2(mo - mf);
-                st[r * 2] = mf;
-                st[r * 2 + 1] = zf;
+                st[(row_base + r) * 2] = mf;
+                st[(row_base + r) * 2 + 1] = zf;
             }
         }
     }
@@ -603,15 +662,16 @@ int32_t padded_rows(int32_t rows)
 
 int compute_units()
 {
-    static int cached = 0;
-    if (cached == 0) {
-        int dev = 0, cu = 0;
+    static std::atomic<int> cached{0};                     // callers on several threads may race to fill it
+    int cu = cached.load(std::memory_order_relaxed);
+    if (cu == 0) {
+        int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
             cu = 256;                                      // MI355X
-        cached = cu;
+        cached.store(cu, std::memory_order_relaxed);
     }
-    return cached;
+    return cu;
 }
 
 struct ScorePlan {
@@ -708,7 +768,8 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
         // per SIMD instead of two - was measured: same time at 128 rows, 5 % slower at 256)
         case 128: launch_rg<2, 2>(a, p.units, rider, st); break;
         case 256: launch_rg<4, 2>(a, p.units, rider, st); break;
-        default: launch_rg<8, 2>(a, p.units, rider, st); break;
+        default: launch_rg<4, 2>(a, p.units, rider, st); break;   // 512 rows: two passes of 256 (eight row groups
+                                                                  // at once leave 128 registers per lane: spills, 3x slower)
     }
     return hipGetLastError();
 }

@@ -166,7 +166,8 @@ def test_score_c1_shape():
     (1000, 8, 2, 32, False),      # no mask
     (700, 6, 2, 5, True),         # 15 rows: padded row tile, rows of one tile span several heads
     (1500, 8, 2, 64, True),       # 256 rows: two row tiles per wavefront
-    (600, 16, 2, 64, True),       # 512 rows: four row tiles per wavefront
+    (600, 16, 2, 64, True),       # 512 rows: two passes of 256 rows over each chunk
+    (2500, 10, 2, 64, True),      # 320 rows: the second pass has 64 live rows; two chunks
     (64, 4, 1, 64, True),         # window as long as the context
     (33, 4, 4, 1, True),          # one query row per head
     (8192, 4, 1, 32, True),       # 128 rows, 4 chunks of 2048 keys
