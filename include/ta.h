@@ -476,7 +476,8 @@ typedef struct ta_decode_state {
  *   anchor_B float [batch][n] or NULL, A float [layers][batch][hkv][n] or NULL,
  *   idx int32 [layers][batch][hkv][K], cnt int32 [layers][batch][hkv],
  *   Kout, Vout bf16 [layers][batch][hkv][K][d]           (all DEVICE)
- * Errors: NULL, SHAPE (n > cap, K out of range, d != 128, hq % hkv != 0), ALIGN.
+ * Errors: NULL, SHAPE (n > cap, K out of range, d != 128, hq % hkv != 0, more than 16 query
+ * heads per KV head, (hq/hkv) * (K + 1) > 15360), ALIGN.
  */
 int32_t ta_decode_init(const ta_decode_state *st, const int32_t *tok, const int32_t *seq_len, int32_t n,
                        const uint8_t *anchor, const float *anchor_B, const float *A,

@@ -154,7 +154,7 @@ int32_t check_decode_state(const ta_decode_state* st)
         !st->pos || !st->A)
         return TA_ERR_NULL;
     if (st->layers < 1 || st->batch < 1 || st->hkv < 1 || st->hq < 1 || st->hq % st->hkv != 0) return TA_ERR_SHAPE;
-    if (st->hq / st->hkv > 8) return TA_ERR_SHAPE;
+    if (st->hq / st->hkv > 16) return TA_ERR_SHAPE;        // the heads of a group are the 16 columns of an MFMA tile
     if (st->d != TA_HEAD_DIM) return TA_ERR_SHAPE;
     if (st->K < 1 || st->K > TA_MAX_DECODE_K) return TA_ERR_SHAPE;
     if ((int64_t)(st->hq / st->hkv) * (st->K + 1) > 15360) return TA_ERR_SHAPE;      // logits of a unit sit in LDS

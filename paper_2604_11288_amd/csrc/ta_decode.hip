@@ -28,7 +28,7 @@ namespace {
 
 constexpr int DU_THREADS = 256;
 constexpr int DU_WAVES = DU_THREADS / 64;
-constexpr int MAX_GROUP = 8;                               // query heads per KV head
+constexpr int MAX_GROUP = 16;                              // query heads per KV head (the columns of an MFMA tile)
 
 struct DecodeTable {
     int32_t rid[TA_MAX_TABLE][TA_MAX_GRAM];                // n-grams reversed: rid[e][0] = last token
@@ -250,7 +250,7 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
 
     // The logits of the group's decode queries over the cached rows are a [slots x d] x [d x G]
     // contraction: v_mfma_f32_16x16x16_bf16 with 16 key rows as the rows of a tile and the heads
-    // as its columns (G <= 8 of the 16 are used; the matrix pipe is idle otherwise).
+    // as its columns (G <= 16 of them are used; the matrix pipe is idle otherwise).
     // Key rows are loaded the way memory likes them - a wavefront instruction takes four whole
     // consecutive rows, 16 lanes x 16 bytes each - and turned into operand fragments through a
     // 4 KB tile in LDS: lane (i16, kq) of the matrix layout needs 16 bytes of row i16 at chunk
@@ -525,11 +525,15 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
         attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<4>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<8>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr_err == hipSuccess)
             attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<MAX_GROUP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     });
     if (attr_err != hipSuccess) return attr_err;
     if (G <= 4) hipLaunchKernelGGL(decode_unit_kernel<4>, dim3(units), dim3(64), lds, s, st, a);
+    else if (G <= 8) hipLaunchKernelGGL(decode_unit_kernel<8>, dim3(units), dim3(64), lds, s, st, a);
     else hipLaunchKernelGGL(decode_unit_kernel<MAX_GROUP>, dim3(units), dim3(64), lds, s, st, a);
 
     dim3 g3((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);

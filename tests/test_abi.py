@@ -249,7 +249,7 @@ def test_decode_error_paths(L):
     assert L.ta_decode_step(*step(q=None)) == tb.TA_ERR_NULL                        # alpha != 0 needs queries
     assert L.ta_decode_step(*step(E=70)) == tb.TA_ERR_SHAPE
     assert L.ta_decode_step(*step(_decode_state(K=6))) == tb.TA_ERR_BUDGET          # K < n_sink + n_recent
-    assert L.ta_decode_step(*step(_decode_state(hq=128))) == tb.TA_ERR_SHAPE        # 16 heads per group
+    assert L.ta_decode_step(*step(_decode_state(hq=136))) == tb.TA_ERR_SHAPE        # 17 heads per group
     a = step(); a[3] = ctypes.c_void_p(0x7f0000001004)
     assert L.ta_decode_step(*a) == tb.TA_ERR_ALIGN
     a = step(); a[1] = None

@@ -147,3 +147,10 @@ def test_decode_large_budget_eight_heads_per_group():
     w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=1, n=1700, hq=8, hkv=1, ragged=None)
     ev, _ = _run_decode(w, K=1500, steps=5, p_anchor=0.2, check_every=2)
     assert ev == 5
+
+
+def test_decode_sixteen_heads_per_group():
+    # the heads of a group fill all 16 columns of the logits' MFMA tiles
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=2, n=600, hq=32, hkv=2, ragged=(300, 600))
+    ev, _ = _run_decode(w, K=100, steps=6, p_anchor=0.2, check_every=2)
+    assert ev == 6 * w.layers * w.batch * w.hkv               # every unit is full: one eviction per unit and step
