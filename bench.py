@@ -79,6 +79,11 @@ def main():
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_SIZE",
                     help="also time scoring and compaction over a paged (block-table) copy of the same cache with "
                          "pages of this many positions (a multiple of 64; reported as paged)")
+    ap.add_argument("--query-heads", type=int, default=0,
+                    help="run the workload with this many query heads instead of its own (more heads per KV head: "
+                         "more query rows per unit in the score step); the workload name in the output says so")
+    ap.add_argument("--window", type=int, default=0,
+                    help="run the workload with this many observation-window rows instead of its own")
     ap.add_argument("--layer-tensors", action="store_true",
                     help="also time the pass over the same cache kept as one tensor per layer (ta_evict_layers), "
                          "and the same work issued as one ta_evict call per layer (reported as layer_tensors)")
@@ -115,6 +120,11 @@ def main():
     ta.lib()
 
     w = wl.CONFIGS[args.workload]
+    variant = args.workload
+    if args.query_heads > 0 or args.window > 0:
+        w = wl.scaled(w, hq=args.query_heads or w.hq, window=args.window or w.window,
+                      name="%s with %d query heads, window %d" % (w.name, args.query_heads or w.hq, args.window or w.window))
+        variant = w.name                     # not the profiled workload: no stored traffic figure
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     td = wl.make_tokens(w)
@@ -180,7 +190,7 @@ def main():
         achieved = alg_bytes / dur / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": measured_score_traffic(args.workload, budget),
+                    "traffic": measured_score_traffic(variant, budget),
                     "avg_launch_us": round(kern_us["score"], 2),
                     "mfma_tflops": round(alg_flops / dur / 1e12, 1),
                     "mfma_frac": round(alg_flops / dur / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}

@@ -425,7 +425,7 @@ int32_t evict_pass(const int32_t* tok, const int32_t* seq_len,
 
     hipStream_t st = (hipStream_t)stream;
     if (lp) {
-        rc = hip_status(ta::launch_layer_table(layer_ptrs, lptr, st));
+        rc = hip_status(ta::launch_layer_table(layer_ptrs, lptr, lay->layers, st));
         if (rc != TA_OK) return rc;
     }
     if (scored) {

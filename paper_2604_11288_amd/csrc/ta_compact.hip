@@ -113,19 +113,45 @@ compact_kernel(CompactArgs a)
 // pass then read their layer's entries from there.  (Handing the table to those kernels by value
 // was measured: with argument blocks of a few KB every scalar load of an argument becomes slow, and
 // the compaction took 690 us instead of 42.)
-__global__ void layer_table_kernel(LayerPtrs t, LayerPtrs* dst)
+// N layers of the five tables, packed: small argument blocks stay on the fast path (the table of
+// a 32-layer model is 1.3 KB).
+template <int N>
+struct PackedLayerPtrs {
+    const void* p[5][N];
+};
+
+template <int N>
+__global__ void layer_table_kernel(PackedLayerPtrs<N> t, LayerPtrs* dst, int32_t layers)
 {
-    constexpr int WORDS = (int)(sizeof(LayerPtrs) / sizeof(uint64_t));
-    const uint64_t* src = reinterpret_cast<const uint64_t*>(&t);
-    uint64_t* out = reinterpret_cast<uint64_t*>(dst);
-    for (int i = (int)threadIdx.x; i < WORDS; i += (int)blockDim.x) out[i] = src[i];
+    const void** out[5] = {dst->Q, dst->K, dst->V, const_cast<const void**>(reinterpret_cast<void* const*>(dst->Kout)),
+                           const_cast<const void**>(reinterpret_cast<void* const*>(dst->Vout))};
+    for (int i = (int)threadIdx.x; i < 5 * layers; i += (int)blockDim.x) {
+        const int arr = i / layers, l = i - arr * layers;
+        out[arr][l] = t.p[arr][l];
+    }
+}
+
+template <int N>
+void launch_layer_table_n(const LayerPtrs& h, LayerPtrs* dev_table, int32_t layers, hipStream_t st)
+{
+    PackedLayerPtrs<N> t;
+    for (int l = 0; l < N; ++l) {
+        const bool on = l < layers;
+        t.p[0][l] = on ? h.Q[l] : nullptr;
+        t.p[1][l] = on ? h.K[l] : nullptr;
+        t.p[2][l] = on ? h.V[l] : nullptr;
+        t.p[3][l] = on ? h.Kout[l] : nullptr;
+        t.p[4][l] = on ? h.Vout[l] : nullptr;
+    }
+    hipLaunchKernelGGL(layer_table_kernel<N>, dim3(1), dim3(256), 0, st, t, dev_table, layers);
 }
 
 }  // namespace
 
-hipError_t launch_layer_table(const LayerPtrs& host_table, LayerPtrs* dev_table, hipStream_t st)
+hipError_t launch_layer_table(const LayerPtrs& host_table, LayerPtrs* dev_table, int32_t layers, hipStream_t st)
 {
-    hipLaunchKernelGGL(layer_table_kernel, dim3(1), dim3(512), 0, st, host_table, dev_table);
+    if (layers <= 32) launch_layer_table_n<32>(host_table, dev_table, layers, st);
+    else launch_layer_table_n<TA_MAX_LAYER_PTRS>(host_table, dev_table, layers, st);
     return hipGetLastError();
 }
 

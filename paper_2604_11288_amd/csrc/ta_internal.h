@@ -62,7 +62,8 @@ struct LayerPtrs {
     void* Vout[TA_MAX_LAYER_PTRS];
 };
 
-hipError_t launch_layer_table(const LayerPtrs& host_table, LayerPtrs* dev_table, hipStream_t st);
+// writes the first `layers` entries of each table (the kernels read no others)
+hipError_t launch_layer_table(const LayerPtrs& host_table, LayerPtrs* dev_table, int32_t layers, hipStream_t st);
 
 // ---- score ------------------------------------------------------------------
 // Scratch bytes and grid size of the score step for a validated layout.

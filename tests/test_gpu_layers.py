@@ -38,6 +38,7 @@ def _scatter(stacked, heads_last=False):
     (1000, 2, 3, 64, None, False),
     (4096, 1, 5, 256, None, True),            # rows of a position interleaved over the heads
     (2500, 3, 2, 100, (17, 2500), False),
+    (300, 1, 40, 50, None, False),            # more layers than the small form of the address table holds
 ])
 def test_layers_scored_pass_equals_stacked_pass_and_oracle(n, batch, layers, K, ragged, heads_last):
     w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=layers, batch=batch, n=n, hq=8, hkv=2, window=32,
