@@ -110,9 +110,10 @@ compact_kernel(CompactArgs a)
 }
 
 // Writes a table of per-layer addresses, handed over by value, to device memory: the kernels of the
-// pass then read their layer's entries from there.  (Handing the table to those kernels by value
-// was measured: with argument blocks of a few KB every scalar load of an argument becomes slow, and
-// the compaction took 690 us instead of 42.)
+// pass then read their layer's entries from there.  (Arrays inside those kernels' own argument
+// structs were measured first: a run-time choice between a table entry and the base pointer made
+// the compiler copy the whole argument block to scratch memory per lane - the compaction took
+// 690 us instead of 42 - and the statistics sweep reloaded arguments inside its stage loop.)
 // N layers of the five tables, packed: small argument blocks stay on the fast path (the table of
 // a 32-layer model is 1.3 KB).
 template <int N>
