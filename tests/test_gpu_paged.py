@@ -24,6 +24,7 @@ def _close(got, ref):
     (64, False, 3000, 32, (700, 3000)),       # smallest page the score kernel takes; last page partly filled
     (256, True, 4096, 32, None),
     (128, False, 9000, 64, (4000, 9000)),     # several chunks, 256 rows per unit
+    (64, True, 2600, 128, (150, 2600)),       # 512 rows per unit: two passes over each chunk of pages
 ])
 def test_paged_score_and_compact_match_oracle(page_size, heads_first, n, window, ragged):
     w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=2, batch=2, n=n, hq=8, hkv=2, window=window, ragged=ragged, planted=6)
