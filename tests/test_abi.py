@@ -346,3 +346,11 @@ def test_decode_rejects_one_shot_options(L):
     assert call(tb.Params(n_sink=4, n_recent=4, pool_k=5).c()) == tb.TA_ERR_SHAPE
     assert call(tb.Params(n_sink=4, n_recent=4, k_protected=4).c()) == tb.TA_ERR_SHAPE
     assert call(tb.Params(n_sink=10, n_recent=10).c()) == tb.TA_ERR_BUDGET
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
