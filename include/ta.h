@@ -441,6 +441,8 @@ int32_t ta_evict_layers_paged(const int32_t *tok, const int32_t *seq_len,
  *                 vouch  float [batch][cap]   scratch of a step: voucher of each position from
  *                 spons  uint8 [batch][cap]   the current budgets, and its sponsor flag (Eq. 2);
  *                                             rewritten by every ta_decode_step, never read back
+ *                 stepped int32 [batch]       scratch of a step: 1 if the step appended a token to the
+ *                                             sequence, 0 if it was at capacity and left alone
  *   per unit      Kc, Vc bf16  [layers][batch][hkv][K+1][d]  cache slots
  *                 pos    int32 [layers][batch][hkv][K+1]     absolute position of a slot, -1 = free
  *                 A      float [layers][batch][hkv][K+1]     cumulative attention of a slot
@@ -461,6 +463,7 @@ typedef struct ta_decode_state {
     void *Kc, *Vc;
     int32_t *pos;
     float *A;
+    int32_t *stepped;
 } ta_decode_state;
 
 #define TA_MAX_DECODE_K 2047
@@ -498,13 +501,24 @@ int32_t ta_decode_init(const ta_decode_state *st, const int32_t *tok, const int3
  *   new_tok int32 [batch]; q_new bf16 [layers][batch][hq][d] (NULL when alpha == 0);
  *   k_new, v_new bf16 [layers][batch][hkv][d]; table as in ta_match_anchors (HOST);
  *   evicted int32 [layers][batch][hkv] or NULL: position freed in step 3, -1 if none.
- * The caller keeps len[b] < cap; a sequence at capacity is left unchanged.
+ * The caller keeps len[b] < cap; a sequence at capacity (len[b] >= cap) is left unchanged:
+ * nothing is appended, no attention is added, nothing is evicted (evicted = -1 for its
+ * units) and its budgets do not decay.
  * Errors: NULL, SHAPE, BUDGET (K < n_sink + n_recent), ALIGN.
  */
 int32_t ta_decode_step(const ta_decode_state *st, const int32_t *new_tok, const void *q_new,
                        const void *k_new, const void *v_new,
                        const int32_t *tab_ids, const int32_t *tab_len, int32_t E,
                        const ta_params *prm, int32_t *evicted, void *stream);
+
+/*
+ * One-time set-up of the library on the CURRENT device: kernel attributes (dynamic LDS sizes).
+ * Every entry point performs the part it needs on its first call on a device, so calling
+ * ta_init is optional - except before a stream capture or inside code that must not touch the
+ * runtime beyond launches: call it once per device beforehand.  Allocates nothing.  Returns
+ * TA_OK or TA_ERR_HIP.
+ */
+int32_t ta_init(void);
 
 /* Text for a ta_status value (static storage). */
 const char *ta_strerror(int32_t status);

@@ -28,7 +28,7 @@ TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
            "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged",
-           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_evict_layers_paged", "ta_decode_init", "ta_decode_step", "ta_strerror", "ta_last_hip_error")
+           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_evict_layers_paged", "ta_decode_init", "ta_decode_step", "ta_init", "ta_strerror", "ta_last_hip_error")
 
 
 class TaError(RuntimeError):
@@ -55,7 +55,7 @@ class CDecodeState(ctypes.Structure):
                 ("tok", ctypes.c_void_p), ("len", ctypes.c_void_p), ("anchor", ctypes.c_void_p),
                 ("budget", ctypes.c_void_p), ("vouch", ctypes.c_void_p), ("spons", ctypes.c_void_p),
                 ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
-                ("pos", ctypes.c_void_p), ("A", ctypes.c_void_p)]
+                ("pos", ctypes.c_void_p), ("A", ctypes.c_void_p), ("stepped", ctypes.c_void_p)]
 
 
 class CLayout(ctypes.Structure):
@@ -156,12 +156,19 @@ def lib():
         L.ta_decode_init.restype = i32
         L.ta_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
         L.ta_decode_step.restype = i32
+        L.ta_init.argtypes = []
+        L.ta_init.restype = i32
         L.ta_strerror.argtypes = [i32]
         L.ta_strerror.restype = ctypes.c_char_p
         L.ta_last_hip_error.argtypes = []
         L.ta_last_hip_error.restype = i32
         _lib = L
     return _lib
+
+
+def ta_init():
+    """One-time set-up on the current device (kernel attributes); optional except before a stream capture."""
+    _check(lib().ta_init(), "ta_init")
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -671,13 +678,14 @@ class DecodeState:
         self.Vc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
         self.pos = torch.full((layers, batch, hkv, K + 1), -1, dtype=i32, device=dev)
         self.A = torch.zeros((layers, batch, hkv, K + 1), dtype=torch.float32, device=dev)
+        self.stepped = torch.zeros((batch,), dtype=i32, device=dev)
 
     def c(self) -> CDecodeState:
         return CDecodeState(self.layers, self.batch, self.hq, self.hkv, self.d, self.K, self.cap,
                             self.tok.data_ptr(), self.len.data_ptr(), self.anchor.data_ptr(),
                             self.budget.data_ptr(), self.vouch.data_ptr(), self.spons.data_ptr(),
                             self.Kc.data_ptr(), self.Vc.data_ptr(),
-                            self.pos.data_ptr(), self.A.data_ptr())
+                            self.pos.data_ptr(), self.A.data_ptr(), self.stepped.data_ptr())
 
 
 def ta_decode_init(state: DecodeState, tok, anchor, idx, cnt, Kout, Vout, params: Params,

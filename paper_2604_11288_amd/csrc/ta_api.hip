@@ -151,7 +151,7 @@ int32_t check_decode_state(const ta_decode_state* st)
 {
     if (!st) return TA_ERR_NULL;
     if (!st->tok || !st->len || !st->anchor || !st->budget || !st->vouch || !st->spons || !st->Kc || !st->Vc ||
-        !st->pos || !st->A)
+        !st->pos || !st->A || !st->stepped)
         return TA_ERR_NULL;
     if (st->layers < 1 || st->batch < 1 || st->hkv < 1 || st->hq < 1 || st->hq % st->hkv != 0) return TA_ERR_SHAPE;
     if (st->hq / st->hkv > 16) return TA_ERR_SHAPE;        // the heads of a group are the 16 columns of an MFMA tile
@@ -491,6 +491,13 @@ int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
 {
     return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
                       idx, cnt, Kout, Vout, ws, ws_bytes, nullptr, nullptr, nullptr, stream);
+}
+
+int32_t ta_init(void)
+{
+    hipError_t e = ta::select_setup();
+    if (e == hipSuccess) e = ta::decode_setup();
+    return hip_status(e);
 }
 
 int32_t ta_evict_lse(const int32_t* tok, const int32_t* seq_len,

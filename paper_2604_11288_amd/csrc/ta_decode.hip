@@ -5,7 +5,8 @@
 // Kernels per step:
 //   decode_seq_kernel    one workgroup per sequence: append the token, test the
 //                        anchor table at the new position only, set its budget
-//   decode_unit_kernel   one workgroup per unit: write the new k/v row into the
+//   decode_vouch_kernel  voucher and sponsor flag of every position from the current budgets
+//   decode_unit_kernel   one wavefront per unit: write the new k/v row into the
 //                        free slot, add the decode queries' softmax weights over
 //                        the cached rows to A (H2O-style cumulative attention,
 //                        Eq. 1), free the slot that ranks last under the
@@ -17,8 +18,6 @@
 // head columns), fed with whole key rows that are turned into operand fragments
 // through a small LDS tile.
 #include <math.h>
-
-#include <mutex>
 
 #include "ta_internal.h"
 
@@ -96,7 +95,10 @@ decode_seq_kernel(ta_decode_state st, const int32_t* new_tok, DecodeTable tab)
 {
     const int b = blockIdx.x;
     const int32_t p = st.len[b];
-    if (p < 0 || p >= st.cap) return;                      // at capacity: sequence left unchanged
+    if (p < 0 || p >= st.cap) {                            // at capacity: the step leaves this sequence and its units alone
+        if (threadIdx.x == 0) st.stepped[b] = 0;
+        return;
+    }
     int32_t* tok = st.tok + (size_t)b * st.cap;
     const int32_t t0 = new_tok[b];
     const int e = threadIdx.x;
@@ -112,6 +114,7 @@ decode_seq_kernel(ta_decode_state st, const int32_t* new_tok, DecodeTable tab)
         st.anchor[(size_t)b * st.cap + p] = any ? 1 : 0;
         st.budget[(size_t)b * st.cap + p] = any ? tab.B : 0.0f;
         st.len[b] = p + 1;
+        st.stepped[b] = 1;
     }
 }
 
@@ -119,7 +122,7 @@ __global__ void decode_decay_kernel(ta_decode_state st, float decay)
 {
     const int b = blockIdx.y;
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < st.len[b] && p < st.cap) {
+    if (p < st.len[b] && p < st.cap && st.stepped[b]) {
         float* B = st.budget + (size_t)b * st.cap + p;
         *B = __fmul_rn(decay, *B);
     }
@@ -304,7 +307,7 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
         first_free = other < first_free ? other : first_free;
     }
     const int f = first_free;
-    if (f >= slots || p_new < 0) {                         // no room (or empty sequence): nothing to do
+    if (f >= slots || p_new < 0 || !st.stepped[b]) {       // no room, empty sequence, or a sequence at capacity: nothing to do
         if (lane == 0 && a.evicted) a.evicted[unit] = -1;
         return;
     }
@@ -467,7 +470,24 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
     if (lane == 0 && a.evicted) a.evicted[unit] = evict_pos;
 }
 
+DeviceOnce g_setup;
+
 }  // namespace
+
+hipError_t decode_setup()
+{
+    return g_setup.run([](int) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<4>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<8>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<MAX_GROUP>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        return e;
+    });
+}
 
 hipError_t launch_decode_init(const ta_decode_state& st, const int32_t* tok, const int32_t* seq_len, int32_t n,
                               const uint8_t* anchor, const float* anchor_B, const float* A,
@@ -519,18 +539,7 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     const size_t lds = (prm.alpha != 0.0f ? (size_t)((2 * slots + 3) & ~3) + 1024 + (size_t)G * ((slots + 3) & ~3) : (size_t)2 * slots) *
                        sizeof(float);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    static std::once_flag once;                            // dynamic LDS above 64 KB (large budgets) needs the attribute
-    hipError_t attr_err = hipSuccess;
-    std::call_once(once, [&]() {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<4>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<8>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<MAX_GROUP>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    });
+    const hipError_t attr_err = decode_setup();            // dynamic LDS above 64 KB (large budgets) needs the attribute
     if (attr_err != hipSuccess) return attr_err;
     if (G <= 4) hipLaunchKernelGGL(decode_unit_kernel<4>, dim3(units), dim3(64), lds, s, st, a);
     else if (G <= 8) hipLaunchKernelGGL(decode_unit_kernel<8>, dim3(units), dim3(64), lds, s, st, a);

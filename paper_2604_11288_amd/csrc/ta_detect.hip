@@ -21,7 +21,6 @@
 // compares it with the threshold.
 #include <math.h>
 
-#include <mutex>
 
 #include "ta_internal.h"
 #include "ta_score_common.h"
@@ -325,11 +324,10 @@ hipError_t launch_one(const DetectArgs& a, hipStream_t st)
     constexpr int M = 32 * HT * MH;
     constexpr int DT_TOKENS = 64 * TW;
     const size_t lds = (size_t)DT_RING * (DT_TOKENS * 64 + M * 64) + (size_t)M * 4 + (size_t)(MH + 1) * DT_TOKENS * 4;
-    static std::once_flag once;                            // dynamic LDS above 64 KB needs the attribute once
-    hipError_t attr_err = hipSuccess;
-    std::call_once(once, [&]() {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&detect_kernel<TW, HT, MH, MODE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static DeviceOnce setup;                               // dynamic LDS above 64 KB needs the attribute (per instantiation)
+    const hipError_t attr_err = setup.run([&](int) {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&detect_kernel<TW, HT, MH, MODE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     if (attr_err != hipSuccess) return attr_err;
     const unsigned blocks = (unsigned)((a.total + DT_TOKENS - 1) / DT_TOKENS);

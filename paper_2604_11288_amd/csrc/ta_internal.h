@@ -4,9 +4,41 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/ta.h"
 
 namespace ta {
+
+// Set-up that has to happen once per device before a kernel's first launch there (kernel
+// attributes, symbol addresses).  `run` calls `f` with that device current until it has
+// succeeded once on it: a failure is returned to the caller and tried again by the next call,
+// so nothing is ever launched without its set-up.
+class DeviceOnce {
+public:
+    template <typename F>
+    hipError_t run(F&& f)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> guard(mu_);
+        if ((done_ >> dev) & 1ull) return hipSuccess;
+        e = f(dev);
+        if (e == hipSuccess) done_ |= 1ull << dev;
+        return e;
+    }
+
+private:
+    std::mutex mu_;
+    uint64_t done_ = 0;
+};
+
+// Kernel attributes of the select and decode kernels (dynamic LDS above 64 KB) for the current
+// device; called by their launchers and by ta_init.
+hipError_t select_setup();
+hipError_t decode_setup();
 
 // ---- match + voucher expansion -------------------------------------------
 struct MatchTable {

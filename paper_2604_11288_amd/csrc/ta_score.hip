@@ -610,12 +610,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs& a, uint4 (*s_k)[STAG
 }
 
 template <int RG, int RT, bool COLSUM>
-void launch_sweep(const ScoreArgs& a, unsigned blocks, const MatchRider* rider, hipStream_t st)
+hipError_t launch_sweep(const ScoreArgs& a, unsigned blocks, const MatchRider* rider, hipStream_t st)
 {
     if (rider && a.table) {
         // paged keys: the match runs as a launch of its own in front of the sweep
-        (void)launch_match(rider->tok, a.seq_len, a.batch, a.n, *rider->tab, rider->anchor_B, rider->allow, rider->anchor,
-                     rider->spons, rider->vouch, st);
+        const hipError_t e = launch_match(rider->tok, a.seq_len, a.batch, a.n, *rider->tab, rider->anchor_B, rider->allow,
+                                          rider->anchor, rider->spons, rider->vouch, st);
+        if (e != hipSuccess) return e;
         rider = nullptr;
     }
     if (rider) {
@@ -631,22 +632,22 @@ void launch_sweep(const ScoreArgs& a, unsigned blocks, const MatchRider* rider, 
     } else {
         hipLaunchKernelGGL((score_kernel<RG, RT, COLSUM, false>), dim3(blocks), dim3(128 * RG), 0, st, a);
     }
+    return hipGetLastError();
 }
 
 template <int RG, int RT>
-void launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t st)
+hipError_t launch_rg(ScoreArgs a, int64_t units, const MatchRider* rider, hipStream_t st)
 {
     // One launch per sweep over all units.  (Splitting the units into cache-sized groups
     // so that sweep 2 re-reads its keys from the last-level cache was measured slower.)
     a.units = (int32_t)units;
     a.units_per_xcd = (int32_t)((units + 7) / 8);
     const unsigned blocks = (unsigned)(8ll * a.units_per_xcd * a.nchunks);
-    if (a.lse) {                                           // the row normalisers are given: column sums alone
-        launch_sweep<RG, RT, true>(a, blocks, rider, st);
-        return;
-    }
-    launch_sweep<RG, RT, false>(a, blocks, rider, st);
-    launch_sweep<RG, RT, true>(a, blocks, nullptr, st);
+    if (a.lse)                                             // the row normalisers are given: column sums alone
+        return launch_sweep<RG, RT, true>(a, blocks, rider, st);
+    const hipError_t e = launch_sweep<RG, RT, false>(a, blocks, rider, st);
+    if (e != hipSuccess) return e;
+    return launch_sweep<RG, RT, true>(a, blocks, nullptr, st);
 }
 
 }  // namespace
@@ -766,12 +767,11 @@ hipError_t launch_score(const void* Q, const void* K, const ta_layout& lay, cons
     switch (a.rows_pad) {
         // two 32-row tiles per wavefront (one tile per wavefront with twice the wavefronts - four
         // per SIMD instead of two - was measured: same time at 128 rows, 5 % slower at 256)
-        case 128: launch_rg<2, 2>(a, p.units, rider, st); break;
-        case 256: launch_rg<4, 2>(a, p.units, rider, st); break;
-        default: launch_rg<4, 2>(a, p.units, rider, st); break;   // 512 rows: two passes of 256 (eight row groups
+        case 128: return launch_rg<2, 2>(a, p.units, rider, st);
+        case 256: return launch_rg<4, 2>(a, p.units, rider, st);
+        default: return launch_rg<4, 2>(a, p.units, rider, st);   // 512 rows: two passes of 256 (eight row groups
                                                                   // at once leave 128 registers per lane: spills, 3x slower)
     }
-    return hipGetLastError();
 }
 
 }  // namespace ta

@@ -22,8 +22,6 @@
 //                takes the k_protected best sponsored tokens, everything else that is not
 //                mandatory competes for the main pool by (u, position) alone - two threshold
 //                searches instead of one
-#include <mutex>
-
 #include "ta_internal.h"
 
 namespace ta {
@@ -477,9 +475,23 @@ select_kernel(SelectArgs a)
     if (tid == 0) a.cnt[unit] = base < K ? base : K;
 }
 
-std::once_flag g_attr_once;
+DeviceOnce g_setup;
 
 }  // namespace
+
+hipError_t select_setup()
+{
+    return g_setup.run([](int) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
+        return e;
+    });
+}
 
 hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* spons,
                          const float* vouch, const int32_t* seq_len,
@@ -514,16 +526,7 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
     const unsigned blocks = 8u * (unsigned)a.units_per_xcd;
     const bool capped = prm.k_protected >= 0;
     if (n <= SEL_CACHE_MAX_N) {
-        hipError_t attr_err = hipSuccess;
-        std::call_once(g_attr_once, [&]() {
-            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
-            if (attr_err == hipSuccess)
-                attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
-        });
+        const hipError_t attr_err = select_setup();
         if (attr_err != hipSuccess) return attr_err;
         const size_t lds = (size_t)((n + 3) / 4 * 4) * sizeof(uint32_t);
         if (capped) hipLaunchKernelGGL((select_kernel<true, true>), dim3(blocks), dim3(SEL_THREADS), lds, st, a);

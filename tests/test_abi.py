@@ -223,7 +223,7 @@ def test_evict_layers_checks_every_table_entry(L):
 
 
 def _decode_state(**kw):
-    st = tb.CDecodeState(2, 3, 32, 8, 128, 256, 5000, *([0x7f0000001000] * 10))
+    st = tb.CDecodeState(2, 3, 32, 8, 128, 256, 5000, *([0x7f0000001000] * 11))
     for k, v in kw.items():
         setattr(st, k, v)
     return st
@@ -240,6 +240,7 @@ def test_decode_error_paths(L):
     assert L.ta_decode_init(*init(_decode_state(d=64))) == tb.TA_ERR_SHAPE
     assert L.ta_decode_init(*init(_decode_state(hq=30))) == tb.TA_ERR_SHAPE
     assert L.ta_decode_init(*init(_decode_state(pos=None))) == tb.TA_ERR_NULL
+    assert L.ta_decode_init(*init(_decode_state(stepped=None))) == tb.TA_ERR_NULL
     assert L.ta_decode_init(*init(n=6000)) == tb.TA_ERR_SHAPE                       # prefill longer than cap
     assert L.ta_decode_init(*init(_decode_state(Kc=0x7f0000001008))) == tb.TA_ERR_ALIGN
     a = init(); a[1] = None
@@ -338,7 +339,7 @@ def test_lse_and_paged_error_paths(L):
 def test_decode_rejects_one_shot_options(L):
     st = tb.CDecodeState()
     st.layers, st.batch, st.hq, st.hkv, st.d, st.K, st.cap = 1, 1, 8, 2, 128, 16, 64
-    for name in ("tok", "len", "anchor", "budget", "vouch", "spons", "Kc", "Vc", "pos", "A"):
+    for name in ("tok", "len", "anchor", "budget", "vouch", "spons", "Kc", "Vc", "pos", "A", "stepped"):
         setattr(st, name, FAKE.value)
     ids, lens = _table()
     call = lambda prm: L.ta_decode_step(ctypes.byref(st), FAKE, FAKE, FAKE, FAKE, ids.ctypes.data, lens.ctypes.data, 2,

@@ -22,7 +22,14 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def _run_decode(w, K, steps, p_anchor=0.05, check_every=1):
+def _same_bits(x, y):
+    as_int = {torch.float32: torch.int32, torch.bfloat16: torch.int16}
+    if x.dtype in as_int:
+        x, y = x.contiguous().view(as_int[x.dtype]), y.contiguous().view(as_int[y.dtype])
+    return torch.equal(x, y)
+
+
+def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None):
     td = wl.make_tokens(w, clean=False)
     lyr, B, G = w.layers, w.batch, w.hq // w.hkv
     scored = w.alpha != 0.0
@@ -35,7 +42,7 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1):
     A = ta.ta_score(Q, Kc, prm, seq_len=seq_len) if scored else None
     idx, cnt = ta.ta_select(A, anchor, spons, vouch, K, prm, lyr, w.hkv, seq_len=seq_len)
     Ko, Vo = ta.ta_compact(Kc, Vc, idx, cnt, K)
-    cap = w.n + steps + 4
+    cap = w.n + steps + 4 if cap is None else cap        # a smaller cap: sequences reach capacity and are left alone
     st = ta.DecodeState(lyr, B, w.hq, w.hkv, K, cap, DEV)
     ta.ta_decode_init(st, tok, anchor, idx, cnt, Ko, Vo, prm, seq_len=seq_len, A=A)
     torch.cuda.synchronize()
@@ -64,14 +71,27 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1):
     stream = wl.make_decode_stream(w, td, steps, p_anchor=p_anchor, clean=False)
     evicted = torch.zeros((lyr, B, w.hkv), dtype=torch.int32, device=DEV)
     n_evictions = 0
+    at_capacity_steps = 0
     for t in range(steps):
         q, kn, vn = wl.make_decode_qkv(w, t, device=DEV)
+        full = [b for b in range(B) if seqs[b].len >= cap]
+        before = {b: [x[:, b].clone() for x in (st.A, st.pos, st.Kc, st.Vc)] +
+                     [x[b].clone() for x in (st.tok, st.anchor, st.budget, st.len)] for b in full}
         ta.ta_decode_step(st, _dev(stream[t]), q if scored else None, kn, vn, td.tab_ids, td.tab_len, prm,
                           evicted=evicted)
         torch.cuda.synchronize()
         gA, gpos, gev = st.A.cpu().numpy(), st.pos.cpu().numpy(), evicted.cpu().numpy()
         qb, kb, vb = wl.bf16_bits(q), wl.bf16_bits(kn), wl.bf16_bits(vn)
         for b in range(B):
+            if b in before:
+                # a sequence at capacity is left unchanged, bit for bit: nothing appended, no attention
+                # added, nothing evicted, no budget decay (the oracle's state of it simply does not step)
+                after = [x[:, b] for x in (st.A, st.pos, st.Kc, st.Vc)] + [x[b] for x in (st.tok, st.anchor, st.budget, st.len)]
+                for x0, x1 in zip(before[b], after):
+                    assert _same_bits(x0, x1), (t, b)
+                assert (gev[:, b] == -1).all(), (t, b)
+                at_capacity_steps += 1
+                continue
             p = seqs[b].append(int(stream[t, b]))
             for l in range(lyr):
                 for g in range(w.hkv):
@@ -105,6 +125,8 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1):
         occ = u.pos >= 0
         assert np.array_equal(gK[l, b, g][occ], u.Kc[occ]) and np.array_equal(gV[l, b, g][occ], u.Vc[occ])
     anchors_in_decode = sum(int(seqs[b].anchor[int(td.seq_len[b]):seqs[b].len].sum()) for b in range(B))
+    if cap is not None and cap < w.n + steps:
+        return n_evictions, anchors_in_decode, at_capacity_steps
     return n_evictions, anchors_in_decode
 
 
@@ -154,3 +176,17 @@ def test_decode_sixteen_heads_per_group():
     w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=2, n=600, hq=32, hkv=2, ragged=(300, 600))
     ev, _ = _run_decode(w, K=100, steps=6, p_anchor=0.2, check_every=2)
     assert ev == 6 * w.layers * w.batch * w.hkv               # every unit is full: one eviction per unit and step
+
+
+def test_decode_sequence_at_capacity_is_left_unchanged():
+    # cap equals the padded prefill length: the longest sequence is at capacity from the first step on,
+    # a shorter one reaches it after a few steps; the others keep stepping and must still match the oracle
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=4, n=640, hq=8, hkv=2, ragged=(560, 640))
+    td = wl.make_tokens(w, clean=False)
+    lens = sorted(int(x) for x in td.seq_len)
+    steps = 24
+    cap = w.n
+    ev, _, idle = _run_decode(w, K=64, steps=steps, p_anchor=0.1, cap=cap)
+    want_idle = sum(max(0, steps - (cap - l)) for l in lens)
+    assert idle == want_idle and idle > 0
+    assert ev == (steps * w.batch - idle) * w.layers * w.hkv

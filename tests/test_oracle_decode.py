@@ -147,3 +147,19 @@ def test_decode_needle_survives_with_zero_attention():
         if span is not None and t >= 3 + L and t < 3 + L + 40:
             assert span <= set(unit.pos[unit.pos >= 0].tolist()), t
     assert seq.anchor[n + 2] == 1
+
+
+def test_sequence_at_capacity_does_not_step():
+    """The boundary leaves a sequence at capacity unchanged; the oracle's sequence state refuses the
+    append (its arrays end at cap), and a caller that skips the step changes nothing."""
+    tab = np.array([[7, 8, -1, -1]], np.int32)
+    ln = np.array([2], np.int32)
+    seq = ora.DecodeSeq(np.array([1, 7, 8, 2, 3], np.int32), tab, ln, cap=6, B=15.0)
+    seq.append(7)
+    assert seq.len == seq.cap
+    tok, anc, bud = seq.tok.copy(), seq.anchor.copy(), seq.budget.copy()
+    with pytest.raises(AssertionError):
+        seq.append(8)
+    assert seq.len == seq.cap
+    assert np.array_equal(seq.tok, tok) and np.array_equal(seq.anchor, anc)
+    assert np.array_equal(seq.budget.view(np.uint32), bud.view(np.uint32))
