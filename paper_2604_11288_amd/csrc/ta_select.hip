@@ -475,6 +475,398 @@ select_kernel(SelectArgs a)
     if (tid == 0) a.cnt[unit] = base < K ? base : K;
 }
 
+
+// ---- streaming form: every input is read once, whatever the length ----------------------------
+// One workgroup of four wavefronts per unit walks the sequence from its end in segments and keeps
+// the best candidates of the boundary class seen so far in LDS as (key, position) pairs.  A
+// position joins the list if it beats the current threshold - the R-th largest (key, position) at
+// the last shrink, nothing before the first - and the list is cut back to its R best whenever the
+// next segment might not fit (an MSD radix select over the LDS list, the same search as above).
+// Walking from the end meets the recent positions first, whose recency term is largest: with a
+// non-negative beta the threshold is high after the first shrink and few later positions pass it.
+// The order of the walk and of the list only affect the time, never the result: the retained set
+// is defined by the total order, and the output is written in ascending position order from a
+// bitmap of the sequence (bits of the mandatory positions, of the sponsored ones when they are
+// all kept, and of the final R candidates).
+constexpr int SS_THREADS = 256;
+constexpr int SS_WAVES = SS_THREADS / 64;
+#ifndef TA_SELECT_STREAM_QPT
+#define TA_SELECT_STREAM_QPT 1
+#endif
+#ifndef TA_SELECT_STREAM_SLACK
+#define TA_SELECT_STREAM_SLACK 256
+#endif
+constexpr int SS_QPT = TA_SELECT_STREAM_QPT;               // quads per thread and segment
+constexpr int SS_SLACK = TA_SELECT_STREAM_SLACK;           // list entries beyond R + one segment: new entries between two cuts
+constexpr int SS_SEG_QUADS = SS_THREADS * SS_QPT;
+constexpr int SS_SEG = SS_SEG_QUADS * 4;                   // positions per segment
+constexpr int SS_HIST_COPIES = 4;
+constexpr int SS_MAX_PER_THREAD = 24;                      // list entries a thread holds while the list is compacted
+constexpr int SS_MAX_CAP = SS_THREADS * SS_MAX_PER_THREAD;
+constexpr int SS_MAX_LDS = 144 * 1024;                     // dynamic LDS of a workgroup (list + bitmap)
+// Which form runs: the streaming form whenever the keys of a row do not fit the LDS cache of the
+// kernel above, and for shorter rows when there are enough units to fill the chip several times
+// (its workgroups are small and many fit a compute unit; measured on 16 384 ragged units of up to
+// 16 384 positions: 560 us against 1270).  With few units the latency of one workgroup counts, and
+// the cached kernel's is half as long (13 us against 25 for 256 units of 4096 positions).
+#ifndef TA_SELECT_STREAM_MIN_UNITS
+#define TA_SELECT_STREAM_MIN_UNITS 2048
+#endif
+constexpr int64_t SS_MIN_UNITS = TA_SELECT_STREAM_MIN_UNITS;
+
+struct StreamLds {
+    uint32_t hist[SS_HIST_COPIES][HIST_STRIDE];
+    uint32_t h[256];
+    int red[SS_WAVES];
+    RadixState state;
+    uint32_t count;                                        // entries in the candidate list
+};
+
+// The same search as radix_pick, for a workgroup of SS_THREADS threads and SS_HIST_COPIES histograms.
+__device__ __forceinline__ RadixState stream_pick(StreamLds& L, uint32_t need)
+{
+    const int tid = threadIdx.x;
+    {
+        uint32_t t = 0;
+#pragma unroll
+        for (int c = 0; c < SS_HIST_COPIES; ++c) {
+            t += L.hist[c][tid];
+            L.hist[c][tid] = 0;
+        }
+        L.h[tid] = t;
+    }
+    __syncthreads();
+    if (tid < 64) {
+        const uint32_t h0 = L.h[255 - 4 * tid], h1 = L.h[254 - 4 * tid];
+        const uint32_t h2 = L.h[253 - 4 * tid], h3 = L.h[252 - 4 * tid];
+        const uint32_t mine = h0 + h1 + h2 + h3;
+        uint32_t incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o);
+            if (tid >= o) incl += up;
+        }
+        const unsigned long long m = __ballot(incl >= need);
+        const int first = __ffsll((long long)m) - 1;
+        if (tid == first) {
+            uint32_t above = incl - mine;
+            const uint32_t hs[4] = {h0, h1, h2, h3};
+            RadixState r;
+            r.digit = 0; r.need = 0; r.bin_count = 0; r.all_of_bin = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (above + hs[j] >= need) {
+                    r.digit = (uint32_t)(255 - 4 * tid - j);
+                    r.need = need - above;
+                    r.bin_count = hs[j];
+                    r.all_of_bin = (above + hs[j] == need) ? 1u : 0u;
+                    break;
+                }
+                above += hs[j];
+            }
+            L.state = r;
+        }
+    }
+    __syncthreads();
+    return L.state;
+}
+
+__global__ void __launch_bounds__(SS_THREADS)
+select_stream_kernel(SelectArgs a, int32_t cap)
+{
+    extern __shared__ uint32_t s_dyn[];                    // [cap] keys, [cap] positions, [ceil(n / 32)] bitmap
+    __shared__ StreamLds L;
+    uint32_t* ckey = s_dyn;
+    uint32_t* cpos = s_dyn + cap;
+    uint32_t* bitmap = s_dyn + 2 * cap;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int32_t unit = (int32_t)(blockIdx.x & 7u) * a.units_per_xcd + (int32_t)(blockIdx.x >> 3);
+    if (unit >= a.units) return;
+    const int32_t b = (unit / a.hkv) % a.batch;
+    const int32_t n = a.n;
+    int32_t K = a.K;
+    if (a.layer_K) {
+        int32_t lo = a.n_sink + a.n_recent;
+        lo = lo < 1 ? 1 : lo;
+        const int32_t kl = a.layer_K[unit / (a.batch * a.hkv)];
+        K = kl < lo ? lo : (kl > K ? K : kl);
+    }
+    int32_t nb = a.seq_len ? a.seq_len[b] : n;
+    nb = nb < 0 ? 0 : (nb > n ? n : nb);
+    int32_t* idx = a.idx + (size_t)unit * (size_t)a.K;
+    if (nb <= K) {                                         // nothing to evict
+        for (int32_t p = tid; p < nb; p += SS_THREADS) idx[p] = p;
+        if (tid == 0) a.cnt[unit] = nb;
+        return;
+    }
+
+    const float* A = a.A ? a.A + (size_t)unit * (size_t)n : nullptr;
+    const size_t row = (size_t)b * (size_t)n;
+    const uint8_t* anchor = a.anchor + row;
+    const uint8_t* spons = a.spons + row;
+    const float* vouch = a.vouch + row;
+    const int32_t ns = a.n_sink < nb ? a.n_sink : nb;
+    int32_t rs = nb - a.n_recent;
+    rs = rs < ns ? ns : rs;
+    const int32_t c2 = ns + (nb - rs);
+    const int32_t nquads = (nb + 3) >> 2;                  // rows are padded to whole quads (n % 4 == 0)
+    const bool use_A = (a.alpha != 0.0f);
+    const int32_t words = (nb + 31) >> 5;
+
+    for (int i = tid; i < SS_HIST_COPIES * HIST_STRIDE; i += SS_THREADS) (&L.hist[0][0])[i] = 0;
+    for (int32_t i = tid; i < words; i += SS_THREADS) bitmap[i] = 0u;
+    if (tid == 0) L.count = 0u;
+
+    // ---- sponsored positions outside the mandatory ranges (16 flags per load) -------------------
+    int local = 0;
+    {
+        const int32_t n16 = ((uintptr_t)spons & 15u) == 0 ? nb >> 4 : 0;     // (a row that is not 16-byte aligned: byte by byte)
+        const uint4* sp16 = reinterpret_cast<const uint4*>(spons);
+        for (int32_t i = tid; i < n16; i += SS_THREADS) {
+            const uint4 f = sp16[i];
+            const uint32_t w4[4] = {f.x, f.y, f.z, f.w};
+            const int32_t p0 = 16 * i;
+            if (p0 >= ns && p0 + 15 < rs) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    // a flag byte is 0 or not: count the non-zero bytes of the word
+                    const uint32_t x = w4[j];
+                    const uint32_t nz = ((x | (x >> 1) | (x >> 2) | (x >> 3) | (x >> 4) | (x >> 5) | (x >> 6) | (x >> 7)) & 0x01010101u);
+                    local += __popc(nz);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int32_t p = p0 + j;
+                    const uint32_t byte = (w4[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+                    local += (p >= ns && p < rs && byte) ? 1 : 0;
+                }
+            }
+        }
+        for (int32_t p = 16 * n16 + tid; p < nb; p += SS_THREADS) local += (p >= ns && p < rs && spons[p]) ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) local += __shfl_xor(local, o);
+    if (lane == 0) L.red[wave] = local;
+    __syncthreads();                                       // also: histograms, bitmap and count are cleared
+    int32_t c1 = 0;
+#pragma unroll
+    for (int w = 0; w < SS_WAVES; ++w) c1 += L.red[w];
+
+    const int bclass = (c2 + c1 <= K) ? 0 : 1;
+    const int32_t R = bclass == 0 ? K - c2 - c1 : K - c2;  // slots of the boundary class (more members than that exist)
+    const float nf = (float)nb;
+
+    auto key_of = [&](int32_t p, float Ap, uint32_t an, float v) -> uint32_t {
+        float r = __fdiv_rn((float)(p + 1), nf);
+        float t = use_A ? __fmul_rn(a.alpha, Ap) : 0.0f;
+        t = __fadd_rn(t, __fmul_rn(a.beta, r));
+        t = __fadd_rn(t, __fmul_rn(a.gamma, an ? 1.0f : 0.0f));
+        t = __fadd_rn(t, v);
+        const uint32_t k = ordered_bits(t);
+        return k == 0u ? 1u : k;
+    };
+
+    struct Loaded {
+        float4 A, v;
+        uint32_t sp, an;
+    };
+    const auto load_quad = [&](int32_t q, Loaded& x) {
+        if (q >= 0 && q < nquads) {
+            x.sp = *reinterpret_cast<const uint32_t*>(spons + 4 * q);
+            x.an = *reinterpret_cast<const uint32_t*>(anchor + 4 * q);
+            x.v = *reinterpret_cast<const float4*>(vouch + 4 * q);
+            x.A = use_A ? *reinterpret_cast<const float4*>(A + 4 * q) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        } else {
+            x.sp = x.an = 0u;
+            x.v = x.A = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+    };
+
+    // ---- the list is cut back to its R best entries; returns their threshold -----------------------
+    uint32_t T = 0u;              // a position joins the list iff key > T, or key == T and p >= Pt
+    int32_t Pt = 0x7FFFFFFF;
+    const auto shrink = [&](const uint32_t m) {            // m: entries in the list (the same value in every thread)
+        uint32_t prefix = 0, need = (uint32_t)R;
+        uint32_t Tn = 0u;
+        int32_t Pn = 0x7FFFFFFF;
+        bool done = false;
+        for (int pass = 0; pass < 4 && !done; ++pass) {
+            const int shift = 24 - 8 * pass;
+            for (uint32_t e = tid; e < m; e += SS_THREADS) {
+                const uint32_t k = ckey[e];
+                const bool in = pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8));
+                if (in) atomicAdd(&L.hist[lane & (SS_HIST_COPIES - 1)][(k >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            const RadixState r = stream_pick(L, need);
+            prefix |= r.digit << shift;
+            need = r.need;
+            if (r.all_of_bin) {
+                Tn = prefix - 1u;
+                Pn = 0x7FFFFFFF;
+                done = true;
+            } else if (pass == 3) {
+                Tn = prefix;
+                const int bits = 32 - __clz(nb - 1);
+                const int ppasses = (bits + 7) / 8;
+                uint32_t pprefix = 0, pneed = need;
+                for (int pp = 0; pp < ppasses; ++pp) {
+                    const int ps = 8 * (ppasses - 1 - pp);
+                    for (uint32_t e = tid; e < m; e += SS_THREADS) {
+                        const uint32_t p = cpos[e];
+                        const bool in = ckey[e] == Tn && (pp == 0 || (p >> (ps + 8)) == (pprefix >> (ps + 8)));
+                        if (in) atomicAdd(&L.hist[lane & (SS_HIST_COPIES - 1)][(p >> ps) & 255u], 1u);
+                    }
+                    __syncthreads();
+                    const RadixState qs = stream_pick(L, pneed);
+                    pprefix |= qs.digit << ps;
+                    pneed = qs.need;
+                }
+                Pn = (int32_t)pprefix;
+                done = true;
+            }
+        }
+        // compaction in place: every thread takes its entries into registers, then the kept ones
+        // are appended from slot 0 (exactly R of them; their order in the list does not matter)
+        uint32_t mk[SS_MAX_PER_THREAD], mp[SS_MAX_PER_THREAD];
+#pragma unroll
+        for (int j = 0; j < SS_MAX_PER_THREAD; ++j) {
+            const uint32_t e = (uint32_t)tid + (uint32_t)j * SS_THREADS;
+            mk[j] = e < m ? ckey[e] : 0u;
+            mp[j] = e < m ? cpos[e] : 0u;
+        }
+        if (tid == 0) L.count = 0u;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < SS_MAX_PER_THREAD; ++j) {
+            if ((uint32_t)j * SS_THREADS >= m) break;      // uniform
+            const bool keep = mk[j] > Tn || (mk[j] == Tn && mk[j] != 0u && (int32_t)mp[j] >= Pn);
+            const unsigned long long bal = __ballot(keep);
+            uint32_t base = 0;
+            if (lane == 0 && bal) base = atomicAdd(&L.count, (uint32_t)__popcll(bal));
+            base = __shfl(base, 0);
+            if (keep) {
+                const uint32_t slot = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+                if (slot < (uint32_t)cap) {
+                    ckey[slot] = mk[j];
+                    cpos[slot] = mp[j];
+                }
+            }
+        }
+        __syncthreads();
+        T = Tn;
+        Pt = Pn;
+    };
+
+    // ---- the walk, from the last segment to the first; the next segment's operands are requested
+    // before the current one is worked on
+    const int32_t nseg = (nquads + SS_SEG_QUADS - 1) / SS_SEG_QUADS;
+    Loaded cur[SS_QPT], nxt[SS_QPT];
+#pragma unroll
+    for (int j = 0; j < SS_QPT; ++j) load_quad((nseg - 1) * SS_SEG_QUADS + j * SS_THREADS + tid, cur[j]);
+    for (int32_t sg = nseg - 1; sg >= 0; --sg) {
+        if (sg > 0) {
+#pragma unroll
+            for (int j = 0; j < SS_QPT; ++j) load_quad((sg - 1) * SS_SEG_QUADS + j * SS_THREADS + tid, nxt[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < SS_QPT; ++j) {
+            const int32_t q = sg * SS_SEG_QUADS + j * SS_THREADS + tid;
+            const float Aq[4] = {cur[j].A.x, cur[j].A.y, cur[j].A.z, cur[j].A.w};
+            const float vq[4] = {cur[j].v.x, cur[j].v.y, cur[j].v.z, cur[j].v.w};
+            uint32_t keys[4];
+            bool join[4];
+            uint32_t always = 0u;                          // bits of this quad that are retained whatever the ranking says
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int32_t p = 4 * q + c;
+                const uint32_t sp = (cur[j].sp >> (8 * c)) & 0xFFu, an = (cur[j].an >> (8 * c)) & 0xFFu;
+                keys[c] = 0u;
+                join[c] = false;
+                if (p < nb && q < nquads) {
+                    if (p < ns || p >= rs) always |= 1u << c;
+                    else if ((sp != 0u) != (bclass == 1)) always |= (sp != 0u) ? (1u << c) : 0u;   // class 1 above the boundary class, class 0 below it
+                    else if (R > 0) {
+                        keys[c] = key_of(p, Aq[c], an, vq[c]);
+                        join[c] = keys[c] > T || (keys[c] == T && p >= Pt);
+                    }
+                }
+            }
+            if (always) atomicOr(&bitmap[(4 * q) >> 5], always << ((4 * q) & 31));
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const unsigned long long bal = __ballot(join[c]);
+                if (bal) {                                 // uniform
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&L.count, (uint32_t)__popcll(bal));
+                    base = __shfl(base, 0);
+                    if (join[c]) {
+                        const uint32_t slot = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+                        if (slot < (uint32_t)cap) {        // holds by construction: the list is cut back before it could overflow
+                            ckey[slot] = keys[c];
+                            cpos[slot] = (uint32_t)(4 * q + c);
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();                                   // the segment's entries are in the list
+        const uint32_t m = L.count;
+        __syncthreads();                                   // every thread has read the count before anyone adds to it again
+        // Cut back when the next segment might not fit, at the end (to exactly R), and once early: the
+        // first cut gives the threshold that keeps most later positions out of the list.
+        const bool early = T == 0u && m >= 2u * (uint32_t)R && m >= 512u;
+        if (R > 0 && ((sg > 0 && (m + (uint32_t)SS_SEG > (uint32_t)cap || early)) || (sg == 0 && m > (uint32_t)R))) shrink(m);
+        if (sg > 0) {
+#pragma unroll
+            for (int j = 0; j < SS_QPT; ++j) cur[j] = nxt[j];
+        }
+    }
+
+    // ---- the final candidates join the bitmap; ascending write-out from it --------------------------
+    {
+        const uint32_t m = L.count;                        // == R (or 0)
+        for (uint32_t e = tid; e < m; e += SS_THREADS) {
+            const uint32_t p = cpos[e];
+            atomicOr(&bitmap[p >> 5], 1u << (p & 31u));
+        }
+    }
+    __syncthreads();
+    const int32_t wpt = (words + SS_THREADS - 1) / SS_THREADS;            // consecutive words per thread
+    const int32_t w0 = tid * wpt;
+    int mine = 0;
+    for (int32_t w = w0; w < w0 + wpt && w < words; ++w) mine += __popc(bitmap[w]);
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) L.red[wave] = incl;
+    __syncthreads();
+    int woff = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < SS_WAVES; ++w) {
+        const int c = L.red[w];
+        woff += (w < wave) ? c : 0;
+        total += c;
+    }
+    int32_t slot = woff + incl - mine;
+    for (int32_t w = w0; w < w0 + wpt && w < words; ++w) {
+        uint32_t bits = bitmap[w];
+        while (bits) {
+            const int bit = __ffs((int)bits) - 1;
+            bits &= bits - 1u;
+            if (slot < K) idx[slot] = 32 * w + bit;
+            ++slot;
+        }
+    }
+    if (tid == 0) a.cnt[unit] = total < K ? total : K;
+}
+
 DeviceOnce g_setup;
 
 }  // namespace
@@ -489,6 +881,9 @@ hipError_t select_setup()
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
         return e;
     });
 }
@@ -525,6 +920,20 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
                ((uintptr_t)vouch % 16 == 0) && (a.A == nullptr || (uintptr_t)a.A % 16 == 0);
     const unsigned blocks = 8u * (unsigned)a.units_per_xcd;
     const bool capped = prm.k_protected >= 0;
+    // The streaming form serves the plain (elastic, unpooled) selection on quad-aligned rows when
+    // its candidate list and the bitmap of the sequence fit the LDS of a workgroup.
+    if (!capped && a.pool_r == 0 && a.vec_ok && (n > SEL_CACHE_MAX_N || units >= SS_MIN_UNITS)) {
+        const int64_t rmax = (int64_t)K - prm.n_sink - prm.n_recent;      // most slots the boundary class can have
+        int64_t cap = rmax + SS_SEG + SS_SLACK;
+        cap = (cap + SS_THREADS - 1) / SS_THREADS * SS_THREADS;
+        const int64_t lds = cap * 8 + ((int64_t)n + 31) / 32 * 4;
+        if (cap <= SS_MAX_CAP && lds <= SS_MAX_LDS) {
+            const hipError_t attr_err = select_setup();
+            if (attr_err != hipSuccess) return attr_err;
+            hipLaunchKernelGGL(select_stream_kernel, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
+            return hipGetLastError();
+        }
+    }
     if (n <= SEL_CACHE_MAX_N) {
         const hipError_t attr_err = select_setup();
         if (attr_err != hipSuccess) return attr_err;

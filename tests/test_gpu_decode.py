@@ -29,7 +29,12 @@ def _same_bits(x, y):
     return torch.equal(x, y)
 
 
-def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None):
+def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu", stats=None):
+    """rank="gpu": the oracle ranks the slots with the GPU's fp32 cumulative attention (the decision is then
+    exact on both sides).  rank="oracle": the oracle ranks with its own double-accumulated attention; an
+    eviction that differs is excused only if both slots are in the same class and their oracle utilities
+    are within 1e-3 relative of each other - counted in stats["excused"] - and the oracle's cache then
+    follows the GPU's choice so that the run can go on."""
     td = wl.make_tokens(w, clean=False)
     lyr, B, G = w.layers, w.batch, w.hq // w.hkv
     scored = w.alpha != 0.0
@@ -97,14 +102,30 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None):
                 for g in range(w.hkv):
                     u = units[(l, b, g)]
                     pos_before = u.pos.copy()
-                    e, _ = u.step(seqs[b], qb[l, b, g * G:(g + 1) * G], kb[l, b, g], vb[l, b, g], p,
-                                  w.n_sink, w.n_recent, alpha=w.alpha, beta=w.beta, gamma=w.gamma,
-                                  rank_A=gA[l, b, g])
+                    e, util = u.step(seqs[b], qb[l, b, g * G:(g + 1) * G], kb[l, b, g], vb[l, b, g], p,
+                                     w.n_sink, w.n_recent, alpha=w.alpha, beta=w.beta, gamma=w.gamma,
+                                     rank_A=gA[l, b, g] if rank == "gpu" else None)
                     if e >= 0:
                         ev_pos = p if pos_before[e] < 0 else int(pos_before[e])
                         n_evictions += 1
                     else:
                         ev_pos = -1
+                    if rank == "oracle" and e >= 0 and gev[l, b, g] != ev_pos:
+                        # the GPU freed another slot: excused only at a near-tie inside one class
+                        pos_now = u.pos.copy()
+                        pos_now[e] = ev_pos                                    # the cache as it was ranked
+                        (sg,) = np.flatnonzero(pos_now == gev[l, b, g])
+                        cls = []
+                        for pp in (ev_pos, int(gev[l, b, g])):
+                            _, sp = seqs[b].vouch(pp)
+                            cls.append(2 if (pp < w.n_sink or pp >= seqs[b].len - w.n_recent) else (1 if sp else 0))
+                        assert cls[0] == cls[1], (t, l, b, g, cls)
+                        assert abs(util[e] - util[sg]) <= 1e-3 * max(abs(util[e]), abs(util[sg])), (t, l, b, g, util[e], util[sg])
+                        u.pos[e] = ev_pos                                      # follow the GPU's choice
+                        u.pos[sg] = -1
+                        ev_pos = int(gev[l, b, g])
+                        if stats is not None:
+                            stats["excused"] = stats.get("excused", 0) + 1
                     assert gev[l, b, g] == ev_pos, (t, l, b, g)
                     assert np.array_equal(gpos[l, b, g], u.pos), (t, l, b, g)
                     occ = u.pos >= 0
@@ -190,3 +211,26 @@ def test_decode_sequence_at_capacity_is_left_unchanged():
     want_idle = sum(max(0, steps - (cap - l)) for l in lens)
     assert idle == want_idle and idle > 0
     assert ev == (steps * w.batch - idle) * w.layers * w.hkv
+
+
+def test_decode_256_steps_ranked_with_the_oracles_own_attention():
+    """The agentic configuration's 256 generation steps on a scaled shape (1 layer x 4 ragged sequences,
+    32 query / 8 KV heads, K = 256): every eviction is decided by the oracle from its own
+    double-accumulated attention and compared with the GPU's; near-tie differences are counted."""
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=4, n=2400, ragged=(2048, 2400))
+    stats = {}
+    ev, anc = _run_decode(w, K=256, steps=256, p_anchor=0.02, check_every=32, rank="oracle", stats=stats)
+    print("decode, 256 steps x 32 units ranked on the oracle's own A: %d evictions, %d anchors completed during decode, "
+          "%d excused near-tie evictions" % (ev, anc, stats.get("excused", 0)))
+    assert ev == 256 * 4 * 8
+    assert stats.get("excused", 0) <= ev // 100
+
+
+def test_decode_ranked_with_the_oracles_own_attention_near_ties():
+    """Small budget and coarse utilities (no attention weight on recency: beta = 0) make near-ties common;
+    whatever the count, every differing eviction must be an excusable one."""
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=2, n=700, hq=8, hkv=2, ragged=(400, 700), beta=0.0)
+    stats = {}
+    ev, _ = _run_decode(w, K=48, steps=64, p_anchor=0.1, rank="oracle", stats=stats)
+    print("decode near-tie run: %d evictions, %d excused" % (ev, stats.get("excused", 0)))
+    assert ev == 64 * 2 * 2 * 2

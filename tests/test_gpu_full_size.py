@@ -1,11 +1,15 @@
 """Full-size configurations in the launch configuration bench.py times.
 
-The oracle checks sampled units one by one; every other unit is covered by
-properties that hold at any size: softmax rows sum to one (sum of A = G * W per
-unit), |S| = min(K, len), ascending unique indices that contain the sinks, the
-recent window and (when they fit) every sponsored position, and compacted rows
-equal to a library gather on the device.
+The oracle checks every unit of the full-model configuration and, of the larger ones, every unit of
+two whole layers plus a seeded 5 % sample of the rest that touches every layer, sequence and KV
+head, one unit per host thread: scores, selection (with the GPU's scores: exact;
+with the oracle's own: up to counted near-ties) and the compacted rows.  Every other unit is
+covered by properties that hold at any size: softmax rows sum to one (sum of A = G * W per unit),
+|S| = min(K, len), ascending unique indices that contain the sinks, the recent window and (when
+they fit) every sponsored position.
 """
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -27,7 +31,36 @@ def _prm(w):
                      rho=w.rho, alpha=w.alpha, beta=w.beta, gamma=w.gamma)
 
 
-def _check_full(w, K, sample_units, gather_units):
+def _unit_sample(w, seed, full_layers=None, frac=0.05):
+    """Every unit of `full_layers` (default: the first and the last layer) plus a seeded sample of at
+    least `frac` of the other units that touches every layer, every sequence and every KV head."""
+    rng = np.random.default_rng(seed)
+    full_layers = (0, w.layers - 1) if full_layers is None else full_layers
+    units = {(l, b, g) for l in full_layers for b in range(w.batch) for g in range(w.hkv)}
+    rest = w.layers * w.batch * w.hkv - len(units)
+    lp, bp, gp = rng.permutation(w.layers), rng.permutation(w.batch), rng.permutation(w.hkv)
+    units |= {(int(lp[i % w.layers]), int(bp[i % w.batch]), int(gp[i % w.hkv])) for i in range(max(w.layers, w.batch, w.hkv))}
+    want = len(units) + int(np.ceil(frac * rest))
+    while len(units) < want:
+        units.add((int(rng.integers(w.layers)), int(rng.integers(w.batch)), int(rng.integers(w.hkv))))
+    units = sorted(units)
+    assert {u[0] for u in units} == set(range(w.layers)) and {u[1] for u in units} == set(range(w.batch))
+    assert {u[2] for u in units} == set(range(w.hkv))
+    return units
+
+
+def _classes(nb, s, n_sink, n_recent):
+    cls = np.where(s.astype(bool), 1, 0)
+    p = np.arange(nb)
+    cls[(p < n_sink) | (p >= nb - n_recent)] = 2
+    return cls
+
+
+def _check_full(w, K, sample_units, workers=16):
+    """Runs the fused pass at full size; properties over every unit, and every unit of `sample_units`
+    against the oracle: scores within tolerance, the selection exact given the same scores, the
+    oracle's end-to-end selection (its own scores) equal up to excused near-ties, and the compacted
+    rows bit for bit against the oracle's gather.  Returns (plan, td, refs, excused)."""
     td = wl.make_tokens(w)
     Q, Kc, Vc = wl.make_qkv(w, device=DEV)
     prm = _prm(w)
@@ -48,14 +81,13 @@ def _check_full(w, K, sample_units, gather_units):
         assert np.array_equal(plan.spons[b, :nb].cpu().numpy(), s)
         assert np.array_equal(plan.vouch[b, :nb].cpu().numpy().view(np.uint32), v.view(np.uint32))
         assert sorted(np.flatnonzero(a).tolist()) == sorted(td.planted[b])        # clean stream
+    idx_all, cnt_all = plan.idx, plan.cnt
     if scored:
         sums = plan.A.double().sum(-1)                                            # [Lyr][B][Hkv]
         live = torch.clamp(lens, max=w.window).double().view(1, -1, 1)
         assert torch.allclose(sums, G * live.expand_as(sums), rtol=2e-4)
-        idx_all, cnt_all = plan.idx, plan.cnt
         want_cnt = torch.clamp(lens, max=K).view(1, -1, 1).expand_as(cnt_all)
     else:
-        idx_all, cnt_all = plan.idx, plan.cnt
         want_cnt = torch.clamp(lens, max=K)
     assert torch.equal(cnt_all.long(), want_cnt.long())
     if int(td.seq_len.min()) >= K:
@@ -73,60 +105,90 @@ def _check_full(w, K, sample_units, gather_units):
             for r in flat[:: max(1, flat.shape[0] // 16)]:
                 assert bool(torch.isin(want, r).all())
 
-    # ---- compacted rows against a device gather ----------------------------------------------
-    for (l, b, g) in gather_units:
-        sel = (plan.idx[l, b, g] if scored else plan.idx[b])[: int(td.seq_len[b]) if td.seq_len[b] < K else K].long()
-        assert torch.equal(plan.Kout[l, b, g, :len(sel)].view(torch.int16), Kc[l, b, g].index_select(0, sel).view(torch.int16))
-        assert torch.equal(plan.Vout[l, b, g, :len(sel)].view(torch.int16), Vc[l, b, g].index_select(0, sel).view(torch.int16))
-
-    # ---- sampled units against the oracle ---------------------------------------------------------
-    refs = {}
-    for (l, b, g) in sample_units:
+    # ---- sampled units against the oracle (the oracle is single-threaded: one unit per worker) -------
+    def one_unit(job):
+        (l, b, g), Qb, Kb, Vb, A_gpu, idx_gpu, Ko, Vo = job
         nb = int(td.seq_len[b])
         a, s, v = seqs[b]
+        excused, A_ref = 0, None
         if scored:
-            A_gpu = plan.A[l, b, g, :nb].cpu().numpy()
-            A_ref = ora.score(wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]), wl.bf16_bits(Kc[l, b, g, :nb]))
+            A_ref = ora.score(Qb, Kb[:nb])
             assert np.all(np.abs(A_gpu - A_ref) <= 1e-3 * np.abs(A_ref) + 1e-7), (l, b, g)
-            ref = ora.select(A_gpu, a, s, v, K, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
-            got = plan.idx[l, b, g, :len(ref)].cpu().numpy()
+            same = ora.select(A_gpu, a, s, v, K, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
+            assert np.array_equal(idx_gpu[:len(same)], same), (l, b, g)
+            # the oracle end to end: its own scores decide; differences only at ties within 1e-3 of the K-th utility
+            ref = ora.select(A_ref, a, s, v, K, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
+            diff = set(ref.tolist()) ^ set(same.tolist())
+            if diff:
+                u = ora.utility(A_ref, a, v, w.alpha, w.beta, w.gamma)
+                cls = _classes(nb, s, w.n_sink, w.n_recent)
+                bclass = cls[ref].min()
+                kth = u[ref][cls[ref] == bclass].min()
+                for p_ in diff:
+                    assert cls[p_] == bclass and abs(u[p_] - kth) <= 1e-3 * abs(kth), (l, b, g, p_)
+                excused = len(diff) // 2
         else:
-            ref = ora.select(None, a, s, v, K, w.n_sink, w.n_recent, 0.0, w.beta, w.gamma)
-            got = plan.idx[b, :len(ref)].cpu().numpy()
-        assert np.array_equal(got, ref), (l, b, g)
-        assert np.array_equal(wl.bf16_bits(plan.Kout[l, b, g, :len(ref)]), ora.compact(wl.bf16_bits(Kc[l, b, g]), ref))
-        assert np.array_equal(wl.bf16_bits(plan.Vout[l, b, g, :len(ref)]), ora.compact(wl.bf16_bits(Vc[l, b, g]), ref))
-        refs[(l, b, g)] = (A_ref if scored else None, ref, ora.compact(wl.bf16_bits(Kc[l, b, g]), ref),
-                           ora.compact(wl.bf16_bits(Vc[l, b, g]), ref))
-    return plan, td, refs
+            same = ora.select(None, a, s, v, K, w.n_sink, w.n_recent, 0.0, w.beta, w.gamma)
+            assert np.array_equal(idx_gpu[:len(same)], same), (l, b, g)
+        Kref, Vref = ora.compact(Kb, same), ora.compact(Vb, same)
+        assert np.array_equal(Ko[:len(same)], Kref) and np.array_equal(Vo[:len(same)], Vref), (l, b, g)
+        return (l, b, g), (A_ref, same, Kref, Vref), excused
+
+    def jobs():
+        for (l, b, g) in sample_units:
+            nb = int(td.seq_len[b])
+            yield ((l, b, g), wl.bf16_bits(Q[l, b, g * G:(g + 1) * G]) if scored else None,
+                   wl.bf16_bits(Kc[l, b, g]), wl.bf16_bits(Vc[l, b, g]),
+                   plan.A[l, b, g, :nb].cpu().numpy() if scored else None,
+                   (plan.idx[l, b, g] if scored else plan.idx[b]).cpu().numpy(),
+                   wl.bf16_bits(plan.Kout[l, b, g]), wl.bf16_bits(plan.Vout[l, b, g]))
+
+    refs, excused = {}, 0
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        pending = []
+        for job in jobs():                                   # at most 2 * workers units on the host at a time
+            pending.append(pool.submit(one_unit, job))
+            if len(pending) >= 2 * workers:
+                key, ref, ex = pending.pop(0).result()
+                refs[key] = ref
+                excused += ex
+        for f in pending:
+            key, ref, ex = f.result()
+            refs[key] = ref
+            excused += ex
+    print("%s K=%d: %d of %d units against the oracle, %d excused near-tie selections"
+          % (w.name, K, len(sample_units), w.layers * w.batch * w.hkv, excused), flush=True)
+    return plan, td, refs, excused
 
 
 @pytest.mark.parametrize("K", [16, 1024])
 def test_c2_full_model_all_32_layers(K):
     w = wl.CONFIGS["c2_full_model"]
-    units = [(0, 0, 0), (7, 0, 3), (19, 0, 6), (31, 0, 7)]
-    _check_full(w, K, units, [(l, 0, g) for l in range(0, 32, 5) for g in (1, 4)])
+    every = [(l, b, g) for l in range(w.layers) for b in range(w.batch) for g in range(w.hkv)]
+    _check_full(w, K, every)                                 # all 256 units
 
 
 def test_c3_ta_fast_full():
     w = wl.CONFIGS["c3_ta_fast"]
     print("c3: generating 64 GiB of K/V", flush=True)
-    units = [(0, 0, 0), (13, 5, 2), (31, 15, 7)]
-    _check_full(w, 512, units, [(l, b, g) for (l, b, g) in [(1, 1, 1), (9, 7, 3), (22, 12, 5), (30, 3, 0)]])
+    # the retained set is per sequence: every sequence is selected by the oracle; the units of two whole
+    # layers and 5 % of the others (every layer, sequence and head among them) have their rows gathered by it
+    _check_full(w, 512, _unit_sample(w, seed=3))
 
 
 def test_c4_long_context_full():
     w = wl.CONFIGS["c4_long_context"]
     print("c4: generating 64 GiB of K/V", flush=True)
-    _check_full(w, 1024, [(0, 0, 0), (31, 3, 7)], [(5, 1, 2), (17, 2, 6)])
+    _check_full(w, 1024, _unit_sample(w, seed=4))
 
 
 def test_c5_agentic_full_prefill_and_decode_steps():
     w = wl.CONFIGS["c5_agentic_prefill"]
     print("c5: generating 128 GiB of K/V", flush=True)
     K = 256
-    sample = [(0, 0, 0), (15, 31, 4), (31, 63, 7)]
-    plan, td, refs = _check_full(w, K, sample, [(3, 10, 2), (20, 40, 5)])
+    sample = _unit_sample(w, seed=5)
+    plan, td, refs, _ = _check_full(w, K, sample)
+    sample = sample[:: max(1, len(sample) // 96)]          # the generation steps below follow about a hundred of them
     prm = _prm(w)
     steps = 3
     cap = w.n + 16
