@@ -63,7 +63,9 @@ typedef enum ta_status {
     TA_ERR_BUDGET = -3,    /* K < 1 or K < n_sink + n_recent                               */
     TA_ERR_WORKSPACE = -4, /* workspace missing or smaller than ta_workspace_bytes()       */
     TA_ERR_ALIGN = -5,     /* a K/V/Q pointer or stride is not 16-byte aligned             */
-    TA_ERR_HIP = -6        /* a launch failed; see ta_last_hip_error()                     */
+    TA_ERR_HIP = -6,       /* a launch failed; see ta_last_hip_error()                     */
+    TA_ERR_SCRATCH = -7    /* ta_evict_static: the layout needs more scratch than
+                              TA_STATIC_SCRATCH_BYTES                                      */
 } ta_status;
 
 /*
@@ -512,13 +514,39 @@ int32_t ta_decode_step(const ta_decode_state *st, const int32_t *new_tok, const 
                        const ta_params *prm, int32_t *evicted, void *stream);
 
 /*
- * One-time set-up of the library on the CURRENT device: kernel attributes (dynamic LDS sizes).
- * Every entry point performs the part it needs on its first call on a device, so calling
- * ta_init is optional - except before a stream capture or inside code that must not touch the
- * runtime beyond launches: call it once per device beforehand.  Allocates nothing.  Returns
- * TA_OK or TA_ERR_HIP.
+ * One-time set-up of the library on the CURRENT device: kernel attributes (dynamic LDS sizes)
+ * and the device address of the static scratch buffer of ta_evict_static.  Every entry point
+ * performs the part it needs on its first call on a device, so calling ta_init is optional -
+ * except before a stream capture or inside code that must not touch the runtime beyond
+ * launches: call it once per device beforehand.  Allocates nothing.  Returns TA_OK or TA_ERR_HIP.
  */
 int32_t ta_init(void);
+
+/*
+ * ta_evict for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * outputs, kernels and errors as ta_evict, minus `ws` / `ws_bytes`: the per-chunk softmax row
+ * statistics of the score step go to a static device buffer of TA_STATIC_SCRATCH_BYTES that
+ * lives inside the library (one copy per GPU, held until the process ends).  The call
+ * allocates and frees nothing and calls no allocating routine.
+ *   - A layout whose ta_workspace_bytes() exceeds TA_STATIC_SCRATCH_BYTES is refused with
+ *     TA_ERR_SCRATCH before anything is launched (the full-model, long-context and agentic
+ *     prefill shapes need 0.5, 2 and 16 MiB).
+ *   - `stream` must belong to the current device.
+ *   - Every call on a GPU uses that GPU's one buffer: calls that may overlap on one GPU
+ *     (different streams, different threads) race on it and must be serialised by the caller.
+ *     Nothing in the buffer has to start at zero (every statistic is written by the first
+ *     sweep before the second reads it), so the previous call's contents do no harm.
+ *   - The first call on a device looks up the buffer's address (ta_init does the same ahead
+ *     of time).
+ */
+#define TA_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t ta_evict_static(const int32_t *tok, const int32_t *seq_len,
+                        const int32_t *tab_ids, const int32_t *tab_len, int32_t E, const float *anchor_B,
+                        const void *Q, const void *Kin, const void *Vin,
+                        const ta_layout *lay, const ta_params *prm, int32_t K,
+                        uint8_t *anchor, uint8_t *spons, float *vouch, float *A,
+                        int32_t *idx, int32_t *cnt, void *Kout, void *Vout, void *stream);
 
 /* Text for a ta_status value (static storage). */
 const char *ta_strerror(int32_t status);

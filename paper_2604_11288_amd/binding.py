@@ -24,11 +24,12 @@ TA_MAX_LAYER_PTRS = 96
 TA_LAYER_WS_BYTES = 4096
 
 TA_OK, TA_ERR_NULL, TA_ERR_SHAPE, TA_ERR_BUDGET = 0, -1, -2, -3
-TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP = -4, -5, -6
+TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP, TA_ERR_SCRATCH = -4, -5, -6, -7
+TA_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
            "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged",
-           "ta_evict", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_evict_layers_paged", "ta_decode_init", "ta_decode_step", "ta_init", "ta_strerror", "ta_last_hip_error")
+           "ta_evict", "ta_evict_static", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_evict_layers_paged", "ta_decode_init", "ta_decode_step", "ta_init", "ta_strerror", "ta_last_hip_error")
 
 
 class TaError(RuntimeError):
@@ -140,6 +141,9 @@ def lib():
         L.ta_evict.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32,
                                vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ta_evict.restype = i32
+        L.ta_evict_static.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32,
+                                      vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ta_evict_static.restype = i32
         L.ta_evict_lse.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, i32,
                                    vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ta_evict_lse.restype = i32
@@ -450,8 +454,10 @@ class EvictPlan:
     """
 
     def __init__(self, tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params,
-                 seq_len=None, anchor_B=None, lse=None, paged=None):
+                 seq_len=None, anchor_B=None, lse=None, paged=None, static_scratch=False):
         self.paged = paged                 # PagedKV: Kin / Vin are then its pools (pass None for both)
+        self.static_scratch = static_scratch   # ta_evict_static: no workspace tensor, the library's own scratch
+        assert not (static_scratch and (lse is not None or paged is not None))
         if paged is not None:
             Kin, Vin = paged.Kpool, paged.Vpool
         dev = Kin.device
@@ -480,7 +486,7 @@ class EvictPlan:
                 sized = CLayout.from_buffer_copy(lay)
                 sized.kv_stride[3] = lay.d
             nbytes = ta_workspace_bytes(sized, params) if lse is None else 0
-            self.ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+            self.ws = None if static_scratch else torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
             if lse is not None:
                 assert lse.dtype == torch.float32 and lse.is_contiguous()
                 assert tuple(lse.shape) == (lay.layers, B, lay.hq, lay.window)
@@ -513,6 +519,14 @@ class EvictPlan:
                                     _ptr(self.idx), _ptr(self.cnt), _ptr(self.Kout), _ptr(self.Vout), _stream(stream))
             _check(rc, "ta_evict_lse")
             return self
+        if self.static_scratch:
+            rc = lib().ta_evict_static(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
+                                       self.E, _ptr(self.anchor_B), _ptr(self.Q), _ptr(self.Kin), _ptr(self.Vin),
+                                       ctypes.byref(self.lay), ctypes.byref(self._cp), self.K,
+                                       _ptr(self.anchor), _ptr(self.spons), _ptr(self.vouch), _ptr(self.A),
+                                       _ptr(self.idx), _ptr(self.cnt), _ptr(self.Kout), _ptr(self.Vout), _stream(stream))
+            _check(rc, "ta_evict_static")
+            return self
         rc = lib().ta_evict(_ptr(self.tok), _ptr(self.seq_len), self.ids.ctypes.data, self.lens.ctypes.data,
                             self.E, _ptr(self.anchor_B), _ptr(self.Q), _ptr(self.Kin), _ptr(self.Vin),
                             ctypes.byref(self.lay), ctypes.byref(self._cp), self.K,
@@ -527,6 +541,13 @@ def ta_evict(tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params, seq_len
              stream=None) -> EvictPlan:
     """The whole pass in one call; returns the plan object holding every output tensor."""
     return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B).run(stream)
+
+
+def ta_evict_static(tok, tab_ids, tab_len, Q, Kin, Vin, K: int, params: Params, seq_len=None, anchor_B=None,
+                    stream=None) -> EvictPlan:
+    """ta_evict with the library's static scratch in place of a workspace (the outputs are still
+    allocated here, by the binding; build an EvictPlan(static_scratch=True) once to call without that)."""
+    return EvictPlan(tok, tab_ids, tab_len, Q, Kin, Vin, K, params, seq_len, anchor_B, static_scratch=True).run(stream)
 
 
 def ta_evict_paged(tok, tab_ids, tab_len, Q, paged: "PagedKV", K: int, params: Params, seq_len=None, anchor_B=None,

@@ -6,7 +6,31 @@
 
 #include "ta_internal.h"
 
+// Scratch of ta_evict_static: per-chunk softmax row statistics of the score step.  Host code
+// never uses this name as an address (it is a host-side stand-in): the device address is looked
+// up once per device with hipGetSymbolAddress and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[TA_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+ta::DeviceOnce g_scratch_once;
+void* g_scratch_ptr[64];                                   // per device, valid once g_scratch_once has run there
+
+// (a plain host function: the compiler gives the array a symbol the runtime can find only when
+// it sees host code name it, and the call operator of a lambda does not count as host code)
+hipError_t scratch_address(void** p) { return hipGetSymbolAddress(p, HIP_SYMBOL(scratch)); }
+
+hipError_t scratch_setup()
+{
+    return g_scratch_once.run([](int dev) {
+        void* p = nullptr;
+        const hipError_t e = scratch_address(&p);
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+        return hipSuccess;
+    });
+}
 
 thread_local int32_t t_last_hip_error = 0;
 
@@ -497,7 +521,26 @@ int32_t ta_init(void)
 {
     hipError_t e = ta::select_setup();
     if (e == hipSuccess) e = ta::decode_setup();
+    if (e == hipSuccess) e = scratch_setup();
     return hip_status(e);
+}
+
+int32_t ta_evict_static(const int32_t* tok, const int32_t* seq_len,
+                        const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
+                        const void* Q, const void* Kin, const void* Vin,
+                        const ta_layout* lay, const ta_params* prm, int32_t K,
+                        uint8_t* anchor, uint8_t* spons, float* vouch, float* A,
+                        int32_t* idx, int32_t* cnt, void* Kout, void* Vout, void* stream)
+{
+    if (!lay || !prm) return TA_ERR_NULL;
+    if (ta_workspace_bytes(lay, prm) > (size_t)TA_STATIC_SCRATCH_BYTES) return TA_ERR_SCRATCH;
+    hipError_t e = scratch_setup();
+    int dev = 0;
+    if (e == hipSuccess) e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_status(e);
+    return evict_pass(tok, seq_len, tab_ids, tab_len, E, anchor_B, Q, Kin, Vin, lay, prm, K, anchor, spons, vouch, A,
+                      idx, cnt, Kout, Vout, g_scratch_ptr[dev], (size_t)TA_STATIC_SCRATCH_BYTES, nullptr, nullptr, nullptr,
+                      stream);
 }
 
 int32_t ta_evict_lse(const int32_t* tok, const int32_t* seq_len,
@@ -598,6 +641,7 @@ const char* ta_strerror(int32_t status)
         case TA_ERR_WORKSPACE: return "workspace missing or too small";
         case TA_ERR_ALIGN: return "a K/V/Q pointer or stride is not 16-byte aligned";
         case TA_ERR_HIP: return "a HIP launch failed";
+        case TA_ERR_SCRATCH: return "the layout needs more scratch than the static buffer of ta_evict_static holds";
         default: return "unknown status";
     }
 }

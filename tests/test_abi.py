@@ -31,11 +31,11 @@ def test_exports_match_header(L):
 
 def test_strerror_covers_every_status(L):
     seen = set()
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         msg = L.ta_strerror(code).decode()
         assert msg and msg != "unknown status"
         seen.add(msg)
-    assert len(seen) == 7
+    assert len(seen) == 8
     assert L.ta_strerror(-99).decode() == "unknown status"
     assert L.ta_last_hip_error() == 0
 
@@ -255,6 +255,21 @@ def test_decode_error_paths(L):
     assert L.ta_decode_step(*a) == tb.TA_ERR_ALIGN
     a = step(); a[1] = None
     assert L.ta_decode_step(*a) == tb.TA_ERR_NULL
+
+
+def test_static_scratch_entry_refuses_oversized_layouts_on_the_host(L):
+    # 96 layers x 96 sequences x 8 heads x 128 rows x 8 B = 72 MiB of row statistics: beyond the static buffer
+    lay = _lay(layers=96, batch=96, n=1024, kv_stride=[96 * 8 * 1024 * 128, 8 * 1024 * 128, 1024 * 128, 128],
+               q_stride=[96 * 32 * 32 * 128, 32 * 32 * 128, 32 * 128])
+    cp = tb.Params().c()
+    assert L.ta_workspace_bytes(ctypes.byref(lay), ctypes.byref(cp)) > tb.TA_STATIC_SCRATCH_BYTES
+    ids, lens = _table()
+    args = [FAKE, None, ids.ctypes.data, lens.ctypes.data, 2, None, FAKE, FAKE, FAKE, ctypes.byref(lay), ctypes.byref(cp), 64,
+            FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None]
+    assert L.ta_evict_static(*args) == tb.TA_ERR_SCRATCH
+    assert "scratch" in L.ta_strerror(tb.TA_ERR_SCRATCH).decode()
+    args[9] = None
+    assert L.ta_evict_static(*args) == tb.TA_ERR_NULL
 
 
 def test_layer_budgets_host_function_matches_oracle(L):
