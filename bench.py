@@ -44,10 +44,18 @@ def kv_bytes_per_pass(w, budget, seq_len=None):
 # size.  A figure belongs to one version of the score kernels: it is reported only while their
 # sources still hash to what was profiled, and is null otherwise.
 SCORE_TRAFFIC = {
-    "c2_full_model": {
+    "c4_long_context": {      # profiles/evict_pass_c4_long_context_K1024.txt
+        "bytes_per_step": 69.40e9,
+        "sources": {
+            "ta_score.hip": "d586b676b008b66c77dcd736a4dda21b8437eed7104d9782f522f756f6b1b06c",
+            "ta_score_common.h": "3e4b78495a5669b06b80090303e2ac50ab9622f4b9ead1de520e8aee81424db4",
+            "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
+        },
+    },
+    "c2_full_model": {        # profiles/score_two_sweep_c2_full_model_K1024.txt
         "bytes_per_step": 559.4e6,
         "sources": {
-            "ta_score.hip": "3d4c1d0d73c0a6bcc86fbff7ae068b3f33b1357248de3595f22667017ae339f7",
+            "ta_score.hip": "d586b676b008b66c77dcd736a4dda21b8437eed7104d9782f522f756f6b1b06c",
             "ta_score_common.h": "3e4b78495a5669b06b80090303e2ac50ab9622f4b9ead1de520e8aee81424db4",
             "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
         },
