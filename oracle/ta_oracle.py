@@ -14,7 +14,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ta_oracle.c")
-_SO = os.path.join(_HERE, "libta_oracle.so")
+# TA_ORACLE_SANITIZE=1: the same source built with AddressSanitizer and UndefinedBehaviorSanitizer
+# (any report aborts the process).  The interpreter must then be started with the sanitizer
+# runtime preloaded (LD_PRELOAD=$(gcc -print-file-name=libasan.so)); tests/test_sanitizers.py does.
+SANITIZE = os.environ.get("TA_ORACLE_SANITIZE", "") not in ("", "0")
+_SO = os.path.join(_HERE, "libta_oracle_san.so" if SANITIZE else "libta_oracle.so")
 
 _lib = None
 
@@ -22,7 +26,8 @@ _lib = None
 def build(force=False):
     """Compile the oracle with gcc (plain C11, no contraction, no fast-math)."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] if SANITIZE else ["-O2"]
+        cmd = ["gcc", "-std=c11", *opt, "-ffp-contract=off", "-fno-fast-math",
                "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO

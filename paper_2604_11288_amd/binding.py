@@ -13,7 +13,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libta.so")
+# TA_LIBTA_PATH names another build of the same library (the host-sanitizer build of the tests)
+LIB_PATH = os.environ.get("TA_LIBTA_PATH") or os.path.join(_HERE, "libta.so")
 
 TA_MAX_TABLE = 64
 TA_MAX_GRAM = 4

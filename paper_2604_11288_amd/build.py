@@ -19,21 +19,32 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-ffp-c
          "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
-def _compile(src):
-    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    subprocess.run([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+# Host-side sanitizers (the argument checks and launch logic of the C ABI; GPU code is not
+# instrumented): every -fsanitize= goes to the host pass only.
+LIB_HOSTSAN = os.path.join(HERE, "libta_hostsan.so")
+HOSTSAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def _compile(src, extra=(), suffix=".o"):
+    obj = os.path.join(CSRC, src.replace(".hip", suffix))
+    subprocess.run([HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
     return obj
 
 
-def build_lib(verbose=False):
-    """Compile every source and link libta.so next to this file."""
+def build_lib(verbose=False, host_sanitizers=False):
+    """Compile every source and link libta.so next to this file (host_sanitizers: libta_hostsan.so,
+    the same code with AddressSanitizer and UndefinedBehaviorSanitizer in the host pass)."""
+    extra, suffix, lib = ((HOSTSAN_FLAGS, ".san.o", LIB_HOSTSAN) if host_sanitizers else ((), ".o", LIB))
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+        objs = list(ex.map(lambda s: _compile(s, extra, suffix), SOURCES))
+    link = ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"] if host_sanitizers else []
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *link, "-o", lib, *objs], check=True)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":
-    build_lib(verbose=True)
+    import sys
+    build_lib(verbose=True, host_sanitizers="--host-sanitizers" in sys.argv)
