@@ -8,11 +8,20 @@ namespace ta {
 
 namespace {
 
+#ifndef TA_MATCH_MAX_TILES_PER_WG
+#define TA_MATCH_MAX_TILES_PER_WG 16
+#endif
+constexpr int32_t MATCH_MAX_TILES_PER_WG = TA_MATCH_MAX_TILES_PER_WG;
+constexpr int64_t MATCH_MIN_WORKGROUPS = 8192;             // 32 per compute unit before tiles are grouped
+
+// `tpw` consecutive tiles per workgroup (the last workgroup of a sequence may have fewer)
 __global__ void __launch_bounds__(MATCH_THREADS)
-match_expand_kernel(MatchArgs a, MatchTable tab)
+match_expand_kernel(MatchArgs a, MatchTable tab, int32_t tpw)
 {
     __shared__ __align__(16) MatchLds lds;
-    match_expand_tile(a, tab, (int32_t)blockIdx.x, (int32_t)blockIdx.y, (int)threadIdx.x, lds);
+    const int32_t first = (int32_t)blockIdx.x * tpw;
+    const int32_t count = a.tiles - first < tpw ? a.tiles - first : tpw;
+    match_expand_tiles(a, tab, first, count, (int32_t)blockIdx.y, (int)threadIdx.x, lds);
 }
 
 // Step 2 alone, for anchors that do not come from the n-gram table (learned detection,
@@ -102,8 +111,13 @@ hipError_t launch_match(const int32_t* tok, const int32_t* seq_len, int32_t B, i
                         uint8_t* anchor, uint8_t* spons, float* vouch, hipStream_t st)
 {
     const MatchArgs a = make_match_args(tok, seq_len, B, n, anchor_B, allow, anchor, spons, vouch);
-    dim3 grid((unsigned)a.tiles, (unsigned)B);
-    hipLaunchKernelGGL(match_expand_kernel, grid, dim3(MATCH_THREADS), 0, st, a, tab);
+    // Several tiles per workgroup once there are far more tiles than the chip holds workgroups: the
+    // filter is then built once per workgroup instead of once per 1024 tokens.
+    const int64_t total = (int64_t)a.tiles * B;
+    int32_t tpw = 1;
+    while (tpw < MATCH_MAX_TILES_PER_WG && total / (2 * tpw) >= MATCH_MIN_WORKGROUPS) tpw *= 2;
+    dim3 grid((unsigned)((a.tiles + tpw - 1) / tpw), (unsigned)B);
+    hipLaunchKernelGGL(match_expand_kernel, grid, dim3(MATCH_THREADS), 0, st, a, tab, tpw);
     return hipGetLastError();
 }
 

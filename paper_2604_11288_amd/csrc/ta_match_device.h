@@ -4,7 +4,8 @@
 // can carry the match tiles as trailing workgroups of its own launch.
 //
 // MATCH_THREADS threads own a tile of MATCH_TILE consecutive positions of one sequence.
-//   phase 0  build a 32768-bit filter of the table's last-token IDs in LDS
+//   phase 0  build a 32768-bit filter of the table's last-token IDs in LDS (once per workgroup:
+//            on long sequences a workgroup works through several consecutive tiles)
 //   phase 1  stage the tile's tokens plus a left halo of 64 + 3 tokens in LDS
 //   phase 2  anchor flag for every position of [tile - 64, tile end): one LDS
 //            filter probe per position; a position that passes is compared with
@@ -55,60 +56,76 @@ MatchArgs make_match_args(const int32_t* tok, const int32_t* seq_len, int32_t B,
 
 __device__ __forceinline__ uint32_t filter_slot(int32_t t) { return (uint32_t)t & (FILTER_BITS - 1); }
 
-// Phases 0-2: anchor flags of [tile0 - MATCH_MARGIN, tile0 + MATCH_TILE) as bits in lds.bits.
-// Called by exactly MATCH_THREADS threads (tid = 0 .. MATCH_THREADS-1) of a workgroup whose
-// other wavefronts, if any, have already returned; ends with a workgroup barrier.
-__device__ __forceinline__ void match_flags_tile(const MatchArgs& a, const MatchTable& tab, int32_t tile,
-                                                 int32_t b, int tid, MatchLds& lds)
+constexpr int MATCH_TOK_ROUNDS = (MATCH_TILE + MATCH_HALO + MATCH_THREADS - 1) / MATCH_THREADS;
+
+// Table entry of a lane (lane e holds entry e; the table has at most 64 entries).
+struct MatchEntry {
+    int32_t e0, e1, e2, e3, len;
+};
+
+// Tokens of [tile0 - HALO, tile0 + TILE) of one tile, MATCH_TOK_ROUNDS per thread, into registers;
+// positions outside the sequence hold a value no table ID can equal (IDs are validated >= 0).
+__device__ __forceinline__ void match_load_tokens(const MatchArgs& a, int32_t tile, int32_t b, int32_t nb, int tid,
+                                                  int32_t (&tk)[MATCH_TOK_ROUNDS])
+{
+    const int32_t base = tile * MATCH_TILE - MATCH_HALO;
+    const size_t row = (size_t)b * (size_t)a.n;
+#pragma unroll
+    for (int r = 0; r < MATCH_TOK_ROUNDS; ++r) {
+        const int i = tid + r * MATCH_THREADS;
+        const int32_t p = base + i;
+        tk[r] = (i < MATCH_TILE + MATCH_HALO && p >= 0 && p < nb) ? a.tok[row + (size_t)p] : INT32_MIN;
+    }
+}
+
+// Phase 0: the last-token filter of the table in LDS (the same for every tile: a workgroup that
+// works on several tiles builds it once) and this lane's table entry.  Called by exactly
+// MATCH_THREADS threads; the filter is complete after the next workgroup barrier.
+__device__ __forceinline__ MatchEntry match_prepare(const MatchTable& tab, int tid, MatchLds& lds)
+{
+    for (int i = tid; i < FILTER_BITS / 32; i += MATCH_THREADS) lds.filter[i] = 0u;
+    __syncthreads();
+    if (tid < tab.E) {
+        const uint32_t h = filter_slot(tab.rid[tid][0]);
+        atomicOr(&lds.filter[h >> 5], 1u << (h & 31));
+    }
+    const int lane = tid & 63;
+    MatchEntry e = {-1, -1, -1, -1, 0};
+    if (lane < tab.E) {
+        e.e0 = tab.rid[lane][0];
+        e.e1 = tab.rid[lane][1];
+        e.e2 = tab.rid[lane][2];
+        e.e3 = tab.rid[lane][3];
+        e.len = tab.len[lane];
+    }
+    return e;
+}
+
+// Phases 1-2 of one tile: the tokens in `tk` go to LDS, then the anchor flags of
+// [tile0 - MATCH_MARGIN, tile0 + MATCH_TILE) are left as bits in lds.bits.  With `next_tile` >= 0
+// the tokens of that tile are requested into `tk` as soon as the current ones are in LDS, so that
+// their latency hides behind this tile's work.  Starts and ends with a workgroup barrier (the first
+// also orders the previous tile's reads of lds.bits before this tile's writes).
+__device__ __forceinline__ void match_flags_tile(const MatchArgs& a, const MatchEntry& e, int32_t tile, int32_t b, int32_t nb,
+                                                 int tid, MatchLds& lds, int32_t (&tk)[MATCH_TOK_ROUNDS], int32_t next_tile)
 {
     uint32_t* s_filter = lds.filter;
     int32_t* s_tok = lds.tok;
     uint32_t* s_bits = lds.bits;
     const int lane = tid & 63, wave = tid >> 6;
-    const int32_t n = a.n;
-    int32_t nb = a.seq_len ? a.seq_len[b] : n;
-    nb = nb < 0 ? 0 : (nb > n ? n : nb);
     const int32_t tile0 = tile * MATCH_TILE;
-    const size_t row = (size_t)b * (size_t)n;
-
-    // phase 1 first: the tokens of [tile0 - HALO, tile0 + TILE) are requested before the filter is
-    // built, so that their latency overlaps it; positions outside the sequence hold a value no
-    // table ID can equal (IDs are validated >= 0)
     const int32_t base = tile0 - MATCH_HALO;
-    constexpr int TOK_ROUNDS = (MATCH_TILE + MATCH_HALO + MATCH_THREADS - 1) / MATCH_THREADS;
-    int32_t tk[TOK_ROUNDS];
+    const size_t row = (size_t)b * (size_t)a.n;
 #pragma unroll
-    for (int r = 0; r < TOK_ROUNDS; ++r) {
-        const int i = tid + r * MATCH_THREADS;
-        const int32_t p = base + i;
-        tk[r] = (i < MATCH_TILE + MATCH_HALO && p >= 0 && p < nb) ? a.tok[row + (size_t)p] : INT32_MIN;
-    }
-
-    // phase 0: last-token filter
-    for (int i = tid; i < FILTER_BITS / 32; i += MATCH_THREADS) s_filter[i] = 0u;
-    __syncthreads();
-    if (tid < tab.E) {
-        uint32_t h = filter_slot(tab.rid[tid][0]);
-        atomicOr(&s_filter[h >> 5], 1u << (h & 31));
-    }
-#pragma unroll
-    for (int r = 0; r < TOK_ROUNDS; ++r) {
+    for (int r = 0; r < MATCH_TOK_ROUNDS; ++r) {
         const int i = tid + r * MATCH_THREADS;
         if (i < MATCH_TILE + MATCH_HALO) s_tok[i] = tk[r];
     }
+    if (next_tile >= 0) match_load_tokens(a, next_tile, b, nb, tid, tk);
     __syncthreads();
 
-    // phase 2: anchor flags of [tile0 - MARGIN, tile0 + TILE), 64 positions per wavefront and
-    // round.  Lane e keeps table entry e in registers (the table has at most 64 entries); a
-    // position that passes the filter is compared with all entries at once, one entry per lane.
-    int32_t e0 = -1, e1 = -1, e2 = -1, e3 = -1, elen = 0;
-    if (lane < tab.E) {
-        e0 = tab.rid[lane][0];
-        e1 = tab.rid[lane][1];
-        e2 = tab.rid[lane][2];
-        e3 = tab.rid[lane][3];
-        elen = tab.len[lane];
-    }
+    // phase 2: 64 positions per wavefront and round.  A position that passes the filter is compared
+    // with all table entries at once, one entry per lane.
     for (int j0 = 64 * wave; j0 < MATCH_TILE + MATCH_MARGIN; j0 += MATCH_THREADS) {
         const int32_t q = tile0 - MATCH_MARGIN + j0 + lane;
         bool cand = false;
@@ -123,8 +140,8 @@ __device__ __forceinline__ void match_flags_tile(const MatchArgs& a, const Match
             todo &= todo - 1ull;
             const int32_t* t = &s_tok[tile0 - MATCH_MARGIN + j0 + i - base];   // same address in every lane; t[-3] >= s_tok
             const int32_t a0 = t[0], a1 = t[-1], a2 = t[-2], a3 = t[-3];
-            const bool ok = elen >= 1 && a0 == e0 && (elen < 2 || a1 == e1) && (elen < 3 || a2 == e2) &&
-                            (elen < 4 || a3 == e3);
+            const bool ok = e.len >= 1 && a0 == e.e0 && (e.len < 2 || a1 == e.e1) && (e.len < 3 || a2 == e.e2) &&
+                            (e.len < 4 || a3 == e.e3);
             if (__ballot(ok) != 0ull) m |= 1ull << i;
         }
         if (lane == 0) {
@@ -200,12 +217,28 @@ __device__ __forceinline__ void expand_tile(const MatchArgs& a, const MatchTable
     }
 }
 
-// Steps 1+2 for one tile: flags by n-gram match, then the expansion.
+// Steps 1+2 for `count` consecutive tiles of one sequence, starting at `tile`: flags by n-gram
+// match, then the expansion.  The filter is built once; a tile's tokens are requested while the
+// tile before it is worked on.
+__device__ __forceinline__ void match_expand_tiles(const MatchArgs& a, const MatchTable& tab, int32_t tile, int32_t count,
+                                                   int32_t b, int tid, MatchLds& lds)
+{
+    int32_t nb = a.seq_len ? a.seq_len[b] : a.n;
+    nb = nb < 0 ? 0 : (nb > a.n ? a.n : nb);
+    int32_t tk[MATCH_TOK_ROUNDS];
+    match_load_tokens(a, tile, b, nb, tid, tk);            // requested before the filter is built: the latencies overlap
+    const MatchEntry e = match_prepare(tab, tid, lds);
+    for (int32_t t = tile; t < tile + count; ++t) {
+        match_flags_tile(a, e, t, b, nb, tid, lds, tk, t + 1 < tile + count ? t + 1 : -1);
+        expand_tile(a, tab, t, b, tid, lds.bits, true);
+    }
+}
+
+// One tile (the form the score sweep's trailing workgroups use).
 __device__ __forceinline__ void match_expand_tile(const MatchArgs& a, const MatchTable& tab, int32_t tile,
                                                   int32_t b, int tid, MatchLds& lds)
 {
-    match_flags_tile(a, tab, tile, b, tid, lds);
-    expand_tile(a, tab, tile, b, tid, lds.bits, true);
+    match_expand_tiles(a, tab, tile, 1, b, tid, lds);
 }
 
 }  // namespace ta

@@ -78,6 +78,40 @@ def test_match_expand_bit_exact(n, batch, clean, ragged, L):
         assert total >= batch * 6 - 6
 
 
+@pytest.mark.parametrize("batch,n,ragged", [
+    (16, 1 << 20, False),       # 16 384 tiles: two consecutive tiles per workgroup
+    (64, (1 << 20) + 4, True),  # 65 600 tiles: eight per workgroup, ragged ends inside and between tiles
+])
+def test_match_many_tiles_per_workgroup(batch, n, ragged):
+    """Long streams: a workgroup walks through several consecutive tiles (filter built once, the next
+    tile's tokens requested ahead).  Unrestricted token IDs over a small vocabulary, so that anchors,
+    overlapping spans and matches across tile borders are frequent; sampled sequences go through the oracle."""
+    g = torch.Generator(device=DEV).manual_seed(91 + batch)
+    tok = torch.randint(0, 200, (batch, n), dtype=torch.int32, device=DEV, generator=g)
+    rng = np.random.default_rng(batch)
+    tab_len = rng.integers(1, 5, size=24).astype(np.int32)
+    tab_ids = np.full((24, 4), -1, np.int32)
+    for e in range(24):
+        tab_ids[e, :tab_len[e]] = rng.integers(0, 200, size=tab_len[e])
+    tab_len[0] = 1                                           # one 1-gram: about n / 200 hits of it alone
+    tab_ids[0] = [7, -1, -1, -1]
+    lens = np.full(batch, n, np.int32)
+    if ragged:
+        lens = rng.integers(n // 2, n + 1, size=batch).astype(np.int32)
+        lens[0], lens[1], lens[2] = n, 5 * 1024, 5 * 1024 + 1
+    prm = ta.Params(n_sink=4, n_recent=4)
+    anchor, spons, vouch = ta.ta_match_anchors(tok, tab_ids, tab_len, prm, seq_len=_dev(lens) if ragged else None)
+    torch.cuda.synchronize()
+    for b in sorted({0, 1, 2, batch // 2, batch - 1}):
+        nb = int(lens[b])
+        a, s_, v = ora.evict_sequence(tok[b, :nb].cpu().numpy(), tab_ids, tab_len)
+        assert a.sum() > nb // 400
+        assert np.array_equal(anchor[b, :nb].cpu().numpy(), a), b
+        assert np.array_equal(spons[b, :nb].cpu().numpy(), s_), b
+        assert np.array_equal(vouch[b, :nb].cpu().numpy().view(np.uint32), v.view(np.uint32)), b
+        assert not bool(anchor[b, nb:].any()) and not bool(spons[b, nb:].any()) and not bool(vouch[b, nb:].any())
+
+
 def test_match_per_anchor_budget_and_empty_table():
     w = wl.scaled(wl.CONFIGS["c2_full_model"], n=2500, batch=2)
     td = wl.make_tokens(w, clean=False)
