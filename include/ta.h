@@ -85,8 +85,9 @@ typedef struct ta_params {
     int32_t causal;     /* 1: window query w sees keys 0..n-W+w; 0: every key             */
     float budget_decay; /* per-step decay of sponsor budgets (paper: 0.9); decode steps   */
     /* Options around the same selection (baselines of Sec. 2 / Sec. 4 and the partition of
-     * Sec. 3.3 as settings).  Defaults: 1, -1, NULL, NULL.  The per-step form accepts only the
-     * defaults of pool_k and k_protected and ignores layer_K and allow. */
+     * Sec. 3.3 as settings).  Defaults: 1, -1, 0, NULL, NULL.  The per-step form accepts only the
+     * defaults of pool_k and k_protected and ignores layer_K and allow; the one-shot pass ignores
+     * last_query. */
     int32_t pool_k;      /* odd window (1, 3, 5, 7 or 9) of a max-pool applied to A along the sequence
                             before the utility - the clustering step of SnapKV; 1 = none            */
     int32_t k_protected; /* K_protected of Sec. 3.3: the protected pool holds the k_protected best
@@ -95,6 +96,11 @@ typedef struct ta_params {
                             alone, mandatory tokens count against K_main, unused protected slots
                             return to the main pool.  Negative: the elastic pool (every sponsored
                             token outranks every plain one).  0: the strict configuration           */
+    int32_t last_query;  /* per-step form only (0 or 1).  0: a slot's attention term is its cumulative mass
+                            over the steps (H2O-style, Eq. 1).  1: it is the mass the CURRENT step's
+                            queries give it - the step-wise minimum-attention eviction of TOVA (Sec. 2;
+                            corollary of Thm. 1): the state's A array then holds the last step's
+                            attention of every slot instead of a running sum                        */
     const int32_t *layer_K; /* DEVICE int32 [layers] or NULL: budget of each layer (PyramidKV-style
                             schedules, see ta_layer_budgets), clamped on the device to
                             [max(1, n_sink + n_recent), K]; idx rows keep K entries, cnt says how
@@ -496,6 +502,7 @@ int32_t ta_decode_init(const ta_decode_state *st, const int32_t *tok, const int3
  *   2. per unit: the new k/v row goes into the lowest-numbered free slot with A = 0;
  *      with alpha != 0 each of the hq/hkv decode queries of the group adds its
  *      softmax weights over the occupied slots (q.k/sqrt(d), fp32) to A
+ *      (prm->last_query: A of every occupied slot is REPLACED by this step's weights)
  *   3. per unit, if no slot is free: the slot ranking last under the order of
  *      ta_select - classes and the recency term taken from absolute positions and
  *      the new length, vouchers recomputed from the current budgets - is freed

@@ -340,6 +340,11 @@ void ta_oracle_decode_decay(float *budget, int32_t len, float decay)
  * rank_A (nullable): attention values to rank with instead of the unit's own
  * updated A (lets a caller impose scores computed elsewhere, in the same
  * precision on both sides of a comparison).
+ * last_query != 0: the attention term of a slot is the mass that THIS step's
+ * queries give it, not the running sum over the steps - the step-wise
+ * minimum-attention eviction that the corollary of Thm. 1 ascribes to TOVA
+ * (Sec. 2).  A[s] of every occupied slot is then replaced by this step's
+ * mass.
  * Returns the evicted slot or -1; u_out (nullable, [slots]) receives the
  * utilities of the occupied slots.
  */
@@ -350,7 +355,7 @@ int32_t ta_oracle_decode_unit(uint16_t *Kc, uint16_t *Vc, int32_t *pos, float *A
                               const uint8_t *anchor, const float *budget, int32_t len_new,
                               int32_t n_sink, int32_t n_recent, int32_t L, double rho,
                               float alpha, float beta, float gamma,
-                              const float *rank_A, float *u_out)
+                              const float *rank_A, float *u_out, int32_t last_query)
 {
     int32_t f = -1;
     for (int32_t s = slots - 1; s >= 0; --s)
@@ -390,7 +395,7 @@ int32_t ta_oracle_decode_unit(uint16_t *Kc, uint16_t *Vc, int32_t *pos, float *A
         }
         for (int32_t s = 0; s < slots; ++s)
             if (pos[s] >= 0)
-                A[s] = (float)((double)A[s] + add[s]);
+                A[s] = last_query ? (float)add[s] : (float)((double)A[s] + add[s]);
         free(sc);
         free(add);
     }

@@ -58,7 +58,7 @@ def _load():
         lib.ta_oracle_decode_decay.argtypes = [vp, i32, f32]
         lib.ta_oracle_decode_decay.restype = None
         lib.ta_oracle_decode_unit.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, vp, vp, i32,
-                                              i32, i32, i32, f64, f32, f32, f32, vp, vp]
+                                              i32, i32, i32, f64, f32, f32, f32, vp, vp, i32]
         lib.ta_oracle_decode_unit.restype = i32
         lib.ta_oracle_detect.argtypes = [vp, vp, vp, i32, i32, i32, vp]
         lib.ta_oracle_detect.restype = None
@@ -359,8 +359,9 @@ class DecodeUnit:
         self.A[:K] = _c(A_kept, np.float32)
 
     def step(self, seq, q, k_new, v_new, p_new, n_sink, n_recent, L=6, rho=0.8,
-             alpha=1.0, beta=0.5, gamma=0.3, rank_A=None):
-        """q uint16 [G][d].  Returns (evicted slot, utilities [slots])."""
+             alpha=1.0, beta=0.5, gamma=0.3, rank_A=None, last_query=False):
+        """q uint16 [G][d].  Returns (evicted slot, utilities [slots]).  last_query: the attention term is
+        this step's softmax mass alone (TOVA's step-wise rule), not the running sum."""
         q = _c(q, np.uint16)
         k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
         ra = None if rank_A is None else _c(rank_A, np.float32)
@@ -369,5 +370,6 @@ class DecodeUnit:
                                           _p(q), q.shape[0], _p(k_new), _p(v_new), int(p_new),
                                           _p(seq.anchor), _p(seq.budget), seq.len,
                                           int(n_sink), int(n_recent), int(L), float(rho),
-                                          float(alpha), float(beta), float(gamma), _p(ra), _p(u))
+                                          float(alpha), float(beta), float(gamma), _p(ra), _p(u),
+                                          1 if last_query else 0)
         return int(e), u

@@ -47,7 +47,7 @@ class CParams(ctypes.Structure):
                 ("sponsor_B", ctypes.c_float), ("rho", ctypes.c_double),
                 ("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("gamma", ctypes.c_float),
                 ("causal", ctypes.c_int32), ("budget_decay", ctypes.c_float),
-                ("pool_k", ctypes.c_int32), ("k_protected", ctypes.c_int32),
+                ("pool_k", ctypes.c_int32), ("k_protected", ctypes.c_int32), ("last_query", ctypes.c_int32),
                 ("layer_K", ctypes.c_void_p), ("allow", ctypes.c_void_p)]
 
 
@@ -87,6 +87,7 @@ class Params:
     budget_decay: float = 0.9
     pool_k: int = 1                              # max-pool window over A (SnapKV clustering), 1 = none
     k_protected: int = -1                        # K_protected of Sec. 3.3, negative = elastic pool
+    last_query: bool = False                     # per-step form: rank by the current step's attention (TOVA's rule)
     layer_K: Optional[torch.Tensor] = None       # device int32 [layers]: per-layer budgets
     allow: Optional[torch.Tensor] = None         # device uint8 [B][n]: allowlist of positions
 
@@ -95,7 +96,7 @@ class Params:
             assert t is None or (t.dtype == dt and t.is_contiguous())
         return CParams(self.n_sink, self.n_recent, self.span_L, self.sponsor_B, self.rho,
                        self.alpha, self.beta, self.gamma, 1 if self.causal else 0, self.budget_decay,
-                       self.pool_k, self.k_protected,
+                       self.pool_k, self.k_protected, 1 if self.last_query else 0,
                        None if self.layer_K is None else self.layer_K.data_ptr(),
                        None if self.allow is None else self.allow.data_ptr())
 

@@ -55,6 +55,7 @@ int32_t check_params(const ta_params* prm)
     if (prm->pool_k != 0 && prm->pool_k != 1 && prm->pool_k != 3 && prm->pool_k != 5 && prm->pool_k != 7 &&
         prm->pool_k != 9)
         return TA_ERR_SHAPE;
+    if (prm->last_query != 0 && prm->last_query != 1) return TA_ERR_SHAPE;
     return TA_OK;
 }
 

@@ -165,6 +165,7 @@ struct UnitArgs {
     int32_t n_sink, n_recent;
     float alpha, beta, gamma;
     float scale_log2;
+    int32_t last_query;                                    // 1: A holds this step's attention, not the running sum
 };
 
 __device__ __forceinline__ uint32_t ordered_bits(float u)
@@ -404,7 +405,8 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
 #pragma unroll
                 for (int h = 0; h < GH; ++h)
                     if (h < G) add += __builtin_amdgcn_exp2f(s_w[h * wstride + s] - m_h[h]) * inv_h[h];
-                const float v = (s == f ? 0.0f : s_A[s]) + add;
+                // cumulative mass over the steps, or (TOVA's step-wise rule) this step's mass alone
+                const float v = a.last_query ? add : (s == f ? 0.0f : s_A[s]) + add;
                 s_A[s] = v;
                 A[s] = v;
             }
@@ -532,6 +534,7 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     a.beta = prm.beta;
     a.gamma = prm.gamma;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)st.d));
+    a.last_query = prm.last_query;
     const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
     const int G = st.hq / st.hkv;
     const int slots = st.K + 1;

@@ -362,6 +362,9 @@ def test_decode_rejects_one_shot_options(L):
     assert call(tb.Params(n_sink=4, n_recent=4, pool_k=5).c()) == tb.TA_ERR_SHAPE
     assert call(tb.Params(n_sink=4, n_recent=4, k_protected=4).c()) == tb.TA_ERR_SHAPE
     assert call(tb.Params(n_sink=10, n_recent=10).c()) == tb.TA_ERR_BUDGET
+    bad = tb.Params(n_sink=4, n_recent=4).c()
+    bad.last_query = 2                                     # a flag: 0 or 1
+    assert call(bad) == tb.TA_ERR_SHAPE
 
 
 def test_bench_refuses_more_than_one_gpu():

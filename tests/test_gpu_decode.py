@@ -29,7 +29,7 @@ def _same_bits(x, y):
     return torch.equal(x, y)
 
 
-def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu", stats=None):
+def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu", stats=None, last_query=False):
     """rank="gpu": the oracle ranks the slots with the GPU's fp32 cumulative attention (the decision is then
     exact on both sides).  rank="oracle": the oracle ranks with its own double-accumulated attention; an
     eviction that differs is excused only if both slots are in the same class and their oracle utilities
@@ -39,7 +39,7 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu",
     lyr, B, G = w.layers, w.batch, w.hq // w.hkv
     scored = w.alpha != 0.0
     Q, Kc, Vc = wl.make_qkv(w, device=DEV)
-    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent, alpha=w.alpha, beta=w.beta, gamma=w.gamma)
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent, alpha=w.alpha, beta=w.beta, gamma=w.gamma, last_query=last_query)
     tok = _dev(td.tok)
     seq_len = _dev(td.seq_len)
     # prefill eviction on the GPU (per-unit index lists even for the attention-free setting)
@@ -104,7 +104,7 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu",
                     pos_before = u.pos.copy()
                     e, util = u.step(seqs[b], qb[l, b, g * G:(g + 1) * G], kb[l, b, g], vb[l, b, g], p,
                                      w.n_sink, w.n_recent, alpha=w.alpha, beta=w.beta, gamma=w.gamma,
-                                     rank_A=gA[l, b, g] if rank == "gpu" else None)
+                                     rank_A=gA[l, b, g] if rank == "gpu" else None, last_query=last_query)
                     if e >= 0:
                         ev_pos = p if pos_before[e] < 0 else int(pos_before[e])
                         n_evictions += 1
@@ -234,3 +234,17 @@ def test_decode_ranked_with_the_oracles_own_attention_near_ties():
     ev, _ = _run_decode(w, K=48, steps=64, p_anchor=0.1, rank="oracle", stats=stats)
     print("decode near-tie run: %d evictions, %d excused" % (ev, stats.get("excused", 0)))
     assert ev == 64 * 2 * 2 * 2
+
+
+@pytest.mark.parametrize("rank", ["gpu", "oracle"])
+def test_decode_last_query_rule(rank):
+    """TOVA's step-wise rule as a setting of the same step (the attention term is the current step's mass):
+    with the vouchers on top of it, and alone (alpha only, no table hits matter for the ranking)."""
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=3, n=900, hq=8, hkv=2, ragged=(500, 900))
+    stats = {}
+    ev, _ = _run_decode(w, K=64, steps=40, p_anchor=0.08, rank=rank, stats=stats, last_query=True)
+    assert ev == 40 * 2 * 3 * 2
+    w0 = wl.scaled(w, beta=0.0, gamma=0.0, n_sink=0, n_recent=0, table_entries=1, planted=0)
+    ev, _ = _run_decode(w0, K=32, steps=30, p_anchor=0.0, rank=rank, stats=stats, last_query=True)
+    assert ev == 30 * 2 * 3 * 2
+    print("last-query rule, rank=%s: %d excused near-tie evictions" % (rank, stats.get("excused", 0)))

@@ -163,3 +163,59 @@ def test_sequence_at_capacity_does_not_step():
     assert seq.len == seq.cap
     assert np.array_equal(seq.tok, tok) and np.array_equal(seq.anchor, anc)
     assert np.array_equal(seq.budget.view(np.uint32), bud.view(np.uint32))
+
+
+def _attention_f64(q, Krows):
+    """Softmax mass of every row, summed over the heads, in float64 (numpy restatement)."""
+    qf = torch.from_numpy(q.astype(np.int32) << 16).view(torch.float32).double().numpy()
+    kf = torch.from_numpy(Krows.astype(np.int32) << 16).view(torch.float32).double().numpy()
+    S = qf @ kf.T / np.sqrt(kf.shape[1])
+    P = np.exp(S - S.max(axis=1, keepdims=True))
+    P /= P.sum(axis=1, keepdims=True)
+    return P.sum(axis=0)
+
+
+def test_last_query_rule_evicts_the_arg_min_of_the_current_steps_attention():
+    """The step-wise minimum-attention rule ascribed to TOVA (Sec. 2; corollary of Thm. 1): with alpha = 1,
+    beta = gamma = 0, no anchors and no mandatory positions, the evicted row is the arg-min of the
+    attention of THIS step's queries, whatever the rows accumulated before."""
+    n, K, d, G = 60, 20, 32, 3
+    seq = ora.DecodeSeq(np.arange(n, dtype=np.int32), np.zeros((0, 4), np.int32), np.zeros(0, np.int32), cap=n + 40)
+    unit = _unit_from_prefill(n, K, d, 11)
+    unit.A[:K] = np.linspace(5.0, 9.0, K).astype(np.float32)          # a history that the rule must ignore
+    for t in range(25):
+        p = seq.append(500 + t)
+        q, kn, vn = _bits(_rand((G, d), 300 + t)), _bits(_rand((d,), 400 + t)), _bits(_rand((d,), 500 + t))
+        f = int(np.flatnonzero(unit.pos < 0)[0])
+        Kall = unit.Kc.copy()
+        Kall[f] = kn
+        pos_all = unit.pos.copy()
+        pos_all[f] = p
+        want = _attention_f64(q, Kall)                                 # every slot is occupied once the row is in
+        e, _ = unit.step(seq, q, kn, vn, p, n_sink=0, n_recent=0, alpha=1.0, beta=0.0, gamma=0.0, last_query=True)
+        seq.decay()
+        assert e == int(np.argmin(want)), t
+        occ = np.ones(K + 1, bool)
+        assert np.allclose(unit.A[occ], want[occ].astype(np.float32), rtol=1e-6, atol=0)
+        assert unit.pos[e] == -1 and (unit.pos < 0).sum() == 1
+
+
+def test_last_query_and_cumulative_rules_disagree_when_history_matters():
+    """One row with a large accumulated mass but (by construction) the smallest current attention: the
+    cumulative rule keeps it, the step-wise rule evicts it."""
+    n, K, d = 30, 8, 16
+    seq_a = ora.DecodeSeq(np.arange(n, dtype=np.int32), np.zeros((0, 4), np.int32), np.zeros(0, np.int32), cap=n + 8)
+    seq_b = ora.DecodeSeq(np.arange(n, dtype=np.int32), np.zeros((0, 4), np.int32), np.zeros(0, np.int32), cap=n + 8)
+    q = _rand((1, d), 5)
+    Krows = _rand((K, d), 6)
+    Krows[3] = -4.0 * q[0]                                               # strongly anti-aligned with the query
+    Vrows = _rand((K, d), 7)
+    idx = np.arange(n - K, n, dtype=np.int32)
+    outs = []
+    for last_query, seq in ((False, seq_a), (True, seq_b)):
+        u = ora.DecodeUnit(_bits(Krows), _bits(Vrows), idx, np.where(np.arange(K) == 3, 50.0, 0.0).astype(np.float32))
+        p = seq.append(77)
+        e, _ = u.step(seq, _bits(q), _bits(_rand((d,), 8)), _bits(_rand((d,), 9)), p, n_sink=0, n_recent=0,
+                      alpha=1.0, beta=0.0, gamma=0.0, last_query=last_query)
+        outs.append(e)
+    assert outs[1] == 3 and outs[0] != 3
