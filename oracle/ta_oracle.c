@@ -20,7 +20,8 @@
  * elastic selection, a plain top-K and brute force, the budget-partition table,
  * sum / endpoints / monotonicity of the layer budgets; scores from a given
  * log-sum-exp: torch.logsumexp, agreement with the two-pass scores, row sums;
- * paged gather: numpy fancy indexing on both common page layouts).
+ * paged gather and scatter: numpy fancy indexing on both common page layouts,
+ * gather after scatter returns the rows).
  * Unpinned: nothing in this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
@@ -730,3 +731,19 @@ void ta_oracle_paged_gather(const uint16_t *pool, const int32_t *table, int32_t 
     }
 }
 
+/*
+ * The inverse of the gather: rows [cnt][d] of one (sequence, head) are written to slots
+ * 0 .. cnt-1 of a paged cache - compaction straight into the page pool, and the layout of a
+ * generation-step cache whose K+1 slots live in pages (slot s of the unit is "position" s of
+ * the addressing above).  Nothing else in the pool is touched.
+ */
+void ta_oracle_paged_scatter(const uint16_t *rows, int32_t cnt, const int32_t *table, int32_t page_size,
+                             int64_t stride_page, int64_t stride_pos, int64_t stride_head, int32_t head,
+                             int32_t d, uint16_t *pool)
+{
+    for (int32_t r = 0; r < cnt; ++r) {
+        uint16_t *dst = pool + (int64_t)table[r / page_size] * stride_page +
+                        (int64_t)(r % page_size) * stride_pos + (int64_t)head * stride_head;
+        memcpy(dst, rows + (size_t)r * d, sizeof(uint16_t) * (size_t)d);
+    }
+}

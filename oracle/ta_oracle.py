@@ -67,6 +67,8 @@ def _load():
         i64 = ctypes.c_int64
         lib.ta_oracle_paged_gather.argtypes = [vp, vp, i32, i32, i64, i64, i64, i32, i32, vp]
         lib.ta_oracle_paged_gather.restype = None
+        lib.ta_oracle_paged_scatter.argtypes = [vp, i32, vp, i32, i64, i64, i64, i32, i32, vp]
+        lib.ta_oracle_paged_scatter.restype = None
         lib.ta_oracle_row_lse.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
         lib.ta_oracle_row_lse.restype = None
         lib.ta_oracle_score_lse.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
@@ -144,6 +146,19 @@ def paged_gather(pool, table, n, page_size, stride_page, stride_pos, stride_head
     _load().ta_oracle_paged_gather(_p(pool), _p(table), int(n), int(page_size), int(stride_page), int(stride_pos),
                                    int(stride_head), int(head), int(d), _p(out))
     return out
+
+
+def paged_scatter(pool, rows, table, page_size, stride_page, stride_pos, stride_head, head):
+    """Writes rows [cnt][d] (uint16) to slots 0..cnt-1 of one (sequence, head) of a paged cache pool of one
+    layer, in place.  pool: flat, contiguous uint16 array (modified); strides in elements."""
+    assert pool.dtype == np.uint16 and pool.flags["C_CONTIGUOUS"]
+    rows = _c(rows, np.uint16)
+    table = _c(table, np.int32)
+    cnt, d = rows.shape
+    assert table.shape[0] * page_size >= cnt
+    _load().ta_oracle_paged_scatter(_p(rows), int(cnt), _p(table), int(page_size), int(stride_page), int(stride_pos),
+                                    int(stride_head), int(head), int(d), _p(pool.reshape(-1)))
+    return pool
 
 
 def row_lse(Q, K, causal=True):
