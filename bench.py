@@ -247,12 +247,32 @@ class Bench:
                 "pass_us": round(pass1_us, 1), "pass_GB/s": round((self.score_b + self.compact_b) / pass1_us / 1e3, 1)}
 
     # ---- incremental form: append / accumulate / evict-one / decay, per generation step ---------
-    def decode_step(self, nsteps):
+    def decode_step(self, nsteps, page_size=0):
+        """Generation steps after a pass.  page_size > 0: the K + 1 slots of every unit live in a page pool
+        (pages of `page_size` slots behind a block table); the pass's retained rows are compacted straight
+        into those pages (timed, reported as compact_into_pages_us) and the state takes them in place."""
         ta, torch, wl, w, td, plan = self.ta, self.torch, self.wl, self.w, self.td, self.plan
         dev, stream, budget = self.dev, self.stream, self.budget
         cap = w.n + nsteps + 16
-        st = ta.DecodeState(w.layers, w.batch, w.hq, w.hkv, budget, cap, dev)
-        ta.ta_decode_init(st, self.tok, plan.anchor, plan.idx, plan.cnt, plan.Kout, plan.Vout, self.prm, seq_len=self.seq, A=plan.A)
+        into_us = None
+        if page_size > 0:
+            Kp, Vp, table, num_pages, strides = wl.make_slot_pool(w.layers, w.batch, w.hkv, w.d, budget + 1, page_size, dev)
+            pool = ta.PagedKV(Kp, Vp, torch.from_numpy(table).to(dev), page_size, num_pages, strides, w.layers, w.batch,
+                              w.hkv, budget + 1)
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            ta.ta_compact_into_pages(self.K, self.V, plan.idx, plan.cnt, budget, pool, stream=stream)
+            c0.record(stream)
+            for _ in range(reps):
+                ta.ta_compact_into_pages(self.K, self.V, plan.idx, plan.cnt, budget, pool, stream=stream)
+            c1.record(stream)
+            torch.cuda.synchronize()
+            into_us = c0.elapsed_time(c1) * 1e3 / reps
+            st = ta.DecodeState(w.layers, w.batch, w.hq, w.hkv, budget, cap, dev, pages=pool)
+            ta.ta_decode_init(st, self.tok, plan.anchor, plan.idx, plan.cnt, None, None, self.prm, seq_len=self.seq, A=plan.A)
+        else:
+            st = ta.DecodeState(w.layers, w.batch, w.hq, w.hkv, budget, cap, dev)
+            ta.ta_decode_init(st, self.tok, plan.anchor, plan.idx, plan.cnt, plan.Kout, plan.Vout, self.prm, seq_len=self.seq, A=plan.A)
         warm = min(8, nsteps)
         toks = torch.from_numpy(wl.make_decode_stream(w, td, warm + nsteps, p_anchor=0.02)).to(dev)
         q1, k1, v1 = wl.make_decode_qkv(w, 0, device=dev)
@@ -267,7 +287,9 @@ class Bench:
         torch.cuda.synchronize()
         step_us = d0.elapsed_time(d1) * 1e3 / nsteps
         row_bytes = self.units * (budget + 1) * w.d * 2              # every slot's key row once per step
-        return {"us_per_step": round(step_us, 1), "steps": nsteps, "units": self.units, "slots": budget + 1,
+        paged = {} if page_size <= 0 else {"slot_page_size": page_size, "compact_into_pages_us": round(into_us, 1),
+                                           "compact_into_pages_GB/s": round(self.compact_b / into_us / 1e3, 1)}
+        return {**paged, "us_per_step": round(step_us, 1), "steps": nsteps, "units": self.units, "slots": budget + 1,
                 "key_rows_GB/s": round(row_bytes / step_us / 1e3, 1),
                 "hbm_frac": round(row_bytes / step_us / 1e3 / HBM_PEAK_GBS, 4),
                 "roofline": {"kernel": "decode_unit_kernel (+ the per-sequence kernels of the step)", "bound": "hbm",
@@ -370,7 +392,8 @@ class Bench:
         return cpu, parity
 
 
-def measure_extra(ta, wl, torch, np, name, budget, dev, steps, warmup, copies=1, decode_steps=0, oracle_s=0.0):
+def measure_extra(ta, wl, torch, np, name, budget, dev, steps, warmup, copies=1, decode_steps=0, oracle_s=0.0,
+                  decode_page_size=0):
     """One of the other workloads as a sub-object of the line."""
     w = wl.CONFIGS[name]
     b = Bench(ta, wl, torch, np, w, budget, dev, copies=copies)
@@ -389,6 +412,8 @@ def measure_extra(ta, wl, torch, np, name, budget, dev, steps, warmup, copies=1,
         b.plan.run(b.stream)
         torch.cuda.synchronize()
         extra = b.decode_step(decode_steps)
+        if decode_page_size > 0:
+            extra["paged_slots"] = b.decode_step(decode_steps, decode_page_size)
     if oracle_s > 0:
         b.plan.run(b.stream)
         torch.cuda.synchronize()
@@ -416,6 +441,9 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="also time this many generation steps of the incremental form after the pass "
                          "(needs a scored workload; reported as decode_step)")
+    ap.add_argument("--decode-paged", type=int, default=0, metavar="PAGE_SIZE",
+                    help="with --decode-steps: keep the state's K/V slots in a page pool of this page size (rows "
+                         "compacted straight into the pages, state initialised in place)")
     ap.add_argument("--score-lse", action="store_true",
                     help="also time the one-sweep score from given row log-sum-exps (what a flash-style prefill "
                          "kernel leaves behind; computed here with torch, outside the timing; reported as score_one_sweep; "
@@ -584,7 +612,7 @@ def main():
     if args.decode_steps > 0 and scored:
         plan.run(stream)                                        # the state starts from the outputs of a pass at this budget
         torch.cuda.synchronize()
-        decode = bench.decode_step(args.decode_steps)
+        decode = bench.decode_step(args.decode_steps, args.decode_paged)
 
     # ---- anchor match + voucher expansion alone on a shape that is bound by memory ---------------
     match_stress = None
@@ -711,7 +739,7 @@ def main():
         workloads["c2_full_model"] = c2
         workloads["c3_ta_fast"], _ = measure_extra(ta, wl, torch, np, "c3_ta_fast", 512, dev, st, wu, oracle_s=2 * ora_s)
         workloads["c5_agentic_prefill"], workloads["c5_agentic_decode_step"] = measure_extra(
-            ta, wl, torch, np, "c5_agentic_prefill", 256, dev, st, wu, decode_steps=32, oracle_s=4 * ora_s)
+            ta, wl, torch, np, "c5_agentic_prefill", 256, dev, st, wu, decode_steps=32, oracle_s=4 * ora_s, decode_page_size=16)
 
     out = {
         "metric": "evict+compact GB/s of KV",

@@ -16,11 +16,15 @@
  *      ta_evict_lse
  *      ta_score_paged /  steps 3 and 5, and the whole pass, over paged (block-table) caches
  *      ta_compact_paged / ta_evict_paged
+ *      ta_compact_into_pages  step 5 writing its rows into the pages of a block table
  *      ta_evict          all of the above in one call
  *      ta_evict_layers / the same over caches that are one tensor (or one page pool)
  *      ta_evict_layers_paged  per layer
  *      ta_decode_init /  the same policy applied after every generation step
- *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets)
+ *      ta_decode_step    (append, accumulate attention, evict one row, decay budgets),
+ *                        over dense slots or slots in a page pool
+ *      ta_evict_static / ta_evict with its scratch in a static device buffer, for callers
+ *      ta_init           that cannot allocate
  *
  * Conventions shared by every entry point
  *   - Pointers marked DEVICE are GPU global memory owned by the caller;
@@ -363,6 +367,22 @@ int32_t ta_compact_paged(const void *Kpool, const void *Vpool, const ta_paged_kv
                          int32_t idx_shared, void *Kout, void *Vout, void *stream);
 
 /*
+ * Step 5 straight into a page pool (Sec. 3.2 "Token selection" on the block-table caches of serving
+ * engines): the r-th retained row of unit (l, b, g) is written to slot r of sequence b's pages in the
+ * destination pool,
+ *   Kdst[l*dst->stride[0] + dst->block_table[b][r / ps]*dst->stride[1] + (r % ps)*dst->stride[2] + g*dst->stride[3]]
+ * (ps = dst->page_size, dst->max_pages * ps >= K), Vdst likewise: the layout a paged ta_decode_state
+ * reads, so the generation steps can start from these pages without another copy.
+ * The source is dense (`src` NULL, strides from lay->kv_stride) or paged (`src`).  Source and
+ * destination may be the same pool as long as no destination page holds source rows of the call:
+ * pages are read and written in no fixed order.
+ * Errors: as ta_compact_paged for both descriptions; SHAPE if dst->max_pages * ps < K.
+ */
+int32_t ta_compact_into_pages(const void *Kin, const void *Vin, const ta_paged_kv *src,
+                              const int32_t *idx, const int32_t *cnt, const ta_layout *lay, int32_t K,
+                              int32_t idx_shared, void *Kdst, void *Vdst, const ta_paged_kv *dst, void *stream);
+
+/*
  * The whole pass with the one-sweep score of ta_score_lse: as ta_evict for prm->alpha != 0,
  * with the row log-sum-exps of the prefill attention kernel in place of the workspace.
  * Errors: as ta_evict; SHAPE when prm->alpha == 0.
@@ -457,6 +477,14 @@ int32_t ta_evict_layers_paged(const int32_t *tok, const int32_t *seq_len,
  * A unit keeps at most K rows; the extra slot receives the next token.  Slots
  * are stable: an evicted slot is reused, rows are never moved (keys are stored
  * with their positional encoding, so slot order does not matter to attention).
+ *
+ * `pages` (HOST pointer, NULL = the dense layout above) keeps the K/V slots in a paged pool, the
+ * cache layout of serving engines (see ta_paged_kv): Kc and Vc are then the pools, and slot s of
+ * KV head g of sequence b in layer l starts at element
+ *   l*stride[0] + block_table[b][s / page_size]*stride[1] + (s % page_size)*stride[2] + g*stride[3];
+ * max_pages * page_size >= K + 1; table entries are clamped to the pool on the device.  pos and A
+ * stay dense.  Every sequence needs pages of its own (a page shared by two sequences would be
+ * written by both).
  */
 typedef struct ta_decode_state {
     int32_t layers, batch, hq, hkv, d;
@@ -472,6 +500,7 @@ typedef struct ta_decode_state {
     int32_t *pos;
     float *A;
     int32_t *stepped;
+    const ta_paged_kv *pages;
 } ta_decode_state;
 
 #define TA_MAX_DECODE_K 2047
@@ -487,8 +516,12 @@ typedef struct ta_decode_state {
  *   anchor_B float [batch][n] or NULL, A float [layers][batch][hkv][n] or NULL,
  *   idx int32 [layers][batch][hkv][K], cnt int32 [layers][batch][hkv],
  *   Kout, Vout bf16 [layers][batch][hkv][K][d]           (all DEVICE)
+ * With a paged state (st->pages) Kout and Vout may both be NULL: the retained rows are then taken
+ * to be in place already - row r of a unit in its slot r, as ta_compact_into_pages leaves them -
+ * and only positions and attention are filled in.
  * Errors: NULL, SHAPE (n > cap, K out of range, d != 128, hq % hkv != 0, more than 16 query
- * heads per KV head, (hq/hkv) * (K + 1) > 15360), ALIGN.
+ * heads per KV head, (hq/hkv) * (K + 1) > 15360; paged: sizes and strides as in ta_paged_kv,
+ * max_pages * page_size < K + 1), ALIGN.
  */
 int32_t ta_decode_init(const ta_decode_state *st, const int32_t *tok, const int32_t *seq_len, int32_t n,
                        const uint8_t *anchor, const float *anchor_B, const float *A,

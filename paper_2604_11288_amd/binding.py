@@ -29,7 +29,7 @@ TA_ERR_WORKSPACE, TA_ERR_ALIGN, TA_ERR_HIP, TA_ERR_SCRATCH = -4, -5, -6, -7
 TA_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ("ta_workspace_bytes", "ta_match_anchors", "ta_detect_anchors", "ta_expand_vouchers", "ta_embed_anchors",
-           "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged",
+           "ta_lookup_anchors", "ta_layer_budgets", "ta_score", "ta_score_lse", "ta_score_paged", "ta_select", "ta_compact", "ta_compact_paged", "ta_compact_into_pages",
            "ta_evict", "ta_evict_static", "ta_evict_lse", "ta_evict_paged", "ta_evict_layers", "ta_evict_layers_paged", "ta_decode_init", "ta_decode_step", "ta_init", "ta_strerror", "ta_last_hip_error")
 
 
@@ -57,7 +57,8 @@ class CDecodeState(ctypes.Structure):
                 ("tok", ctypes.c_void_p), ("len", ctypes.c_void_p), ("anchor", ctypes.c_void_p),
                 ("budget", ctypes.c_void_p), ("vouch", ctypes.c_void_p), ("spons", ctypes.c_void_p),
                 ("Kc", ctypes.c_void_p), ("Vc", ctypes.c_void_p),
-                ("pos", ctypes.c_void_p), ("A", ctypes.c_void_p), ("stepped", ctypes.c_void_p)]
+                ("pos", ctypes.c_void_p), ("A", ctypes.c_void_p), ("stepped", ctypes.c_void_p),
+                ("pages", ctypes.c_void_p)]
 
 
 class CLayout(ctypes.Structure):
@@ -138,6 +139,8 @@ def lib():
         L.ta_compact_paged.restype = i32
         L.ta_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         L.ta_select.restype = i32
+        L.ta_compact_into_pages.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        L.ta_compact_into_pages.restype = i32
         L.ta_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.ta_compact.restype = i32
         L.ta_evict.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32,
@@ -417,6 +420,24 @@ def ta_compact_paged(paged: PagedKV, idx, cnt, K: int, idx_shared: bool = False,
     return Kout, Vout
 
 
+def ta_compact_into_pages(Kin, Vin, idx, cnt, K: int, dst: PagedKV, src: Optional[PagedKV] = None,
+                          idx_shared: bool = False, stream=None):
+    """Step 5 straight into a page pool: row r of a unit goes to slot r of its sequence's pages in
+    dst.Kpool / dst.Vpool.  The source is the dense pair (Kin, Vin), or the paged cache `src`
+    (then Kin and Vin are ignored)."""
+    if src is not None:
+        lay, spg = src.layout(), src.c()
+        Kin, Vin = src.Kpool, src.Vpool
+    else:
+        lay, spg = layout_of(Kin), None
+    dpg = dst.c()
+    rc = lib().ta_compact_into_pages(_ptr(Kin), _ptr(Vin), None if spg is None else ctypes.byref(spg), _ptr(idx), _ptr(cnt),
+                                     ctypes.byref(lay), K, 1 if idx_shared else 0, _ptr(dst.Kpool), _ptr(dst.Vpool),
+                                     ctypes.byref(dpg), _stream(stream))
+    _check(rc, "ta_compact_into_pages")
+    return dst
+
+
 def ta_select(A, anchor, spons, vouch, K: int, params: Params, layers: int, hkv: int,
               seq_len=None, out=None, stream=None):
     """Step 4.  Returns (idx i32 [layers][B][hkv][K], cnt i32 [layers][B][hkv])."""
@@ -688,8 +709,12 @@ def ta_evict_layers(tok, tab_ids, tab_len, Q_layers, K_layers, V_layers, K: int,
 class DecodeState:
     """Device tensors of the incremental pass (see ta_decode_state in include/ta.h)."""
 
-    def __init__(self, layers, batch, hq, hkv, K, cap, device, d=TA_HEAD_DIM):
+    def __init__(self, layers, batch, hq, hkv, K, cap, device, d=TA_HEAD_DIM, pages: Optional["PagedKV"] = None):
+        """pages: a PagedKV whose pools hold the K/V slots (slot s of a unit is position s of its addressing;
+        max_pages * page_size >= K + 1); None: dense [layers][batch][hkv][K+1][d] tensors allocated here."""
         self.layers, self.batch, self.hq, self.hkv, self.K, self.cap, self.d = layers, batch, hq, hkv, K, cap, d
+        self.pages = pages
+        self._cpages = None if pages is None else pages.c()
         i32, dev = torch.int32, device
         self.tok = torch.zeros((batch, cap), dtype=i32, device=dev)
         self.len = torch.zeros((batch,), dtype=i32, device=dev)
@@ -697,8 +722,11 @@ class DecodeState:
         self.budget = torch.zeros((batch, cap), dtype=torch.float32, device=dev)
         self.vouch = torch.zeros((batch, cap), dtype=torch.float32, device=dev)
         self.spons = torch.zeros((batch, cap), dtype=torch.uint8, device=dev)
-        self.Kc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
-        self.Vc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
+        if pages is None:
+            self.Kc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
+            self.Vc = torch.zeros((layers, batch, hkv, K + 1, d), dtype=torch.bfloat16, device=dev)
+        else:
+            self.Kc, self.Vc = pages.Kpool, pages.Vpool
         self.pos = torch.full((layers, batch, hkv, K + 1), -1, dtype=i32, device=dev)
         self.A = torch.zeros((layers, batch, hkv, K + 1), dtype=torch.float32, device=dev)
         self.stepped = torch.zeros((batch,), dtype=i32, device=dev)
@@ -708,7 +736,8 @@ class DecodeState:
                             self.tok.data_ptr(), self.len.data_ptr(), self.anchor.data_ptr(),
                             self.budget.data_ptr(), self.vouch.data_ptr(), self.spons.data_ptr(),
                             self.Kc.data_ptr(), self.Vc.data_ptr(),
-                            self.pos.data_ptr(), self.A.data_ptr(), self.stepped.data_ptr())
+                            self.pos.data_ptr(), self.A.data_ptr(), self.stepped.data_ptr(),
+                            None if self._cpages is None else ctypes.addressof(self._cpages))
 
 
 def ta_decode_init(state: DecodeState, tok, anchor, idx, cnt, Kout, Vout, params: Params,

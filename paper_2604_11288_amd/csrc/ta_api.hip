@@ -157,8 +157,10 @@ int32_t check_select(const float* A, const uint8_t* anchor, const uint8_t* spons
     return check_budget(prm, K);
 }
 
+// `same_pool_ok`: the outputs are page pools that may be the input pools (the caller keeps source and
+// destination pages apart); otherwise outputs must not alias the inputs.
 int32_t check_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
-                      const ta_layout* lay, int32_t K, const void* Kout, const void* Vout)
+                      const ta_layout* lay, int32_t K, const void* Kout, const void* Vout, bool same_pool_ok = false)
 {
     int32_t rc = check_layout(lay, false);
     if (rc != TA_OK) return rc;
@@ -166,7 +168,8 @@ int32_t check_compact(const void* Kin, const void* Vin, const int32_t* idx, cons
     if (K < 1) return TA_ERR_SHAPE;
     if (!aligned16(Kin) || !aligned16(Vin) || !aligned16(Kout) || !aligned16(Vout)) return TA_ERR_ALIGN;
     // outputs must not alias the inputs or each other: workgroups read and write rows in no fixed order
-    if (Kout == Kin || Kout == Vin || Vout == Kin || Vout == Vin || Kout == Vout) return TA_ERR_SHAPE;
+    if (Kout == Vout || Kout == Vin || Vout == Kin) return TA_ERR_SHAPE;
+    if (!same_pool_ok && (Kout == Kin || Vout == Vin)) return TA_ERR_SHAPE;
     const int64_t units = (int64_t)lay->layers * lay->batch * lay->hkv;
     if (units * ((K + 63) / 64) > 0x7FFFFFFFll) return TA_ERR_SHAPE;
     return TA_OK;
@@ -186,6 +189,17 @@ int32_t check_decode_state(const ta_decode_state* st)
     if (st->cap < 1 || st->cap >= (1 << 30) || st->batch > 65535) return TA_ERR_SHAPE;
     if ((int64_t)st->layers * st->batch * st->hkv > (1 << 24)) return TA_ERR_SHAPE;
     if (!aligned16(st->Kc) || !aligned16(st->Vc)) return TA_ERR_ALIGN;
+    if (st->pages) {                                       // K/V slots in a paged pool
+        const ta_paged_kv* pg = st->pages;
+        if (!pg->block_table) return TA_ERR_NULL;
+        if (pg->page_size < 1 || pg->max_pages < 1 || pg->num_pages < 1) return TA_ERR_SHAPE;
+        if ((int64_t)pg->max_pages * pg->page_size < (int64_t)st->K + 1) return TA_ERR_SHAPE;
+        for (int i = 0; i < 4; ++i) {
+            if (pg->stride[i] < 0) return TA_ERR_SHAPE;
+            if (pg->stride[i] % 8 != 0) return TA_ERR_ALIGN;
+        }
+        if (pg->stride[2] < st->d) return TA_ERR_SHAPE;
+    }
     return TA_OK;
 }
 
@@ -506,6 +520,29 @@ int32_t ta_compact_paged(const void* Kpool, const void* Vpool, const ta_paged_kv
                                          nullptr, (hipStream_t)stream));
 }
 
+int32_t ta_compact_into_pages(const void* Kin, const void* Vin, const ta_paged_kv* src,
+                              const int32_t* idx, const int32_t* cnt, const ta_layout* lay, int32_t K,
+                              int32_t idx_shared, void* Kdst, void* Vdst, const ta_paged_kv* dst, void* stream)
+{
+    if (!dst || !lay) return TA_ERR_NULL;
+    ta_layout dense = *lay;
+    int32_t rc = TA_OK;
+    if (src) {
+        rc = check_paged(src, lay, &dense, false);
+        if (rc != TA_OK) return rc;
+    }
+    ta_layout dst_sized = *lay;                             // the destination holds K slots per unit, not n positions
+    dst_sized.n = K < 1 ? 1 : K;
+    ta_layout unused;
+    rc = check_paged(dst, &dst_sized, &unused, false);
+    if (rc != TA_OK) return rc;
+    // the shared checks of step 5; a destination pool may be the source pool (distinct pages: the caller's contract)
+    rc = check_compact(Kin, Vin, idx, cnt, &dense, K, Kdst, Vdst, src != nullptr);
+    if (rc != TA_OK) return rc;
+    return hip_status(ta::launch_compact(Kin, Vin, idx, cnt, dense, K, idx_shared, Kdst, Vdst, src, nullptr,
+                                         (hipStream_t)stream, dst));
+}
+
 int32_t ta_evict(const int32_t* tok, const int32_t* seq_len,
                  const int32_t* tab_ids, const int32_t* tab_len, int32_t E, const float* anchor_B,
                  const void* Q, const void* Kin, const void* Vin,
@@ -602,7 +639,8 @@ int32_t ta_decode_init(const ta_decode_state* st, const int32_t* tok, const int3
     if (rc != TA_OK) return rc;
     rc = check_decode_state(st);
     if (rc != TA_OK) return rc;
-    if (!tok || !anchor || !idx || !cnt || !Kout || !Vout) return TA_ERR_NULL;
+    if (!tok || !anchor || !idx || !cnt) return TA_ERR_NULL;
+    if ((!Kout || !Vout) && !(st->pages && !Kout && !Vout)) return TA_ERR_NULL;   // both, or (paged, rows in place) neither
     if (n < 1 || n > st->cap) return TA_ERR_SHAPE;
     if (!aligned16(Kout) || !aligned16(Vout)) return TA_ERR_ALIGN;
     return hip_status(ta::launch_decode_init(*st, tok, seq_len, n, anchor, anchor_B, A, idx, cnt, Kout, Vout,

@@ -40,6 +40,10 @@ struct CompactArgs {
     const uint4* const* Vin_l;
     uint4* const* Kout_l;
     uint4* const* Vout_l;
+    // paged output: row r of a unit goes to slot r of its sequence's pages in the destination pools
+    const int32_t* d_table;
+    int64_t d_layer, d_page, d_pos, d_head;    // destination strides in 16-byte units
+    int32_t d_page_size, d_max_pages, d_num_pages;
 };
 
 // marks a pointer read from a device table as a global address (else it is accessed with flat instructions)
@@ -50,7 +54,7 @@ __device__ __forceinline__ T* global_ptr(T* p)
     return (T*)(gp)(uintptr_t)p;
 }
 
-template <bool PAGED, bool LAYERED>
+template <bool PAGED, bool LAYERED, bool DST_PAGED = false>
 __global__ void __launch_bounds__(COMPACT_THREADS)
 compact_kernel(CompactArgs a)
 {
@@ -98,7 +102,13 @@ compact_kernel(CompactArgs a)
     const u32x4 v2 = __builtin_nontemporal_load(&Vin[o2]), v3 = __builtin_nontemporal_load(&Vin[o3]);
     auto put = [&](int32_t r, const u32x4& kk, const u32x4& vv) {
         if (r < cnt) {
-            const int64_t off = out_base + (int64_t)r * 16 + lane16;
+            int64_t off = out_base + (int64_t)r * 16 + lane16;
+            if (DST_PAGED) {
+                const int32_t slot = r / a.d_page_size;
+                int32_t page = a.d_table[(size_t)b * a.d_max_pages + slot];
+                page = page < 0 ? 0 : (page >= a.d_num_pages ? a.d_num_pages - 1 : page);
+                off = l * a.d_layer + (int64_t)page * a.d_page + (int64_t)(r - slot * a.d_page_size) * a.d_pos + h * a.d_head + lane16;
+            }
             __builtin_nontemporal_store(kk, &Kout[off]);
             __builtin_nontemporal_store(vv, &Vout[off]);
         }
@@ -158,9 +168,18 @@ hipError_t launch_layer_table(const LayerPtrs& host_table, LayerPtrs* dev_table,
 
 hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
                           const ta_layout& lay, int32_t K, int32_t idx_shared,
-                          void* Kout, void* Vout, const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st)
+                          void* Kout, void* Vout, const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st,
+                          const ta_paged_kv* dst_pg)
 {
     CompactArgs a;
+    a.d_table = dst_pg ? dst_pg->block_table : nullptr;
+    a.d_layer = dst_pg ? dst_pg->stride[0] / 8 : 0;
+    a.d_page = dst_pg ? dst_pg->stride[1] / 8 : 0;
+    a.d_pos = dst_pg ? dst_pg->stride[2] / 8 : 0;
+    a.d_head = dst_pg ? dst_pg->stride[3] / 8 : 0;
+    a.d_page_size = dst_pg ? dst_pg->page_size : 1;
+    a.d_max_pages = dst_pg ? dst_pg->max_pages : 0;
+    a.d_num_pages = dst_pg ? dst_pg->num_pages : 0;
     a.Kin_l = lp ? reinterpret_cast<const uint4* const*>(&lp->K[0]) : nullptr;
     a.Vin_l = lp ? reinterpret_cast<const uint4* const*>(&lp->V[0]) : nullptr;
     a.Kout_l = lp ? reinterpret_cast<uint4* const*>(&lp->Kout[0]) : nullptr;
@@ -199,7 +218,9 @@ hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, 
     int64_t units = (int64_t)lay.layers * lay.batch * lay.hkv;
     int64_t blocks = units * a.blocks_per_unit;
     const dim3 grid((unsigned)blocks), block(COMPACT_THREADS);
-    if (pg && lp) hipLaunchKernelGGL((compact_kernel<true, true>), grid, block, 0, st, a);
+    if (dst_pg && pg) hipLaunchKernelGGL((compact_kernel<true, false, true>), grid, block, 0, st, a);
+    else if (dst_pg) hipLaunchKernelGGL((compact_kernel<false, false, true>), grid, block, 0, st, a);
+    else if (pg && lp) hipLaunchKernelGGL((compact_kernel<true, true>), grid, block, 0, st, a);
     else if (pg) hipLaunchKernelGGL((compact_kernel<true, false>), grid, block, 0, st, a);
     else if (lp) hipLaunchKernelGGL((compact_kernel<false, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((compact_kernel<false, false>), grid, block, 0, st, a);

@@ -36,6 +36,24 @@ struct DecodeTable {
     float B;
 };
 
+// K/V slots kept in a paged pool (ta_decode_state::pages): strides in 16-byte units.
+struct SlotPages {
+    const int32_t* table;                                  // [batch][max_pages]
+    int64_t s_layer, s_page, s_slot, s_head;
+    int32_t page_size, max_pages, num_pages;
+    int32_t page_shift;                                    // log2(page_size) when it is a power of two, else -1
+};
+
+__device__ __forceinline__ int32_t page_index(const SlotPages& pg, int32_t slot)
+{
+    return pg.page_shift >= 0 ? slot >> pg.page_shift : slot / pg.page_size;
+}
+
+__device__ __forceinline__ int32_t clamp_page(const SlotPages& pg, int32_t page)
+{
+    return page < 0 ? 0 : (page >= pg.num_pages ? pg.num_pages - 1 : page);
+}
+
 // ---- state initialisation -----------------------------------------------------
 __global__ void decode_init_seq_kernel(ta_decode_state st, const int32_t* tok, const int32_t* seq_len, int32_t n,
                                        const uint8_t* anchor, const float* anchor_B, float B)
@@ -60,9 +78,10 @@ __global__ void decode_init_seq_kernel(ta_decode_state st, const int32_t* tok, c
     }
 }
 
+template <bool PAGED>
 __global__ void __launch_bounds__(DU_THREADS)
 decode_init_unit_kernel(ta_decode_state st, int32_t n, const float* A, const int32_t* idx, const int32_t* cnt,
-                        const uint4* Kout, const uint4* Vout)
+                        const uint4* Kout, const uint4* Vout, SlotPages pg)
 {
     const int unit = blockIdx.x;
     const int slots = st.K + 1;
@@ -79,9 +98,26 @@ decode_init_unit_kernel(ta_decode_state st, int32_t n, const float* A, const int
         st.pos[(size_t)unit * slots + s] = p;
         st.A[(size_t)unit * slots + s] = a;
     }
+    if (!Kout) return;                                     // paged state whose rows are in place already
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    if (PAGED) {
+        const int g = unit % st.hkv;
+        const int b = (unit / st.hkv) % st.batch;
+        const int l = unit / (st.hkv * st.batch);
+        uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + l * pg.s_layer + g * pg.s_head;
+        uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + l * pg.s_layer + g * pg.s_head;
+        for (int i = threadIdx.x; i < slots * 16; i += DU_THREADS) {
+            const int s = i >> 4;
+            const int32_t j = page_index(pg, s);
+            const int32_t page = clamp_page(pg, pg.table[(size_t)b * pg.max_pages + j]);
+            const int64_t at = (int64_t)page * pg.s_page + (int64_t)(s - j * pg.page_size) * pg.s_slot + (i & 15);
+            Kc[at] = s < c ? Kout[(size_t)unit * st.K * 16 + i] : zero;
+            Vc[at] = s < c ? Vout[(size_t)unit * st.K * 16 + i] : zero;
+        }
+        return;
+    }
     uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (size_t)unit * slots * 16;
     uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (size_t)unit * slots * 16;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
     for (int i = threadIdx.x; i < slots * 16; i += DU_THREADS) {
         const int s = i >> 4;
         Kc[i] = s < c ? Kout[(size_t)unit * st.K * 16 + i] : zero;
@@ -166,6 +202,7 @@ struct UnitArgs {
     float alpha, beta, gamma;
     float scale_log2;
     int32_t last_query;                                    // 1: A holds this step's attention, not the running sum
+    int32_t pg_off;                                        // paged slots: offset (in floats) of the page list in the wavefront's LDS
 };
 
 __device__ __forceinline__ uint32_t ordered_bits(float u)
@@ -225,9 +262,9 @@ __device__ __forceinline__ s16x4 hi_half(const uint4& v)
 // One wavefront per unit, no workgroup barriers: the step of a unit is a chain of short
 // phases, and what hides their latency is the number of units in flight per compute unit.
 // LDS (private to the wavefront): slot table, accumulated attention, [G][slots] logits.
-template <int GH>                                         // query heads per KV head the loops are unrolled for
+template <int GH, bool PAGED>                             // query heads per KV head the loops are unrolled for; K/V slots in pages
 __global__ void __launch_bounds__(64)
-decode_unit_kernel(ta_decode_state st, UnitArgs a)
+decode_unit_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 {
     extern __shared__ float s_dyn[];
 
@@ -243,9 +280,22 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
     const int32_t p_new = len_new - 1;
     int32_t* pos = st.pos + (size_t)unit * slots;
     float* A = st.A + (size_t)unit * slots;
-    uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (size_t)unit * slots * 16;
-    uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (size_t)unit * slots * 16;
+    uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (PAGED ? l * pg.s_layer + g * pg.s_head : (int64_t)unit * slots * 16);
+    uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (PAGED ? l * pg.s_layer + g * pg.s_head : (int64_t)unit * slots * 16);
     const bool scored = a.alpha != 0.0f;
+    // Paged slots: the pages of this unit's slots go to LDS first (one dependent round trip through
+    // the L2 per unit), so that a row's address afterwards costs an LDS read and no memory access.
+    int32_t* s_pg = reinterpret_cast<int32_t*>(s_dyn + a.pg_off);
+    if (PAGED) {
+        const int npg = page_index(pg, slots - 1) + 1;
+        for (int j = lane; j < npg; j += 64) s_pg[j] = clamp_page(pg, pg.table[(size_t)b * pg.max_pages + j]);
+        __builtin_amdgcn_wave_barrier();
+    }
+    const auto row_at = [&](int row) -> int64_t {           // 16-byte index of a slot's first chunk
+        if (!PAGED) return (int64_t)row * 16;
+        const int32_t j = page_index(pg, row);
+        return (int64_t)s_pg[j] * pg.s_page + (int64_t)(row - j * pg.page_size) * pg.s_slot;
+    };
     int32_t* s_pos = reinterpret_cast<int32_t*>(s_dyn);
     float* s_A = s_dyn + slots;
     const int wstride = (slots + 3) & ~3;                  // logits of a head: padded to whole 16-byte groups
@@ -271,7 +321,7 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
         for (int t = 0; t < 4; ++t) {
             int row = tile * 16 + 4 * t + grp;
             row = row < slots ? row : slots - 1;           // past the last slot: a valid row, masked at the store
-            dst[t] = Kc[row * 16 + sub];
+            dst[t] = Kc[row_at(row) + sub];
         }
     };
     if (scored) {
@@ -314,8 +364,8 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
     }
     const uint4* kn = a.k_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
     const uint4* vn = a.v_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
-    if (lane < 16) Kc[f * 16 + lane] = kn[lane];
-    else if (lane < 32) Vc[f * 16 + lane - 16] = vn[lane - 16];
+    if (lane < 16) Kc[row_at(f) + lane] = kn[lane];
+    else if (lane < 32) Vc[row_at(f) + lane - 16] = vn[lane - 16];
     __builtin_amdgcn_wave_barrier();                       // the slot table is in LDS for every lane
 
     // ---- attention of the group's decode queries over the occupied slots ----------
@@ -474,19 +524,55 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a)
 
 DeviceOnce g_setup;
 
+SlotPages slot_pages(const ta_decode_state& st)
+{
+    SlotPages pg = {};
+    pg.page_size = 1;
+    pg.page_shift = -1;
+    if (st.pages) {
+        const ta_paged_kv& p = *st.pages;
+        pg.table = p.block_table;
+        pg.s_layer = p.stride[0] / 8;
+        pg.s_page = p.stride[1] / 8;
+        pg.s_slot = p.stride[2] / 8;
+        pg.s_head = p.stride[3] / 8;
+        pg.page_size = p.page_size;
+        pg.max_pages = p.max_pages;
+        pg.num_pages = p.num_pages;
+        if ((p.page_size & (p.page_size - 1)) == 0) {
+            pg.page_shift = 0;
+            while ((1 << pg.page_shift) < p.page_size) ++pg.page_shift;
+        }
+    }
+    return pg;
+}
+
+template <int GH>
+hipError_t unit_attributes()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<GH, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<GH, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return e;
+}
+
+template <int GH>
+void launch_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg, unsigned units, size_t lds, hipStream_t s)
+{
+    if (st.pages) hipLaunchKernelGGL((decode_unit_kernel<GH, true>), dim3(units), dim3(64), lds, s, st, a, pg);
+    else hipLaunchKernelGGL((decode_unit_kernel<GH, false>), dim3(units), dim3(64), lds, s, st, a, pg);
+}
+
 }  // namespace
 
 hipError_t decode_setup()
 {
     return g_setup.run([](int) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<4>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<8>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<MAX_GROUP>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipError_t e = unit_attributes<4>();
+        if (e == hipSuccess) e = unit_attributes<8>();
+        if (e == hipSuccess) e = unit_attributes<MAX_GROUP>();
         return e;
     });
 }
@@ -499,8 +585,13 @@ hipError_t launch_decode_init(const ta_decode_state& st, const int32_t* tok, con
     dim3 g1((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
     hipLaunchKernelGGL(decode_init_seq_kernel, g1, dim3(256), 0, s, st, tok, seq_len, n, anchor, anchor_B, B);
     const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
-    hipLaunchKernelGGL(decode_init_unit_kernel, dim3(units), dim3(DU_THREADS), 0, s, st, n, A, idx, cnt,
-                       (const uint4*)Kout, (const uint4*)Vout);
+    const SlotPages pg = slot_pages(st);
+    if (st.pages)
+        hipLaunchKernelGGL(decode_init_unit_kernel<true>, dim3(units), dim3(DU_THREADS), 0, s, st, n, A, idx, cnt,
+                           (const uint4*)Kout, (const uint4*)Vout, pg);
+    else
+        hipLaunchKernelGGL(decode_init_unit_kernel<false>, dim3(units), dim3(DU_THREADS), 0, s, st, n, A, idx, cnt,
+                           (const uint4*)Kout, (const uint4*)Vout, pg);
     return hipGetLastError();
 }
 
@@ -539,14 +630,17 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     const int G = st.hq / st.hkv;
     const int slots = st.K + 1;
     // slot table and accumulated attention; with an attention term also one key tile and the logits
-    const size_t lds = (prm.alpha != 0.0f ? (size_t)((2 * slots + 3) & ~3) + 1024 + (size_t)G * ((slots + 3) & ~3) : (size_t)2 * slots) *
-                       sizeof(float);
+    size_t lds_floats = prm.alpha != 0.0f ? (size_t)((2 * slots + 3) & ~3) + 1024 + (size_t)G * ((slots + 3) & ~3) : (size_t)2 * slots;
+    const SlotPages pg = slot_pages(st);
+    a.pg_off = (int32_t)lds_floats;
+    if (st.pages) lds_floats += (size_t)((slots - 1) / pg.page_size + 1);      // the pages of the unit's slots
+    const size_t lds = lds_floats * sizeof(float);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     const hipError_t attr_err = decode_setup();            // dynamic LDS above 64 KB (large budgets) needs the attribute
     if (attr_err != hipSuccess) return attr_err;
-    if (G <= 4) hipLaunchKernelGGL(decode_unit_kernel<4>, dim3(units), dim3(64), lds, s, st, a);
-    else if (G <= 8) hipLaunchKernelGGL(decode_unit_kernel<8>, dim3(units), dim3(64), lds, s, st, a);
-    else hipLaunchKernelGGL(decode_unit_kernel<MAX_GROUP>, dim3(units), dim3(64), lds, s, st, a);
+    if (G <= 4) launch_unit<4>(st, a, pg, units, lds, s);
+    else if (G <= 8) launch_unit<8>(st, a, pg, units, lds, s);
+    else launch_unit<MAX_GROUP>(st, a, pg, units, lds, s);
 
     dim3 g3((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
     hipLaunchKernelGGL(decode_decay_kernel, g3, dim3(256), 0, s, st, prm.budget_decay);

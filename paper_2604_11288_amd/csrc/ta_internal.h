@@ -119,9 +119,11 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
 
 // ---- compact ----------------------------------------------------------------
 // `lp` != null: layer l reads lp->K[l], lp->V[l] and writes lp->Kout[l], lp->Vout[l].
+// `dst_pg` != null: the outputs are page pools, row r of a unit goes to slot r of its sequence's pages.
 hipError_t launch_compact(const void* Kin, const void* Vin, const int32_t* idx, const int32_t* cnt,
                           const ta_layout& lay, int32_t K, int32_t idx_shared,
-                          void* Kout, void* Vout, const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st);
+                          void* Kout, void* Vout, const ta_paged_kv* pg, const LayerPtrs* lp, hipStream_t st,
+                          const ta_paged_kv* dst_pg = nullptr);
 
 // ---- incremental (decode) form ------------------------------------------------
 hipError_t launch_decode_init(const ta_decode_state& st, const int32_t* tok, const int32_t* seq_len, int32_t n,

@@ -298,3 +298,23 @@ def make_paged(K: torch.Tensor, V: torch.Tensor, page_size: int, heads_first: bo
     else:
         strides = (num_pages * page_size * H * d, page_size * H * d, H * d, d)
     return pools[0], pools[1], torch.from_numpy(table).to(K.device), num_pages, strides
+
+
+def make_slot_pool(layers: int, batch: int, hkv: int, d: int, slots: int, page_size: int, device, heads_first: bool = False,
+                   spare_pages: int = 5, seed: int = BASE_SEED + 19):
+    """Empty page pools for `slots` cache slots per (sequence, head): every sequence's pages at random
+    places of a pool that also holds spare pages, junk values everywhere.  Pools are
+    [Lyr][pages][page_size][Hkv][d], or [Lyr][pages][Hkv][page_size][d] with heads_first.  Returns
+    (Kpool, Vpool, table int32 [B][max_pages] as a numpy array, num_pages, element strides
+    (layer, page, position, head)).  Pure allocation."""
+    max_pages = (slots + page_size - 1) // page_size
+    num_pages = batch * max_pages + spare_pages
+    table = np.random.default_rng(seed).permutation(num_pages)[: batch * max_pages].astype(np.int32).reshape(batch, max_pages)
+    shape = (layers, num_pages, hkv, page_size, d) if heads_first else (layers, num_pages, page_size, hkv, d)
+    Kp = torch.full(shape, 3.0, dtype=torch.bfloat16, device=device)
+    Vp = torch.full(shape, -5.0, dtype=torch.bfloat16, device=device)
+    if heads_first:
+        strides = (num_pages * hkv * page_size * d, hkv * page_size * d, d, page_size * d)
+    else:
+        strides = (num_pages * page_size * hkv * d, page_size * hkv * d, hkv * d, d)
+    return Kp, Vp, table, num_pages, strides

@@ -223,7 +223,7 @@ def test_evict_layers_checks_every_table_entry(L):
 
 
 def _decode_state(**kw):
-    st = tb.CDecodeState(2, 3, 32, 8, 128, 256, 5000, *([0x7f0000001000] * 11))
+    st = tb.CDecodeState(2, 3, 32, 8, 128, 256, 5000, *([0x7f0000001000] * 11), None)
     for k, v in kw.items():
         setattr(st, k, v)
     return st
@@ -255,6 +255,25 @@ def test_decode_error_paths(L):
     assert L.ta_decode_step(*a) == tb.TA_ERR_ALIGN
     a = step(); a[1] = None
     assert L.ta_decode_step(*a) == tb.TA_ERR_NULL
+    # slots in a paged pool: the table must hold K + 1 slots per sequence
+    def pages(page_size=16, max_pages=17, num_pages=40, table=FAKE, stride=(40 * 16 * 8 * 128, 16 * 8 * 128, 8 * 128, 128)):
+        p = tb.CPaged()
+        p.page_size, p.max_pages, p.num_pages = page_size, max_pages, num_pages
+        p.block_table = table.value if table is not None else None
+        for i in range(4):
+            p.stride[i] = stride[i]
+        return p
+    keep = []
+    def paged(p):
+        keep.append(p)
+        return _decode_state(pages=ctypes.addressof(p))
+    assert L.ta_decode_step(*step(paged(pages(max_pages=16)))) == tb.TA_ERR_SHAPE   # 256 slots < K + 1
+    assert L.ta_decode_step(*step(paged(pages(table=None)))) == tb.TA_ERR_NULL
+    assert L.ta_decode_step(*step(paged(pages(page_size=0)))) == tb.TA_ERR_SHAPE
+    assert L.ta_decode_step(*step(paged(pages(stride=(0, 16 * 8 * 128, 8 * 128 + 4, 128))))) == tb.TA_ERR_ALIGN
+    assert L.ta_decode_step(*step(paged(pages(stride=(0, 16 * 8 * 64, 64, 128))))) == tb.TA_ERR_SHAPE   # rows overlap
+    a = init(); a[9] = None                                 # rows in place (no compacted K/V) only with a paged state
+    assert L.ta_decode_init(*a) == tb.TA_ERR_NULL
 
 
 def test_static_scratch_entry_refuses_oversized_layouts_on_the_host(L):
@@ -342,6 +361,17 @@ def test_lse_and_paged_error_paths(L):
     assert L.ta_compact_paged(*cm(pg(), K=0)) == tb.TA_ERR_SHAPE
     a = cm(pg()); a[8] = None
     assert L.ta_compact_paged(*a) == tb.TA_ERR_NULL
+    # compaction into a page pool: the destination table is sized for K slots, the source for n positions
+    F2, F3, F4 = (ctypes.c_void_p(FAKE.value + 4096 * i) for i in (1, 2, 3))
+    ci = lambda dst, src=None, K=16, Kd=F3: [FAKE, F2, ctypes.byref(src) if src is not None else None, FAKE, FAKE,
+                                                ctypes.byref(lay), K, 0, Kd, F4, ctypes.byref(dst) if dst is not None else None, None]
+    assert L.ta_compact_into_pages(*ci(None)) == tb.TA_ERR_NULL
+    assert L.ta_compact_into_pages(*ci(pg(page_size=16, max_pages=1), K=17)) == tb.TA_ERR_SHAPE
+    assert L.ta_compact_into_pages(*ci(pg(page_size=16, max_pages=1), src=pg(page_size=16, max_pages=255))) == tb.TA_ERR_SHAPE
+    assert L.ta_compact_into_pages(*ci(pg(table=None))) == tb.TA_ERR_NULL
+    assert L.ta_compact_into_pages(*ci(pg(), K=0)) == tb.TA_ERR_SHAPE
+    assert L.ta_compact_into_pages(*ci(pg(), Kd=None)) == tb.TA_ERR_NULL
+    assert L.ta_compact_into_pages(*ci(pg(), Kd=FAKE)) == tb.TA_ERR_SHAPE          # dense source: outputs alias the inputs
     # ta_evict_lse: needs an attention term and the log-sum-exps
     ids, lens = _table()
     cp0 = tb.Params(alpha=0.0).c()

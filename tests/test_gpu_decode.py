@@ -29,7 +29,29 @@ def _same_bits(x, y):
     return torch.equal(x, y)
 
 
-def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu", stats=None, last_query=False):
+def _slot_pool(w, K, page_size, heads_first, seed=3):
+    """An empty page pool for the K + 1 slots of every unit (pages of each sequence at random places, a few
+    spare pages, junk everywhere) as a PagedKV; pools are [Lyr][pages][page_size][Hkv][d] or, heads_first,
+    [Lyr][pages][Hkv][page_size][d]."""
+    Kp, Vp, table, num_pages, strides = wl.make_slot_pool(w.layers, w.batch, w.hkv, w.d, K + 1, page_size, DEV,
+                                                          heads_first=heads_first, seed=seed)
+    return ta.PagedKV(Kp, Vp, _dev(table), page_size, num_pages, strides, w.layers, w.batch, w.hkv, K + 1), table, heads_first
+
+
+def _slots_dense(pool, table, page_size, slots, heads_first):
+    """[Lyr][B][Hkv][slots][d] view of the slots kept in a page pool (torch indexing through the table)."""
+    s = torch.arange(slots, device=pool.device)
+    pages = torch.from_numpy(table).to(pool.device)[:, s // page_size]            # [B][slots]
+    if heads_first:
+        pool = pool.permute(0, 1, 3, 2, 4)                                          # [Lyr][pages][page_size][H][d]
+    return pool[:, pages, (s % page_size)[None, :]].permute(0, 1, 3, 2, 4)         # [Lyr][B][slots][H][d] -> [Lyr][B][H][slots][d]
+
+
+def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu", stats=None, last_query=False,
+                paged=None, in_place=False):
+    """paged = (page_size, heads_first): the state's K/V slots live in a page pool; in_place: the prefill's
+    rows are compacted straight into those pages (ta_compact_into_pages) and the state is initialised
+    without copying them."""
     """rank="gpu": the oracle ranks the slots with the GPU's fp32 cumulative attention (the decision is then
     exact on both sides).  rank="oracle": the oracle ranks with its own double-accumulated attention; an
     eviction that differs is excused only if both slots are in the same class and their oracle utilities
@@ -48,8 +70,15 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu",
     idx, cnt = ta.ta_select(A, anchor, spons, vouch, K, prm, lyr, w.hkv, seq_len=seq_len)
     Ko, Vo = ta.ta_compact(Kc, Vc, idx, cnt, K)
     cap = w.n + steps + 4 if cap is None else cap        # a smaller cap: sequences reach capacity and are left alone
-    st = ta.DecodeState(lyr, B, w.hq, w.hkv, K, cap, DEV)
-    ta.ta_decode_init(st, tok, anchor, idx, cnt, Ko, Vo, prm, seq_len=seq_len, A=A)
+    pool = None
+    if paged is not None:
+        pool, ptable, heads_first = _slot_pool(w, K, paged[0], paged[1])
+    st = ta.DecodeState(lyr, B, w.hq, w.hkv, K, cap, DEV, pages=pool)
+    if in_place:
+        ta.ta_compact_into_pages(Kc, Vc, idx, cnt, K, pool)
+        ta.ta_decode_init(st, tok, anchor, idx, cnt, None, None, prm, seq_len=seq_len, A=A)
+    else:
+        ta.ta_decode_init(st, tok, anchor, idx, cnt, Ko, Vo, prm, seq_len=seq_len, A=A)
     torch.cuda.synchronize()
 
     # the oracle's own prefill and state
@@ -80,7 +109,7 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu",
     for t in range(steps):
         q, kn, vn = wl.make_decode_qkv(w, t, device=DEV)
         full = [b for b in range(B) if seqs[b].len >= cap]
-        before = {b: [x[:, b].clone() for x in (st.A, st.pos, st.Kc, st.Vc)] +
+        before = {b: [x[:, b].clone() for x in (st.A, st.pos)] + ([] if pool is not None else [st.Kc[:, b].clone(), st.Vc[:, b].clone()]) +
                      [x[b].clone() for x in (st.tok, st.anchor, st.budget, st.len)] for b in full}
         ta.ta_decode_step(st, _dev(stream[t]), q if scored else None, kn, vn, td.tab_ids, td.tab_len, prm,
                           evicted=evicted)
@@ -91,7 +120,8 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu",
             if b in before:
                 # a sequence at capacity is left unchanged, bit for bit: nothing appended, no attention
                 # added, nothing evicted, no budget decay (the oracle's state of it simply does not step)
-                after = [x[:, b] for x in (st.A, st.pos, st.Kc, st.Vc)] + [x[b] for x in (st.tok, st.anchor, st.budget, st.len)]
+                after = [x[:, b] for x in (st.A, st.pos)] + ([] if pool is not None else [st.Kc[:, b], st.Vc[:, b]]) + \
+                        [x[b] for x in (st.tok, st.anchor, st.budget, st.len)]
                 for x0, x1 in zip(before[b], after):
                     assert _same_bits(x0, x1), (t, b)
                 assert (gev[:, b] == -1).all(), (t, b)
@@ -141,7 +171,11 @@ def _run_decode(w, K, steps, p_anchor=0.05, check_every=1, cap=None, rank="gpu",
                 assert np.array_equal(gtok[b, :n_], seqs[b].tok[:n_])
                 assert np.array_equal(ganc[b, :n_], seqs[b].anchor[:n_])
                 assert np.array_equal(gbud[b, :n_].view(np.uint32), seqs[b].budget[:n_].view(np.uint32))
-    gK, gV = wl.bf16_bits(st.Kc), wl.bf16_bits(st.Vc)
+    if pool is not None:
+        gK = wl.bf16_bits(_slots_dense(pool.Kpool, ptable, paged[0], K + 1, heads_first))
+        gV = wl.bf16_bits(_slots_dense(pool.Vpool, ptable, paged[0], K + 1, heads_first))
+    else:
+        gK, gV = wl.bf16_bits(st.Kc), wl.bf16_bits(st.Vc)
     for (l, b, g), u in units.items():
         occ = u.pos >= 0
         assert np.array_equal(gK[l, b, g][occ], u.Kc[occ]) and np.array_equal(gV[l, b, g][occ], u.Vc[occ])
@@ -248,3 +282,49 @@ def test_decode_last_query_rule(rank):
     ev, _ = _run_decode(w0, K=32, steps=30, p_anchor=0.0, rank=rank, stats=stats, last_query=True)
     assert ev == 30 * 2 * 3 * 2
     print("last-query rule, rank=%s: %d excused near-tie evictions" % (rank, stats.get("excused", 0)))
+
+
+@pytest.mark.parametrize("page_size,heads_first,in_place", [
+    (16, False, False),      # [pages][16][heads][d]: a unit's 65 slots over 5 pages
+    (64, True, False),       # [pages][heads][64][d]
+    (24, False, True),       # a page size that is no power of two; rows compacted straight into the pages
+    (128, True, True),       # all slots of a unit in one page
+])
+def test_decode_over_a_paged_slot_pool(page_size, heads_first, in_place):
+    """The generation step with the K/V slots in a page pool behind a block table: every comparison of the
+    dense runs (anchors, budgets, slot positions, evicted positions, attention, cached rows) against the
+    oracle, the rows read back through the table."""
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=3, n=1100, hq=8, hkv=2, ragged=(40, 1100))
+    ev, anc = _run_decode(w, K=64, steps=36, p_anchor=0.08, paged=(page_size, heads_first), in_place=in_place)
+    assert ev > 0
+
+
+def test_compact_into_pages_touches_nothing_else():
+    """ta_compact_into_pages from a dense and from a paged source: the whole destination pool equals the
+    oracle's gather scattered into a copy of the untouched pool (so no other page or slot changed)."""
+    w = wl.scaled(wl.CONFIGS["c2_full_model"], layers=2, batch=3, n=1500, hq=8, hkv=2, ragged=(300, 1500))
+    K = 100
+    td = wl.make_tokens(w, clean=False)
+    Q, Kc, Vc = wl.make_qkv(w, device=DEV)
+    prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent)
+    seq = _dev(td.seq_len)
+    anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, prm, seq_len=seq)
+    A = ta.ta_score(Q, Kc, prm, seq_len=seq)
+    idx, cnt = ta.ta_select(A, anchor, spons, vouch, K, prm, w.layers, w.hkv, seq_len=seq)
+    Kp, Vp, stable, snum, sstr = wl.make_paged(Kc, Vc, 64)
+    src = ta.PagedKV(Kp, Vp, stable, 64, snum, sstr, w.layers, w.batch, w.hkv, w.n)
+    for page_size, heads_first, source in ((16, False, None), (32, True, src), (100, False, src)):
+        wK = wl.scaled(w, n=K)                               # the helper sizes the pool for K + 1 slots; K are written
+        pool, ptable, _ = _slot_pool(wK, K, page_size, heads_first, seed=page_size)
+        want_K, want_V = wl.bf16_bits(pool.Kpool).copy(), wl.bf16_bits(pool.Vpool).copy()
+        ta.ta_compact_into_pages(Kc, Vc, idx, cnt, K, pool, src=source)
+        torch.cuda.synchronize()
+        sp, spos, sh = pool.strides[1], pool.strides[2], pool.strides[3]
+        for l in range(w.layers):
+            for b in range(w.batch):
+                for g in range(w.hkv):
+                    c = int(cnt[l, b, g])
+                    sel = idx[l, b, g, :c].cpu().numpy()
+                    ora.paged_scatter(want_K[l], ora.compact(wl.bf16_bits(Kc[l, b, g]), sel), ptable[b], page_size, sp, spos, sh, g)
+                    ora.paged_scatter(want_V[l], ora.compact(wl.bf16_bits(Vc[l, b, g]), sel), ptable[b], page_size, sp, spos, sh, g)
+        assert np.array_equal(wl.bf16_bits(pool.Kpool), want_K) and np.array_equal(wl.bf16_bits(pool.Vpool), want_V)
