@@ -49,7 +49,7 @@ SCORE_TRAFFIC = {
         "sources": {
             "ta_score.hip": "d586b676b008b66c77dcd736a4dda21b8437eed7104d9782f522f756f6b1b06c",
             "ta_score_common.h": "3e4b78495a5669b06b80090303e2ac50ab9622f4b9ead1de520e8aee81424db4",
-            "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
+            "ta_match_device.h": "37bdb219a8d33ec055dec043135dc59baa6bb3078a260fc18fd0d5fdc3f6b979",
         },
     },
     "c2_full_model": {        # profiles/score_two_sweep_c2_full_model_K1024.txt
@@ -57,7 +57,7 @@ SCORE_TRAFFIC = {
         "sources": {
             "ta_score.hip": "d586b676b008b66c77dcd736a4dda21b8437eed7104d9782f522f756f6b1b06c",
             "ta_score_common.h": "3e4b78495a5669b06b80090303e2ac50ab9622f4b9ead1de520e8aee81424db4",
-            "ta_match_device.h": "ea1c659034745b1c86ea139df7a64bd4b0e33ccf9b061b77a80be957bb4e3717",
+            "ta_match_device.h": "37bdb219a8d33ec055dec043135dc59baa6bb3078a260fc18fd0d5fdc3f6b979",
         },
     },
 }
