@@ -466,11 +466,13 @@ int32_t ta_evict_layers_paged(const int32_t *tok, const int32_t *seq_len,
  *                 len    int32 [batch]        current length
  *                 anchor uint8 [batch][cap]   anchor flags
  *                 budget float [batch][cap]   CURRENT budget B_i of each anchor, 0 elsewhere
- *                 vouch  float [batch][cap]   scratch of a step: voucher of each position from
- *                 spons  uint8 [batch][cap]   the current budgets, and its sponsor flag (Eq. 2);
- *                                             rewritten by every ta_decode_step, never read back
- *                 stepped int32 [batch]       scratch of a step: 1 if the step appended a token to the
- *                                             sequence, 0 if it was at capacity and left alone
+ *                 vouch  float [batch][cap]   scratch of a step: voucher of each position from the
+ *                 spons  uint8 [batch][cap]   current budgets (Eq. 2), and its flags (bit 0: sponsored,
+ *                                             bit 1: an anchor itself, except at the position just
+ *                                             appended); rewritten by every ta_decode_step
+ *                 stepped int32 [batch]       scratch of a step: 0 if the sequence was at capacity and
+ *                                             left alone, else its new length in bits 0-29 and, in
+ *                                             bit 30, whether the appended token is an anchor
  *   per unit      Kc, Vc bf16  [layers][batch][hkv][K+1][d]  cache slots
  *                 pos    int32 [layers][batch][hkv][K+1]     absolute position of a slot, -1 = free
  *                 A      float [layers][batch][hkv][K+1]     cumulative attention of a slot

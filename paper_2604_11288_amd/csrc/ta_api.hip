@@ -188,6 +188,8 @@ int32_t check_decode_state(const ta_decode_state* st)
     if ((int64_t)(st->hq / st->hkv) * (st->K + 1) > 15360) return TA_ERR_SHAPE;      // logits of a unit sit in LDS
     if (st->cap < 1 || st->cap >= (1 << 30) || st->batch > 65535) return TA_ERR_SHAPE;
     if ((int64_t)st->layers * st->batch * st->hkv > (1 << 24)) return TA_ERR_SHAPE;
+    // one launch holds the units and one workgroup per 256 positions of every sequence
+    if ((int64_t)st->batch * ((st->cap + 255) / 256) > 0x7F000000ll - (1 << 24)) return TA_ERR_SHAPE;
     if (!aligned16(st->Kc) || !aligned16(st->Vc)) return TA_ERR_ALIGN;
     if (st->pages) {                                       // K/V slots in a paged pool
         const ta_paged_kv* pg = st->pages;

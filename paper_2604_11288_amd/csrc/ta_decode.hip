@@ -2,16 +2,16 @@
 // sequence and unit (Sec. 3.1 "after each generation step"; Alg. 1 with its
 // budget-decay step; Sec. 3.2 "Token selection").
 //
-// Kernels per step:
-//   decode_seq_kernel    one workgroup per sequence: append the token, test the
-//                        anchor table at the new position only, set its budget
-//   decode_vouch_kernel  voucher and sponsor flag of every position from the current budgets
-//   decode_unit_kernel   one wavefront per unit: write the new k/v row into the
-//                        free slot, add the decode queries' softmax weights over
-//                        the cached rows to A (H2O-style cumulative attention,
-//                        Eq. 1), free the slot that ranks last under the
-//                        (class, u, position) order
-//   decode_decay_kernel  B_i <- decay * B_i for every position
+// Two launches per step:
+//   decode_seq_vouch_kernel  per sequence: append the token, test the anchor table at the new
+//                            position only, set its budget; voucher and sponsor flag of every
+//                            position from the current budgets
+//   decode_unit_kernel       one wavefront per unit: write the new k/v row into the
+//                            free slot, add the decode queries' softmax weights over
+//                            the cached rows to A (H2O-style cumulative attention,
+//                            Eq. 1), free the slot that ranks last under the
+//                            (class, u, position) order; trailing workgroups of the same
+//                            launch do B_i <- decay * B_i for every position
 // The unit kernel is the hot one: it reads the unit's K slots once (HBM bound,
 // (K+1) * 256 B per unit per step).  The logits of the group's query heads over the
 // slots are a thin contraction that runs on the matrix cores (16-row key tiles x 16
@@ -26,7 +26,6 @@ namespace ta {
 namespace {
 
 constexpr int DU_THREADS = 256;
-constexpr int DU_WAVES = DU_THREADS / 64;
 constexpr int MAX_GROUP = 16;                              // query heads per KV head (the columns of an MFMA tile)
 
 struct DecodeTable {
@@ -126,44 +125,6 @@ decode_init_unit_kernel(ta_decode_state st, int32_t n, const float* A, const int
 }
 
 // ---- step, sequence part ---------------------------------------------------------
-__global__ void __launch_bounds__(64)
-decode_seq_kernel(ta_decode_state st, const int32_t* new_tok, DecodeTable tab)
-{
-    const int b = blockIdx.x;
-    const int32_t p = st.len[b];
-    if (p < 0 || p >= st.cap) {                            // at capacity: the step leaves this sequence and its units alone
-        if (threadIdx.x == 0) st.stepped[b] = 0;
-        return;
-    }
-    int32_t* tok = st.tok + (size_t)b * st.cap;
-    const int32_t t0 = new_tok[b];
-    const int e = threadIdx.x;
-    bool hit = false;
-    if (e < tab.E && t0 == tab.rid[e][0]) {
-        const int32_t len = tab.len[e];
-        hit = p - len + 1 >= 0;
-        for (int k = 1; k < len && hit; ++k) hit = tok[p - k] == tab.rid[e][k];
-    }
-    const bool any = __ballot(hit) != 0ull;
-    if (threadIdx.x == 0) {
-        tok[p] = t0;
-        st.anchor[(size_t)b * st.cap + p] = any ? 1 : 0;
-        st.budget[(size_t)b * st.cap + p] = any ? tab.B : 0.0f;
-        st.len[b] = p + 1;
-        st.stepped[b] = 1;
-    }
-}
-
-__global__ void decode_decay_kernel(ta_decode_state st, float decay)
-{
-    const int b = blockIdx.y;
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < st.len[b] && p < st.cap && st.stepped[b]) {
-        float* B = st.budget + (size_t)b * st.cap + p;
-        *B = __fmul_rn(decay, *B);
-    }
-}
-
 // Voucher and sponsor flag of every position from the current budgets (Eq. 2): the same for all
 // units of a sequence, so it is computed once per sequence and step, not once per cached row.
 struct VouchArgs {
@@ -171,12 +132,42 @@ struct VouchArgs {
     float pw[TA_MAX_SPAN + 1];
 };
 
-__global__ void decode_vouch_kernel(ta_decode_state st, VouchArgs a)
+// Sequence part of a step, one launch: every workgroup reads the old length (nobody writes it here),
+// the first wavefront of a sequence's first workgroup appends the token, tests the table at the new
+// position and publishes the new length in `stepped` (0: the sequence is at capacity and is left
+// alone); all workgroups compute the vouchers of their positions, which depend on earlier positions
+// only and so not on anything the append writes.
+__global__ void __launch_bounds__(256)
+decode_seq_vouch_kernel(ta_decode_state st, const int32_t* new_tok, DecodeTable tab, VouchArgs a)
 {
     const int b = blockIdx.y;
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= st.len[b] || p >= st.cap) return;
+    const int32_t len_old = st.len[b];
+    if (len_old < 0 || len_old >= st.cap) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) st.stepped[b] = 0;
+        return;
+    }
     const size_t row = (size_t)b * st.cap;
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+        const int32_t p = len_old;
+        int32_t* tok = st.tok + row;
+        const int32_t t0 = new_tok[b];
+        const int e = threadIdx.x;
+        bool hit = false;
+        if (e < tab.E && t0 == tab.rid[e][0]) {
+            const int32_t len = tab.len[e];
+            hit = p - len + 1 >= 0;
+            for (int k = 1; k < len && hit; ++k) hit = tok[p - k] == tab.rid[e][k];
+        }
+        const bool any = __ballot(hit) != 0ull;
+        if (threadIdx.x == 0) {
+            tok[p] = t0;
+            st.anchor[row + p] = any ? 1 : 0;
+            st.budget[row + p] = any ? tab.B : 0.0f;
+            st.stepped[b] = (p + 1) | (any ? (1 << 30) : 0);   // new length; bit 30: the new token is an anchor
+        }
+    }
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > len_old) return;                               // positions 0 .. len_old exist after the append
     const uint8_t* anchor = st.anchor + row;
     const float* budget = st.budget + row;
     float v = 0.0f;
@@ -189,7 +180,33 @@ __global__ void decode_vouch_kernel(ta_decode_state st, VouchArgs a)
         }
     }
     st.vouch[row + p] = v;
-    st.spons[row + p] = sp;
+    // bit 0: sponsored; bit 1: the position is an anchor itself (the new position's flag travels in
+    // `stepped`: it is being written by another workgroup of this launch)
+    st.spons[row + p] = sp | (p < len_old && anchor[p] ? 2 : 0);
+}
+
+// Trailing workgroups of the unit launch: budget decay of 256 positions each, and the new length.
+// Units read neither array (they take the length from `stepped`), so the two kinds of workgroup
+// touch disjoint memory.
+__device__ __forceinline__ void decay_rider(const ta_decode_state& st, int r, float decay)
+{
+    const int tiles = (st.cap + 255) >> 8;
+    const int b = r / tiles, tile = r - b * tiles;
+    const int32_t len_new = st.stepped[b] & 0x3FFFFFFF;
+    if (len_new == 0) return;
+    float* B = st.budget + (size_t)b * st.cap;
+    float v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int p = tile * 256 + j * 64 + (int)threadIdx.x;
+        v[j] = B[p < len_new ? p : 0];                      // len_new >= 1
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int p = tile * 256 + j * 64 + (int)threadIdx.x;
+        if (p < len_new) B[p] = __fmul_rn(decay, v[j]);
+    }
+    if (tile == 0 && threadIdx.x == 0) st.len[b] = len_new;
 }
 
 // ---- step, unit part ----------------------------------------------------------------
@@ -203,6 +220,8 @@ struct UnitArgs {
     float scale_log2;
     int32_t last_query;                                    // 1: A holds this step's attention, not the running sum
     int32_t pg_off;                                        // paged slots: offset (in floats) of the page list in the wavefront's LDS
+    int32_t units;                                         // workgroups beyond this many decay the budgets
+    float decay;
 };
 
 __device__ __forceinline__ uint32_t ordered_bits(float u)
@@ -211,36 +230,7 @@ __device__ __forceinline__ uint32_t ordered_bits(float u)
     return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 
-template <typename T, typename Op>
-__device__ __forceinline__ T block_reduce(T v, T* s_red, Op op)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = op(v, __shfl_xor(v, o));
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    __syncthreads();
-    if (lane == 0) s_red[wave] = v;
-    __syncthreads();
-    T r = s_red[0];
-#pragma unroll
-    for (int w = 1; w < DU_WAVES; ++w) r = op(r, s_red[w]);
-    return r;
-}
-
-constexpr int DT_RING = 4;                                 // 16-row key tiles held per wavefront: one multiplied, the others in flight
-
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
-}
-
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
+constexpr int SLOTS_PER_LANE = 5;                          // budgets up to 5 * 64 - 1 keep a lane's slots in registers
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -259,32 +249,95 @@ __device__ __forceinline__ s16x4 hi_half(const uint4& v)
     return c.s;
 }
 
-// One wavefront per unit, no workgroup barriers: the step of a unit is a chain of short
-// phases, and what hides their latency is the number of units in flight per compute unit.
-// LDS (private to the wavefront): slot table, accumulated attention, [G][slots] logits.
-template <int GH, bool PAGED>                             // query heads per KV head the loops are unrolled for; K/V slots in pages
-__global__ void __launch_bounds__(64)
-decode_unit_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
+// ---- cross-lane reductions on the data-parallel-primitive path (no LDS round trips) ----------
+// Steps: neighbours within quads, quads within a row of 16 by rotation, then the last lane of a row
+// broadcast to the next row(s); lane 63 ends up with the reduction over the wavefront.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+#define TA_DPP_STEPS(STEP) STEP(0xb1) STEP(0x4e) STEP(0x124) STEP(0x128) STEP(0x142) STEP(0x143)
+
+__device__ __forceinline__ float wave_max_dpp(float v)
+{
+#define STEP(C) v = fmaxf(v, __int_as_float(dpp_move<C>(__float_as_int(v))));
+    TA_DPP_STEPS(STEP)
+#undef STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+#define STEP(C) v += __int_as_float(dpp_move<C>(__float_as_int(v)));
+    TA_DPP_STEPS(STEP)
+#undef STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ int wave_sum_dpp(int v)
+{
+#define STEP(C) v += dpp_move<C>(v);
+    TA_DPP_STEPS(STEP)
+#undef STEP
+    return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ int wave_min_dpp(int v)
+{
+#define STEP(C) { const int o = dpp_move<C>(v); v = o < v ? o : v; }
+    TA_DPP_STEPS(STEP)
+#undef STEP
+    return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ unsigned long long wave_min_dpp(unsigned long long v)
+{
+#define STEP(C) { const unsigned lo = (unsigned)dpp_move<C>((int)(unsigned)v), hi = (unsigned)dpp_move<C>((int)(unsigned)(v >> 32)); \
+                  const unsigned long long o = ((unsigned long long)hi << 32) | lo; v = o < v ? o : v; }
+    TA_DPP_STEPS(STEP)
+#undef STEP
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, 63);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), 63);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// One wavefront per unit, no workgroup barriers.  SMALL: at most SLOTS_PER_LANE * 64 slots, so a
+// lane's slots (position, voucher, flags, accumulated attention) stay in its registers from the
+// first round trip to the ranking and nothing loops over slots.
+// DT_RING: 16-row key tiles in flight per wavefront.
+template <int GH, bool PAGED, bool SCORED, bool SMALL, int DT_RING>
+__device__ __forceinline__ void decode_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg)
 {
     extern __shared__ float s_dyn[];
 
     const int lane = threadIdx.x;
     const int sub = lane & 15, grp = lane >> 4;            // 16 lanes per key row, 4 rows per instruction
+    if ((int)blockIdx.x >= a.units) {                      // trailing workgroups: budget decay
+        decay_rider(st, (int)blockIdx.x - a.units, a.decay);
+        return;
+    }
     const int unit = blockIdx.x;
     const int slots = st.K + 1;
     const int G = st.hq / st.hkv;
     const int g = unit % st.hkv;
     const int b = (unit / st.hkv) % st.batch;
     const int l = unit / (st.hkv * st.batch);
-    const int32_t len_new = st.len[b];                     // the sequence part of the step has run
-    const int32_t p_new = len_new - 1;
     int32_t* pos = st.pos + (size_t)unit * slots;
     float* A = st.A + (size_t)unit * slots;
     uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (PAGED ? l * pg.s_layer + g * pg.s_head : (int64_t)unit * slots * 16);
     uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (PAGED ? l * pg.s_layer + g * pg.s_head : (int64_t)unit * slots * 16);
-    const bool scored = a.alpha != 0.0f;
-    // Paged slots: the pages of this unit's slots go to LDS first (one dependent round trip through
-    // the L2 per unit), so that a row's address afterwards costs an LDS read and no memory access.
+    constexpr int SPL = SLOTS_PER_LANE;                            // slots per lane that one round trip covers
+
+    // Everything that does not depend on loaded data is requested first, in the order it is needed
+    // (loads of a wavefront return in order), and unconditionally (clamped addresses, results masked
+    // afterwards): straight-line loads let the compiler wait for exactly the load it needs.
+    const int32_t stepped = st.stepped[b];                 // the sequence part of the step has run
+    int32_t p0[SPL];
+#pragma unroll
+    for (int j = 0; j < SPL; ++j) {
+        const int s = lane + 64 * j;
+        p0[j] = SMALL ? pos[s < slots ? s : slots - 1] : 0;
+    }
+    const uint4* nsrc = ((lane & 16) ? a.v_new : a.k_new) + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
+    const uint4 nrow = nsrc[lane & 15];                    // lanes 0-15: the new key row, 16-31: the new value row
+
     int32_t* s_pg = reinterpret_cast<int32_t*>(s_dyn + a.pg_off);
     if (PAGED) {
         const int npg = page_index(pg, slots - 1) + 1;
@@ -297,79 +350,116 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
         return (int64_t)s_pg[j] * pg.s_page + (int64_t)(row - j * pg.page_size) * pg.s_slot;
     };
     int32_t* s_pos = reinterpret_cast<int32_t*>(s_dyn);
-    float* s_A = s_dyn + slots;
     const int wstride = (slots + 3) & ~3;                  // logits of a head: padded to whole 16-byte groups
-    uint4* s_t = reinterpret_cast<uint4*>(s_dyn + ((2 * slots + 3) & ~3));   // one 16-row key tile, 4 KB (scored only)
-    float* s_w = reinterpret_cast<float*>(s_t + 256);
+    uint4* s_t = reinterpret_cast<uint4*>(s_dyn + wstride);                  // one 16-row key tile, 4 KB (scored only)
+    uint4* s_kn = s_t + 256;                                                 // the new key row
+    float* s_w = reinterpret_cast<float*>(s_kn + 16);
 
-    // The logits of the group's decode queries over the cached rows are a [slots x d] x [d x G]
-    // contraction: v_mfma_f32_16x16x16_bf16 with 16 key rows as the rows of a tile and the heads
-    // as its columns (G <= 16 of them are used; the matrix pipe is idle otherwise).
-    // Key rows are loaded the way memory likes them - a wavefront instruction takes four whole
-    // consecutive rows, 16 lanes x 16 bytes each - and turned into operand fragments through a
-    // 4 KB tile in LDS: lane (i16, kq) of the matrix layout needs 16 bytes of row i16 at chunk
-    // kq + 4 t, t = 0..3, and uses their two halves as two k-steps.  (Loading the fragments
-    // straight from global memory - 16 rows x 64 bytes per instruction - streams at 4.6 TB/s,
-    // whole rows at 5.8.)  The query fragments are loaded with the fragment addressing, so both
-    // operands see the features in the same (permuted) order, which a contraction does not
-    // care about.  The first tiles and the queries are requested before anything else.
     const int i16 = sub, kq = grp;
     const int ntiles = (slots + 15) >> 4;
-    uint4 qf[4], tiles[DT_RING][4];                        // DT_RING - 1 tiles in flight while one is multiplied
+    uint4 qf[4], tiles[DT_RING][4];                        // DT_RING tiles in flight
     const auto load_tile = [&](int tile, uint4 (&dst)[4]) {
+        if (!PAGED) {                                      // dense unit: one uniform base, a 32-bit byte offset per lane
+            const char* base = reinterpret_cast<const char*>(Kc);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                int row = tile * 16 + 4 * t + grp;
+                row = row < slots ? row : slots - 1;       // past the last slot: a valid row, masked at the store
+                {
+                    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+                    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (uint32_t)(row * 256 + sub * 16)));
+                    dst[t] = make_uint4(v.x, v.y, v.z, v.w);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             int row = tile * 16 + 4 * t + grp;
-            row = row < slots ? row : slots - 1;           // past the last slot: a valid row, masked at the store
-            dst[t] = Kc[row_at(row) + sub];
+            row = row < slots ? row : slots - 1;
+            typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(&Kc[row_at(row) + sub]));
+            dst[t] = make_uint4(v.x, v.y, v.z, v.w);
         }
     };
-    if (scored) {
+    if (SCORED) {
         const uint4* qrow = a.q_new + ((size_t)(l * st.batch + b) * st.hq + g * G + (i16 < G ? i16 : 0)) * 16;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) qf[t] = i16 < G ? qrow[kq + 4 * t] : make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int j = 0; j < DT_RING - 1; ++j)
-            if (j < ntiles) load_tile(j, tiles[j]);
-    }
-    int first_free = 0x7FFFFFFF;                           // lowest-numbered free slot
-    for (int s0 = lane; s0 < slots; s0 += 4 * 64) {        // four slots per lane and round trip
-        int32_t p4[4];
-        float a4[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int s = s0 + 64 * j;
-            p4[j] = s < slots ? pos[s] : 0;
-            a4[j] = s < slots ? A[s] : 0.0f;
+        for (int t = 0; t < 4; ++t) {
+            const uint4 v = qrow[kq + 4 * t];
+            qf[t] = i16 < G ? v : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < DT_RING; ++j) load_tile(j, tiles[j]);     // past the last tile: the last row again, never used
+    }
+
+    // ---- the slot table goes to LDS; lowest-numbered free slot ---------------------------------
+    int first_free = 0x7FFFFFFF;
+    if (SMALL) {
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) {
+            const int s = lane + 64 * j;
+            if (s < slots) {
+                s_pos[s] = p0[j];
+                if (p0[j] < 0) first_free = first_free < s ? first_free : s;
+            }
+        }
+    }
+    for (int s0 = lane; !SMALL && s0 < slots; s0 += SPL * 64) {    // more slots than a lane's registers hold
+        int32_t p4[SPL];
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) {
+            const int s = s0 + 64 * j;
+            p4[j] = pos[s < slots ? s : slots - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) {
             const int s = s0 + 64 * j;
             if (s < slots) {
                 s_pos[s] = p4[j];
-                s_A[s] = a4[j];
                 if (p4[j] < 0) first_free = first_free < s ? first_free : s;
             }
         }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const int other = __shfl_xor(first_free, o);
-        first_free = other < first_free ? other : first_free;
-    }
-    const int f = first_free;
-    if (f >= slots || p_new < 0 || !st.stepped[b]) {       // no room, empty sequence, or a sequence at capacity: nothing to do
+    const int f = wave_min_dpp(first_free);
+    const int32_t len_new = stepped & 0x3FFFFFFF;
+    const uint8_t an_new = (uint8_t)((stepped >> 30) & 1);
+    if (len_new == 0 || f >= slots) {                      // a sequence at capacity, or no room: nothing to do
         if (lane == 0 && a.evicted) a.evicted[unit] = -1;
         return;
     }
-    const uint4* kn = a.k_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
-    const uint4* vn = a.v_new + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
-    if (lane < 16) Kc[row_at(f) + lane] = kn[lane];
-    else if (lane < 32) Vc[row_at(f) + lane - 16] = vn[lane - 16];
+    const int32_t p_new = len_new - 1;
+
+    // the per-position inputs of the utility and the accumulated attention of the first SPL * 64 slots
+    // are requested now and used after the key stream: they travel while the keys do
+    const size_t srow = (size_t)b * st.cap;
+    const uint8_t* spons = st.spons + srow;               // bit 0: sponsored, bit 1: anchor
+    const float* vouch = st.vouch + srow;
+    float v0[SPL], a0[SPL];
+    uint8_t fl0[SPL];
+#pragma unroll
+    for (int j = 0; SMALL && j < SPL; ++j) {
+        const int s = lane + 64 * j;
+        if (s == f) p0[j] = p_new;
+        if (s >= slots) p0[j] = -2;
+        const int32_t pc = p0[j] < 0 ? 0 : p0[j];
+        v0[j] = vouch[pc];
+        fl0[j] = spons[pc];
+        if (SCORED) {
+            const float av = A[s < slots ? s : slots - 1];
+            a0[j] = (!a.last_query && p0[j] >= 0 && s != f) ? av : 0.0f;
+        } else {
+            a0[j] = 0.0f;
+        }
+    }
+    if (lane < 16) {
+        Kc[row_at(f) + lane] = nrow;
+        if (SCORED) s_kn[lane] = nrow;
+    } else if (lane < 32) Vc[row_at(f) + lane - 16] = nrow;
     __builtin_amdgcn_wave_barrier();                       // the slot table is in LDS for every lane
 
-    // ---- attention of the group's decode queries over the occupied slots ----------
-    if (scored) {
+    float m_h[GH], inv_h[GH];
+    if (SCORED) {
         const auto frag_logits = [&](const uint4 (&frag)[4]) -> f32x4 {
             f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
@@ -379,28 +469,10 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
             }
             return acc;                                    // rows 4 kq .. 4 kq + 3 of the tile, head i16
         };
-        // whole rows -> fragments through the LDS tile: row r chunk c sits at r * 16 + (c ^ r), which
-        // keeps both the row-wise writes and the column-wise reads free of bank conflicts.  LDS
-        // operations of a wavefront execute in order, so the tile needs no barrier (a wave-barrier
-        // builtin here would also keep the staging registers in scratch memory).
-        const auto tile_logits = [&](const uint4 (&rows)[4]) -> f32x4 {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int r = 4 * t + grp;
-                s_t[r * 16 + (sub ^ r)] = make_uint4(rows[t].x, rows[t].y, rows[t].z, rows[t].w);   // by components: a struct copy keeps `rows` in scratch memory
-            }
-            uint4 frag[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const uint4 v = s_t[i16 * 16 + ((kq + 4 * t) ^ i16)];
-                frag[t] = make_uint4(v.x, v.y, v.z, v.w);
-            }
-            return frag_logits(frag);
-        };
         const auto store_tile = [&](int tile, const f32x4& acc) {
             const int s = tile * 16 + 4 * kq;
             if (i16 < G && s < wstride) {
-                const int4 p4 = *reinterpret_cast<const int4*>(&s_pos[s]);   // past `slots`: other LDS of this wavefront, masked
+                const int4 p4 = *reinterpret_cast<const int4*>(&s_pos[s]);   // padded to whole groups of four
                 float4 o;
                 o.x = (s + 0 < slots && p4.x >= 0) ? acc[0] * a.scale_log2 : -INFINITY;
                 o.y = (s + 1 < slots && p4.y >= 0) ? acc[1] * a.scale_log2 : -INFINITY;
@@ -409,117 +481,154 @@ decode_unit_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
                 *reinterpret_cast<float4*>(&s_w[i16 * wstride + s]) = o;
             }
         };
-        // the tiles rotate through the registers (constant indices once unrolled)
-        for (int tb = 0; tb < ntiles; tb += DT_RING) {
+        // One tile: its rows go to LDS as soon as they are there, which frees its registers for the
+        // tile DT_RING further on; the fragments come back out of LDS in the matrix layout.
+        const auto one_tile = [&](int tile, uint4 (&regs)[4], bool reload) {
 #pragma unroll
-            for (int j = 0; j < DT_RING; ++j) {
-                if (tb + j < ntiles) {
-                    if (tb + j + DT_RING - 1 < ntiles) load_tile(tb + j + DT_RING - 1, tiles[(j + DT_RING - 1) % DT_RING]);
-                    store_tile(tb + j, tile_logits(tiles[j]));
-                }
+            for (int t = 0; t < 4; ++t) {
+                const int r = 4 * t + grp;
+                s_t[r * 16 + (sub ^ r)] = make_uint4(regs[t].x, regs[t].y, regs[t].z, regs[t].w);
+            }
+            if (reload) load_tile(tile + DT_RING, regs);
+            uint4 frag[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint4 v = s_t[i16 * 16 + ((kq + 4 * t) ^ i16)];
+                frag[t] = make_uint4(v.x, v.y, v.z, v.w);
+            }
+            store_tile(tile, frag_logits(frag));
+        };
+        // Passes of DT_RING tiles.  While every tile of a pass has a successor DT_RING further on, the
+        // pass is straight-line code (first pass apart from the loop: other loads are still in flight
+        // around it); the last one or two passes test every tile.
+        int tb = 0;
+        if (2 * DT_RING <= ntiles) {
+#pragma unroll
+            for (int j = 0; j < DT_RING; ++j) one_tile(j, tiles[j], true);
+            for (tb = DT_RING; tb + 2 * DT_RING <= ntiles; tb += DT_RING) {
+#pragma unroll
+                for (int j = 0; j < DT_RING; ++j) one_tile(tb + j, tiles[j], true);
             }
         }
-        // the row that has just been written is not read back: its logits come from the new key
-        // itself (whatever the loop stored for that slot is replaced here)
+        for (; tb < ntiles; tb += DT_RING) {
+#pragma unroll
+            for (int j = 0; j < DT_RING; ++j)
+                if (tb + j < ntiles) one_tile(tb + j, tiles[j], tb + j + DT_RING < ntiles);
+        }
         {
             uint4 knf[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) knf[t] = kn[kq + 4 * t];          // every row of this tile is the new key
+            for (int t = 0; t < 4; ++t) {                                  // every row of this tile is the new key
+                const uint4 v = s_kn[kq + 4 * t];
+                knf[t] = make_uint4(v.x, v.y, v.z, v.w);
+            }
             const f32x4 acc = frag_logits(knf);
             __builtin_amdgcn_wave_barrier();
             if (i16 < G && kq == 0) s_w[i16 * wstride + f] = acc[0] * a.scale_log2;
             __builtin_amdgcn_wave_barrier();
         }
-        // softmax statistics of every head, then the weights are added per slot in head order
-        // (H2O-style cumulative attention)
-        float m_h[GH], inv_h[GH];
+        // softmax statistics of all heads at once: one pass for the maxima, one for the sums
 #pragma unroll
-        for (int h = 0; h < GH; ++h) {
-            m_h[h] = 0.0f;
-            inv_h[h] = 0.0f;
-            if (h < G) {
-                const float* sh = s_w + h * wstride;
-                float m = -INFINITY;
-                for (int s = lane; s < slots; s += 64) m = fmaxf(m, sh[s]);
-                m = wave_max(m);
-                float z = 0.0f;
-                for (int s = lane; s < slots; s += 64) z += __builtin_amdgcn_exp2f(sh[s] - m);
-                z = wave_sum(z);
-                m_h[h] = m;
-                inv_h[h] = 1.0f / z;
-            }
-        }
+        for (int h = 0; h < GH; ++h) m_h[h] = -INFINITY;
         for (int s = lane; s < slots; s += 64) {
-            if (s == f || s_pos[s] >= 0) {
-                float add = 0.0f;
 #pragma unroll
-                for (int h = 0; h < GH; ++h)
-                    if (h < G) add += __builtin_amdgcn_exp2f(s_w[h * wstride + s] - m_h[h]) * inv_h[h];
-                // cumulative mass over the steps, or (TOVA's step-wise rule) this step's mass alone
-                const float v = a.last_query ? add : (s == f ? 0.0f : s_A[s]) + add;
-                s_A[s] = v;
-                A[s] = v;
-            }
+            for (int h = 0; h < GH; ++h)
+                if (h < G) m_h[h] = fmaxf(m_h[h], s_w[h * wstride + s]);
         }
-    } else {
-        if (lane == 0) {
-            s_A[f] = 0.0f;
-            A[f] = 0.0f;
+#pragma unroll
+        for (int h = 0; h < GH; ++h) m_h[h] = wave_max_dpp(m_h[h]);
+        float z_h[GH];
+#pragma unroll
+        for (int h = 0; h < GH; ++h) z_h[h] = 0.0f;
+        for (int s = lane; s < slots; s += 64) {
+#pragma unroll
+            for (int h = 0; h < GH; ++h)
+                if (h < G) z_h[h] += __builtin_amdgcn_exp2f(s_w[h * wstride + s] - m_h[h]);
         }
+#pragma unroll
+        for (int h = 0; h < GH; ++h) inv_h[h] = h < G ? __builtin_amdgcn_rcpf(wave_sum_dpp(z_h[h])) : 0.0f;
     }
 
-    // ---- rank the occupied slots; evict the last one if the cache is over budget -----
-    // (every lane ranks the slots it wrote s_A for)
-    const size_t srow = (size_t)b * st.cap;
-    const uint8_t* anchor = st.anchor + srow;
-    const uint8_t* spons = st.spons + srow;
-    const float* vouch = st.vouch + srow;
+    // ---- new attention mass per slot, then the rank of the slot, in one pass (a lane handles the
+    // same slots in both, so the mass stays in a register)
     const float lenf = (float)len_new;
     unsigned long long worst = ~0ull;
     int nfree = 0;
-    for (int s0 = lane; s0 < slots; s0 += 4 * 64) {        // four slots per lane and round trip
-        int32_t p4[4];
-        float v4[4];
-        uint8_t sp4[4], an4[4];
+    const auto rank_slot = [&](int s, int32_t p, float v, uint8_t fl, float a_old) {
+        const uint8_t sp = fl & 1, an = (s == f) ? an_new : (uint8_t)((fl >> 1) & 1);
+        if (p == -2) return;                               // past the last slot
+        if (p < 0) { ++nfree; return; }
+        float mass = 0.0f;
+        if (SCORED) {
+            float add = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+            for (int h = 0; h < GH; ++h)
+                if (h < G) add += __builtin_amdgcn_exp2f(s_w[h * wstride + s] - m_h[h]) * inv_h[h];
+            // cumulative mass over the steps, or (TOVA's step-wise rule) this step's mass alone
+            mass = a_old + add;
+            A[s] = mass;
+        } else if (s == f) {
+            A[s] = 0.0f;
+        }
+        const float r = __fdiv_rn((float)(p + 1), lenf);
+        float t = SCORED ? __fmul_rn(a.alpha, mass) : 0.0f;
+        t = __fadd_rn(t, __fmul_rn(a.beta, r));
+        t = __fadd_rn(t, __fmul_rn(a.gamma, (float)an));
+        t = __fadd_rn(t, v);
+        const unsigned cls = (p < a.n_sink || p >= len_new - a.n_recent) ? 2u : (sp ? 1u : 0u);
+        // (class, u, position) packed so that the smallest integer ranks last
+        const unsigned long long key = ((unsigned long long)cls << 62) |
+                                       ((unsigned long long)ordered_bits(t) << 30) | (unsigned long long)(uint32_t)p;
+        worst = key < worst ? key : worst;
+    };
+#pragma unroll
+    for (int j = 0; SMALL && j < SPL; ++j) rank_slot(lane + 64 * j, p0[j], v0[j], fl0[j], a0[j]);
+    for (int s0 = lane; !SMALL && s0 < slots; s0 += SPL * 64) {    // more slots than a lane's registers hold
+        int32_t p4[SPL];
+        float v4[SPL], a4[SPL];
+        uint8_t fl4[SPL];
+#pragma unroll
+        for (int j = 0; j < SPL; ++j) {
             const int s = s0 + 64 * j;
             p4[j] = s < slots ? ((s == f) ? p_new : s_pos[s]) : -2;
             const int32_t pc = p4[j] < 0 ? 0 : p4[j];
             v4[j] = vouch[pc];
-            sp4[j] = spons[pc];
-            an4[j] = anchor[pc];
+            fl4[j] = spons[pc];
+            if (SCORED) {
+                const float av = A[s < slots ? s : slots - 1];
+                a4[j] = (!a.last_query && p4[j] >= 0 && s != f) ? av : 0.0f;
+            } else {
+                a4[j] = 0.0f;
+            }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int s = s0 + 64 * j;
-            const int32_t p = p4[j];
-            if (p == -2) continue;                         // past the last slot
-            if (p < 0) { ++nfree; continue; }
-            const float r = __fdiv_rn((float)(p + 1), lenf);
-            float t = scored ? __fmul_rn(a.alpha, s_A[s]) : 0.0f;
-            t = __fadd_rn(t, __fmul_rn(a.beta, r));
-            t = __fadd_rn(t, __fmul_rn(a.gamma, (float)an4[j]));
-            t = __fadd_rn(t, v4[j]);
-            const unsigned cls = (p < a.n_sink || p >= len_new - a.n_recent) ? 2u : (sp4[j] ? 1u : 0u);
-            // (class, u, position) packed so that the smallest integer ranks last
-            const unsigned long long key = ((unsigned long long)cls << 62) |
-                                           ((unsigned long long)ordered_bits(t) << 30) | (unsigned long long)(uint32_t)p;
-            worst = key < worst ? key : worst;
-        }
+        for (int j = 0; j < SPL; ++j) rank_slot(s0 + 64 * j, p4[j], v4[j], fl4[j], a4[j]);
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        nfree += __shfl_xor(nfree, o);
-        const unsigned long long other = __shfl_xor(worst, o);
-        worst = other < worst ? other : worst;
-    }
+    nfree = wave_sum_dpp(nfree);
+    worst = wave_min_dpp(worst);
     const int32_t evict_pos = nfree > 0 ? -1 : (int32_t)(worst & 0x3FFFFFFFull);
     for (int s = lane; s < slots; s += 64) {
         const int32_t p = (s == f) ? p_new : s_pos[s];
         if (s == f || (p >= 0 && p == evict_pos)) pos[s] = (p == evict_pos) ? -1 : p;
     }
     if (lane == 0 && a.evicted) a.evicted[unit] = evict_pos;
+}
+
+// Dense slots: three tiles in flight at four wavefronts per SIMD (124 registers).  Paged slots need
+// more registers for their addresses: four tiles in flight at three wavefronts per SIMD instead of
+// spilling.  The same number of key bytes is in flight per SIMD either way.
+template <int GH, bool SCORED, bool SMALL>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4)))
+decode_unit_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
+{
+    decode_unit<GH, false, SCORED, SMALL, 3>(st, a, pg);
+}
+
+template <int GH, bool SCORED, bool SMALL>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(3)))
+decode_unit_paged_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
+{
+    decode_unit<GH, true, SCORED, SMALL, 4>(st, a, pg);
 }
 
 DeviceOnce g_setup;
@@ -550,19 +659,31 @@ SlotPages slot_pages(const ta_decode_state& st)
 template <int GH>
 hipError_t unit_attributes()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<GH, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_unit_kernel<GH, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    // dynamic LDS above 64 KB (large budgets with an attention term) needs the attribute
+    const void* fns[] = {reinterpret_cast<const void*>(&decode_unit_kernel<GH, true, true>),
+                         reinterpret_cast<const void*>(&decode_unit_kernel<GH, true, false>),
+                         reinterpret_cast<const void*>(&decode_unit_paged_kernel<GH, true, true>),
+                         reinterpret_cast<const void*>(&decode_unit_paged_kernel<GH, true, false>)};
+    hipError_t e = hipSuccess;
+    for (const void* fn : fns)
+        if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     return e;
 }
 
 template <int GH>
-void launch_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg, unsigned units, size_t lds, hipStream_t s)
+void launch_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg, unsigned grid, size_t lds, hipStream_t s)
 {
-    if (st.pages) hipLaunchKernelGGL((decode_unit_kernel<GH, true>), dim3(units), dim3(64), lds, s, st, a, pg);
-    else hipLaunchKernelGGL((decode_unit_kernel<GH, false>), dim3(units), dim3(64), lds, s, st, a, pg);
+    const bool scored = a.alpha != 0.0f, small = st.K + 1 <= SLOTS_PER_LANE * 64;
+#define TA_LAUNCH_UNIT(KERNEL, S, M) \
+    hipLaunchKernelGGL((KERNEL<GH, S, M>), dim3(grid), dim3(64), lds, s, st, a, pg)
+    if (st.pages) {
+        if (scored) { if (small) TA_LAUNCH_UNIT(decode_unit_paged_kernel, true, true); else TA_LAUNCH_UNIT(decode_unit_paged_kernel, true, false); }
+        else { if (small) TA_LAUNCH_UNIT(decode_unit_paged_kernel, false, true); else TA_LAUNCH_UNIT(decode_unit_paged_kernel, false, false); }
+    } else {
+        if (scored) { if (small) TA_LAUNCH_UNIT(decode_unit_kernel, true, true); else TA_LAUNCH_UNIT(decode_unit_kernel, true, false); }
+        else { if (small) TA_LAUNCH_UNIT(decode_unit_kernel, false, true); else TA_LAUNCH_UNIT(decode_unit_kernel, false, false); }
+    }
+#undef TA_LAUNCH_UNIT
 }
 
 }  // namespace
@@ -606,13 +727,11 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     }
     dt.E = tab.E;
     dt.B = tab.B;
-    hipLaunchKernelGGL(decode_seq_kernel, dim3((unsigned)st.batch), dim3(64), 0, s, st, new_tok, dt);
-
     VouchArgs va;
     va.L = prm.span_L;
     for (int k = 0; k <= TA_MAX_SPAN; ++k) va.pw[k] = tab.pw[k];
-    dim3 gv((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
-    hipLaunchKernelGGL(decode_vouch_kernel, gv, dim3(256), 0, s, st, va);
+    const unsigned tiles = (unsigned)((st.cap + 255) / 256);            // 256 positions per workgroup
+    hipLaunchKernelGGL(decode_seq_vouch_kernel, dim3(tiles, (unsigned)st.batch), dim3(256), 0, s, st, new_tok, dt, va);
 
     UnitArgs a;
     a.q_new = (const uint4*)q_new;
@@ -629,21 +748,24 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     const unsigned units = (unsigned)(st.layers * st.batch * st.hkv);
     const int G = st.hq / st.hkv;
     const int slots = st.K + 1;
-    // slot table and accumulated attention; with an attention term also one key tile and the logits
-    size_t lds_floats = prm.alpha != 0.0f ? (size_t)((2 * slots + 3) & ~3) + 1024 + (size_t)G * ((slots + 3) & ~3) : (size_t)2 * slots;
+    // slot table; with an attention term also one key tile, the new key row and the logits
+    const size_t wstride = (size_t)((slots + 3) & ~3);
+    size_t lds_floats = prm.alpha != 0.0f ? wstride + 1024 + 64 + (size_t)G * wstride : wstride;
     const SlotPages pg = slot_pages(st);
     a.pg_off = (int32_t)lds_floats;
+    a.units = (int32_t)units;
+    a.decay = prm.budget_decay;
     if (st.pages) lds_floats += (size_t)((slots - 1) / pg.page_size + 1);      // the pages of the unit's slots
     const size_t lds = lds_floats * sizeof(float);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    const hipError_t attr_err = decode_setup();            // dynamic LDS above 64 KB (large budgets) needs the attribute
+    const hipError_t attr_err = decode_setup();
     if (attr_err != hipSuccess) return attr_err;
-    if (G <= 4) launch_unit<4>(st, a, pg, units, lds, s);
-    else if (G <= 8) launch_unit<8>(st, a, pg, units, lds, s);
-    else launch_unit<MAX_GROUP>(st, a, pg, units, lds, s);
-
-    dim3 g3((unsigned)((st.cap + 255) / 256), (unsigned)st.batch);
-    hipLaunchKernelGGL(decode_decay_kernel, g3, dim3(256), 0, s, st, prm.budget_decay);
+    // the units, then one workgroup per 256 positions for the budget decay
+    const uint64_t grid = (uint64_t)units + (uint64_t)tiles * (uint64_t)st.batch;
+    if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (G <= 4) launch_unit<4>(st, a, pg, (unsigned)grid, lds, s);
+    else if (G <= 8) launch_unit<8>(st, a, pg, (unsigned)grid, lds, s);
+    else launch_unit<MAX_GROUP>(st, a, pg, (unsigned)grid, lds, s);
     return hipGetLastError();
 }
 
