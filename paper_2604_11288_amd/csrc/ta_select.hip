@@ -500,8 +500,13 @@ constexpr int SS_QPT = TA_SELECT_STREAM_QPT;               // quads per thread a
 constexpr int SS_SLACK = TA_SELECT_STREAM_SLACK;           // list entries beyond R + one segment: new entries between two cuts
 constexpr int SS_SEG_QUADS = SS_THREADS * SS_QPT;
 constexpr int SS_SEG = SS_SEG_QUADS * 4;                   // positions per segment
+#ifndef TA_SELECT_STREAM_DEPTH
+#define TA_SELECT_STREAM_DEPTH 2
+#endif
+constexpr int SS_DEPTH = TA_SELECT_STREAM_DEPTH;           // segments whose operands are in flight
 constexpr int SS_HIST_COPIES = 4;
 constexpr int SS_MAX_PER_THREAD = 24;                      // list entries a thread holds while the list is compacted
+constexpr int SS_FEW_PER_THREAD = 10;                      // ... in the instance for short lists (budgets up to about 1300)
 constexpr int SS_MAX_CAP = SS_THREADS * SS_MAX_PER_THREAD;
 constexpr int SS_MAX_LDS = 144 * 1024;                     // dynamic LDS of a workgroup (list + bitmap)
 // Which form runs: the streaming form whenever the keys of a row do not fit the LDS cache of the
@@ -571,6 +576,7 @@ __device__ __forceinline__ RadixState stream_pick(StreamLds& L, uint32_t need)
     return L.state;
 }
 
+template <int PER_THREAD>                                  // cap <= SS_THREADS * PER_THREAD
 __global__ void __launch_bounds__(SS_THREADS)
 select_stream_kernel(SelectArgs a, int32_t cap)
 {
@@ -614,6 +620,31 @@ select_stream_kernel(SelectArgs a, int32_t cap)
     const int32_t nquads = (nb + 3) >> 2;                  // rows are padded to whole quads (n % 4 == 0)
     const bool use_A = (a.alpha != 0.0f);
     const int32_t words = (nb + 31) >> 5;
+
+    struct Loaded {
+        float4 A, v;
+        uint32_t sp, an;
+    };
+    // unconditional loads (the quad index is clamped into the row, the caller masks what lies outside):
+    // straight-line loads let the compiler wait for exactly the segment it needs
+    const float* A_src = use_A ? A : vouch;                // no attention term: any readable row, the values are not used
+    const auto load_quad = [&](int32_t q, Loaded& x) {
+        q = q < 0 ? 0 : (q >= nquads ? nquads - 1 : q);
+        x.sp = *reinterpret_cast<const uint32_t*>(spons + 4 * q);
+        x.an = *reinterpret_cast<const uint32_t*>(anchor + 4 * q);
+        x.v = *reinterpret_cast<const float4*>(vouch + 4 * q);
+        x.A = *reinterpret_cast<const float4*>(A_src + 4 * q);
+    };
+
+    // the first segments' operands are requested before anything else: they travel while the sponsored
+    // positions are counted
+    const int32_t nseg = (nquads + SS_SEG_QUADS - 1) / SS_SEG_QUADS;
+    Loaded ring[SS_DEPTH][SS_QPT];
+#pragma unroll
+    for (int d = 0; d < SS_DEPTH; ++d)
+#pragma unroll
+        for (int j = 0; j < SS_QPT; ++j) load_quad((nseg - 1 - d) * SS_SEG_QUADS + j * SS_THREADS + tid, ring[d][j]);
+
 
     for (int i = tid; i < SS_HIST_COPIES * HIST_STRIDE; i += SS_THREADS) (&L.hist[0][0])[i] = 0;
     for (int32_t i = tid; i < words; i += SS_THREADS) bitmap[i] = 0u;
@@ -669,22 +700,6 @@ select_stream_kernel(SelectArgs a, int32_t cap)
         return k == 0u ? 1u : k;
     };
 
-    struct Loaded {
-        float4 A, v;
-        uint32_t sp, an;
-    };
-    const auto load_quad = [&](int32_t q, Loaded& x) {
-        if (q >= 0 && q < nquads) {
-            x.sp = *reinterpret_cast<const uint32_t*>(spons + 4 * q);
-            x.an = *reinterpret_cast<const uint32_t*>(anchor + 4 * q);
-            x.v = *reinterpret_cast<const float4*>(vouch + 4 * q);
-            x.A = use_A ? *reinterpret_cast<const float4*>(A + 4 * q) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        } else {
-            x.sp = x.an = 0u;
-            x.v = x.A = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        }
-    };
-
     // ---- the list is cut back to its R best entries; returns their threshold -----------------------
     uint32_t T = 0u;              // a position joins the list iff key > T, or key == T and p >= Pt
     int32_t Pt = 0x7FFFFFFF;
@@ -731,9 +746,9 @@ select_stream_kernel(SelectArgs a, int32_t cap)
         }
         // compaction in place: every thread takes its entries into registers, then the kept ones
         // are appended from slot 0 (exactly R of them; their order in the list does not matter)
-        uint32_t mk[SS_MAX_PER_THREAD], mp[SS_MAX_PER_THREAD];
+        uint32_t mk[PER_THREAD], mp[PER_THREAD];
 #pragma unroll
-        for (int j = 0; j < SS_MAX_PER_THREAD; ++j) {
+        for (int j = 0; j < PER_THREAD; ++j) {
             const uint32_t e = (uint32_t)tid + (uint32_t)j * SS_THREADS;
             mk[j] = e < m ? ckey[e] : 0u;
             mp[j] = e < m ? cpos[e] : 0u;
@@ -741,7 +756,7 @@ select_stream_kernel(SelectArgs a, int32_t cap)
         if (tid == 0) L.count = 0u;
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < SS_MAX_PER_THREAD; ++j) {
+        for (int j = 0; j < PER_THREAD; ++j) {
             if ((uint32_t)j * SS_THREADS >= m) break;      // uniform
             const bool keep = mk[j] > Tn || (mk[j] == Tn && mk[j] != 0u && (int32_t)mp[j] >= Pn);
             const unsigned long long bal = __ballot(keep);
@@ -761,68 +776,72 @@ select_stream_kernel(SelectArgs a, int32_t cap)
         Pt = Pn;
     };
 
-    // ---- the walk, from the last segment to the first; the next segment's operands are requested
-    // before the current one is worked on
-    const int32_t nseg = (nquads + SS_SEG_QUADS - 1) / SS_SEG_QUADS;
-    Loaded cur[SS_QPT], nxt[SS_QPT];
+    // ---- the walk, from the last segment to the first; the operands of SS_DEPTH segments are in flight
+    // (a segment is worked on in about a microsecond, a round trip under load takes several)
+    for (int32_t top = nseg - 1; top >= 0; top -= SS_DEPTH) {
 #pragma unroll
-    for (int j = 0; j < SS_QPT; ++j) load_quad((nseg - 1) * SS_SEG_QUADS + j * SS_THREADS + tid, cur[j]);
-    for (int32_t sg = nseg - 1; sg >= 0; --sg) {
-        if (sg > 0) {
+        for (int d = 0; d < SS_DEPTH; ++d) {
+            const int32_t sg = top - d;
+            uint32_t keys[SS_QPT][4];
+            bool join[SS_QPT][4];
+            uint32_t always[SS_QPT];                       // bits of a quad that are retained whatever the ranking says
 #pragma unroll
-            for (int j = 0; j < SS_QPT; ++j) load_quad((sg - 1) * SS_SEG_QUADS + j * SS_THREADS + tid, nxt[j]);
-        }
+            for (int j = 0; j < SS_QPT; ++j) {
+                const Loaded& x = ring[d][j];
+                const int32_t q = sg * SS_SEG_QUADS + j * SS_THREADS + tid;
+                const float Aq[4] = {x.A.x, x.A.y, x.A.z, x.A.w};
+                const float vq[4] = {x.v.x, x.v.y, x.v.z, x.v.w};
+                always[j] = 0u;
 #pragma unroll
-        for (int j = 0; j < SS_QPT; ++j) {
-            const int32_t q = sg * SS_SEG_QUADS + j * SS_THREADS + tid;
-            const float Aq[4] = {cur[j].A.x, cur[j].A.y, cur[j].A.z, cur[j].A.w};
-            const float vq[4] = {cur[j].v.x, cur[j].v.y, cur[j].v.z, cur[j].v.w};
-            uint32_t keys[4];
-            bool join[4];
-            uint32_t always = 0u;                          // bits of this quad that are retained whatever the ranking says
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int32_t p = 4 * q + c;
-                const uint32_t sp = (cur[j].sp >> (8 * c)) & 0xFFu, an = (cur[j].an >> (8 * c)) & 0xFFu;
-                keys[c] = 0u;
-                join[c] = false;
-                if (p < nb && q < nquads) {
-                    if (p < ns || p >= rs) always |= 1u << c;
-                    else if ((sp != 0u) != (bclass == 1)) always |= (sp != 0u) ? (1u << c) : 0u;   // class 1 above the boundary class, class 0 below it
-                    else if (R > 0) {
-                        keys[c] = key_of(p, Aq[c], an, vq[c]);
-                        join[c] = keys[c] > T || (keys[c] == T && p >= Pt);
-                    }
-                }
-            }
-            if (always) atomicOr(&bitmap[(4 * q) >> 5], always << ((4 * q) & 31));
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const unsigned long long bal = __ballot(join[c]);
-                if (bal) {                                 // uniform
-                    uint32_t base = 0;
-                    if (lane == 0) base = atomicAdd(&L.count, (uint32_t)__popcll(bal));
-                    base = __shfl(base, 0);
-                    if (join[c]) {
-                        const uint32_t slot = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-                        if (slot < (uint32_t)cap) {        // holds by construction: the list is cut back before it could overflow
-                            ckey[slot] = keys[c];
-                            cpos[slot] = (uint32_t)(4 * q + c);
+                for (int c = 0; c < 4; ++c) {
+                    const int32_t p = 4 * q + c;
+                    const uint32_t sp = (x.sp >> (8 * c)) & 0xFFu, an = (x.an >> (8 * c)) & 0xFFu;
+                    keys[j][c] = 0u;
+                    join[j][c] = false;
+                    if (sg >= 0 && p < nb && q < nquads) {
+                        if (p < ns || p >= rs) always[j] |= 1u << c;
+                        else if ((sp != 0u) != (bclass == 1)) always[j] |= (sp != 0u) ? (1u << c) : 0u;   // class 1 above the boundary class, class 0 below it
+                        else if (R > 0) {
+                            keys[j][c] = key_of(p, Aq[c], an, vq[c]);
+                            join[j][c] = keys[j][c] > T || (keys[j][c] == T && p >= Pt);
                         }
                     }
                 }
             }
-        }
-        __syncthreads();                                   // the segment's entries are in the list
-        const uint32_t m = L.count;
-        __syncthreads();                                   // every thread has read the count before anyone adds to it again
-        // Cut back when the next segment might not fit, at the end (to exactly R), and once early: the
-        // first cut gives the threshold that keeps most later positions out of the list.
-        const bool early = T == 0u && m >= 2u * (uint32_t)R && m >= 512u;
-        if (R > 0 && ((sg > 0 && (m + (uint32_t)SS_SEG > (uint32_t)cap || early)) || (sg == 0 && m > (uint32_t)R))) shrink(m);
-        if (sg > 0) {
+            // the segment SS_DEPTH further on takes over the registers (past the first segment: a clamped
+            // address whose data nobody uses)
 #pragma unroll
-            for (int j = 0; j < SS_QPT; ++j) cur[j] = nxt[j];
+            for (int j = 0; j < SS_QPT; ++j) load_quad((sg - SS_DEPTH) * SS_SEG_QUADS + j * SS_THREADS + tid, ring[d][j]);
+            if (sg >= 0) {                                 // uniform
+#pragma unroll
+                for (int j = 0; j < SS_QPT; ++j) {
+                    const int32_t q = sg * SS_SEG_QUADS + j * SS_THREADS + tid;
+                    if (always[j]) atomicOr(&bitmap[(4 * q) >> 5], always[j] << ((4 * q) & 31));
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const unsigned long long bal = __ballot(join[j][c]);
+                        if (bal) {                         // uniform
+                            uint32_t base = 0;
+                            if (lane == 0) base = atomicAdd(&L.count, (uint32_t)__popcll(bal));
+                            base = __shfl(base, 0);
+                            if (join[j][c]) {
+                                const uint32_t slot = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+                                if (slot < (uint32_t)cap) {    // holds by construction: the list is cut back before it could overflow
+                                    ckey[slot] = keys[j][c];
+                                    cpos[slot] = (uint32_t)(4 * q + c);
+                                }
+                            }
+                        }
+                    }
+                }
+                __syncthreads();                           // the segment's entries are in the list
+                const uint32_t m = L.count;
+                __syncthreads();                           // every thread has read the count before anyone adds to it again
+                // Cut back when the next segment might not fit, at the end (to exactly R), and once early: the
+                // first cut gives the threshold that keeps most later positions out of the list.
+                const bool early = T == 0u && m >= 2u * (uint32_t)R && m >= 512u;
+                if (R > 0 && ((sg > 0 && (m + (uint32_t)SS_SEG > (uint32_t)cap || early)) || (sg == 0 && m > (uint32_t)R))) shrink(m);
+            }
         }
     }
 
@@ -882,7 +901,10 @@ hipError_t select_setup()
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel<SS_FEW_PER_THREAD>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel<SS_MAX_PER_THREAD>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
         return e;
     });
@@ -930,7 +952,10 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
         if (cap <= SS_MAX_CAP && lds <= SS_MAX_LDS) {
             const hipError_t attr_err = select_setup();
             if (attr_err != hipSuccess) return attr_err;
-            hipLaunchKernelGGL(select_stream_kernel, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
+            if (cap <= SS_THREADS * SS_FEW_PER_THREAD)
+                hipLaunchKernelGGL(select_stream_kernel<SS_FEW_PER_THREAD>, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
+            else
+                hipLaunchKernelGGL(select_stream_kernel<SS_MAX_PER_THREAD>, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
             return hipGetLastError();
         }
     }
