@@ -205,10 +205,36 @@ def test_c5_agentic_full_prefill_and_decode_steps():
         units[key] = ora.DecodeUnit(Krows, Vrows, idx_ref, A_ref[idx_ref])
     stream = wl.make_decode_stream(w, td, steps, p_anchor=0.02)
     evicted = torch.zeros((w.layers, w.batch, w.hkv), dtype=torch.int32, device=DEV)
+    # the same steps over slots kept in a page pool (pages of 16 slots), the prefill's rows compacted straight
+    # into the pages: every array of that state must equal the dense state's, bit for bit, after every step
+    page_size = 16
+    Kp, Vp, ptable, num_pages, pstrides = wl.make_slot_pool(w.layers, w.batch, w.hkv, w.d, K + 1, page_size, DEV)
+    pool = ta.PagedKV(Kp, Vp, _dev(ptable), page_size, num_pages, pstrides, w.layers, w.batch, w.hkv, K + 1)
+    ta.ta_compact_into_pages(plan.Kin, plan.Vin, plan.idx, plan.cnt, K, pool)
+    stp = ta.DecodeState(w.layers, w.batch, w.hq, w.hkv, K, cap, DEV, pages=pool)
+    ta.ta_decode_init(stp, _dev(td.tok), plan.anchor, plan.idx, plan.cnt, None, None, prm, seq_len=_dev(td.seq_len), A=plan.A)
+    evicted_p = torch.zeros_like(evicted)
+    slot = torch.arange(K + 1, device=DEV)
+    slot_page = _dev(ptable)[:, slot // page_size].long()                  # [B][slots]
+
+    def pool_slots(pool_t):                                                 # [Lyr][pages][page_size][H][d] -> [Lyr][B][H][slots][d]
+        return pool_t[:, slot_page, (slot % page_size)[None, :]].permute(0, 1, 3, 2, 4)
+
     for t in range(steps):
         q, kn, vn = wl.make_decode_qkv(w, t, device=DEV)
         ta.ta_decode_step(st, _dev(stream[t]), q, kn, vn, td.tab_ids, td.tab_len, prm, evicted=evicted)
+        ta.ta_decode_step(stp, _dev(stream[t]), q, kn, vn, td.tab_ids, td.tab_len, prm, evicted=evicted_p)
         torch.cuda.synchronize()
+        assert torch.equal(evicted, evicted_p) and torch.equal(st.pos, stp.pos)
+        assert torch.equal(st.A.view(torch.int32), stp.A.view(torch.int32))
+        assert torch.equal(st.budget.view(torch.int32), stp.budget.view(torch.int32)) and torch.equal(st.len, stp.len)
+        occupied = (st.pos >= 0)[..., None]
+        for l in range(w.layers):                                           # layer by layer: the gathered copy is 34 MB each
+            occ = occupied[l:l + 1]
+            for paged_rows, dense_rows in ((pool_slots(Kp[l:l + 1]), st.Kc[l:l + 1]), (pool_slots(Vp[l:l + 1]), st.Vc[l:l + 1])):
+                zero = torch.zeros((), dtype=torch.int16, device=DEV)
+                assert torch.equal(torch.where(occ, paged_rows.contiguous().view(torch.int16), zero),
+                                   torch.where(occ, dense_rows.view(torch.int16), zero))
         # every unit: exactly one free slot, one eviction, K occupied
         assert bool(((st.pos < 0).sum(-1) == 1).all())
         assert bool((evicted >= 0).all())
