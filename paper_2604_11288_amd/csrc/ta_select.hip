@@ -577,8 +577,7 @@ __device__ __forceinline__ RadixState stream_pick(StreamLds& L, uint32_t need)
 }
 
 template <int PER_THREAD>                                  // cap <= SS_THREADS * PER_THREAD
-__global__ void __launch_bounds__(SS_THREADS)
-select_stream_kernel(SelectArgs a, int32_t cap)
+__device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t cap)
 {
     extern __shared__ uint32_t s_dyn[];                    // [cap] keys, [cap] positions, [ceil(n / 32)] bitmap
     __shared__ StreamLds L;
@@ -886,6 +885,21 @@ select_stream_kernel(SelectArgs a, int32_t cap)
     if (tid == 0) a.cnt[unit] = total < K ? total : K;
 }
 
+// Short candidate lists (budgets up to about 1300): six wavefronts per SIMD, which the many short units
+// of a ragged batch need to hide their round trips (two registers go to scratch for it).  Long lists keep
+// the registers.
+__global__ void __launch_bounds__(SS_THREADS) __attribute__((amdgpu_waves_per_eu(6)))
+select_stream_few_kernel(SelectArgs a, int32_t cap)
+{
+    select_stream<SS_FEW_PER_THREAD>(a, cap);
+}
+
+__global__ void __launch_bounds__(SS_THREADS) __attribute__((amdgpu_waves_per_eu(4)))
+select_stream_kernel(SelectArgs a, int32_t cap)
+{
+    select_stream<SS_MAX_PER_THREAD>(a, cap);
+}
+
 DeviceOnce g_setup;
 
 }  // namespace
@@ -901,10 +915,10 @@ hipError_t select_setup()
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel<SS_FEW_PER_THREAD>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_few_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel<SS_MAX_PER_THREAD>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
         return e;
     });
@@ -953,9 +967,9 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
             const hipError_t attr_err = select_setup();
             if (attr_err != hipSuccess) return attr_err;
             if (cap <= SS_THREADS * SS_FEW_PER_THREAD)
-                hipLaunchKernelGGL(select_stream_kernel<SS_FEW_PER_THREAD>, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
+                hipLaunchKernelGGL(select_stream_few_kernel, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
             else
-                hipLaunchKernelGGL(select_stream_kernel<SS_MAX_PER_THREAD>, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
+                hipLaunchKernelGGL(select_stream_kernel, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
             return hipGetLastError();
         }
     }
