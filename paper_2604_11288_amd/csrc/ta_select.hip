@@ -756,7 +756,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < PER_THREAD; ++j) {
-            if ((uint32_t)j * SS_THREADS >= m) break;      // uniform
+            if ((uint32_t)j * SS_THREADS >= m) continue;   // uniform: nothing of the list lies this far
             const bool keep = mk[j] > Tn || (mk[j] == Tn && mk[j] != 0u && (int32_t)mp[j] >= Pn);
             const unsigned long long bal = __ballot(keep);
             uint32_t base = 0;
