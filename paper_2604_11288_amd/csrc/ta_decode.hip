@@ -110,8 +110,13 @@ decode_init_unit_kernel(ta_decode_state st, int32_t n, const float* A, const int
             const int32_t j = page_index(pg, s);
             const int32_t page = clamp_page(pg, pg.table[(size_t)b * pg.max_pages + j]);
             const int64_t at = (int64_t)page * pg.s_page + (int64_t)(s - j * pg.page_size) * pg.s_slot + (i & 15);
-            Kc[at] = s < c ? Kout[(size_t)unit * st.K * 16 + i] : zero;
-            Vc[at] = s < c ? Vout[(size_t)unit * st.K * 16 + i] : zero;
+            uint4 kv = zero, vv = zero;                        // (a conditional expression on the structs goes through scratch memory)
+            if (s < c) {
+                kv = Kout[(size_t)unit * st.K * 16 + i];
+                vv = Vout[(size_t)unit * st.K * 16 + i];
+            }
+            Kc[at] = kv;
+            Vc[at] = vv;
         }
         return;
     }
@@ -119,8 +124,13 @@ decode_init_unit_kernel(ta_decode_state st, int32_t n, const float* A, const int
     uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (size_t)unit * slots * 16;
     for (int i = threadIdx.x; i < slots * 16; i += DU_THREADS) {
         const int s = i >> 4;
-        Kc[i] = s < c ? Kout[(size_t)unit * st.K * 16 + i] : zero;
-        Vc[i] = s < c ? Vout[(size_t)unit * st.K * 16 + i] : zero;
+        uint4 kv = zero, vv = zero;
+        if (s < c) {
+            kv = Kout[(size_t)unit * st.K * 16 + i];
+            vv = Vout[(size_t)unit * st.K * 16 + i];
+        }
+        Kc[i] = kv;
+        Vc[i] = vv;
     }
 }
 
