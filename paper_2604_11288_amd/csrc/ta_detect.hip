@@ -30,7 +30,6 @@ namespace ta {
 namespace {
 
 constexpr int DT_KS = 32;                        // input features per slice
-constexpr int DT_RING = 3;
 
 struct DetectArgs {
     const uint4* h;
@@ -94,6 +93,11 @@ __device__ __forceinline__ float add_squares(uint4 v, float acc)
 }
 
 enum { MODE_MLP = 0, MODE_COSINE = 1 };
+// Slice buffers of a workgroup.  Three (loads two slices ahead), except where two leave room for a third
+// resident workgroup per compute unit (24 KB buffers of the 128-unit detector: 881 us against 903), which
+// the long streams of the learned detector gain more from than from the deeper ring (the 256-unit
+// detector, one large workgroup per compute unit either way, loses 8 % with two).
+constexpr int detect_ring(int M, int MODE) { return (MODE == MODE_MLP && M == 128) ? 2 : 3; }
 
 // TW: wavefront rows over the positions (64 TW positions per workgroup); HT: 32-unit hidden tiles
 // per wavefront; MH: wavefront columns over the hidden units (m = 32 HT MH); MODE: which epilogue
@@ -112,6 +116,7 @@ detect_kernel(DetectArgs a)
     constexpr int LPS = LH + LW;
     constexpr int H_BYTES = DT_TOKENS * 64;                // bytes of the h part of a buffer
     constexpr int BUF_BYTES = H_BYTES + M * 64;
+    constexpr int DT_RING = detect_ring(M, MODE);
 
     extern __shared__ uint4 s_buf[];                       // DT_RING buffers, then W2 as floats
     float* s_w2 = reinterpret_cast<float*>(reinterpret_cast<char*>(s_buf) + DT_RING * BUF_BYTES);
@@ -341,7 +346,7 @@ hipError_t launch_one(const DetectArgs& a, hipStream_t st)
 {
     constexpr int M = 32 * HT * MH;
     constexpr int DT_TOKENS = 64 * TW;
-    const size_t lds = (size_t)DT_RING * (DT_TOKENS * 64 + M * 64) + (size_t)M * 4 + (size_t)(MH + 1) * DT_TOKENS * 4;
+    const size_t lds = (size_t)detect_ring(M, MODE) * (DT_TOKENS * 64 + M * 64) + (size_t)M * 4 + (size_t)(MH + 1) * DT_TOKENS * 4;
     static DeviceOnce setup;                               // dynamic LDS above 64 KB needs the attribute (per instantiation)
     const hipError_t attr_err = setup.run([&](int) {
         return hipFuncSetAttribute(reinterpret_cast<const void*>(&detect_kernel<TW, HT, MH, MODE>),
