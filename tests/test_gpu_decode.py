@@ -284,18 +284,21 @@ def test_decode_last_query_rule(rank):
     print("last-query rule, rank=%s: %d excused near-tie evictions" % (rank, stats.get("excused", 0)))
 
 
-@pytest.mark.parametrize("page_size,heads_first,in_place,K,steps", [
-    (16, False, False, 64, 36),     # [pages][16][heads][d]: a unit's 65 slots over 5 pages
-    (64, True, False, 64, 36),      # [pages][heads][64][d]
-    (24, False, True, 64, 36),      # a page size that is no power of two; rows compacted straight into the pages
-    (128, True, True, 64, 36),      # all slots of a unit in one page
-    (16, False, True, 400, 8),      # more slots than a lane keeps in registers: the looping form of the unit kernel
+@pytest.mark.parametrize("page_size,heads_first,in_place,K,steps,hq", [
+    (16, False, False, 64, 36, 8),     # [pages][16][heads][d]: a unit's 65 slots over 5 pages
+    (64, True, False, 64, 36, 8),      # [pages][heads][64][d]
+    (24, False, True, 64, 36, 8),      # a page size that is no power of two; rows compacted straight into the pages
+    (128, True, True, 64, 36, 8),      # all slots of a unit in one page
+    (16, False, True, 400, 8, 8),      # more slots than a lane keeps in registers: the looping form of the unit kernel
+    (16, False, False, 64, 10, 16),    # 8 query heads per KV head
+    (16, False, True, 400, 6, 16),
+    (32, True, True, 64, 10, 32),      # 16 query heads per KV head (512 query rows per unit in the prefill)
 ])
-def test_decode_over_a_paged_slot_pool(page_size, heads_first, in_place, K, steps):
+def test_decode_over_a_paged_slot_pool(page_size, heads_first, in_place, K, steps, hq):
     """The generation step with the K/V slots in a page pool behind a block table: every comparison of the
     dense runs (anchors, budgets, slot positions, evicted positions, attention, cached rows) against the
     oracle, the rows read back through the table."""
-    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=3, n=1100, hq=8, hkv=2, ragged=(40, 1100))
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=3, n=1100, hq=hq, hkv=2, ragged=(40, 1100))
     ev, anc = _run_decode(w, K=K, steps=steps, p_anchor=0.08, paged=(page_size, heads_first), in_place=in_place)
     assert ev > 0
 
