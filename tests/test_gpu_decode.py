@@ -198,14 +198,15 @@ def test_decode_steps_match_oracle_c5_shape_one_layer():
     assert ev == 12 * 2 * 8
 
 
-def test_decode_attention_free_and_partly_filled_cache():
+@pytest.mark.parametrize("K,paged", [(256, None), (350, None), (256, (16, False)), (350, (32, True))])
+def test_decode_attention_free_and_partly_filled_cache(K, paged):
     # TA-Fast setting (no queries); sequence 0 is shorter than the budget, so its cache fills up
-    # before anything is evicted
+    # before anything is evicted.  Budgets on both sides of what a lane keeps in registers, dense and paged slots.
     w = wl.scaled(wl.CONFIGS["c3_ta_fast"], layers=1, batch=2, n=400, hq=8, hkv=2, n_recent=8, planted=3,
                   ragged=(40, 400))
     td = wl.make_tokens(w, clean=False)
     assert td.seq_len.min() < 256 < td.seq_len.max()
-    ev, _ = _run_decode(w, K=256, steps=70, p_anchor=0.1, check_every=10)
+    ev, _ = _run_decode(w, K=K, steps=70, p_anchor=0.1, check_every=10, paged=paged, in_place=paged is not None)
     assert 0 < ev < 70 * 2 * 2
 
 
