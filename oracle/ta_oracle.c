@@ -21,7 +21,8 @@
  * sum / endpoints / monotonicity of the layer budgets; scores from a given
  * log-sum-exp: torch.logsumexp, agreement with the two-pass scores, row sums;
  * paged gather and scatter: numpy fancy indexing on both common page layouts,
- * gather after scatter returns the rows).
+ * gather after scatter returns the rows; margin of the cut: hand-read cases, and
+ * the minimum / maximum restated on the selection's own output).
  * Unpinned: nothing in this file; the values
  * of A on a trained model and the paper's accuracy tables are not reproduced.
  */
@@ -246,6 +247,46 @@ int32_t ta_oracle_select(const float *A, const uint8_t *anchor,
     free(keys);
     free(u);
     return cnt;
+}
+
+/*
+ * Margin of the cut that ta_oracle_select makes (a diagnostic of the total order of
+ * Sec. 3.3 / Eq. 1, not a quantity of the paper): with the positions ranked as above, the
+ * first evicted one is ranked min(K, n); its class c is the class the cut falls in (every
+ * higher class is kept whole).
+ *   margin[0] = smallest u among the retained positions of class c, +inf if none is retained
+ *   margin[1] = largest u among the evicted positions of class c  (the first evicted one's)
+ * Nothing evicted (n <= K): (+inf, -inf).  margin[0] == margin[1] means positions tie at the
+ * cut and the position order decided; a small gap means a selection that rounding can flip.
+ */
+void ta_oracle_select_margin(const float *A, const uint8_t *anchor,
+                             const uint8_t *spons, const float *V,
+                             int32_t n, int32_t K, int32_t n_sink, int32_t n_recent,
+                             float alpha, float beta, float gamma, float *margin)
+{
+    margin[0] = INFINITY;
+    margin[1] = -INFINITY;
+    if (n <= K || K <= 0)
+        return;
+    float *u = (float *)malloc(sizeof(float) * (size_t)n);
+    ta_oracle_key *keys = (ta_oracle_key *)malloc(sizeof(ta_oracle_key) * (size_t)n);
+    ta_oracle_utility(A, anchor, V, n, alpha, beta, gamma, u);
+    for (int32_t p = 0; p < n; ++p) {
+        int32_t cls = 0;
+        if (p < n_sink || p >= n - n_recent)
+            cls = 2;
+        else if (spons[p])
+            cls = 1;
+        keys[p].cls = cls;
+        keys[p].u = u[p];
+        keys[p].pos = p;
+    }
+    qsort(keys, (size_t)n, sizeof(ta_oracle_key), key_before);
+    margin[1] = keys[K].u;
+    if (keys[K - 1].cls == keys[K].cls)
+        margin[0] = keys[K - 1].u;
+    free(keys);
+    free(u);
 }
 
 /*
@@ -615,6 +656,59 @@ int32_t ta_oracle_select_partition(const float *A, const uint8_t *anchor,
     free(keys);
     free(u);
     return cnt;
+}
+
+/*
+ * Margin of the main-pool cut of ta_oracle_select_partition (a diagnostic, as
+ * ta_oracle_select_margin): among the positions that are neither mandatory nor protected,
+ *   margin[0] = smallest u among the retained ones, +inf if the main pool has no slot for them
+ *   margin[1] = largest u among the evicted ones
+ * Nothing evicted (n <= K): (+inf, -inf).
+ */
+void ta_oracle_select_partition_margin(const float *A, const uint8_t *anchor,
+                                       const uint8_t *spons, const float *V,
+                                       int32_t n, int32_t K, int32_t k_protected,
+                                       int32_t n_sink, int32_t n_recent,
+                                       float alpha, float beta, float gamma, float *margin)
+{
+    margin[0] = INFINITY;
+    margin[1] = -INFINITY;
+    if (n <= K || K <= 0)
+        return;
+    float *u = (float *)malloc(sizeof(float) * (size_t)n);
+    ta_oracle_key *keys = (ta_oracle_key *)malloc(sizeof(ta_oracle_key) * (size_t)n);
+    ta_oracle_utility(A, anchor, V, n, alpha, beta, gamma, u);
+    int32_t mandatory = 0;
+    for (int32_t p = 0; p < n; ++p) {
+        int32_t cls = 0;
+        if (p < n_sink || p >= n - n_recent) {
+            cls = 2;
+            ++mandatory;
+        } else if (spons[p])
+            cls = 1;
+        keys[p].cls = cls;
+        keys[p].u = u[p];
+        keys[p].pos = p;
+    }
+    qsort(keys, (size_t)n, sizeof(ta_oracle_key), key_before);
+    int32_t sponsored = 0;
+    for (int32_t r = mandatory; r < n && keys[r].cls == 1; ++r)
+        ++sponsored;
+    int32_t prot = k_protected < sponsored ? k_protected : sponsored;
+    if (prot > K - mandatory)
+        prot = K - mandatory > 0 ? K - mandatory : 0;
+    const int32_t first = mandatory + prot;          /* rank of the main pool's best candidate */
+    for (int32_t r = first; r < n; ++r)
+        keys[r].cls = 0;
+    if (first < n)
+        qsort(keys + first, (size_t)(n - first), sizeof(ta_oracle_key), key_before);
+    if (K >= first) {                                /* else the mandatory tokens alone overflow K */
+        margin[1] = keys[K].u;
+        if (K - 1 >= first)
+            margin[0] = keys[K - 1].u;
+    }
+    free(keys);
+    free(u);
 }
 
 /*

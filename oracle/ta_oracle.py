@@ -49,6 +49,8 @@ def _load():
         lib.ta_oracle_utility.restype = None
         lib.ta_oracle_select.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
         lib.ta_oracle_select.restype = i32
+        lib.ta_oracle_select_margin.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32, vp]
+        lib.ta_oracle_select_margin.restype = None
         lib.ta_oracle_compact.argtypes = [vp, vp, i32, i32, vp]
         lib.ta_oracle_compact.restype = None
         lib.ta_oracle_decode_append.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, i32, f32]
@@ -77,6 +79,8 @@ def _load():
         lib.ta_oracle_maxpool.restype = None
         lib.ta_oracle_select_partition.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, f32, vp]
         lib.ta_oracle_select_partition.restype = i32
+        lib.ta_oracle_select_partition_margin.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, f32, vp]
+        lib.ta_oracle_select_partition_margin.restype = None
         lib.ta_oracle_layer_budgets.argtypes = [i32, i32, i32, vp]
         lib.ta_oracle_layer_budgets.restype = None
         lib.ta_oracle_allow_filter.argtypes = [vp, vp, i32, vp]
@@ -209,6 +213,27 @@ def select(A, anchor, spons, V, K, n_sink, n_recent, alpha=1.0, beta=0.5, gamma=
                                    int(n_sink), int(n_recent),
                                    float(alpha), float(beta), float(gamma), _p(idx))
     return idx[:cnt].copy()
+
+
+def select_margin(A, anchor, spons, V, K, n_sink, n_recent, alpha=1.0, beta=0.5, gamma=0.3, k_protected=-1):
+    """(smallest retained u, largest evicted u) of the class - with k_protected >= 0: of the main pool -
+    that the cut of select / select_partition falls in; (+inf, -inf) when nothing is evicted."""
+    anchor = _c(anchor, np.uint8)
+    spons = _c(spons, np.uint8)
+    V = _c(V, np.float32)
+    n = anchor.shape[0]
+    a = None if A is None else _c(A, np.float32)
+    if a is None:
+        assert alpha == 0.0
+    out = np.zeros(2, np.float32)
+    if k_protected < 0:
+        _load().ta_oracle_select_margin(_p(a), _p(anchor), _p(spons), _p(V), n, int(K), int(n_sink), int(n_recent),
+                                        float(alpha), float(beta), float(gamma), _p(out))
+    else:
+        _load().ta_oracle_select_partition_margin(_p(a), _p(anchor), _p(spons), _p(V), n, int(K), int(k_protected),
+                                                  int(n_sink), int(n_recent), float(alpha), float(beta),
+                                                  float(gamma), _p(out))
+    return out
 
 
 def compact(rows, idx):

@@ -332,6 +332,95 @@ def test_select_tie_break_prefers_later_position_and_k_ge_n():
     assert ora.select(zf, z8, z8, zf, K=n, n_sink=2, n_recent=2).tolist() == list(range(n))
 
 
+def test_select_margin_hand_case_and_degenerate_cuts():
+    """alpha = 1, beta = gamma = 0, no vouchers: u is A itself, so the margin can be read off by hand."""
+    n = 12
+    z8, zf = np.zeros(n, np.uint8), np.zeros(n, np.float32)
+    A = np.array([9, 9, 1, 7, 3, 8, 2, 6, 5, 4, 9, 9], np.float32)
+    kw = dict(n_sink=2, n_recent=2, alpha=1.0, beta=0.0, gamma=0.0)
+    # nothing sponsored: the mandatory four, then 8 7 6 5 | 4 3 2 1
+    assert ora.select_margin(A, z8, z8, zf, K=8, **kw).tolist() == [5.0, 4.0]
+    assert ora.select_margin(A, z8, z8, zf, K=7, **kw).tolist() == [6.0, 5.0]
+    # K = 4: only the mandatory tokens stay; class 0 keeps nothing
+    assert ora.select_margin(A, z8, z8, zf, K=4, **kw).tolist() == [np.inf, 8.0]
+    # nothing evicted
+    assert ora.select_margin(A, z8, z8, zf, K=n, **kw).tolist() == [np.inf, -np.inf]
+    assert ora.select_margin(A, z8, z8, zf, K=n + 5, **kw).tolist() == [np.inf, -np.inf]
+    # positions 2, 4, 6 sponsored (u = 1, 3, 2): they outrank every plain token
+    sp = z8.copy()
+    sp[[2, 4, 6]] = 1
+    # K = 8: 4 mandatory + 3 sponsored + one plain slot (8); the cut is in class 0 between 8 and 7
+    assert ora.select_margin(A, z8, sp, zf, K=8, **kw).tolist() == [8.0, 7.0]
+    # K = 7: the sponsored fit exactly, no plain token is kept
+    assert ora.select_margin(A, z8, sp, zf, K=7, **kw).tolist() == [np.inf, 8.0]
+    # K = 6: pool overflow, the cut is inside class 1: 3 2 | 1
+    assert ora.select_margin(A, z8, sp, zf, K=6, **kw).tolist() == [2.0, 1.0]
+    # an exact tie at the cut: both sides report the same value
+    T = np.array([9, 9, 5, 5, 5, 5, 5, 1, 1, 1, 9, 9], np.float32)
+    assert ora.select_margin(T, z8, z8, zf, K=7, **kw).tolist() == [5.0, 5.0]
+    # fixed partition, one protected slot: the best sponsored token (u = 3) is protected, the other two
+    # compete by u alone; main pool of K = 8: 8 7 6 | 5
+    assert ora.select_margin(A, z8, sp, zf, K=8, k_protected=1, **kw).tolist() == [6.0, 5.0]
+    # the protected pool takes every slot the mandatory tokens leave: the main pool keeps nothing
+    assert ora.select_margin(A, z8, sp, zf, K=6, k_protected=2, **kw).tolist() == [np.inf, 8.0]
+
+
+def test_select_margin_follows_from_the_selection():
+    """The margin restated on the selection's own (independently pinned) output: the class of the cut is
+    the highest class that loses a member."""
+    rng = np.random.default_rng(77)
+    seen_tie = seen_inf = 0
+    for trial in range(60):
+        n = int(rng.integers(12, 300))
+        ns, nr = int(rng.integers(0, 4)), int(rng.integers(0, 6))
+        K = int(rng.integers(max(1, ns + nr), n))
+        A = np.round(rng.random(n) * 3, 1).astype(np.float32)
+        anchor = (rng.random(n) < 0.06).astype(np.uint8)
+        spons, V = ora.expand(anchor, L=4, B=15.0)
+        beta = 0.0 if trial % 2 else 0.5
+        idx = ora.select(A, anchor, spons, V, K=K, n_sink=ns, n_recent=nr, beta=beta)
+        u = ora.utility(A, anchor, V, beta=beta)
+        cls = _classes(n, spons, ns, nr)
+        kept = np.zeros(n, bool)
+        kept[idx] = True
+        c = cls[~kept].max()
+        lo = u[kept & (cls == c)]
+        want = [lo.min() if lo.size else np.inf, u[~kept & (cls == c)].max()]
+        got = ora.select_margin(A, anchor, spons, V, K=K, n_sink=ns, n_recent=nr, beta=beta)
+        assert got.tolist() == [float(w) for w in want], (trial, n, K)
+        assert got[0] >= got[1]
+        seen_tie += got[0] == got[1]
+        seen_inf += not lo.size
+    assert seen_tie >= 5                                    # coarse scores without recency: ties at the cut occur
+
+
+@pytest.mark.parametrize("kp", [0, 1, 3, 1000])
+def test_partition_margin_follows_from_the_selection(kp):
+    rng = np.random.default_rng(300 + kp)
+    for trial in range(25):
+        n = int(rng.integers(12, 120))
+        ns, nr = int(rng.integers(0, 3)), int(rng.integers(0, 4))
+        K = int(rng.integers(ns + nr + 1, n))
+        A = (rng.integers(0, 8, n) * 1.5).astype(np.float32)
+        anchor = (rng.random(n) < 0.1).astype(np.uint8)
+        spons, V = ora.expand(anchor, L=3)
+        idx = ora.select_partition(A, anchor, spons, V, K, kp, ns, nr)
+        u = ora.utility(A, anchor, V)
+        p = np.arange(n)
+        mand = (p < ns) | (p >= n - nr)
+        # the protected tokens: the best sponsored ones by (u, position), as many as the pool and K allow
+        sp = sorted([q for q in p[~mand] if spons[q]], key=lambda q: (u[q], q), reverse=True)
+        prot = np.zeros(n, bool)
+        prot[sp[:max(0, min(kp, len(sp), K - int(mand.sum())))]] = True
+        kept = np.zeros(n, bool)
+        kept[idx] = True
+        cand = ~mand & ~prot
+        lo = u[kept & cand]
+        want = [float(lo.min()) if lo.size else np.inf, float(u[~kept & cand].max())]
+        got = ora.select_margin(A, anchor, spons, V, K, ns, nr, k_protected=kp)
+        assert got.tolist() == want, (trial, n, K, kp)
+
+
 # --------------------------------------------------------------------------
 # Step 5: compaction
 # --------------------------------------------------------------------------
