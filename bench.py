@@ -11,6 +11,7 @@ its own roofline.  Inputs are synthetic and resident in HBM before the timed
 region starts.  Prints ONE JSON line.
 """
 import argparse
+import dataclasses
 import gc
 import hashlib
 import json
@@ -296,6 +297,25 @@ class Bench:
                              "achieved": round(row_bytes / step_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": round(row_bytes / step_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None}}
 
+    # ---- how close every unit's cut is to flipping: the margin output of the selection, all units -------
+    def cut_margins(self):
+        """Selects once more with the margin output on (not timed) and counts, over ALL units of the workload,
+        those whose smallest retained and largest evicted utility lie within the parity tolerance of each
+        other: the units where a retained set may legitimately differ from the oracle's."""
+        ta, torch, w, plan = self.ta, self.torch, self.w, self.plan
+        layers, hkv = (w.layers, w.hkv) if self.scored else (1, 1)
+        prm = dataclasses.replace(self.prm, margin=torch.empty((layers * w.batch * hkv, 2), device=self.dev))
+        ta.ta_select(plan.A if self.scored else None, plan.anchor, plan.spons, plan.vouch, self.budget, prm,
+                     layers, hkv, seq_len=self.seq)
+        torch.cuda.synchronize()
+        m = prm.margin.double().cpu().numpy()
+        cut = self.np.isfinite(m).all(axis=1)                  # units that evict and keep something of the cut's class
+        gap = (m[cut, 0] - m[cut, 1]) / self.np.abs(m[cut, 0])
+        return {"units": int(m.shape[0]), "units_with_a_cut": int(cut.sum()),
+                "near_tie_units_rel_gap_le_1e-3": int((gap <= 1e-3).sum()),
+                "exact_tie_units": int((gap == 0).sum()),
+                "median_rel_gap": float("%.3e" % self.np.median(gap)) if gap.size else None}
+
     # ---- the oracle: timed on the host cores and compared with the GPU's outputs -------------------
     def oracle_leg(self, single_s, multi_s):
         """Runs the CPU oracle on a bounded, seeded sample of this workload's units.
@@ -418,6 +438,7 @@ def measure_extra(ta, wl, torch, np, name, budget, dev, steps, warmup, copies=1,
         b.plan.run(b.stream)
         torch.cuda.synchronize()
         _, parity = b.oracle_leg(oracle_s / 2, oracle_s / 2)
+        parity["cut_margins_all_units"] = b.cut_margins()
         out["parity"] = parity
     del b
     free_device_memory(torch)
@@ -717,6 +738,7 @@ def main():
         plan.run(stream)                                        # the outputs of the fused pass at this budget
         torch.cuda.synchronize()
         cpu, parity = bench.oracle_leg(single_s=10.0, multi_s=8.0)
+        parity["cut_margins_all_units"] = bench.cut_margins()
 
     config = {"workload": describe(w), "budget_K": budget, "entry_point": "ta_evict"}
     if args.rotate > 1:

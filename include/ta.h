@@ -89,7 +89,7 @@ typedef struct ta_params {
     int32_t causal;     /* 1: window query w sees keys 0..n-W+w; 0: every key             */
     float budget_decay; /* per-step decay of sponsor budgets (paper: 0.9); decode steps   */
     /* Options around the same selection (baselines of Sec. 2 / Sec. 4 and the partition of
-     * Sec. 3.3 as settings).  Defaults: 1, -1, 0, NULL, NULL.  The per-step form accepts only the
+     * Sec. 3.3 as settings).  Defaults: 1, -1, 0, NULL, NULL, NULL.  The per-step form accepts only the
      * defaults of pool_k and k_protected and ignores layer_K and allow; the one-shot pass ignores
      * last_query. */
     int32_t pool_k;      /* odd window (1, 3, 5, 7 or 9) of a max-pool applied to A along the sequence
@@ -111,6 +111,18 @@ typedef struct ta_params {
                             many are valid                                                         */
     const uint8_t *allow;   /* DEVICE uint8 [B][n] or NULL: allowlist of positions (Sec. 5.2): an
                             anchor only counts where allow != 0                                    */
+    float *margin;          /* DEVICE float [units][2] (out) or NULL: the margin of every selection the
+                            call makes - units as the idx rows of that call.  With the positions in
+                            the order of ta_select, the cut falls in one class (the highest that
+                            loses a member; with k_protected >= 0: among the tokens that are neither
+                            mandatory nor protected):
+                              margin[unit][0] = smallest u among its retained members, +inf if none
+                              margin[unit][1] = largest u among its evicted members
+                            and (+inf, -inf) when nothing is evicted.  Equal values: positions tie
+                            at the cut and the position decided; a relative gap within the rounding
+                            of A names the units whose retained set another summation order of A
+                            may change (the near-ties a parity check excuses).  The per-step form
+                            does not write it                                                      */
 } ta_params;
 
 /*
@@ -291,7 +303,7 @@ int32_t ta_score_lse(const void *Q, const void *K, const ta_layout *lay, const i
  * The retained set of TA-Fast does not depend on layer or head: call with
  * layers = hkv = 1 and share idx across units (see ta_compact).
  * prm->pool_k, prm->k_protected and prm->layer_K modify the selection as described
- * at ta_params.
+ * at ta_params; prm->margin, if set, receives the margin of every unit's cut.
  * Errors: NULL, SHAPE (also pool_k not in {1,3,5,7,9}), BUDGET.
  */
 int32_t ta_select(const float *A, const uint8_t *anchor, const uint8_t *spons, const float *vouch,

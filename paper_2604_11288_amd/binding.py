@@ -48,7 +48,7 @@ class CParams(ctypes.Structure):
                 ("alpha", ctypes.c_float), ("beta", ctypes.c_float), ("gamma", ctypes.c_float),
                 ("causal", ctypes.c_int32), ("budget_decay", ctypes.c_float),
                 ("pool_k", ctypes.c_int32), ("k_protected", ctypes.c_int32), ("last_query", ctypes.c_int32),
-                ("layer_K", ctypes.c_void_p), ("allow", ctypes.c_void_p)]
+                ("layer_K", ctypes.c_void_p), ("allow", ctypes.c_void_p), ("margin", ctypes.c_void_p)]
 
 
 class CDecodeState(ctypes.Structure):
@@ -91,15 +91,17 @@ class Params:
     last_query: bool = False                     # per-step form: rank by the current step's attention (TOVA's rule)
     layer_K: Optional[torch.Tensor] = None       # device int32 [layers]: per-layer budgets
     allow: Optional[torch.Tensor] = None         # device uint8 [B][n]: allowlist of positions
+    margin: Optional[torch.Tensor] = None        # device float [units][2] (out): margin of every unit's cut
 
     def c(self) -> CParams:
-        for t, dt in ((self.layer_K, torch.int32), (self.allow, torch.uint8)):
+        for t, dt in ((self.layer_K, torch.int32), (self.allow, torch.uint8), (self.margin, torch.float32)):
             assert t is None or (t.dtype == dt and t.is_contiguous())
         return CParams(self.n_sink, self.n_recent, self.span_L, self.sponsor_B, self.rho,
                        self.alpha, self.beta, self.gamma, 1 if self.causal else 0, self.budget_decay,
                        self.pool_k, self.k_protected, 1 if self.last_query else 0,
                        None if self.layer_K is None else self.layer_K.data_ptr(),
-                       None if self.allow is None else self.allow.data_ptr())
+                       None if self.allow is None else self.allow.data_ptr(),
+                       None if self.margin is None else self.margin.data_ptr())
 
 
 _lib = None

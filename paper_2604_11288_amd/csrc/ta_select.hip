@@ -43,6 +43,7 @@ struct SelectArgs {
     const int32_t* layer_K;
     int32_t* idx;
     int32_t* cnt;
+    float* margin;                  // [units][2] or null: smallest retained / largest evicted u of the class the cut falls in
     int32_t batch, hkv, n, K;
     int32_t pool_r, k_protected;
     int32_t units, units_per_xcd;
@@ -56,6 +57,14 @@ __device__ __forceinline__ uint32_t ordered_bits(float u)
 {
     uint32_t b = __float_as_uint(u);
     return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+// The inverse map; the ends of the key range stand for "no such position".
+__device__ __forceinline__ float margin_value(uint32_t k)
+{
+    if (k == 0xFFFFFFFFu) return INFINITY;                  // no retained member
+    if (k == 0u) return -INFINITY;                          // no evicted member
+    return __uint_as_float((k >> 31) ? (k ^ 0x80000000u) : ~k);
 }
 
 __device__ __forceinline__ int block_sum(int v, int* s_red)
@@ -172,7 +181,13 @@ select_kernel(SelectArgs a)
 
     if (nb <= K) {                                           // nothing to evict
         for (int32_t p = tid; p < nb; p += SEL_THREADS) idx[p] = p;
-        if (tid == 0) a.cnt[unit] = nb;
+        if (tid == 0) {
+            a.cnt[unit] = nb;
+            if (a.margin) {
+                a.margin[2 * (size_t)unit] = INFINITY;
+                a.margin[2 * (size_t)unit + 1] = -INFINITY;
+            }
+        }
         return;
     }
 
@@ -417,6 +432,7 @@ select_kernel(SelectArgs a)
 
     // ---- ascending write-out: one scan over per-quad counts per round of 4096 positions ----
     int32_t base = 0;
+    uint32_t kept_min = 0xFFFFFFFFu, gone_max = 0u;          // keys at the cut, over this thread's candidates
     for (int32_t q0 = 0; q0 < nquads; q0 += SEL_THREADS) {
         const int32_t q = q0 + tid;
         uint32_t keep = 0;                                   // bit c: position 4q + c is retained
@@ -435,14 +451,21 @@ select_kernel(SelectArgs a)
             for (int c = 0; c < 4; ++c) {
                 const int32_t p = 4 * q + c;
                 bool kp = false;
+                bool ranked = false;                         // competes for the slots the cut divides
                 if (p < nb) {
                     if (p < ns || p >= rs) kp = true;
-                    else if (CAPPED)
-                        kp = (sp[c] && (k4[c] > T1 || (k4[c] == T1 && p >= Pt1))) ||     // protected pool
-                             (k4[c] > T) || (k4[c] == T && p >= Pt);                     // main pool
-                    else if ((sp[c] != 0) != (bclass == 1)) kp = sp[c] != 0;   // class 1 above the boundary class, class 0 below it
-                    else kp = (k4[c] > T) || (k4[c] == T && p >= Pt);
+                    else if (CAPPED) {
+                        const bool prot = sp[c] && (k4[c] > T1 || (k4[c] == T1 && p >= Pt1));   // protected pool
+                        kp = prot || (k4[c] > T) || (k4[c] == T && p >= Pt);                  // main pool
+                        ranked = !prot;
+                    } else if ((sp[c] != 0) != (bclass == 1)) kp = sp[c] != 0;   // class 1 above the boundary class, class 0 below it
+                    else {
+                        kp = (k4[c] > T) || (k4[c] == T && p >= Pt);
+                        ranked = true;
+                    }
                 }
+                if (ranked && kp) kept_min = k4[c] < kept_min ? k4[c] : kept_min;
+                if (ranked && !kp) gone_max = k4[c] > gone_max ? k4[c] : gone_max;
                 keep |= kp ? (1u << c) : 0u;
             }
         }
@@ -473,6 +496,28 @@ select_kernel(SelectArgs a)
         base += total;
     }
     if (tid == 0) a.cnt[unit] = base < K ? base : K;
+    if (a.margin) {                                          // uniform
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const uint32_t lo = __shfl_xor(kept_min, o), hi = __shfl_xor(gone_max, o);
+            kept_min = lo < kept_min ? lo : kept_min;
+            gone_max = hi > gone_max ? hi : gone_max;
+        }
+        __syncthreads();
+        if (lane == 0) {
+            s_h[wave] = kept_min;
+            s_h[SEL_WAVES + wave] = gone_max;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 0; w < SEL_WAVES; ++w) {
+                kept_min = s_h[w] < kept_min ? s_h[w] : kept_min;
+                gone_max = s_h[SEL_WAVES + w] > gone_max ? s_h[SEL_WAVES + w] : gone_max;
+            }
+            a.margin[2 * (size_t)unit] = margin_value(kept_min);
+            a.margin[2 * (size_t)unit + 1] = margin_value(gone_max);
+        }
+    }
 }
 
 
@@ -576,7 +621,9 @@ __device__ __forceinline__ RadixState stream_pick(StreamLds& L, uint32_t need)
     return L.state;
 }
 
-template <int PER_THREAD>                                  // cap <= SS_THREADS * PER_THREAD
+// MARGIN: the keys turned away are tracked for the margin output (instances of their own: the default
+// ones keep their registers)
+template <int PER_THREAD, bool MARGIN>                     // cap <= SS_THREADS * PER_THREAD
 __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t cap)
 {
     extern __shared__ uint32_t s_dyn[];                    // [cap] keys, [cap] positions, [ceil(n / 32)] bitmap
@@ -603,7 +650,13 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t
     int32_t* idx = a.idx + (size_t)unit * (size_t)a.K;
     if (nb <= K) {                                         // nothing to evict
         for (int32_t p = tid; p < nb; p += SS_THREADS) idx[p] = p;
-        if (tid == 0) a.cnt[unit] = nb;
+        if (tid == 0) {
+            a.cnt[unit] = nb;
+            if (a.margin) {
+                a.margin[2 * (size_t)unit] = INFINITY;
+                a.margin[2 * (size_t)unit + 1] = -INFINITY;
+            }
+        }
         return;
     }
 
@@ -702,6 +755,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t
     // ---- the list is cut back to its R best entries; returns their threshold -----------------------
     uint32_t T = 0u;              // a position joins the list iff key > T, or key == T and p >= Pt
     int32_t Pt = 0x7FFFFFFF;
+    uint32_t gone_max = 0u;       // largest key this thread has turned away from the list or cut out of it
     const auto shrink = [&](const uint32_t m) {            // m: entries in the list (the same value in every thread)
         uint32_t prefix = 0, need = (uint32_t)R;
         uint32_t Tn = 0u;
@@ -758,6 +812,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t
         for (int j = 0; j < PER_THREAD; ++j) {
             if ((uint32_t)j * SS_THREADS >= m) continue;   // uniform: nothing of the list lies this far
             const bool keep = mk[j] > Tn || (mk[j] == Tn && mk[j] != 0u && (int32_t)mp[j] >= Pn);
+            if (MARGIN && !keep) gone_max = mk[j] > gone_max ? mk[j] : gone_max;   // (0 beyond the list's end)
             const unsigned long long bal = __ballot(keep);
             uint32_t base = 0;
             if (lane == 0 && bal) base = atomicAdd(&L.count, (uint32_t)__popcll(bal));
@@ -800,9 +855,10 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t
                     if (sg >= 0 && p < nb && q < nquads) {
                         if (p < ns || p >= rs) always[j] |= 1u << c;
                         else if ((sp != 0u) != (bclass == 1)) always[j] |= (sp != 0u) ? (1u << c) : 0u;   // class 1 above the boundary class, class 0 below it
-                        else if (R > 0) {
+                        else if (MARGIN || R > 0) {
                             keys[j][c] = key_of(p, Aq[c], an, vq[c]);
-                            join[j][c] = keys[j][c] > T || (keys[j][c] == T && p >= Pt);
+                            join[j][c] = R > 0 && (keys[j][c] > T || (keys[j][c] == T && p >= Pt));
+                            if (MARGIN && !join[j][c]) gone_max = keys[j][c] > gone_max ? keys[j][c] : gone_max;
                         }
                     }
                 }
@@ -883,6 +939,32 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t
         }
     }
     if (tid == 0) a.cnt[unit] = total < K ? total : K;
+    if (MARGIN) {
+        uint32_t kept_min = 0xFFFFFFFFu;
+        const uint32_t m = L.count;
+        for (uint32_t e = tid; e < m; e += SS_THREADS) kept_min = ckey[e] < kept_min ? ckey[e] : kept_min;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const uint32_t lo = __shfl_xor(kept_min, o), hi = __shfl_xor(gone_max, o);
+            kept_min = lo < kept_min ? lo : kept_min;
+            gone_max = hi > gone_max ? hi : gone_max;
+        }
+        __syncthreads();                                   // the scan's partial sums have been read
+        if (lane == 0) {
+            L.h[wave] = kept_min;
+            L.h[SS_WAVES + wave] = gone_max;
+        }
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int w = 0; w < SS_WAVES; ++w) {
+                kept_min = L.h[w] < kept_min ? L.h[w] : kept_min;
+                gone_max = L.h[SS_WAVES + w] > gone_max ? L.h[SS_WAVES + w] : gone_max;
+            }
+            a.margin[2 * (size_t)unit] = margin_value(kept_min);
+            a.margin[2 * (size_t)unit + 1] = margin_value(gone_max);
+        }
+    }
 }
 
 // Short candidate lists (budgets up to about 1300): six wavefronts per SIMD, which the many short units
@@ -891,13 +973,25 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, const int32_t
 __global__ void __launch_bounds__(SS_THREADS) __attribute__((amdgpu_waves_per_eu(6)))
 select_stream_few_kernel(SelectArgs a, int32_t cap)
 {
-    select_stream<SS_FEW_PER_THREAD>(a, cap);
+    select_stream<SS_FEW_PER_THREAD, false>(a, cap);
+}
+
+__global__ void __launch_bounds__(SS_THREADS) __attribute__((amdgpu_waves_per_eu(6)))
+select_stream_few_margin_kernel(SelectArgs a, int32_t cap)
+{
+    select_stream<SS_FEW_PER_THREAD, true>(a, cap);
 }
 
 __global__ void __launch_bounds__(SS_THREADS) __attribute__((amdgpu_waves_per_eu(4)))
 select_stream_kernel(SelectArgs a, int32_t cap)
 {
-    select_stream<SS_MAX_PER_THREAD>(a, cap);
+    select_stream<SS_MAX_PER_THREAD, false>(a, cap);
+}
+
+__global__ void __launch_bounds__(SS_THREADS) __attribute__((amdgpu_waves_per_eu(4)))
+select_stream_margin_kernel(SelectArgs a, int32_t cap)
+{
+    select_stream<SS_MAX_PER_THREAD, true>(a, cap);
 }
 
 DeviceOnce g_setup;
@@ -920,6 +1014,12 @@ hipError_t select_setup()
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_few_margin_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_stream_margin_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, SS_MAX_LDS);
         return e;
     });
 }
@@ -940,6 +1040,7 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
     a.k_protected = prm.k_protected;
     a.idx = idx;
     a.cnt = cnt;
+    a.margin = prm.margin;
     a.batch = batch;
     a.hkv = hkv;
     a.n = n;
@@ -966,10 +1067,10 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
         if (cap <= SS_MAX_CAP && lds <= SS_MAX_LDS) {
             const hipError_t attr_err = select_setup();
             if (attr_err != hipSuccess) return attr_err;
-            if (cap <= SS_THREADS * SS_FEW_PER_THREAD)
-                hipLaunchKernelGGL(select_stream_few_kernel, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
-            else
-                hipLaunchKernelGGL(select_stream_kernel, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
+            const bool few = cap <= SS_THREADS * SS_FEW_PER_THREAD;
+            auto kernel = few ? (a.margin ? select_stream_few_margin_kernel : select_stream_few_kernel)
+                              : (a.margin ? select_stream_margin_kernel : select_stream_kernel);
+            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(SS_THREADS), (size_t)lds, st, a, (int32_t)cap);
             return hipGetLastError();
         }
     }

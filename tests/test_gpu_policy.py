@@ -44,12 +44,13 @@ def test_select_with_max_pooled_scores(n, ragged, pool_k, mode):
     rng = np.random.default_rng(n + pool_k)
     layers, hkv, K = 2, 2, 200
     A = _scores(rng, (layers, w.batch, hkv, n), mode)
-    prm = _prm(w, pool_k=pool_k)
+    margin = torch.full((layers, w.batch, hkv, 2), 123.0, device=DEV)
+    prm = _prm(w, pool_k=pool_k, margin=margin)
     seq = _dev(td.seq_len)
     anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, prm, seq_len=seq)
     idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, layers, hkv, seq_len=seq)
     torch.cuda.synchronize()
-    idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    idx, cnt, margin = idx.cpu().numpy(), cnt.cpu().numpy(), margin.cpu().numpy()
     differs = 0
     for b in range(w.batch):
         nb = int(td.seq_len[b])
@@ -59,6 +60,8 @@ def test_select_with_max_pooled_scores(n, ragged, pool_k, mode):
                 ref = ora.select(ora.maxpool(A[l, b, h, :nb], pool_k), a, s, v, K, w.n_sink, w.n_recent)
                 assert cnt[l, b, h] == len(ref)
                 assert np.array_equal(idx[l, b, h, :len(ref)], ref), (l, b, h)
+                want = ora.select_margin(ora.maxpool(A[l, b, h, :nb], pool_k), a, s, v, K, w.n_sink, w.n_recent)
+                assert margin[l, b, h].tolist() == want.tolist(), (l, b, h)
                 differs += not np.array_equal(ref, ora.select(A[l, b, h, :nb], a, s, v, K, w.n_sink, w.n_recent))
     assert differs > 0                        # the pooling does change the selection
 
@@ -81,10 +84,11 @@ def test_select_with_fixed_partition(n, K, planted, mode, ragged):
     anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, base, seq_len=seq)
     sets = {}
     for kp in (0, 1, 4, K // 4, K - w.n_sink - w.n_recent, 10 ** 6):
-        prm = _prm(w, k_protected=kp)
+        margin = torch.full((layers, w.batch, hkv, 2), 123.0, device=DEV)
+        prm = _prm(w, k_protected=kp, margin=margin)
         idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, layers, hkv, seq_len=seq)
         torch.cuda.synchronize()
-        idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+        idx, cnt, margin = idx.cpu().numpy(), cnt.cpu().numpy(), margin.cpu().numpy()
         for b in range(w.batch):
             nb = int(td.seq_len[b])
             a, s, v = ora.evict_sequence(td.tok[b, :nb], td.tab_ids, td.tab_len)
@@ -92,6 +96,8 @@ def test_select_with_fixed_partition(n, K, planted, mode, ragged):
                 ref = ora.select_partition(A[0, b, h, :nb], a, s, v, K, kp, w.n_sink, w.n_recent)
                 assert cnt[0, b, h] == len(ref)
                 assert np.array_equal(idx[0, b, h, :len(ref)], ref), (kp, b, h)
+                want = ora.select_margin(A[0, b, h, :nb], a, s, v, K, w.n_sink, w.n_recent, k_protected=kp)
+                assert margin[0, b, h].tolist() == want.tolist(), (kp, b, h, margin[0, b, h], want)
         sets[kp] = idx.copy()
     if mode == "heavy":
         assert not np.array_equal(sets[0], sets[10 ** 6])        # the pool size matters under heavy attention

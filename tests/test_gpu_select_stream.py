@@ -51,12 +51,13 @@ def _check(layers, batch, hkv, n, K, ns, nr, mode, planted=8, ragged=None, beta=
     rng = np.random.default_rng(1000 * n + K + seed)
     A = _scores(mode, (layers, batch, hkv, n), rng)
     lk = None if layer_K is None else _dev(np.asarray(layer_K, np.int32))
-    prm = ta.Params(n_sink=ns, n_recent=nr, beta=beta, layer_K=lk)
+    margin = torch.full((layers, batch, hkv, 2), 123.0, device=DEV)
+    prm = ta.Params(n_sink=ns, n_recent=nr, beta=beta, layer_K=lk, margin=margin)
     seq = _dev(td.seq_len) if ragged else None
     anchor, spons, vouch = ta.ta_match_anchors(_dev(td.tok), td.tab_ids, td.tab_len, prm, seq_len=seq)
     idx, cnt = ta.ta_select(_dev(A), anchor, spons, vouch, K, prm, layers, hkv, seq_len=seq)
     torch.cuda.synchronize()
-    idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    idx, cnt, margin = idx.cpu().numpy(), cnt.cpu().numpy(), margin.cpu().numpy()
     units = [(l, b, h) for l in range(layers) for b in range(batch) for h in range(hkv)]
     if sample is not None and sample < len(units):
         pick = np.random.default_rng(seed + 5).choice(len(units), size=sample, replace=False)
@@ -68,6 +69,9 @@ def _check(layers, batch, hkv, n, K, ns, nr, mode, planted=8, ragged=None, beta=
         ref = ora.select(A[l, b, h, :nb], a, s, v, Kl, ns, nr, alpha=1.0, beta=beta, gamma=0.3)
         assert cnt[l, b, h] == len(ref) == min(Kl, nb), (l, b, h)
         assert np.array_equal(idx[l, b, h, :len(ref)], ref), (l, b, h)
+        # the margin of the cut: the same two utilities, bit for bit
+        want = ora.select_margin(A[l, b, h, :nb], a, s, v, Kl, ns, nr, alpha=1.0, beta=beta, gamma=0.3)
+        assert margin[l, b, h].tolist() == want.tolist(), (l, b, h, margin[l, b, h], want)
     return len(units)
 
 
