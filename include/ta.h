@@ -66,7 +66,7 @@ typedef enum ta_status {
     TA_ERR_SHAPE = -2,     /* a size, stride or table entry is outside the supported range */
     TA_ERR_BUDGET = -3,    /* K < 1 or K < n_sink + n_recent                               */
     TA_ERR_WORKSPACE = -4, /* workspace missing or smaller than ta_workspace_bytes()       */
-    TA_ERR_ALIGN = -5,     /* a K/V/Q pointer or stride is not 16-byte aligned             */
+    TA_ERR_ALIGN = -5,     /* a pointer or stride is not aligned as documented (K/V/Q: 16 bytes) */
     TA_ERR_HIP = -6,       /* a launch failed; see ta_last_hip_error()                     */
     TA_ERR_SCRATCH = -7    /* ta_evict_static: the layout needs more scratch than
                               TA_STATIC_SCRATCH_BYTES                                      */
@@ -122,7 +122,7 @@ typedef struct ta_params {
                             at the cut and the position decided; a relative gap within the rounding
                             of A names the units whose retained set another summation order of A
                             may change (the near-ties a parity check excuses).  The per-step form
-                            does not write it                                                      */
+                            does not write it.  4-byte aligned (else ALIGN)                        */
 } ta_params;
 
 /*

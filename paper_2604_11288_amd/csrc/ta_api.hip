@@ -56,6 +56,7 @@ int32_t check_params(const ta_params* prm)
         prm->pool_k != 9)
         return TA_ERR_SHAPE;
     if (prm->last_query != 0 && prm->last_query != 1) return TA_ERR_SHAPE;
+    if (((uintptr_t)prm->margin & 3u) != 0) return TA_ERR_ALIGN;
     return TA_OK;
 }
 
@@ -680,7 +681,7 @@ const char* ta_strerror(int32_t status)
         case TA_ERR_SHAPE: return "a size, stride or table entry is outside the supported range";
         case TA_ERR_BUDGET: return "budget K is below 1 or below n_sink + n_recent";
         case TA_ERR_WORKSPACE: return "workspace missing or too small";
-        case TA_ERR_ALIGN: return "a K/V/Q pointer or stride is not 16-byte aligned";
+        case TA_ERR_ALIGN: return "a pointer or stride is not aligned as the header requires";
         case TA_ERR_HIP: return "a HIP launch failed";
         case TA_ERR_SCRATCH: return "the layout needs more scratch than the static buffer of ta_evict_static holds";
         default: return "unknown status";

@@ -130,6 +130,9 @@ def test_select_and_compact_error_paths(L):
     assert L.ta_select(*a) == tb.TA_ERR_SHAPE
     a = sel(); a[11] = None
     assert L.ta_select(*a) == tb.TA_ERR_NULL
+    odd = tb.Params(n_sink=4, n_recent=4).c()
+    odd.margin = 0x7f0000001002                                       # a float array at an odd address
+    assert L.ta_select(*sel(prm=odd)) == tb.TA_ERR_ALIGN
     lay = _lay()
     cmp_ = lambda lay_=lay, K=16: [FAKE, FAKE, FAKE, FAKE, ctypes.byref(lay_), K, 0, FAKE, FAKE, None]
     a = cmp_(); a[7] = None
