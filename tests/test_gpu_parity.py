@@ -345,10 +345,13 @@ def test_compact_bit_exact_strided_and_shared():
 # --------------------------------------------------------------------------
 # the fused pass
 # --------------------------------------------------------------------------
-def _check_evict(w, K, clean=True, units=None, layers=None):
+def _check_evict(w, K, clean=True, units=None, layers=None, lengths=None):
     """Runs ta_evict and checks every output; returns the number of excused tie mismatches."""
     lyr = w.layers if layers is None else layers
     td = wl.make_tokens(w, clean=clean)
+    if lengths is not None:                                  # given lengths instead of the drawn ones
+        td.seq_len[:] = np.asarray(lengths, np.int32)
+        td.planted = [[p for p in pl if p + 7 <= int(nb)] for pl, nb in zip(td.planted, td.seq_len)]
     Q, Kc, Vc = wl.make_qkv(w, device=DEV, layers=lyr)
     prm = _prm(w)
     scored = w.alpha != 0.0
@@ -455,6 +458,17 @@ def test_evict_c4_long_context_scaled():
 def test_evict_c5_ragged_prefill_scaled():
     w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=6, n=3000, ragged=(500, 3000))
     _check_evict(w, 256, units=[(0, b, b % 8) for b in range(6)])
+
+
+def test_evict_degenerate_lengths():
+    # sequences that are empty, a single token, shorter than the mandatory ranges, shorter than the observation
+    # window, exactly the budget and one more than it, next to a full one
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=8, n=2048, ragged=(0, 2048))
+    K = 64
+    lengths = [0, 1, 7, 20, K, K + 1, 2048, 33]
+    assert w.n_sink + w.n_recent == 8 and w.window == 32
+    excused = _check_evict(w, K, lengths=lengths)
+    assert excused == 0
 
 
 def test_evict_is_deterministic():
