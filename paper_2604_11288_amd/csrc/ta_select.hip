@@ -33,6 +33,7 @@ constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int HIST_COPIES = 16;               // privatised histograms, one per lane % 16
 constexpr int HIST_STRIDE = 257;              // odd stride: the same bin of different copies sits in different LDS banks
 constexpr int SEL_CACHE_MAX_N = 32768;        // keys cached in LDS up to this length
+constexpr int SEL_BATCH = 2;                  // quads of a thread whose loads are in flight together
 
 struct SelectArgs {
     const float* A;
@@ -265,24 +266,40 @@ select_kernel(SelectArgs a)
         }
     };
 
-    // ---- class-1 population; the first quad's other operands are requested before the
-    // reduction so that their latency hides behind it
-    Quad first;
+    // ---- class-1 population.  A thread's quads are taken SEL_BATCH at a time, all their loads issued
+    // before the first is used (a quad index past the end is clamped and its data ignored): with few units a
+    // workgroup has a compute unit to itself and nothing else hides a round trip.  The first batch's other
+    // operands are requested before the reduction so that their latency hides behind it.
+    Quad first[SEL_BATCH];
     int local = 0;
-    for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
-        uint8_t sp[4];
-        load_flags(spons, q, sp);
-        if (q == tid) {
+    for (int32_t q0 = tid; q0 < nquads; q0 += SEL_BATCH * SEL_THREADS) {
+        uint8_t sp[SEL_BATCH][4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) first.sp[c] = sp[c];
+        for (int u = 0; u < SEL_BATCH; ++u) {
+            const int32_t q = q0 + u * SEL_THREADS;
+            load_flags(spons, q < nquads ? q : nquads - 1, sp[u]);
         }
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int32_t p = 4 * q + c;
-            local += (p >= ns && p < rs && sp[c]) ? 1 : 0;
+        for (int u = 0; u < SEL_BATCH; ++u) {
+            const int32_t q = q0 + u * SEL_THREADS;
+            if (q0 == tid) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) first[u].sp[c] = sp[u][c];
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int32_t p = 4 * q + c;
+                local += (q < nquads && p >= ns && p < rs && sp[u][c]) ? 1 : 0;
+            }
         }
     }
-    if (tid < nquads) load_rest(tid, first);
+    if (CACHED && tid < nquads) {
+#pragma unroll
+        for (int u = 0; u < SEL_BATCH; ++u) {
+            const int32_t q = tid + u * SEL_THREADS;
+            load_rest(q < nquads ? q : nquads - 1, first[u]);
+        }
+    }
     const int32_t c1 = block_sum(local, s_red);
 
     const int bclass = (c2 + c1 <= K) ? 0 : 1;
@@ -326,16 +343,26 @@ select_kernel(SelectArgs a)
     };
 
     if (CACHED) {
-        for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
-            Quad x;
-            if (q == tid) x = first;
-            else {
-                load_flags(spons, q, x.sp);
-                load_rest(q, x);
+        for (int32_t q0 = tid; q0 < nquads; q0 += SEL_BATCH * SEL_THREADS) {
+            Quad x[SEL_BATCH];
+#pragma unroll
+            for (int u = 0; u < SEL_BATCH; ++u) {
+                const int32_t q = q0 + u * SEL_THREADS;
+                if (q0 == tid) x[u] = first[u];
+                else {
+                    load_flags(spons, q < nquads ? q : nquads - 1, x[u].sp);
+                    load_rest(q < nquads ? q : nquads - 1, x[u]);
+                }
             }
-            uint32_t k[4];
-            quad_keys(q, x, k);
-            *reinterpret_cast<uint4*>(&s_key[4 * q]) = make_uint4(k[0], k[1], k[2], k[3]);
+#pragma unroll
+            for (int u = 0; u < SEL_BATCH; ++u) {
+                const int32_t q = q0 + u * SEL_THREADS;
+                if (q < nquads) {
+                    uint32_t k[4];
+                    quad_keys(q, x[u], k);
+                    *reinterpret_cast<uint4*>(&s_key[4 * q]) = make_uint4(k[0], k[1], k[2], k[3]);
+                }
+            }
         }
     }
     __syncthreads();
@@ -437,16 +464,24 @@ select_kernel(SelectArgs a)
         const int32_t q = q0 + tid;
         uint32_t keep = 0;                                   // bit c: position 4q + c is retained
         if (q < nquads) {
-            uint8_t sp[4];
-            load_flags(spons, q, sp);
+            uint8_t sp[4] = {0, 0, 0, 0};
             uint32_t k4[4] = {0u, 0u, 0u, 0u};
-            bool need_keys = false;
+            if (CACHED && !CAPPED) {
+                // no load: a key of 0 between the mandatory ranges is a position of the other class, which is
+                // sponsored exactly when the cut falls among the plain ones
+                keys_at(q, k4);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int32_t p = 4 * q + c;
-                need_keys = need_keys || (p >= ns && p < rs && (CAPPED || (sp[c] != 0) == (bclass == 1)));
+                for (int c = 0; c < 4; ++c) sp[c] = (uint8_t)((k4[c] == 0u) == (bclass == 0) ? 1 : 0);
+            } else {
+                load_flags(spons, q, sp);
+                bool need_keys = false;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int32_t p = 4 * q + c;
+                    need_keys = need_keys || (p >= ns && p < rs && (CAPPED || (sp[c] != 0) == (bclass == 1)));
+                }
+                if (need_keys) keys_at(q, k4);
             }
-            if (need_keys) keys_at(q, k4);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int32_t p = 4 * q + c;
