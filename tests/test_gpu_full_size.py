@@ -64,12 +64,14 @@ def _check_full(w, K, sample_units, workers=16):
     td = wl.make_tokens(w)
     Q, Kc, Vc = wl.make_qkv(w, device=DEV)
     prm = _prm(w)
+    scored = w.alpha != 0.0
+    prm.margin = torch.full((w.layers, w.batch, w.hkv, 2) if scored else (w.batch, 2), 123.0, device=DEV)
     seq = _dev(td.seq_len) if w.ragged else None
     plan = ta.ta_evict(_dev(td.tok), td.tab_ids, td.tab_len, Q, Kc, Vc, K, prm, seq_len=seq)
     torch.cuda.synchronize()
     G = w.hq // w.hkv
-    scored = w.alpha != 0.0
     lens = torch.from_numpy(td.seq_len).to(DEV)
+    margin = prm.margin.cpu().numpy()
 
     # ---- properties over every unit ------------------------------------------------------
     seqs = {}
@@ -90,6 +92,12 @@ def _check_full(w, K, sample_units, workers=16):
     else:
         want_cnt = torch.clamp(lens, max=K)
     assert torch.equal(cnt_all.long(), want_cnt.long())
+    # the margin of every unit's cut: the smallest retained utility is not below the largest evicted one;
+    # a unit that evicts nothing reports (+inf, -inf)
+    evicts = (td.seq_len > K).reshape((1, -1, 1) if scored else (-1,))
+    evicts = np.broadcast_to(evicts, margin.shape[:-1])
+    assert np.all(margin[..., 0] >= margin[..., 1])
+    assert np.all(np.isfinite(margin[..., 1]) == evicts) and np.all(margin[..., 0][~evicts] == np.inf)
     if int(td.seq_len.min()) >= K:
         assert bool((idx_all[..., 1:] > idx_all[..., :-1]).all())                 # ascending, unique
         assert bool((idx_all[..., :w.n_sink] == torch.arange(w.n_sink, device=DEV)).all())
@@ -116,6 +124,8 @@ def _check_full(w, K, sample_units, workers=16):
             assert np.all(np.abs(A_gpu - A_ref) <= 1e-3 * np.abs(A_ref) + 1e-7), (l, b, g)
             same = ora.select(A_gpu, a, s, v, K, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
             assert np.array_equal(idx_gpu[:len(same)], same), (l, b, g)
+            m_same = ora.select_margin(A_gpu, a, s, v, K, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
+            assert margin[l, b, g].tolist() == m_same.tolist(), (l, b, g)
             # the oracle end to end: its own scores decide; differences only at ties within 1e-3 of the K-th utility
             ref = ora.select(A_ref, a, s, v, K, w.n_sink, w.n_recent, w.alpha, w.beta, w.gamma)
             diff = set(ref.tolist()) ^ set(same.tolist())
@@ -126,10 +136,13 @@ def _check_full(w, K, sample_units, workers=16):
                 kth = u[ref][cls[ref] == bclass].min()
                 for p_ in diff:
                     assert cls[p_] == bclass and abs(u[p_] - kth) <= 1e-3 * abs(kth), (l, b, g, p_)
+                assert margin[l, b, g, 0] - margin[l, b, g, 1] <= 2e-3 * abs(kth), (l, b, g)   # a cut the library reports as tight
                 excused = len(diff) // 2
         else:
             same = ora.select(None, a, s, v, K, w.n_sink, w.n_recent, 0.0, w.beta, w.gamma)
             assert np.array_equal(idx_gpu[:len(same)], same), (l, b, g)
+            m_same = ora.select_margin(None, a, s, v, K, w.n_sink, w.n_recent, 0.0, w.beta, w.gamma)
+            assert margin[b].tolist() == m_same.tolist(), b
         Kref, Vref = ora.compact(Kb, same), ora.compact(Vb, same)
         assert np.array_equal(Ko[:len(same)], Kref) and np.array_equal(Vo[:len(same)], Vref), (l, b, g)
         return (l, b, g), (A_ref, same, Kref, Vref), excused
