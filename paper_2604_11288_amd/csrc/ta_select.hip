@@ -33,6 +33,7 @@ constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int HIST_COPIES = 16;               // privatised histograms, one per lane % 16
 constexpr int HIST_STRIDE = 257;              // odd stride: the same bin of different copies sits in different LDS banks
 constexpr int SEL_CACHE_MAX_N = 32768;        // keys cached in LDS up to this length
+constexpr int SEL_ROUNDS = SEL_CACHE_MAX_N / 4 / SEL_THREADS;   // rounds of SEL_THREADS quads in a cached row
 constexpr int SEL_BATCH = 2;                  // quads of a thread whose loads are in flight together
 
 struct SelectArgs {
@@ -380,12 +381,23 @@ select_kernel(SelectArgs a)
                 uint32_t k4[4];
                 keys_at(q, k4);
                 member(q, k4);
+                // neighbouring positions mostly share a digit (the recency term moves slowly): equal digits
+                // in a row go into the histogram as one add
+                int prev = -1;
+                uint32_t run = 0;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const uint32_t k = k4[c];
-                    bool in = k != 0u && (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8)));
-                    if (in) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][(k >> shift) & 255u], 1u);
+                    const bool in = k != 0u && (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8)));
+                    const int bin = in ? (int)((k >> shift) & 255u) : -1;
+                    if (bin != prev) {
+                        if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
+                        prev = bin;
+                        run = 0;
+                    }
+                    ++run;
                 }
+                if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
             }
             __syncthreads();
             RadixState r = radix_pick(s_hist, s_h, &s_state, need);
@@ -457,78 +469,144 @@ select_kernel(SelectArgs a)
         }
     }
 
-    // ---- ascending write-out: one scan over per-quad counts per round of 4096 positions ----
-    int32_t base = 0;
+    // ---- which positions of a quad are retained (bit c: position 4q + c) --------------------------
     uint32_t kept_min = 0xFFFFFFFFu, gone_max = 0u;          // keys at the cut, over this thread's candidates
-    for (int32_t q0 = 0; q0 < nquads; q0 += SEL_THREADS) {
-        const int32_t q = q0 + tid;
-        uint32_t keep = 0;                                   // bit c: position 4q + c is retained
-        if (q < nquads) {
-            uint8_t sp[4] = {0, 0, 0, 0};
-            uint32_t k4[4] = {0u, 0u, 0u, 0u};
-            if (CACHED && !CAPPED) {
-                // no load: a key of 0 between the mandatory ranges is a position of the other class, which is
-                // sponsored exactly when the cut falls among the plain ones
-                keys_at(q, k4);
+    const auto keep_of = [&](int32_t q) -> uint32_t {
+        uint32_t keep = 0;
+        uint8_t sp[4] = {0, 0, 0, 0};
+        uint32_t k4[4] = {0u, 0u, 0u, 0u};
+        if (CACHED && !CAPPED) {
+            // no load: a key of 0 between the mandatory ranges is a position of the other class, which is
+            // sponsored exactly when the cut falls among the plain ones
+            keys_at(q, k4);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) sp[c] = (uint8_t)((k4[c] == 0u) == (bclass == 0) ? 1 : 0);
-            } else {
-                load_flags(spons, q, sp);
-                bool need_keys = false;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int32_t p = 4 * q + c;
-                    need_keys = need_keys || (p >= ns && p < rs && (CAPPED || (sp[c] != 0) == (bclass == 1)));
-                }
-                if (need_keys) keys_at(q, k4);
-            }
+            for (int c = 0; c < 4; ++c) sp[c] = (uint8_t)((k4[c] == 0u) == (bclass == 0) ? 1 : 0);
+        } else {
+            load_flags(spons, q, sp);
+            bool need_keys = false;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int32_t p = 4 * q + c;
-                bool kp = false;
-                bool ranked = false;                         // competes for the slots the cut divides
-                if (p < nb) {
-                    if (p < ns || p >= rs) kp = true;
-                    else if (CAPPED) {
-                        const bool prot = sp[c] && (k4[c] > T1 || (k4[c] == T1 && p >= Pt1));   // protected pool
-                        kp = prot || (k4[c] > T) || (k4[c] == T && p >= Pt);                  // main pool
-                        ranked = !prot;
-                    } else if ((sp[c] != 0) != (bclass == 1)) kp = sp[c] != 0;   // class 1 above the boundary class, class 0 below it
-                    else {
-                        kp = (k4[c] > T) || (k4[c] == T && p >= Pt);
-                        ranked = true;
-                    }
-                }
-                if (ranked && kp) kept_min = k4[c] < kept_min ? k4[c] : kept_min;
-                if (ranked && !kp) gone_max = k4[c] > gone_max ? k4[c] : gone_max;
-                keep |= kp ? (1u << c) : 0u;
+                need_keys = need_keys || (p >= ns && p < rs && (CAPPED || (sp[c] != 0) == (bclass == 1)));
             }
+            if (need_keys) keys_at(q, k4);
         }
-        const int mine = __popc(keep);
-        int incl = mine;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            int up = __shfl_up(incl, o);
-            if (lane >= o) incl += up;
-        }
-        __syncthreads();
-        if (lane == 63) s_red[wave] = incl;
-        __syncthreads();
-        int woff = 0, total = 0;
-        for (int w = 0; w < SEL_WAVES; ++w) {
-            int c = s_red[w];
-            woff += (w < wave) ? c : 0;
-            total += c;
-        }
-        int32_t slot = base + woff + incl - mine;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (keep & (1u << c)) {
-                if (slot < K) idx[slot] = 4 * q + c;
-                ++slot;
+            const int32_t p = 4 * q + c;
+            bool kp = false;
+            bool ranked = false;                             // competes for the slots the cut divides
+            if (p < nb) {
+                if (p < ns || p >= rs) kp = true;
+                else if (CAPPED) {
+                    const bool prot = sp[c] && (k4[c] > T1 || (k4[c] == T1 && p >= Pt1));   // protected pool
+                    kp = prot || (k4[c] > T) || (k4[c] == T && p >= Pt);                  // main pool
+                    ranked = !prot;
+                } else if ((sp[c] != 0) != (bclass == 1)) kp = sp[c] != 0;   // class 1 above the boundary class, class 0 below it
+                else {
+                    kp = (k4[c] > T) || (k4[c] == T && p >= Pt);
+                    ranked = true;
+                }
+            }
+            if (ranked && kp) kept_min = k4[c] < kept_min ? k4[c] : kept_min;
+            if (ranked && !kp) gone_max = k4[c] > gone_max ? k4[c] : gone_max;
+            keep |= kp ? (1u << c) : 0u;
+        }
+        return keep;
+    };
+
+    // ---- ascending write-out -------------------------------------------------------------------
+    int32_t base = 0;
+    if constexpr (CACHED) {
+        // Every round of SEL_THREADS quads at once (at most SEL_ROUNDS of them fit the key cache): a thread keeps
+        // the masks of its quads in one register, the rounds' counts are scanned two to a register, and ONE
+        // scan over the (round, wavefront) totals gives every wavefront its offsets - three barriers instead of
+        // two per round.
+        uint32_t masks = 0;
+#pragma unroll
+        for (int r = 0; r < SEL_ROUNDS; ++r) {
+            const int32_t q = r * SEL_THREADS + tid;
+            if (q < nquads) masks |= keep_of(q) << (4 * r);
+        }
+        uint32_t incl2[SEL_ROUNDS / 2];                      // inclusive counts within the wavefront, rounds 2j and 2j + 1
+#pragma unroll
+        for (int j = 0; j < SEL_ROUNDS / 2; ++j) {
+            uint32_t v = (uint32_t)__popc((masks >> (8 * j)) & 15u) | ((uint32_t)__popc((masks >> (8 * j + 4)) & 15u) << 16);
+            if (2 * j * SEL_THREADS < nquads) {              // uniform: rounds past the row's end hold nothing
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t up = __shfl_up(v, o);
+                    if (lane >= o) v += up;                  // at most 256 per field: no carry between the halves
+                }
+            }
+            incl2[j] = v;
+        }
+        __syncthreads();                                     // s_h is free (the threshold search is over)
+        if (lane == 63) {
+#pragma unroll
+            for (int r = 0; r < SEL_ROUNDS; ++r) s_h[r * SEL_WAVES + wave] = (incl2[r >> 1] >> (16 * (r & 1))) & 0xFFFFu;
+        }
+        __syncthreads();
+        if (tid < 64) {                                      // exclusive scan of the SEL_ROUNDS * SEL_WAVES totals, two per lane
+            static_assert(SEL_ROUNDS * SEL_WAVES == 128, "two entries per lane of one wavefront");
+            const uint32_t t0 = s_h[2 * tid], t1 = s_h[2 * tid + 1];
+            uint32_t v = t0 + t1;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t up = __shfl_up(v, o);
+                if (tid >= o) v += up;
+            }
+            s_h[2 * tid] = v - t0 - t1;
+            s_h[2 * tid + 1] = v - t1;
+            if (tid == 63) s_h[SEL_ROUNDS * SEL_WAVES] = v;  // everything retained
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < SEL_ROUNDS; ++r) {
+            const uint32_t keep = (masks >> (4 * r)) & 15u;
+            const int32_t q = r * SEL_THREADS + tid;
+            const uint32_t incl = (incl2[r >> 1] >> (16 * (r & 1))) & 0xFFFFu;
+            int32_t slot = (int32_t)(s_h[r * SEL_WAVES + wave] + incl) - __popc(keep);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (keep & (1u << c)) {
+                    if (slot < K) idx[slot] = 4 * q + c;
+                    ++slot;
+                }
             }
         }
-        base += total;
+        base = (int32_t)s_h[SEL_ROUNDS * SEL_WAVES];
+    } else {
+        // one scan over per-quad counts per round of 4096 positions
+        for (int32_t q0 = 0; q0 < nquads; q0 += SEL_THREADS) {
+            const int32_t q = q0 + tid;
+            const uint32_t keep = q < nquads ? keep_of(q) : 0u;
+            const int mine = __popc(keep);
+            int incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                int up = __shfl_up(incl, o);
+                if (lane >= o) incl += up;
+            }
+            __syncthreads();
+            if (lane == 63) s_red[wave] = incl;
+            __syncthreads();
+            int woff = 0, total = 0;
+            for (int w = 0; w < SEL_WAVES; ++w) {
+                int c = s_red[w];
+                woff += (w < wave) ? c : 0;
+                total += c;
+            }
+            int32_t slot = base + woff + incl - mine;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (keep & (1u << c)) {
+                    if (slot < K) idx[slot] = 4 * q + c;
+                    ++slot;
+                }
+            }
+            base += total;
+        }
     }
     if (tid == 0) a.cnt[unit] = base < K ? base : K;
     if (a.margin) {                                          // uniform
