@@ -33,8 +33,7 @@ constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int HIST_COPIES = 16;               // privatised histograms, one per lane % 16
 constexpr int HIST_STRIDE = 257;              // odd stride: the same bin of different copies sits in different LDS banks
 constexpr int SEL_CACHE_MAX_N = 32768;        // keys cached in LDS up to this length
-constexpr int SEL_ROUNDS = SEL_CACHE_MAX_N / 4 / SEL_THREADS;   // rounds of SEL_THREADS quads in a cached row
-constexpr int SEL_BATCH = 2;                  // quads of a thread whose loads are in flight together
+constexpr int SEL_MAX_ROUNDS = SEL_CACHE_MAX_N / 4 / SEL_THREADS;   // rounds of SEL_THREADS quads in the longest cached row
 
 struct SelectArgs {
     const float* A;
@@ -151,10 +150,14 @@ struct Quad {
     uint8_t an[4];
 };
 
-template <bool CACHED, bool CAPPED>
+// SEL_ROUNDS: 1 - cached rows of at most 4 * SEL_THREADS positions, a thread has one quad; SEL_MAX_ROUNDS - the longer
+// cached rows; 0 - rows that are not cached (any length)
+template <bool CACHED, bool CAPPED, int SEL_ROUNDS>
 __global__ void __launch_bounds__(SEL_THREADS)
 select_kernel(SelectArgs a)
 {
+    static_assert(CACHED ? (SEL_ROUNDS == 1 || SEL_ROUNDS == SEL_MAX_ROUNDS) : SEL_ROUNDS == 0, "instances");
+    constexpr int SEL_BATCH = SEL_ROUNDS == SEL_MAX_ROUNDS ? 2 : 1;   // quads of a thread whose loads are in flight together
     extern __shared__ uint32_t s_key[];                     // [roundup4(n)] when CACHED
     __shared__ uint32_t s_hist[HIST_COPIES][HIST_STRIDE];
     __shared__ uint32_t s_h[256];
@@ -381,23 +384,32 @@ select_kernel(SelectArgs a)
                 uint32_t k4[4];
                 keys_at(q, k4);
                 member(q, k4);
-                // neighbouring positions mostly share a digit (the recency term moves slowly): equal digits
-                // in a row go into the histogram as one add
-                int prev = -1;
-                uint32_t run = 0;
+                if constexpr (SEL_ROUNDS > 1) {
+                    // long rows: neighbouring positions mostly share a digit (the recency term moves slowly), and
+                    // equal digits in a row go into the histogram as one add
+                    int prev = -1;
+                    uint32_t run = 0;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t k = k4[c];
-                    const bool in = k != 0u && (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8)));
-                    const int bin = in ? (int)((k >> shift) & 255u) : -1;
-                    if (bin != prev) {
-                        if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
-                        prev = bin;
-                        run = 0;
+                    for (int c = 0; c < 4; ++c) {
+                        const uint32_t k = k4[c];
+                        const bool in = k != 0u && (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8)));
+                        const int bin = in ? (int)((k >> shift) & 255u) : -1;
+                        if (bin != prev) {
+                            if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
+                            prev = bin;
+                            run = 0;
+                        }
+                        ++run;
                     }
-                    ++run;
+                    if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const uint32_t k = k4[c];
+                        bool in = k != 0u && (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8)));
+                        if (in) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][(k >> shift) & 255u], 1u);
+                    }
                 }
-                if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
             }
             __syncthreads();
             RadixState r = radix_pick(s_hist, s_h, &s_state, need);
@@ -517,7 +529,7 @@ select_kernel(SelectArgs a)
 
     // ---- ascending write-out -------------------------------------------------------------------
     int32_t base = 0;
-    if constexpr (CACHED) {
+    if constexpr (CACHED && SEL_ROUNDS > 1) {
         // Every round of SEL_THREADS quads at once (at most SEL_ROUNDS of them fit the key cache): a thread keeps
         // the masks of its quads in one register, the rounds' counts are scanned two to a register, and ONE
         // scan over the (round, wavefront) totals gives every wavefront its offsets - three barriers instead of
@@ -1114,11 +1126,11 @@ DeviceOnce g_setup;
 hipError_t select_setup()
 {
     return g_setup.run([](int) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, false>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, false, SEL_MAX_ROUNDS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, true>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<true, true, SEL_MAX_ROUNDS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     SEL_CACHE_MAX_N * (int)sizeof(uint32_t));
         if (e == hipSuccess)
@@ -1191,11 +1203,13 @@ hipError_t launch_select(const float* A, const uint8_t* anchor, const uint8_t* s
         const hipError_t attr_err = select_setup();
         if (attr_err != hipSuccess) return attr_err;
         const size_t lds = (size_t)((n + 3) / 4 * 4) * sizeof(uint32_t);
-        if (capped) hipLaunchKernelGGL((select_kernel<true, true>), dim3(blocks), dim3(SEL_THREADS), lds, st, a);
-        else hipLaunchKernelGGL((select_kernel<true, false>), dim3(blocks), dim3(SEL_THREADS), lds, st, a);
+        const bool one_round = n <= 4 * SEL_THREADS;         // 16 KB of keys: within the default dynamic LDS limit
+        auto kernel = capped ? (one_round ? select_kernel<true, true, 1> : select_kernel<true, true, SEL_MAX_ROUNDS>)
+                             : (one_round ? select_kernel<true, false, 1> : select_kernel<true, false, SEL_MAX_ROUNDS>);
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(SEL_THREADS), lds, st, a);
     } else {
-        if (capped) hipLaunchKernelGGL((select_kernel<false, true>), dim3(blocks), dim3(SEL_THREADS), 0, st, a);
-        else hipLaunchKernelGGL((select_kernel<false, false>), dim3(blocks), dim3(SEL_THREADS), 0, st, a);
+        if (capped) hipLaunchKernelGGL((select_kernel<false, true, 0>), dim3(blocks), dim3(SEL_THREADS), 0, st, a);
+        else hipLaunchKernelGGL((select_kernel<false, false, 0>), dim3(blocks), dim3(SEL_THREADS), 0, st, a);
     }
     return hipGetLastError();
 }
