@@ -158,6 +158,10 @@ select_kernel(SelectArgs a)
 {
     static_assert(CACHED ? (SEL_ROUNDS == 1 || SEL_ROUNDS == SEL_MAX_ROUNDS) : SEL_ROUNDS == 0, "instances");
     constexpr int SEL_BATCH = SEL_ROUNDS == SEL_MAX_ROUNDS ? 2 : 1;   // quads of a thread whose loads are in flight together
+    // long cached rows, one threshold search over every cached key: the histogram of the first digit is taken while
+    // the keys are built, which saves a sweep over the cache (the histograms are cleared before the class count,
+    // whose reduction has a barrier)
+    constexpr bool FIRST_DIGIT_EARLY = CACHED && !CAPPED && SEL_ROUNDS > 1;
     extern __shared__ uint32_t s_key[];                     // [roundup4(n)] when CACHED
     __shared__ uint32_t s_hist[HIST_COPIES][HIST_STRIDE];
     __shared__ uint32_t s_h[256];
@@ -365,6 +369,21 @@ select_kernel(SelectArgs a)
                     uint32_t k[4];
                     quad_keys(q, x[u], k);
                     *reinterpret_cast<uint4*>(&s_key[4 * q]) = make_uint4(k[0], k[1], k[2], k[3]);
+                    if constexpr (FIRST_DIGIT_EARLY) {       // the first pass's histogram, while the keys are at hand
+                        int prev = -1;
+                        uint32_t run = 0;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const int bin = k[c] != 0u ? (int)(k[c] >> 24) : -1;
+                            if (bin != prev) {
+                                if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
+                                prev = bin;
+                                run = 0;
+                            }
+                            ++run;
+                        }
+                        if (prev >= 0) atomicAdd(&s_hist[lane & (HIST_COPIES - 1)][prev], run);
+                    }
                 }
             }
         }
@@ -380,7 +399,7 @@ select_kernel(SelectArgs a)
         bool done = false;
         for (int pass = 0; pass < 4 && !done; ++pass) {
             const int shift = 24 - 8 * pass;
-            for (int32_t q = tid; q < nquads; q += SEL_THREADS) {
+            for (int32_t q = tid; q < nquads && !(FIRST_DIGIT_EARLY && pass == 0); q += SEL_THREADS) {
                 uint32_t k4[4];
                 keys_at(q, k4);
                 member(q, k4);
