@@ -756,8 +756,13 @@ def main():
                                                         copies=3, oracle_s=2 * ora_s)
         c2 = {}
         for kb in ((1024,) if args.no_sweep else wl.CONFIGS["c2_full_model"].budgets):
-            c2["K=%d" % kb], _ = measure_extra(ta, wl, torch, np, "c2_full_model", kb, dev, max(st, 20), max(wu, 5), copies=3,
-                                               oracle_s=4 * ora_s if kb == 1024 else 0.0)
+            # at the largest budget also the generation step of one sequence: 256 units of 1025 slots, which run
+            # several wavefronts per unit
+            c2["K=%d" % kb], c2_step = measure_extra(ta, wl, torch, np, "c2_full_model", kb, dev, max(st, 20), max(wu, 5), copies=3,
+                                                     oracle_s=4 * ora_s if kb == 1024 else 0.0,
+                                                     decode_steps=32 if kb == 1024 else 0, decode_page_size=0)
+            if c2_step is not None:
+                workloads["c2_full_model_decode_step"] = c2_step
         workloads["c2_full_model"] = c2
         workloads["c3_ta_fast"], _ = measure_extra(ta, wl, torch, np, "c3_ta_fast", 512, dev, st, wu, oracle_s=2 * ora_s)
         workloads["c5_agentic_prefill"], workloads["c5_agentic_decode_step"] = measure_extra(

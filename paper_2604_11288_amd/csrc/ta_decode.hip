@@ -312,15 +312,23 @@ __device__ __forceinline__ unsigned long long wave_min_dpp(unsigned long long v)
 // lane's slots (position, voucher, flags, accumulated attention) stay in its registers from the
 // first round trip to the ranking and nothing loops over slots.
 // DT_RING: 16-row key tiles in flight per wavefront.
-template <int GH, bool PAGED, bool SCORED, bool SMALL, int DT_RING>
+// WAVES > 1 (few units with many slots: one wavefront per unit would leave most of the chip idle, stream its
+// keys one tile after the other and loop over its slots): WAVES wavefronts share a unit.  Each keeps its
+// SLOTS_PER_LANE * 64 slots in registers like the SMALL form and streams every WAVES-th key tile; the slot
+// table, the logits and three small exchanges go through LDS (three workgroup barriers).  Every logit, every
+// softmax statistic (each wavefront reduces all of them, in the single wavefront's order) and every slot's
+// key is computed by the same instructions as in the single-wavefront form: the two give the same bits.
+template <int GH, bool PAGED, bool SCORED, bool SMALL, int DT_RING, int WAVES>
 __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg)
 {
     extern __shared__ float s_dyn[];
+    static_assert(WAVES == 1 || (SCORED && SMALL), "several wavefronts: an attention term, slots in registers");
 
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = WAVES > 1 ? (int)(threadIdx.x >> 6) : 0;
     const int sub = lane & 15, grp = lane >> 4;            // 16 lanes per key row, 4 rows per instruction
     if ((int)blockIdx.x >= a.units) {                      // trailing workgroups: budget decay
-        decay_rider(st, (int)blockIdx.x - a.units, a.decay);
+        if (wave == 0) decay_rider(st, (int)blockIdx.x - a.units, a.decay);
         return;
     }
     const int unit = blockIdx.x;
@@ -334,6 +342,7 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
     uint4* Kc = reinterpret_cast<uint4*>(st.Kc) + (PAGED ? l * pg.s_layer + g * pg.s_head : (int64_t)unit * slots * 16);
     uint4* Vc = reinterpret_cast<uint4*>(st.Vc) + (PAGED ? l * pg.s_layer + g * pg.s_head : (int64_t)unit * slots * 16);
     constexpr int SPL = SLOTS_PER_LANE;                            // slots per lane that one round trip covers
+    const int sbase = wave * (SPL * 64);                           // first slot of this wavefront's share
 
     // Everything that does not depend on loaded data is requested first, in the order it is needed
     // (loads of a wavefront return in order), and unconditionally (clamped addresses, results masked
@@ -342,7 +351,7 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
     int32_t p0[SPL];
 #pragma unroll
     for (int j = 0; j < SPL; ++j) {
-        const int s = lane + 64 * j;
+        const int s = sbase + lane + 64 * j;
         p0[j] = SMALL ? pos[s < slots ? s : slots - 1] : 0;
     }
     const uint4* nsrc = ((lane & 16) ? a.v_new : a.k_new) + ((size_t)(l * st.batch + b) * st.hkv + g) * 16;
@@ -361,12 +370,17 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
     };
     int32_t* s_pos = reinterpret_cast<int32_t*>(s_dyn);
     const int wstride = (slots + 3) & ~3;                  // logits of a head: padded to whole 16-byte groups
-    uint4* s_t = reinterpret_cast<uint4*>(s_dyn + wstride);                  // one 16-row key tile, 4 KB (scored only)
-    uint4* s_kn = s_t + 256;                                                 // the new key row
-    float* s_w = reinterpret_cast<float*>(s_kn + 16);
+    // scored only: per wavefront one 16-row key tile (4 KB) and a copy of the new key row; with several
+    // wavefronts 64 words for what they exchange; the logits
+    uint4* s_t = reinterpret_cast<uint4*>(s_dyn + wstride) + 256 * wave;
+    uint4* s_kn = reinterpret_cast<uint4*>(s_dyn + wstride) + 256 * WAVES + 16 * wave;
+    int32_t* s_x = reinterpret_cast<int32_t*>(reinterpret_cast<uint4*>(s_dyn + wstride) + (256 + 16) * WAVES);
+    float* s_w = reinterpret_cast<float*>(s_x) + (WAVES > 1 ? 64 : 0);
 
     const int i16 = sub, kq = grp;
-    const int ntiles = (slots + 15) >> 4;
+    // this wavefront's tiles are wave, wave + WAVES, ...; `tile` below counts them, tile_of gives the unit's tile
+    const int ntiles = (((slots + 15) >> 4) - wave + WAVES - 1) / WAVES;
+    const auto tile_of = [&](int tile) { return wave + WAVES * tile; };
     uint4 qf[4], tiles[DT_RING][4];                        // DT_RING tiles in flight
     // Key rows are read once per step: the non-temporal hint keeps them from displacing the slot tables,
     // the accumulated attention and the per-sequence arrays in the caches (231 -> 210 us on 16 384 units).
@@ -375,7 +389,7 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
             const char* base = reinterpret_cast<const char*>(Kc);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                int row = tile * 16 + 4 * t + grp;
+                int row = tile_of(tile) * 16 + 4 * t + grp;
                 row = row < slots ? row : slots - 1;       // past the last slot: a valid row, masked at the store
                 {
                     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -387,7 +401,7 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
         }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            int row = tile * 16 + 4 * t + grp;
+            int row = tile_of(tile) * 16 + 4 * t + grp;
             row = row < slots ? row : slots - 1;
             typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
             const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(&Kc[row_at(row) + sub]));
@@ -410,7 +424,7 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
     if (SMALL) {
 #pragma unroll
         for (int j = 0; j < SPL; ++j) {
-            const int s = lane + 64 * j;
+            const int s = sbase + lane + 64 * j;
             if (s < slots) {
                 s_pos[s] = p0[j];
                 if (p0[j] < 0) first_free = first_free < s ? first_free : s;
@@ -433,12 +447,19 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
             }
         }
     }
-    const int f = wave_min_dpp(first_free);
+    int f = wave_min_dpp(first_free);
+    if (WAVES > 1) {
+        if (lane == 0) s_x[wave] = f;
+        __syncthreads();                                   // every share of the slot table is in LDS
+        f = s_x[0];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) f = s_x[w] < f ? s_x[w] : f;
+    }
     const int32_t len_new = stepped & 0x3FFFFFFF;
     const uint8_t an_new = (uint8_t)((stepped >> 30) & 1);
     if (len_new == 0 || f >= slots) {                      // a sequence at capacity, or no room: nothing to do
-        if (lane == 0 && a.evicted) a.evicted[unit] = -1;
-        return;
+        if (wave == 0 && lane == 0 && a.evicted) a.evicted[unit] = -1;
+        return;                                            // (every wavefront of the unit: the same test)
     }
     const int32_t p_new = len_new - 1;
 
@@ -451,7 +472,7 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
     uint8_t fl0[SPL];
 #pragma unroll
     for (int j = 0; SMALL && j < SPL; ++j) {
-        const int s = lane + 64 * j;
+        const int s = sbase + lane + 64 * j;
         if (s == f) p0[j] = p_new;
         if (s >= slots) p0[j] = -2;
         const int32_t pc = p0[j] < 0 ? 0 : p0[j];
@@ -465,9 +486,9 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
         }
     }
     if (lane < 16) {
-        Kc[row_at(f) + lane] = nrow;
+        if (wave == 0) Kc[row_at(f) + lane] = nrow;
         if (SCORED) s_kn[lane] = nrow;
-    } else if (lane < 32) Vc[row_at(f) + lane - 16] = nrow;
+    } else if (lane < 32 && wave == 0) Vc[row_at(f) + lane - 16] = nrow;
     __builtin_amdgcn_wave_barrier();                       // the slot table is in LDS for every lane
 
     float m_h[GH], inv_h[GH];
@@ -481,8 +502,20 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
             }
             return acc;                                    // rows 4 kq .. 4 kq + 3 of the tile, head i16
         };
+        // several wavefronts: the new key's logit goes into the free slot with the tile that holds it (every
+        // row of this pseudo-tile is the new key, so every lane of a head gets that head's logit)
+        float new_logit = 0.0f;
+        if (WAVES > 1) {
+            uint4 knf[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint4 v = s_kn[kq + 4 * t];
+                knf[t] = make_uint4(v.x, v.y, v.z, v.w);
+            }
+            new_logit = frag_logits(knf)[0] * a.scale_log2;
+        }
         const auto store_tile = [&](int tile, const f32x4& acc) {
-            const int s = tile * 16 + 4 * kq;
+            const int s = tile_of(tile) * 16 + 4 * kq;
             if (i16 < G && s < wstride) {
                 const int4 p4 = *reinterpret_cast<const int4*>(&s_pos[s]);   // padded to whole groups of four
                 float4 o;
@@ -490,6 +523,12 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
                 o.y = (s + 1 < slots && p4.y >= 0) ? acc[1] * a.scale_log2 : -INFINITY;
                 o.z = (s + 2 < slots && p4.z >= 0) ? acc[2] * a.scale_log2 : -INFINITY;
                 o.w = (s + 3 < slots && p4.w >= 0) ? acc[3] * a.scale_log2 : -INFINITY;
+                if (WAVES > 1) {
+                    o.x = s + 0 == f ? new_logit : o.x;
+                    o.y = s + 1 == f ? new_logit : o.y;
+                    o.z = s + 2 == f ? new_logit : o.z;
+                    o.w = s + 3 == f ? new_logit : o.w;
+                }
                 *reinterpret_cast<float4*>(&s_w[i16 * wstride + s]) = o;
             }
         };
@@ -527,7 +566,9 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
             for (int j = 0; j < DT_RING; ++j)
                 if (tb + j < ntiles) one_tile(tb + j, tiles[j], tb + j + DT_RING < ntiles);
         }
-        {
+        if (WAVES > 1) {
+            __syncthreads();                               // the logits of every wavefront's tiles are in LDS
+        } else {
             uint4 knf[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {                                  // every row of this tile is the new key
@@ -594,7 +635,7 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
         worst = key < worst ? key : worst;
     };
 #pragma unroll
-    for (int j = 0; SMALL && j < SPL; ++j) rank_slot(lane + 64 * j, p0[j], v0[j], fl0[j], a0[j]);
+    for (int j = 0; SMALL && j < SPL; ++j) rank_slot(sbase + lane + 64 * j, p0[j], v0[j], fl0[j], a0[j]);
     for (int s0 = lane; !SMALL && s0 < slots; s0 += SPL * 64) {    // more slots than a lane's registers hold
         int32_t p4[SPL];
         float v4[SPL], a4[SPL];
@@ -618,12 +659,29 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
     }
     nfree = wave_sum_dpp(nfree);
     worst = wave_min_dpp(worst);
+    if (WAVES > 1) {
+        if (lane == 0) {
+            s_x[8 + wave] = nfree;
+            s_x[16 + 2 * wave] = (int32_t)(uint32_t)worst;
+            s_x[17 + 2 * wave] = (int32_t)(uint32_t)(worst >> 32);
+        }
+        __syncthreads();                                   // every wavefront's free count and worst key
+        nfree = 0;
+        worst = ~0ull;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            nfree += s_x[8 + w];
+            const unsigned long long k = ((unsigned long long)(uint32_t)s_x[17 + 2 * w] << 32) | (uint32_t)s_x[16 + 2 * w];
+            worst = k < worst ? k : worst;
+        }
+    }
     const int32_t evict_pos = nfree > 0 ? -1 : (int32_t)(worst & 0x3FFFFFFFull);
-    for (int s = lane; s < slots; s += 64) {
+    const int s_end = (WAVES > 1 && sbase + SPL * 64 < slots) ? sbase + SPL * 64 : slots;   // a wavefront updates its own share
+    for (int s = sbase + lane; s < s_end; s += 64) {
         const int32_t p = (s == f) ? p_new : s_pos[s];
         if (s == f || (p >= 0 && p == evict_pos)) pos[s] = (p == evict_pos) ? -1 : p;
     }
-    if (lane == 0 && a.evicted) a.evicted[unit] = evict_pos;
+    if (wave == 0 && lane == 0 && a.evicted) a.evicted[unit] = evict_pos;
 }
 
 // Dense slots: three tiles in flight at four wavefronts per SIMD (124 registers).  Paged slots need
@@ -633,14 +691,35 @@ template <int GH, bool SCORED, bool SMALL>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4)))
 decode_unit_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 {
-    decode_unit<GH, false, SCORED, SMALL, 3>(st, a, pg);
+    decode_unit<GH, false, SCORED, SMALL, 3, 1>(st, a, pg);
 }
 
 template <int GH, bool SCORED, bool SMALL>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(3)))
 decode_unit_paged_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 {
-    decode_unit<GH, true, SCORED, SMALL, 4>(st, a, pg);
+    decode_unit<GH, true, SCORED, SMALL, 4, 1>(st, a, pg);
+}
+
+// Few units with long key streams: DU_WIDE wavefronts per unit, each with SLOTS_PER_LANE * 64 of its slots.
+constexpr int DU_WIDE = 4;
+#ifndef TA_DECODE_WIDE_MAX_UNITS
+#define TA_DECODE_WIDE_MAX_UNITS 384
+#endif
+constexpr int DU_WIDE_MAX_UNITS = TA_DECODE_WIDE_MAX_UNITS;   // measured: ahead at 256 units, level at 512, behind at 1024
+
+template <int GH>
+__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(4)))
+decode_unit_wide_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
+{
+    decode_unit<GH, false, true, true, 3, DU_WIDE>(st, a, pg);
+}
+
+template <int GH>
+__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(3)))
+decode_unit_paged_wide_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
+{
+    decode_unit<GH, true, true, true, 4, DU_WIDE>(st, a, pg);
 }
 
 DeviceOnce g_setup;
@@ -675,7 +754,9 @@ hipError_t unit_attributes()
     const void* fns[] = {reinterpret_cast<const void*>(&decode_unit_kernel<GH, true, true>),
                          reinterpret_cast<const void*>(&decode_unit_kernel<GH, true, false>),
                          reinterpret_cast<const void*>(&decode_unit_paged_kernel<GH, true, true>),
-                         reinterpret_cast<const void*>(&decode_unit_paged_kernel<GH, true, false>)};
+                         reinterpret_cast<const void*>(&decode_unit_paged_kernel<GH, true, false>),
+                         reinterpret_cast<const void*>(&decode_unit_wide_kernel<GH>),
+                         reinterpret_cast<const void*>(&decode_unit_paged_wide_kernel<GH>)};
     hipError_t e = hipSuccess;
     for (const void* fn : fns)
         if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -683,9 +764,15 @@ hipError_t unit_attributes()
 }
 
 template <int GH>
-void launch_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg, unsigned grid, size_t lds, hipStream_t s)
+void launch_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg, unsigned grid, size_t lds, bool wide,
+                 hipStream_t s)
 {
     const bool scored = a.alpha != 0.0f, small = st.K + 1 <= SLOTS_PER_LANE * 64;
+    if (wide) {
+        if (st.pages) hipLaunchKernelGGL(decode_unit_paged_wide_kernel<GH>, dim3(grid), dim3(64 * DU_WIDE), lds, s, st, a, pg);
+        else hipLaunchKernelGGL(decode_unit_wide_kernel<GH>, dim3(grid), dim3(64 * DU_WIDE), lds, s, st, a, pg);
+        return;
+    }
 #define TA_LAUNCH_UNIT(KERNEL, S, M) \
     hipLaunchKernelGGL((KERNEL<GH, S, M>), dim3(grid), dim3(64), lds, s, st, a, pg)
     if (st.pages) {
@@ -762,12 +849,20 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     const int slots = st.K + 1;
     // slot table; with an attention term also one key tile, the new key row and the logits
     const size_t wstride = (size_t)((slots + 3) & ~3);
-    size_t lds_floats = prm.alpha != 0.0f ? wstride + 1024 + 64 + (size_t)G * wstride : wstride;
     const SlotPages pg = slot_pages(st);
+    const size_t page_list = st.pages ? (size_t)((slots - 1) / pg.page_size + 1) : 0;      // the pages of the unit's slots
+    // per wavefront a key tile and the new key row; several wavefronts: 64 words more
+    const auto scored_floats = [&](int waves) { return wstride + (1024 + 64) * (size_t)waves + (waves > 1 ? 64 : 0) + (size_t)G * wstride; };
+    // several wavefronts per unit when one each would leave the chip mostly idle and the slots do not fit one
+    // wavefront's registers (but do fit those of DU_WIDE)
+    bool wide = prm.alpha != 0.0f && slots > SLOTS_PER_LANE * 64 && slots <= DU_WIDE * SLOTS_PER_LANE * 64 &&
+                units <= (unsigned)DU_WIDE_MAX_UNITS;
+    if (wide && (scored_floats(DU_WIDE) + page_list) * sizeof(float) > 160 * 1024) wide = false;
+    size_t lds_floats = prm.alpha != 0.0f ? scored_floats(wide ? DU_WIDE : 1) : wstride;
     a.pg_off = (int32_t)lds_floats;
     a.units = (int32_t)units;
     a.decay = prm.budget_decay;
-    if (st.pages) lds_floats += (size_t)((slots - 1) / pg.page_size + 1);      // the pages of the unit's slots
+    lds_floats += page_list;
     const size_t lds = lds_floats * sizeof(float);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     const hipError_t attr_err = decode_setup();
@@ -775,9 +870,9 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     // the units, then one workgroup per 256 positions for the budget decay
     const uint64_t grid = (uint64_t)units + (uint64_t)tiles * (uint64_t)st.batch;
     if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    if (G <= 4) launch_unit<4>(st, a, pg, (unsigned)grid, lds, s);
-    else if (G <= 8) launch_unit<8>(st, a, pg, (unsigned)grid, lds, s);
-    else launch_unit<MAX_GROUP>(st, a, pg, (unsigned)grid, lds, s);
+    if (G <= 4) launch_unit<4>(st, a, pg, (unsigned)grid, lds, wide, s);
+    else if (G <= 8) launch_unit<8>(st, a, pg, (unsigned)grid, lds, wide, s);
+    else launch_unit<MAX_GROUP>(st, a, pg, (unsigned)grid, lds, wide, s);
     return hipGetLastError();
 }
 

@@ -333,3 +333,47 @@ def test_compact_into_pages_touches_nothing_else():
                     ora.paged_scatter(want_K[l], ora.compact(wl.bf16_bits(Kc[l, b, g]), sel), ptable[b], page_size, sp, spos, sh, g)
                     ora.paged_scatter(want_V[l], ora.compact(wl.bf16_bits(Vc[l, b, g]), sel), ptable[b], page_size, sp, spos, sh, g)
         assert np.array_equal(wl.bf16_bits(pool.Kpool), want_K) and np.array_equal(wl.bf16_bits(pool.Vpool), want_V)
+
+
+@pytest.mark.parametrize("paged", [None, (16, False)])
+def test_several_wavefronts_per_unit_give_the_single_wavefronts_bits(paged):
+    """Few units with more slots than one wavefront keeps in registers run several wavefronts per unit.  The
+    same sequence alone (8 units) and as every member of a batch of 64 (512 units: one wavefront each) must
+    leave the same state, bit for bit, after the same steps."""
+    K, steps, big = 400, 6, 64
+    w1 = wl.scaled(wl.CONFIGS["c2_full_model"], layers=1, batch=1, n=1024, planted=4)
+    td = wl.make_tokens(w1, clean=False)
+    Q, Kc, Vc = wl.make_qkv(w1, device=DEV)
+    prm = ta.Params(n_sink=w1.n_sink, n_recent=w1.n_recent, alpha=w1.alpha, beta=w1.beta, gamma=w1.gamma)
+    stream = wl.make_decode_stream(w1, td, steps, p_anchor=0.1, clean=False)
+    # one prefill eviction; the batch gets copies of its outputs (the scores of two units with the same data may
+    # differ in the last bit: the score step visits a unit's key stages in an order of its own)
+    plan = ta.ta_evict(_dev(td.tok), td.tab_ids, td.tab_len, Q, Kc, Vc, K, prm)
+    states = []
+    for B in (1, big):
+        wB = wl.scaled(w1, batch=B)
+        rep = lambda t: t.expand(t.shape[0], B, *t.shape[2:]).contiguous()       # [Lyr][1][...] -> [Lyr][B][...]
+        tok = _dev(np.repeat(td.tok, B, axis=0))
+        pool, ptable = _slot_pool(wB, K, paged[0], paged[1])[:2] if paged else (None, None)
+        st = ta.DecodeState(1, B, w1.hq, w1.hkv, K, w1.n + steps + 4, DEV, pages=pool)
+        ta.ta_decode_init(st, tok, plan.anchor.expand(B, -1).contiguous(), rep(plan.idx), rep(plan.cnt), rep(plan.Kout),
+                          rep(plan.Vout), prm, A=rep(plan.A))
+        evicted = torch.zeros((1, B, w1.hkv), dtype=torch.int32, device=DEV)
+        trail = []
+        for t in range(steps):
+            q, kn, vn = wl.make_decode_qkv(w1, t, device=DEV)
+            ta.ta_decode_step(st, _dev(np.repeat(stream[t], B)), rep(q), rep(kn), rep(vn), td.tab_ids, td.tab_len, prm,
+                              evicted=evicted)
+            trail.append(evicted[:, 0].clone())
+        torch.cuda.synchronize()
+        if paged:
+            Ks = _slots_dense(pool.Kpool, ptable, paged[0], K + 1, paged[1])
+            Vs = _slots_dense(pool.Vpool, ptable, paged[0], K + 1, paged[1])
+        else:
+            Ks, Vs = st.Kc, st.Vc
+        states.append((st.pos[:, 0].clone(), st.A[:, 0].clone(), Ks[:, 0].clone(), Vs[:, 0].clone(), torch.stack(trail)))
+        if B == big:                                      # and every member of the batch agrees with the first
+            assert all(_same_bits(st.pos[:, b], st.pos[:, 0]) and _same_bits(st.A[:, b], st.A[:, 0]) for b in range(1, B))
+    for x1, xb in zip(*states):
+        assert _same_bits(x1, xb)
+    assert (states[0][4] >= 0).any()                      # slots were evicted on the way
