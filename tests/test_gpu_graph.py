@@ -63,7 +63,8 @@ def test_captured_pass_replays_to_the_eager_result(form):
             assert torch.equal(got, ref), (form, replay)
 
 
-def test_captured_decode_step_replays_like_eager_steps():
+@pytest.mark.parametrize("K", [120, 400])                  # 400: more slots than a wavefront's registers hold - four wavefronts per unit
+def test_captured_decode_step_replays_like_eager_steps(K):
     # one generation step captured once; before every replay the step's inputs are copied into the
     # captured buffers.  Two states from the same prefill, one stepped eagerly, one by replays.
     w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=3, n=700, hq=8, hkv=2, ragged=(200, 700))
@@ -71,7 +72,7 @@ def test_captured_decode_step_replays_like_eager_steps():
     Q, Kc, Vc = wl.make_qkv(w, device=DEV)
     prm = ta.Params(n_sink=w.n_sink, n_recent=w.n_recent)
     tok, seq = _dev(td.tok), _dev(td.seq_len)
-    K, steps = 120, 6
+    steps = 6
     plan = ta.ta_evict(tok, td.tab_ids, td.tab_len, Q, Kc, Vc, K, prm, seq_len=seq)
     states = []
     for _ in range(2):
