@@ -702,24 +702,27 @@ decode_unit_paged_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 }
 
 // Few units with long key streams: DU_WIDE wavefronts per unit, each with SLOTS_PER_LANE * 64 of its slots.
+// Occupancy does not matter at these sizes: six key tiles in flight per wavefront (seven with paged slots) in two
+// wavefronts' worth of registers per SIMD.
 constexpr int DU_WIDE = 4;
+constexpr int DU_WIDE_RING = 6;
 #ifndef TA_DECODE_WIDE_MAX_UNITS
-#define TA_DECODE_WIDE_MAX_UNITS 384
+#define TA_DECODE_WIDE_MAX_UNITS 640
 #endif
-constexpr int DU_WIDE_MAX_UNITS = TA_DECODE_WIDE_MAX_UNITS;   // measured: ahead at 256 units, level at 512, behind at 1024
+constexpr int DU_WIDE_MAX_UNITS = TA_DECODE_WIDE_MAX_UNITS;   // measured: ahead at 256 and 512 units, level at 768, behind at 1024
 
 template <int GH>
-__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(4)))
+__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(2)))
 decode_unit_wide_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 {
-    decode_unit<GH, false, true, true, 3, DU_WIDE>(st, a, pg);
+    decode_unit<GH, false, true, true, DU_WIDE_RING, DU_WIDE>(st, a, pg);
 }
 
 template <int GH>
-__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(3)))
+__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(2)))
 decode_unit_paged_wide_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 {
-    decode_unit<GH, true, true, true, 4, DU_WIDE>(st, a, pg);
+    decode_unit<GH, true, true, true, DU_WIDE_RING + 1, DU_WIDE>(st, a, pg);
 }
 
 DeviceOnce g_setup;

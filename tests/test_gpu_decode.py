@@ -338,9 +338,9 @@ def test_compact_into_pages_touches_nothing_else():
 @pytest.mark.parametrize("paged", [None, (16, False)])
 def test_several_wavefronts_per_unit_give_the_single_wavefronts_bits(paged):
     """Few units with more slots than one wavefront keeps in registers run several wavefronts per unit.  The
-    same sequence alone (8 units) and as every member of a batch of 64 (512 units: one wavefront each) must
+    same sequence alone (8 units) and as every member of a batch of 96 (768 units: one wavefront each) must
     leave the same state, bit for bit, after the same steps."""
-    K, steps, big = 400, 6, 64
+    K, steps, big = 400, 6, 96
     w1 = wl.scaled(wl.CONFIGS["c2_full_model"], layers=1, batch=1, n=1024, planted=4)
     td = wl.make_tokens(w1, clean=False)
     Q, Kc, Vc = wl.make_qkv(w1, device=DEV)
