@@ -580,26 +580,49 @@ __device__ __forceinline__ void decode_unit(const ta_decode_state& st, const Uni
             if (i16 < G && kq == 0) s_w[i16 * wstride + f] = acc[0] * a.scale_log2;
             __builtin_amdgcn_wave_barrier();
         }
-        // softmax statistics of all heads at once: one pass for the maxima, one for the sums
+        // softmax statistics of all heads at once: one pass for the maxima, one for the sums.  Several
+        // wavefronts: each takes every WAVES-th head (a head's reduction runs in one wavefront, in the
+        // single wavefront's order) and the results are exchanged through LDS.
+        const auto mine = [&](int h) { return h < G && (WAVES == 1 || h % WAVES == wave); };
 #pragma unroll
         for (int h = 0; h < GH; ++h) m_h[h] = -INFINITY;
         for (int s = lane; s < slots; s += 64) {
 #pragma unroll
             for (int h = 0; h < GH; ++h)
-                if (h < G) m_h[h] = fmaxf(m_h[h], s_w[h * wstride + s]);
+                if (mine(h)) m_h[h] = fmaxf(m_h[h], s_w[h * wstride + s]);
         }
 #pragma unroll
-        for (int h = 0; h < GH; ++h) m_h[h] = wave_max_dpp(m_h[h]);
+        for (int h = 0; h < GH; ++h)
+            if (mine(h)) m_h[h] = wave_max_dpp(m_h[h]);
         float z_h[GH];
 #pragma unroll
         for (int h = 0; h < GH; ++h) z_h[h] = 0.0f;
         for (int s = lane; s < slots; s += 64) {
 #pragma unroll
             for (int h = 0; h < GH; ++h)
-                if (h < G) z_h[h] += __builtin_amdgcn_exp2f(s_w[h * wstride + s] - m_h[h]);
+                if (mine(h)) z_h[h] += __builtin_amdgcn_exp2f(s_w[h * wstride + s] - m_h[h]);
         }
 #pragma unroll
-        for (int h = 0; h < GH; ++h) inv_h[h] = h < G ? __builtin_amdgcn_rcpf(wave_sum_dpp(z_h[h])) : 0.0f;
+        for (int h = 0; h < GH; ++h) inv_h[h] = mine(h) ? __builtin_amdgcn_rcpf(wave_sum_dpp(z_h[h])) : 0.0f;
+        if (WAVES > 1) {
+            static_assert(WAVES == 1 || GH <= 16, "the exchange area holds 16 heads");
+            float* s_stat = reinterpret_cast<float*>(s_x) + 32;            // [0..16): maxima, [16..32): reciprocal sums
+            if (lane == 0) {
+#pragma unroll
+                for (int h = 0; h < GH; ++h) {
+                    if (mine(h)) {
+                        s_stat[h] = m_h[h];
+                        s_stat[16 + h] = inv_h[h];
+                    }
+                }
+            }
+            __syncthreads();                               // every head's statistics
+#pragma unroll
+            for (int h = 0; h < GH; ++h) {
+                m_h[h] = h < G ? s_stat[h] : -INFINITY;
+                inv_h[h] = h < G ? s_stat[16 + h] : 0.0f;
+            }
+        }
     }
 
     // ---- new attention mass per slot, then the rank of the slot, in one pass (a lane handles the
@@ -706,10 +729,15 @@ decode_unit_paged_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 // wavefronts' worth of registers per SIMD.
 constexpr int DU_WIDE = 4;
 constexpr int DU_WIDE_RING = 6;
+// When: measured against one wavefront per unit on 32 x batch x 8 units.  From about 700 slots on the shared form is
+// ahead at every unit count (1025 slots: 24 against 44 us per step at 256 units, 198 against 220 us at 4096, 386
+// against 412 us at 8192 - the single wavefront has to loop over its slots there); below that it is ahead up to
+// about 640 units (513 slots: 18 against 27 us at 256 units, level at 768, behind from 1024 on).
 #ifndef TA_DECODE_WIDE_MAX_UNITS
 #define TA_DECODE_WIDE_MAX_UNITS 640
 #endif
-constexpr int DU_WIDE_MAX_UNITS = TA_DECODE_WIDE_MAX_UNITS;   // measured: ahead at 256 and 512 units, level at 768, behind at 1024
+constexpr int DU_WIDE_MAX_UNITS = TA_DECODE_WIDE_MAX_UNITS;   // (0: never)
+constexpr int DU_WIDE_ALWAYS_SLOTS = 704;
 
 template <int GH>
 __global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(2)))
@@ -856,10 +884,10 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     const size_t page_list = st.pages ? (size_t)((slots - 1) / pg.page_size + 1) : 0;      // the pages of the unit's slots
     // per wavefront a key tile and the new key row; several wavefronts: 64 words more
     const auto scored_floats = [&](int waves) { return wstride + (1024 + 64) * (size_t)waves + (waves > 1 ? 64 : 0) + (size_t)G * wstride; };
-    // several wavefronts per unit when one each would leave the chip mostly idle and the slots do not fit one
-    // wavefront's registers (but do fit those of DU_WIDE)
+    // several wavefronts per unit when the slots do not fit one wavefront's registers (but do fit those of DU_WIDE)
+    // and either are many or the units are few
     bool wide = prm.alpha != 0.0f && slots > SLOTS_PER_LANE * 64 && slots <= DU_WIDE * SLOTS_PER_LANE * 64 &&
-                units <= (unsigned)DU_WIDE_MAX_UNITS;
+                DU_WIDE_MAX_UNITS > 0 && (units <= (unsigned)DU_WIDE_MAX_UNITS || slots > DU_WIDE_ALWAYS_SLOTS);
     if (wide && (scored_floats(DU_WIDE) + page_list) * sizeof(float) > 160 * 1024) wide = false;
     size_t lds_floats = prm.alpha != 0.0f ? scored_floats(wide ? DU_WIDE : 1) : wstride;
     a.pg_off = (int32_t)lds_floats;

@@ -227,6 +227,13 @@ def test_decode_large_budget_eight_heads_per_group():
     assert ev == 5
 
 
+def test_decode_budget_of_a_thousand_rows_four_wavefronts_per_unit():
+    # 1001 slots: past the register-resident budget of one wavefront, within that of four
+    w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=2, n=1300, hq=8, hkv=2, ragged=(900, 1300))
+    ev, _ = _run_decode(w, K=1000, steps=6, p_anchor=0.2, check_every=2)
+    assert ev > 0
+
+
 def test_decode_sixteen_heads_per_group():
     # the heads of a group fill all 16 columns of the logits' MFMA tiles
     w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=2, batch=2, n=600, hq=32, hkv=2, ragged=(300, 600))
@@ -293,6 +300,7 @@ def test_decode_last_query_rule(rank):
     (16, False, True, 400, 8, 8),      # more slots than a lane keeps in registers: the looping form of the unit kernel
     (16, False, False, 64, 10, 16),    # 8 query heads per KV head
     (16, False, True, 400, 6, 16),
+    (16, True, True, 1000, 4, 8),      # 1001 slots: four wavefronts per unit at any number of units
     (32, True, True, 64, 10, 32),      # 16 query heads per KV head (512 query rows per unit in the prefill)
 ])
 def test_decode_over_a_paged_slot_pool(page_size, heads_first, in_place, K, steps, hq):
