@@ -724,10 +724,11 @@ decode_unit_paged_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
     decode_unit<GH, true, SCORED, SMALL, 4, 1>(st, a, pg);
 }
 
-// Few units with long key streams: DU_WIDE wavefronts per unit, each with SLOTS_PER_LANE * 64 of its slots.
-// Occupancy does not matter at these sizes: six key tiles in flight per wavefront (seven with paged slots) in two
+// More slots than one wavefront's registers hold: four wavefronts per unit (up to 1280 slots) or eight (up to 2560),
+// each with SLOTS_PER_LANE * 64 of the slots.  Six key tiles in flight per wavefront (seven with paged slots) in two
 // wavefronts' worth of registers per SIMD.
 constexpr int DU_WIDE = 4;
+constexpr int DU_WIDER = 8;
 constexpr int DU_WIDE_RING = 6;
 // When: measured against one wavefront per unit on 32 x batch x 8 units.  From about 700 slots on the shared form is
 // ahead at every unit count (1025 slots: 24 against 44 us per step at 256 units, 198 against 220 us at 4096, 386
@@ -738,19 +739,23 @@ constexpr int DU_WIDE_RING = 6;
 #endif
 constexpr int DU_WIDE_MAX_UNITS = TA_DECODE_WIDE_MAX_UNITS;   // (0: never)
 constexpr int DU_WIDE_ALWAYS_SLOTS = 704;
+// Eight wavefronts (1281 to 2560 slots): 2048 slots: 37 against 74 us at 256 units, 140 against 173 us at 1024, 509
+// against 538 us at 4096; 1501 slots: 32 against 57 us at 256 units, but 207 against 183 us at 2048.
+constexpr int DU_WIDER_MAX_UNITS = 1024;
+constexpr int DU_WIDER_ALWAYS_SLOTS = 1792;
 
-template <int GH>
-__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(2)))
+template <int GH, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
 decode_unit_wide_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 {
-    decode_unit<GH, false, true, true, DU_WIDE_RING, DU_WIDE>(st, a, pg);
+    decode_unit<GH, false, true, true, DU_WIDE_RING, WAVES>(st, a, pg);
 }
 
-template <int GH>
-__global__ void __launch_bounds__(64 * DU_WIDE) __attribute__((amdgpu_waves_per_eu(2)))
+template <int GH, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
 decode_unit_paged_wide_kernel(ta_decode_state st, UnitArgs a, SlotPages pg)
 {
-    decode_unit<GH, true, true, true, DU_WIDE_RING + 1, DU_WIDE>(st, a, pg);
+    decode_unit<GH, true, true, true, DU_WIDE_RING + 1, WAVES>(st, a, pg);
 }
 
 DeviceOnce g_setup;
@@ -786,8 +791,10 @@ hipError_t unit_attributes()
                          reinterpret_cast<const void*>(&decode_unit_kernel<GH, true, false>),
                          reinterpret_cast<const void*>(&decode_unit_paged_kernel<GH, true, true>),
                          reinterpret_cast<const void*>(&decode_unit_paged_kernel<GH, true, false>),
-                         reinterpret_cast<const void*>(&decode_unit_wide_kernel<GH>),
-                         reinterpret_cast<const void*>(&decode_unit_paged_wide_kernel<GH>)};
+                         reinterpret_cast<const void*>(&decode_unit_wide_kernel<GH, DU_WIDE>),
+                         reinterpret_cast<const void*>(&decode_unit_paged_wide_kernel<GH, DU_WIDE>),
+                         reinterpret_cast<const void*>(&decode_unit_wide_kernel<GH, DU_WIDER>),
+                         reinterpret_cast<const void*>(&decode_unit_paged_wide_kernel<GH, DU_WIDER>)};
     hipError_t e = hipSuccess;
     for (const void* fn : fns)
         if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -795,13 +802,14 @@ hipError_t unit_attributes()
 }
 
 template <int GH>
-void launch_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg, unsigned grid, size_t lds, bool wide,
+void launch_unit(const ta_decode_state& st, const UnitArgs& a, const SlotPages& pg, unsigned grid, size_t lds, int waves,
                  hipStream_t s)
 {
     const bool scored = a.alpha != 0.0f, small = st.K + 1 <= SLOTS_PER_LANE * 64;
-    if (wide) {
-        if (st.pages) hipLaunchKernelGGL(decode_unit_paged_wide_kernel<GH>, dim3(grid), dim3(64 * DU_WIDE), lds, s, st, a, pg);
-        else hipLaunchKernelGGL(decode_unit_wide_kernel<GH>, dim3(grid), dim3(64 * DU_WIDE), lds, s, st, a, pg);
+    if (waves > 1) {                                       // several wavefronts per unit
+        auto kernel = st.pages ? (waves == DU_WIDE ? decode_unit_paged_wide_kernel<GH, DU_WIDE> : decode_unit_paged_wide_kernel<GH, DU_WIDER>)
+                               : (waves == DU_WIDE ? decode_unit_wide_kernel<GH, DU_WIDE> : decode_unit_wide_kernel<GH, DU_WIDER>);
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(64 * waves), lds, s, st, a, pg);
         return;
     }
 #define TA_LAUNCH_UNIT(KERNEL, S, M) \
@@ -884,12 +892,18 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     const size_t page_list = st.pages ? (size_t)((slots - 1) / pg.page_size + 1) : 0;      // the pages of the unit's slots
     // per wavefront a key tile and the new key row; several wavefronts: 64 words more
     const auto scored_floats = [&](int waves) { return wstride + (1024 + 64) * (size_t)waves + (waves > 1 ? 64 : 0) + (size_t)G * wstride; };
-    // several wavefronts per unit when the slots do not fit one wavefront's registers (but do fit those of DU_WIDE)
-    // and either are many or the units are few
-    bool wide = prm.alpha != 0.0f && slots > SLOTS_PER_LANE * 64 && slots <= DU_WIDE * SLOTS_PER_LANE * 64 &&
-                DU_WIDE_MAX_UNITS > 0 && (units <= (unsigned)DU_WIDE_MAX_UNITS || slots > DU_WIDE_ALWAYS_SLOTS);
-    if (wide && (scored_floats(DU_WIDE) + page_list) * sizeof(float) > 160 * 1024) wide = false;
-    size_t lds_floats = prm.alpha != 0.0f ? scored_floats(wide ? DU_WIDE : 1) : wstride;
+    // several wavefronts per unit when the slots do not fit one wavefront's registers (but do fit those of four or
+    // eight) and either are many or the units are few
+    int waves = 1;
+    if (prm.alpha != 0.0f && slots > SLOTS_PER_LANE * 64 && DU_WIDE_MAX_UNITS > 0) {
+        if (slots <= DU_WIDE * SLOTS_PER_LANE * 64) {
+            if (units <= (unsigned)DU_WIDE_MAX_UNITS || slots > DU_WIDE_ALWAYS_SLOTS) waves = DU_WIDE;
+        } else if (slots <= DU_WIDER * SLOTS_PER_LANE * 64) {
+            if (units <= (unsigned)DU_WIDER_MAX_UNITS || slots > DU_WIDER_ALWAYS_SLOTS) waves = DU_WIDER;
+        }
+    }
+    if (waves > 1 && (scored_floats(waves) + page_list) * sizeof(float) > 160 * 1024) waves = 1;
+    size_t lds_floats = prm.alpha != 0.0f ? scored_floats(waves) : wstride;
     a.pg_off = (int32_t)lds_floats;
     a.units = (int32_t)units;
     a.decay = prm.budget_decay;
@@ -901,9 +915,9 @@ hipError_t launch_decode_step(const ta_decode_state& st, const int32_t* new_tok,
     // the units, then one workgroup per 256 positions for the budget decay
     const uint64_t grid = (uint64_t)units + (uint64_t)tiles * (uint64_t)st.batch;
     if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    if (G <= 4) launch_unit<4>(st, a, pg, (unsigned)grid, lds, wide, s);
-    else if (G <= 8) launch_unit<8>(st, a, pg, (unsigned)grid, lds, wide, s);
-    else launch_unit<MAX_GROUP>(st, a, pg, (unsigned)grid, lds, wide, s);
+    if (G <= 4) launch_unit<4>(st, a, pg, (unsigned)grid, lds, waves, s);
+    else if (G <= 8) launch_unit<8>(st, a, pg, (unsigned)grid, lds, waves, s);
+    else launch_unit<MAX_GROUP>(st, a, pg, (unsigned)grid, lds, waves, s);
     return hipGetLastError();
 }
 

@@ -221,7 +221,7 @@ def test_decode_dense_anchors_overlapping_decayed_spans():
 
 
 def test_decode_large_budget_eight_heads_per_group():
-    # 1501 slots x 8 query heads: the logits of a unit need more than 64 KB of LDS
+    # 1501 slots x 8 query heads: the logits of a unit need more than 64 KB of LDS; eight wavefronts per unit
     w = wl.scaled(wl.CONFIGS["c5_agentic_prefill"], layers=1, batch=1, n=1700, hq=8, hkv=1, ragged=None)
     ev, _ = _run_decode(w, K=1500, steps=5, p_anchor=0.2, check_every=2)
     assert ev == 5
@@ -344,12 +344,14 @@ def test_compact_into_pages_touches_nothing_else():
 
 
 @pytest.mark.parametrize("paged", [None, (16, False)])
-def test_several_wavefronts_per_unit_give_the_single_wavefronts_bits(paged):
+@pytest.mark.parametrize("K,big,n", [(400, 96, 1024),      # four wavefronts per unit against one (768 units)
+                                     (1400, 136, 1600)])   # eight against one (1088 units)
+def test_several_wavefronts_per_unit_give_the_single_wavefronts_bits(paged, K, big, n):
     """Few units with more slots than one wavefront keeps in registers run several wavefronts per unit.  The
-    same sequence alone (8 units) and as every member of a batch of 96 (768 units: one wavefront each) must
-    leave the same state, bit for bit, after the same steps."""
-    K, steps, big = 400, 6, 96
-    w1 = wl.scaled(wl.CONFIGS["c2_full_model"], layers=1, batch=1, n=1024, planted=4)
+    same sequence alone (8 units) and as every member of a large batch (one wavefront per unit) must leave
+    the same state, bit for bit, after the same steps."""
+    steps = 6
+    w1 = wl.scaled(wl.CONFIGS["c2_full_model"], layers=1, batch=1, n=n, planted=4)
     td = wl.make_tokens(w1, clean=False)
     Q, Kc, Vc = wl.make_qkv(w1, device=DEV)
     prm = ta.Params(n_sink=w1.n_sink, n_recent=w1.n_recent, alpha=w1.alpha, beta=w1.beta, gamma=w1.gamma)
