@@ -297,7 +297,7 @@ def test_decode_last_query_rule(rank):
     (64, True, False, 64, 36, 8),      # [pages][heads][64][d]
     (24, False, True, 64, 36, 8),      # a page size that is no power of two; rows compacted straight into the pages
     (128, True, True, 64, 36, 8),      # all slots of a unit in one page
-    (16, False, True, 400, 8, 8),      # more slots than a lane keeps in registers: the looping form of the unit kernel
+    (16, False, True, 400, 8, 8),      # more slots than one wavefront keeps in registers: four wavefronts per unit
     (16, False, False, 64, 10, 16),    # 8 query heads per KV head
     (16, False, True, 400, 6, 16),
     (16, True, True, 1000, 4, 8),      # 1001 slots: four wavefronts per unit at any number of units
