@@ -630,10 +630,11 @@ def main():
         sweep[str(kb)] = {"us_per_pass": round(us, 1), "GB/s": round((sb + cb) / us / 1e3, 1)}
 
     decode = None
-    if args.decode_steps > 0 and scored:
+    decode_steps = args.decode_steps if args.decode_steps > 0 else (0 if args.no_extras else 32)   # the headline reports its step too
+    if decode_steps > 0 and scored:
         plan.run(stream)                                        # the state starts from the outputs of a pass at this budget
         torch.cuda.synchronize()
-        decode = bench.decode_step(args.decode_steps, args.decode_paged)
+        decode = bench.decode_step(decode_steps, args.decode_paged)
 
     # ---- anchor match + voucher expansion alone on a shape that is bound by memory ---------------
     match_stress = None
